@@ -1,0 +1,238 @@
+/*
+ * sart.h - C ABI of the SART branch-serving hot path for AMD MI355X (gfx950).
+ *
+ * The paper (arXiv 2505.13326) schedules N sampled reasoning branches per
+ * request, decodes them in one batch, and removes branches from the batch when
+ * they complete, are pruned by a reward threshold, or are early-stopped once
+ * enough branches of the request completed (Algorithm 1, functions Prefill and
+ * Decode).  Section 4 (last paragraph before "It is worthy to note") fixes the
+ * KV-cache rule this library implements: the prompt's KV cache is shared by
+ * all branches of a request, a branch's own KV cache is released immediately
+ * when it is pruned, early-stopped or completed, and the shared prefix is
+ * released only when every branch of the request has terminated.
+ *
+ * Everything below is device resident: the paged KV pool, the free-page stack,
+ * the per-request prefix tables, the per-branch block tables and the active
+ * list live in HBM and are only changed by kernels.  Calls enqueue work on the
+ * caller's HIP stream and return; only sart_get_state and sart_sync_status
+ * wait for the device.
+ *
+ * Vocabulary
+ *   Nb      branches sampled per request (the paper's N).
+ *   Q       completions that trigger early stop (the paper's M).
+ *   handle  r*Nb + j, the j-th branch of request r; stable for life.
+ *   active index  row of a branch in the compacted active list.  Rows of q,
+ *           out and scores are in active order.
+ *   page    page_tokens consecutive tokens of one sequence, all KV heads.
+ *
+ * Pointers are marked HOST or DEVICE.  The library never keeps a caller
+ * pointer after the work it enqueued has run, except kv_pool (kept for the
+ * life of the cache).  HOST arrays are copied before the call returns.
+ *
+ * Errors.  A call returns a status right away for what the host can see (null
+ * pointers, ids out of range, duplicate ids in one list, shapes the cache was
+ * not created for); then nothing is enqueued.  What only the device can see
+ * (a listed branch that is not active, pool exhaustion, a row buffer smaller
+ * than the active list) makes the whole call a no-op on the device and stores
+ * the status in a sticky device word; the first such status is kept until
+ * sart_sync_status or sart_get_state returns and clears it.
+ *
+ * One cache may be used by one host thread at a time and on one stream at a
+ * time (calls on different streams must be ordered by the caller).
+ */
+#ifndef SART_H
+#define SART_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sart_cache sart_cache; /* opaque */
+
+typedef enum {
+  SART_OK = 0,
+  SART_E_INVALID = 1,   /* bad argument, bad id, buffer too small              */
+  SART_E_OOM_PAGES = 2, /* free stack holds fewer pages than the call needs    */
+  SART_E_STATE = 3,     /* branch / request not in the state the call requires */
+  SART_E_HIP = 4        /* a HIP runtime call failed; see sart_last_error      */
+} sart_status;
+
+typedef enum { SART_F32 = 0, SART_BF16 = 1 } sart_dtype;
+
+typedef enum { SART_SEQ_PREFIX = 0, SART_SEQ_BRANCH = 1 } sart_seq_kind;
+
+/* Branch life cycle (Algorithm 1: a branch leaves the batch by completing,
+ * by the prune predicate, or by early stop). */
+typedef enum {
+  SART_BRANCH_UNUSED = 0,
+  SART_BRANCH_ACTIVE = 1,
+  SART_BRANCH_COMPLETED = 2,
+  SART_BRANCH_PRUNED = 3,
+  SART_BRANCH_EARLY_STOPPED = 4
+} sart_branch_state;
+
+typedef enum {
+  SART_PRUNE_DROP_LOWEST_K = 0, /* victims: the k lowest (score, handle) keys   */
+  SART_PRUNE_KEEP_TOP_K = 1,    /* victims: all but the k highest keys          */
+  SART_PRUNE_THRESHOLD = 2      /* Algorithm 1's predicate: score < threshold   */
+} sart_prune_mode;
+
+/* KV tile layouts inside a page (per KV head; K tile then V tile).
+ *   NATURAL: K[token][d], V[token][d].
+ *   MFMA16 : only bf16, page_tokens 16, head_dim 64 or 128, Hq/Hkv <= 16.
+ *            16-byte chunks ordered so that one coalesced 1 KiB wave load is
+ *            one matrix-core operand:
+ *              K chunk (d/8)*16 + token          holds K[token][8*(d/8) .. +7]
+ *              V chunk (d/32)*64 + (token/4)*16 + d%16
+ *                      holds V[4*(token/4)+0..3][32*(d/32) + d%16]     then
+ *                            V[4*(token/4)+0..3][32*(d/32) + 16 + d%16]
+ * The layout is chosen by sart_alloc_cache (MFMA16 whenever it applies unless
+ * force_natural_layout is set) and reported by sart_cache_layout. */
+typedef enum { SART_LAYOUT_NATURAL = 0, SART_LAYOUT_MFMA16 = 1 } sart_kv_layout;
+
+typedef struct {
+  int32_t n_layers;             /* must be 1                                     */
+  int32_t n_q_heads;            /* Hq                                            */
+  int32_t n_kv_heads;           /* Hkv, divides Hq                               */
+  int32_t head_dim;             /* d, multiple of 8, <= 256                      */
+  int32_t page_tokens;          /* tokens per page (16 in every paper-like run)  */
+  int32_t num_pages;            /* pages in the pool                             */
+  int32_t max_requests;         /* request ids are 0 .. max_requests-1, used once*/
+  int32_t branches_per_request; /* Nb                                            */
+  int32_t finish_quota;         /* Q; 0 or > Nb disables early stop              */
+  int32_t max_pages_per_branch; /* private pages a branch may hold               */
+  int32_t max_prefix_pages;     /* pages a request's prompt may hold             */
+  int32_t kv_dtype;             /* sart_dtype of Q, K, V                         */
+  int32_t force_natural_layout; /* nonzero: never pick SART_LAYOUT_MFMA16        */
+  void* kv_pool;                /* DEVICE, caller owned, or NULL: library owns   */
+  size_t kv_pool_bytes;         /* >= sart_pool_bytes(desc) when kv_pool != NULL */
+  const int32_t* initial_free_order; /* HOST [num_pages] permutation, or NULL =
+                                        identity.  Page initial_free_order[0] is
+                                        handed out first.                        */
+} sart_cache_desc;
+
+typedef struct {
+  int32_t mode;                 /* sart_prune_mode                               */
+  int32_t k;                    /* modes 0,1: per-request count                  */
+  const int32_t* k_per_request; /* HOST [max_requests] or NULL (use k)           */
+  const float* threshold;       /* HOST [max_requests], mode 2                   */
+  const int32_t* max_pruned;    /* HOST [max_requests] or NULL (no cap): a request
+                                   never exceeds this many pruned branches in
+                                   total (Algorithm 1's max_num_pruned)          */
+} sart_prune_policy;
+
+/* Bytes of KV pool the description needs:
+ * num_pages * page_tokens * 2 * Hkv * d * sizeof(element). */
+size_t sart_pool_bytes(const sart_cache_desc* desc);
+
+/* A0.  Creates the cache: every page free, no request, no branch.  Zero-fills
+ * the pool (so never-written slots hold finite values).  Synchronous. */
+sart_status sart_alloc_cache(const sart_cache_desc* desc, sart_cache** out);
+sart_status sart_free_cache(sart_cache* cache);
+int32_t sart_cache_layout(const sart_cache* cache); /* sart_kv_layout */
+
+/* A1/A2.  Appends n_tokens[i] tokens of K and V to sequence ids[i], for i in
+ * list order; rows of k and v are the sequences' tokens back to back,
+ * DEVICE [sum n, Hkv, d] in kv_dtype.
+ *   SART_SEQ_PREFIX: ids are request ids.  The first append to a request
+ *     creates it together with its Nb active branches (Algorithm 1, Prefill:
+ *     N branches pushed after prefilling), appended to the end of the active
+ *     list in order j = 0..Nb-1, prefix reference count Nb.  Later prefix
+ *     appends extend the prompt and are allowed until the first branch append
+ *     of that request (SART_E_STATE after).  ids must not be NULL.
+ *   SART_SEQ_BRANCH: ids are branch handles, all ACTIVE (else SART_E_STATE);
+ *     ids == NULL means every active branch in active order and then n_seqs
+ *     must equal the active count (else SART_E_INVALID).
+ *   n_tokens == NULL means one token per sequence.
+ * Pages are popped from the free stack sequence by sequence in list order,
+ * each sequence taking its new pages in ascending logical page order.
+ * Fewer free pages than needed: SART_E_OOM_PAGES, nothing changes. */
+sart_status sart_append_tokens(sart_cache* cache, int32_t kind, int32_t n_seqs,
+                               const int32_t* ids /*HOST*/,
+                               const int32_t* n_tokens /*HOST*/,
+                               const void* k /*DEVICE*/, const void* v /*DEVICE*/,
+                               int32_t layer, void* stream);
+
+/* A3-A6.  One decode step of attention ("Batch decoding", Algorithm 1,
+ * Decode): for every active branch b (row a) and query head h,
+ *   out[a,h,:] = sum_t softmax_t(scale * q[a,h,:] . K[t, h/G, :]) * V[t, h/G, :]
+ * over t = the request's prompt tokens followed by b's own tokens (the token
+ * appended this step included).  q: DEVICE [n_rows, Hq, d] kv_dtype;
+ * out: DEVICE [n_rows, Hq, d] float; rows >= active count are left untouched.
+ * n_rows < active count: SART_E_INVALID (sticky), nothing written.
+ * scale <= 0 means 1/sqrt(d).  An empty context gives a zero row. */
+sart_status sart_decode_attention(sart_cache* cache, int32_t layer,
+                                  const void* q, float* out, int32_t n_rows,
+                                  float scale, void* stream);
+
+/* A7.  Prunes branches by score (Algorithm 1, Decode: "Prune the branch").
+ * scores: DEVICE float [n_scores], active order, n_scores >= active count.
+ * Per request, over its active branches:
+ *   DROP_LOWEST_K  the min(k, live) smallest keys (score, handle);
+ *   KEEP_TOP_K     all but the min(k, live) largest keys;
+ *   THRESHOLD      in ascending active index: score < threshold[r] and the
+ *                  request's pruned count still below max_pruned[r].
+ * In modes 0 and 1 max_pruned (if given) limits the victims to the lowest
+ * keys that still fit under the cap.  A NaN score compares as +infinity.
+ * Victims become PRUNED, their private pages return to the free stack at once,
+ * the prefix is released when no branch of the request is left, and the
+ * active list, lengths and block tables are compacted keeping order. */
+sart_status sart_prune_branches(sart_cache* cache, const sart_prune_policy* policy,
+                                const float* scores, int32_t n_scores, void* stream);
+
+/* A8.  Marks the listed ACTIVE branches COMPLETED (Algorithm 1, Decode:
+ * "Remove the completed branch"), frees their pages, counts them, and when a
+ * request has reached Q completions early-stops its remaining active branches
+ * (Section 3, Solution 1).  Any listed branch not ACTIVE: SART_E_STATE,
+ * nothing changes. */
+sart_status sart_finish_branch(sart_cache* cache, int32_t n,
+                               const int32_t* handles /*HOST*/, void* stream);
+
+/* Waits for the cache's last-used stream, returns the sticky device status
+ * and clears it. */
+sart_status sart_sync_status(sart_cache* cache);
+
+/* Waits, then copies the canonical integer state to HOST buffers (any may be
+ * NULL).  Returns the sticky status like sart_sync_status.
+ *   n_active        [1]
+ *   active_handles  [max_requests*Nb]   first n_active valid, rest -1
+ *   seq_lens        [max_requests*Nb]   private tokens, active order, rest 0
+ *   block_tables    [max_requests*Nb, max_pages_per_branch]  active order, -1 padded
+ *   free_stack      [num_pages]         first free_top valid (top = last), rest -1
+ *   free_top        [1]
+ *   prefix_tables   [max_requests, max_prefix_pages]  -1 padded / released
+ *   prefix_lens     [max_requests]      prompt tokens (kept after release)
+ *   prefix_refcnt   [max_requests]      active branches of the request
+ *   branch_state    [max_requests*Nb]   by handle
+ *   req_counters    [max_requests, 2]   completed, pruned */
+sart_status sart_get_state(sart_cache* cache, int32_t* n_active,
+                           int32_t* active_handles, int32_t* seq_lens,
+                           int32_t* block_tables, int32_t* free_stack,
+                           int32_t* free_top, int32_t* prefix_tables,
+                           int32_t* prefix_lens, int32_t* prefix_refcnt,
+                           int32_t* branch_state, int32_t* req_counters);
+
+/* Launch statistics of the last sart_decode_attention on this cache, measured
+ * with HIP events on the stream the kernels ran on (for bench harnesses).
+ * Enable with sart_set_profiling(cache, 1); then each decode call records
+ * events around its dominant kernel.  ms_attn: that kernel; ms_total: the
+ * whole call's device work.  Waits for the events. */
+sart_status sart_set_profiling(sart_cache* cache, int32_t on);
+sart_status sart_last_decode_ms(sart_cache* cache, float* ms_attn, float* ms_total);
+
+/* Tuning knobs of the decode launch (defaults are chosen for MI355X):
+ * workgroups of the persistent attention grid (<= 0: default) and prefix
+ * chunk in pages (<= 0: chosen on the device from the active set). */
+sart_status sart_set_decode_launch(sart_cache* cache, int32_t n_workgroups,
+                                   int32_t prefix_chunk_pages);
+
+/* Text of the last host-side error of this thread. */
+const char* sart_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SART_H */
