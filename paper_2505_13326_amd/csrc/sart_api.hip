@@ -1,0 +1,476 @@
+// C ABI of libsart (see include/sart.h): argument checks, device memory, the
+// staging of small host arrays, and kernel launches.  No arithmetic of the
+// method happens on the host.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <vector>
+
+#include "sart_internal.h"
+
+using namespace sart;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+sart_status fail(sart_status st, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+sart_status fail(sart_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+#define HIP_TRY(expr)                                                                  \
+  do {                                                                                 \
+    hipError_t e_ = (expr);                                                            \
+    if (e_ != hipSuccess) return fail(SART_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr int kStageSlots = 8;
+
+struct StageSlot {
+  int* host = nullptr;  // pinned
+  int* dev = nullptr;
+  hipEvent_t done = nullptr;
+};
+
+}  // namespace
+
+struct sart_cache {
+  Ctx ctx;
+  sart_cache_desc desc;
+  int device = 0;
+  bool owns_pool = false;
+  std::vector<void*> allocs;         // every hipMalloc'ed block except the staging slots
+  StageSlot stage[kStageSlots];
+  size_t stage_ints = 0;
+  int next_slot = 0;
+  int call_seq = 0;
+  hipStream_t last_stream = nullptr;
+  float* partials = nullptr;
+  long long partial_cap = 0;
+  int n_wg = 0;
+  int max_wg = 0;
+  int chunk_pages = 0;
+  bool profiling = false;
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  bool ev_valid = false;
+};
+
+namespace {
+
+template <typename T>
+sart_status dev_alloc(sart_cache* c, T** p, size_t n) {
+  void* q = nullptr;
+  HIP_TRY(hipMalloc(&q, (n ? n : 1) * sizeof(T)));
+  c->allocs.push_back(q);
+  *p = (T*)q;
+  return SART_OK;
+}
+
+// Takes the next staging slot (waiting for the call that used it last) and
+// returns its pinned host buffer.
+sart_status stage_begin(sart_cache* c, StageSlot** slot) {
+  StageSlot* s = &c->stage[c->next_slot];
+  c->next_slot = (c->next_slot + 1) % kStageSlots;
+  HIP_TRY(hipEventSynchronize(s->done));
+  *slot = s;
+  return SART_OK;
+}
+
+sart_status stage_upload(sart_cache* c, StageSlot* s, size_t n_ints, hipStream_t st) {
+  (void)c;
+  if (n_ints) HIP_TRY(hipMemcpyAsync(s->dev, s->host, n_ints * sizeof(int), hipMemcpyHostToDevice, st));
+  return SART_OK;
+}
+
+sart_status check_desc(const sart_cache_desc* d) {
+  if (!d) return fail(SART_E_INVALID, "null description");
+  if (d->n_layers != 1) return fail(SART_E_INVALID, "n_layers must be 1");
+  if (d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->n_q_heads % d->n_kv_heads)
+    return fail(SART_E_INVALID, "n_q_heads must be a positive multiple of n_kv_heads");
+  if (d->head_dim <= 0 || d->head_dim % 8 || d->head_dim > 256)
+    return fail(SART_E_INVALID, "head_dim must be a multiple of 8, at most 256");
+  if (d->page_tokens <= 0 || d->num_pages <= 0 || d->max_requests <= 0 || d->branches_per_request <= 0)
+    return fail(SART_E_INVALID, "page_tokens, num_pages, max_requests, branches_per_request must be positive");
+  if (d->max_pages_per_branch <= 0 || d->max_prefix_pages <= 0)
+    return fail(SART_E_INVALID, "max_pages_per_branch and max_prefix_pages must be positive");
+  if (d->kv_dtype != SART_F32 && d->kv_dtype != SART_BF16) return fail(SART_E_INVALID, "unknown kv_dtype");
+  if ((long long)d->max_requests * d->branches_per_request > (1 << 22))
+    return fail(SART_E_INVALID, "max_requests * branches_per_request too large");
+  return SART_OK;
+}
+
+int pick_layout(const sart_cache_desc* d) {
+  const int G = d->n_q_heads / d->n_kv_heads;
+  if (!d->force_natural_layout && d->kv_dtype == SART_BF16 && d->page_tokens == 16 &&
+      (d->head_dim == 64 || d->head_dim == 128) && G <= kMaxGroup)
+    return SART_LAYOUT_MFMA16;
+  return SART_LAYOUT_NATURAL;
+}
+
+void note_stream(sart_cache* c, void* stream) { c->last_stream = (hipStream_t)stream; }
+
+}  // namespace
+
+extern "C" {
+
+const char* sart_last_error(void) { return g_err; }
+
+size_t sart_pool_bytes(const sart_cache_desc* d) {
+  if (!d) return 0;
+  const size_t es = d->kv_dtype == SART_F32 ? 4 : 2;
+  return (size_t)d->num_pages * d->page_tokens * 2 * d->n_kv_heads * d->head_dim * es;
+}
+
+sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
+  if (!out) return fail(SART_E_INVALID, "null out");
+  *out = nullptr;
+  sart_status st = check_desc(d);
+  if (st != SART_OK) return st;
+  const size_t pool_bytes = sart_pool_bytes(d);
+  if (d->kv_pool && d->kv_pool_bytes < pool_bytes)
+    return fail(SART_E_INVALID, "kv_pool_bytes %zu < required %zu", d->kv_pool_bytes, pool_bytes);
+  if (d->initial_free_order) {
+    std::vector<char> seen(d->num_pages, 0);
+    for (int i = 0; i < d->num_pages; ++i) {
+      const int p = d->initial_free_order[i];
+      if (p < 0 || p >= d->num_pages || seen[p]) return fail(SART_E_INVALID, "initial_free_order is not a permutation");
+      seen[p] = 1;
+    }
+  }
+  sart_cache* c = new sart_cache();
+  c->desc = *d;
+  c->desc.initial_free_order = nullptr;
+  HIP_TRY(hipGetDevice(&c->device));
+  Dims& dm = c->ctx.dm;
+  dm.Hq = d->n_q_heads; dm.Hkv = d->n_kv_heads; dm.G = dm.Hq / dm.Hkv; dm.d = d->head_dim;
+  dm.pt = d->page_tokens; dm.num_pages = d->num_pages; dm.max_req = d->max_requests;
+  dm.Nb = d->branches_per_request; dm.Q = d->finish_quota; dm.max_bp = d->max_pages_per_branch;
+  dm.max_pp = d->max_prefix_pages; dm.H = dm.max_req * dm.Nb; dm.dtype = d->kv_dtype;
+  dm.layout = pick_layout(d); dm.esize = d->kv_dtype == SART_F32 ? 4 : 2;
+  dm.tile_elems = (long long)dm.pt * dm.d;
+  dm.page_elems = (long long)dm.Hkv * 2 * dm.tile_elems;
+
+  Tables& tb = c->ctx.tb;
+  const size_t H = dm.H, R = dm.max_req;
+#define ALLOC(ptr, n)                                           \
+  do {                                                          \
+    st = dev_alloc(c, &(ptr), (n));                             \
+    if (st != SART_OK) { sart_free_cache(c); return st; }       \
+  } while (0)
+  ALLOC(tb.scal, S_COUNT);
+  ALLOC(tb.free_stack, dm.num_pages);
+  ALLOC(tb.req_used, R); ALLOC(tb.prefix_len, R); ALLOC(tb.prefix_table, R * dm.max_pp);
+  ALLOC(tb.refcnt, R); ALLOC(tb.num_completed, R); ALLOC(tb.num_pruned, R); ALLOC(tb.branch_appended, R);
+  ALLOC(tb.br_state, H); ALLOC(tb.active_idx_of, H); ALLOC(tb.active, H); ALLOC(tb.seq_len, H);
+  ALLOC(tb.bt[0], H * dm.max_bp); ALLOC(tb.bt[1], H * dm.max_bp);
+  ALLOC(tb.new_state, H); ALLOC(tb.mv_push_off, H); ALLOC(tb.mv_new_idx, H);
+  ALLOC(tb.tmp_a, H); ALLOC(tb.tmp_b, H);
+  ALLOC(tb.req_first, R); ALLOC(tb.req_push_off, R); ALLOC(tb.req_touched, R);
+  ALLOC(tb.ap_id, H); ALLOC(tb.ap_start, H);
+  ALLOC(tb.page_cum, H + 1); ALLOC(tb.live_req, R); ALLOC(tb.live_item_start, R + 1);
+
+  if (d->kv_pool) {
+    c->ctx.pool = d->kv_pool;
+  } else {
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, pool_bytes);
+    if (e != hipSuccess) { sart_free_cache(c); return fail(SART_E_HIP, "hipMalloc(pool %zu B): %s", pool_bytes, hipGetErrorString(e)); }
+    c->allocs.push_back(p);
+    c->ctx.pool = p;
+    c->owns_pool = true;
+  }
+
+  // decode launch shape: a persistent grid of kAttnWaves-wave workgroups
+  hipDeviceProp_t prop;
+  HIP_TRY(hipGetDeviceProperties(&prop, c->device));
+  const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  c->max_wg = cus * 8;
+  c->n_wg = cus;
+  c->chunk_pages = 0;
+  // partial slots: one per private wave, one per (row, kv head) crossing, and
+  // the prompt chunks of every (row, kv head) at the smallest chunk size
+  const long long S = (long long)H * dm.Hkv;
+  const long long npc_max = (dm.max_pp + kStagePages - 1) / kStagePages;
+  c->partial_cap = (long long)c->max_wg * kAttnWaves + S * (1 + npc_max);
+  const long long pf = (long long)dm.G * dm.d + 2 * dm.G;
+  ALLOC(c->partials, (size_t)(c->partial_cap * pf));
+#undef ALLOC
+
+  // staging slots for small host arrays (ids, counts, offsets, policy arrays)
+  c->stage_ints = 3 * H + 3 * R + 16;
+  for (int i = 0; i < kStageSlots; ++i) {
+    HIP_TRY(hipHostMalloc((void**)&c->stage[i].host, c->stage_ints * sizeof(int), hipHostMallocDefault));
+    HIP_TRY(hipMalloc((void**)&c->stage[i].dev, c->stage_ints * sizeof(int)));
+    HIP_TRY(hipEventCreateWithFlags(&c->stage[i].done, hipEventDisableTiming));
+  }
+  for (int i = 0; i < 4; ++i) HIP_TRY(hipEventCreate(&c->ev[i]));
+
+  // tables + zero-filled pool
+  int* order_dev = nullptr;
+  if (d->initial_free_order) {
+    HIP_TRY(hipMalloc((void**)&order_dev, (size_t)dm.num_pages * sizeof(int)));
+    HIP_TRY(hipMemcpy(order_dev, d->initial_free_order, (size_t)dm.num_pages * sizeof(int), hipMemcpyHostToDevice));
+  }
+  launch_init_tables(c->ctx, order_dev, nullptr);
+  HIP_TRY(hipMemsetAsync(c->ctx.pool, 0, pool_bytes, nullptr));
+  HIP_TRY(hipStreamSynchronize(nullptr));
+  if (order_dev) HIP_TRY(hipFree(order_dev));
+  HIP_TRY(hipGetLastError());
+  *out = c;
+  return SART_OK;
+}
+
+sart_status sart_free_cache(sart_cache* c) {
+  if (!c) return SART_OK;
+  (void)hipDeviceSynchronize();
+  for (void* p : c->allocs) (void)hipFree(p);
+  for (int i = 0; i < kStageSlots; ++i) {
+    if (c->stage[i].host) (void)hipHostFree(c->stage[i].host);
+    if (c->stage[i].dev) (void)hipFree(c->stage[i].dev);
+    if (c->stage[i].done) (void)hipEventDestroy(c->stage[i].done);
+  }
+  for (int i = 0; i < 4; ++i)
+    if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+  delete c;
+  return SART_OK;
+}
+
+int32_t sart_cache_layout(const sart_cache* c) { return c ? c->ctx.dm.layout : -1; }
+
+sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, const int32_t* ids,
+                               const int32_t* n_tokens, const void* k, const void* v, int32_t layer,
+                               void* stream) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  const Dims& dm = c->ctx.dm;
+  if (layer != 0) return fail(SART_E_INVALID, "layer must be 0");
+  if (kind != SART_SEQ_PREFIX && kind != SART_SEQ_BRANCH) return fail(SART_E_INVALID, "unknown sequence kind");
+  if (n_seqs < 0) return fail(SART_E_INVALID, "negative n_seqs");
+  if (kind == SART_SEQ_PREFIX && !ids && n_seqs > 0) return fail(SART_E_INVALID, "prefix append needs request ids");
+  const int limit = kind == SART_SEQ_PREFIX ? dm.max_req : dm.H;
+  if (n_seqs > limit) return fail(SART_E_INVALID, "more sequences than exist");
+  long long total = 0;
+  if (ids) {
+    std::vector<char> seen(limit, 0);
+    for (int i = 0; i < n_seqs; ++i) {
+      if (ids[i] < 0 || ids[i] >= limit) return fail(SART_E_INVALID, "id %d out of range at %d", ids[i], i);
+      if (seen[ids[i]]) return fail(SART_E_INVALID, "duplicate id %d", ids[i]);
+      seen[ids[i]] = 1;
+    }
+  }
+  if (n_tokens) {
+    for (int i = 0; i < n_seqs; ++i) {
+      if (n_tokens[i] < 0) return fail(SART_E_INVALID, "negative token count at %d", i);
+      total += n_tokens[i];
+    }
+    if (total > 0x7fffffffLL) return fail(SART_E_INVALID, "too many tokens in one call");
+  } else {
+    total = n_seqs;
+  }
+  if (total > 0 && (!k || !v)) return fail(SART_E_INVALID, "null k or v");
+  hipStream_t st = (hipStream_t)stream;
+  note_stream(c, stream);
+  AppendArgs a{};
+  a.kind = kind; a.n_seqs = n_seqs; a.total_rows = total; a.k = k; a.v = v; a.call_seq = ++c->call_seq;
+  if (ids || n_tokens) {
+    StageSlot* s;
+    sart_status rc = stage_begin(c, &s);
+    if (rc != SART_OK) return rc;
+    size_t off = 0;
+    if (ids) { memcpy(s->host + off, ids, (size_t)n_seqs * sizeof(int)); a.ids = s->dev + off; off += n_seqs; }
+    if (n_tokens) {
+      memcpy(s->host + off, n_tokens, (size_t)n_seqs * sizeof(int));
+      a.ntok = s->dev + off; off += n_seqs;
+      int run = 0;
+      for (int i = 0; i < n_seqs; ++i) { s->host[off + i] = run; run += n_tokens[i]; }
+      a.tok_off = s->dev + off; off += n_seqs;
+    }
+    rc = stage_upload(c, s, off, st);
+    if (rc != SART_OK) return rc;
+    launch_append(c->ctx, a, st);
+    HIP_TRY(hipEventRecord(s->done, st));
+  } else {
+    launch_append(c->ctx, a, st);
+  }
+  HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
+
+sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows,
+                                  float scale, void* stream) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (layer != 0) return fail(SART_E_INVALID, "layer must be 0");
+  if (n_rows < 0) return fail(SART_E_INVALID, "negative n_rows");
+  if (n_rows > 0 && (!q || !out)) return fail(SART_E_INVALID, "null q or out");
+  const Dims& dm = c->ctx.dm;
+  if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)dm.d);
+  hipStream_t st = (hipStream_t)stream;
+  note_stream(c, stream);
+  DecodeArgs a{};
+  a.q = q; a.out = out; a.n_rows = n_rows;
+  a.scale_log2 = scale * 1.44269504088896340736f;
+  a.n_wg = c->n_wg; a.chunk_pages = c->chunk_pages;
+  a.partials = c->partials; a.partial_cap = c->partial_cap;
+  a.call_seq = ++c->call_seq;
+  for (int i = 0; i < 4; ++i) a.ev[i] = c->profiling ? c->ev[i] : nullptr;
+  launch_decode(c->ctx, a, st);
+  c->ev_valid = c->profiling;
+  HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
+
+sart_status sart_prune_branches(sart_cache* c, const sart_prune_policy* pol, const float* scores,
+                                int32_t n_scores, void* stream) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (!pol) return fail(SART_E_INVALID, "null policy");
+  if (pol->mode < 0 || pol->mode > 2) return fail(SART_E_INVALID, "unknown prune mode");
+  if (!scores || n_scores < 0) return fail(SART_E_INVALID, "null scores");
+  if (pol->mode == SART_PRUNE_THRESHOLD && !pol->threshold) return fail(SART_E_INVALID, "threshold mode needs thresholds");
+  if (pol->mode != SART_PRUNE_THRESHOLD && !pol->k_per_request && pol->k < 0) return fail(SART_E_INVALID, "negative k");
+  const Dims& dm = c->ctx.dm;
+  hipStream_t st = (hipStream_t)stream;
+  note_stream(c, stream);
+  PruneArgs a{};
+  a.mode = pol->mode; a.k = pol->k; a.scores = scores; a.n_scores = n_scores; a.call_seq = ++c->call_seq;
+  const bool need_stage = pol->k_per_request || pol->max_pruned || pol->mode == SART_PRUNE_THRESHOLD;
+  if (need_stage) {
+    StageSlot* s;
+    sart_status rc = stage_begin(c, &s);
+    if (rc != SART_OK) return rc;
+    size_t off = 0;
+    const size_t R = dm.max_req;
+    if (pol->mode != SART_PRUNE_THRESHOLD && pol->k_per_request) {
+      memcpy(s->host + off, pol->k_per_request, R * sizeof(int)); a.k_per_req = s->dev + off; off += R;
+    }
+    if (pol->mode == SART_PRUNE_THRESHOLD) {
+      memcpy(s->host + off, pol->threshold, R * sizeof(float)); a.thr = (const float*)(s->dev + off); off += R;
+    }
+    if (pol->max_pruned) {
+      memcpy(s->host + off, pol->max_pruned, R * sizeof(int)); a.maxp = s->dev + off; off += R;
+    }
+    rc = stage_upload(c, s, off, st);
+    if (rc != SART_OK) return rc;
+    launch_prune(c->ctx, a, st);
+    HIP_TRY(hipEventRecord(s->done, st));
+  } else {
+    launch_prune(c->ctx, a, st);
+  }
+  HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
+
+sart_status sart_finish_branch(sart_cache* c, int32_t n, const int32_t* handles, void* stream) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  const Dims& dm = c->ctx.dm;
+  if (n < 0 || (n > 0 && !handles)) return fail(SART_E_INVALID, "bad handle list");
+  if (n > dm.H) return fail(SART_E_INVALID, "more handles than branches");
+  if (n == 0) return SART_OK;  // nothing completes: the state does not change
+  {
+    std::vector<char> seen(dm.H, 0);
+    for (int i = 0; i < n; ++i) {
+      if (handles[i] < 0 || handles[i] >= dm.H) return fail(SART_E_INVALID, "handle %d out of range", handles[i]);
+      if (seen[handles[i]]) return fail(SART_E_INVALID, "duplicate handle %d", handles[i]);
+      seen[handles[i]] = 1;
+    }
+  }
+  hipStream_t st = (hipStream_t)stream;
+  note_stream(c, stream);
+  StageSlot* s;
+  sart_status rc = stage_begin(c, &s);
+  if (rc != SART_OK) return rc;
+  if (n) memcpy(s->host, handles, (size_t)n * sizeof(int));
+  rc = stage_upload(c, s, n, st);
+  if (rc != SART_OK) return rc;
+  launch_finish(c->ctx, n, s->dev, ++c->call_seq, st);
+  HIP_TRY(hipEventRecord(s->done, st));
+  HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
+
+static sart_status read_and_clear_status(sart_cache* c, int* scal_host) {
+  HIP_TRY(hipStreamSynchronize(c->last_stream));
+  HIP_TRY(hipMemcpy(scal_host, c->ctx.tb.scal, S_COUNT * sizeof(int), hipMemcpyDeviceToHost));
+  if (scal_host[S_ERR] != 0) {
+    const int zero[2] = {0, 0};
+    HIP_TRY(hipMemcpy(c->ctx.tb.scal + S_ERR, zero, 2 * sizeof(int), hipMemcpyHostToDevice));
+    fail((sart_status)scal_host[S_ERR], "device-side status %d raised by call #%d on this cache",
+         scal_host[S_ERR], scal_host[S_ERRCALL]);
+  }
+  return (sart_status)scal_host[S_ERR];
+}
+
+sart_status sart_sync_status(sart_cache* c) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  int scal[S_COUNT];
+  return read_and_clear_status(c, scal);
+}
+
+sart_status sart_get_state(sart_cache* c, int32_t* n_active, int32_t* active_handles, int32_t* seq_lens,
+                           int32_t* block_tables, int32_t* free_stack, int32_t* free_top,
+                           int32_t* prefix_tables, int32_t* prefix_lens, int32_t* prefix_refcnt,
+                           int32_t* branch_state, int32_t* req_counters) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  const Dims& dm = c->ctx.dm;
+  const Tables& tb = c->ctx.tb;
+  int scal[S_COUNT];
+  sart_status status = read_and_clear_status(c, scal);
+  if (status == SART_E_HIP) return status;
+  const size_t H = dm.H, R = dm.max_req;
+  if (n_active) *n_active = scal[S_NACTIVE];
+  if (free_top) *free_top = scal[S_FREETOP];
+#define D2H(dst, src, n) HIP_TRY(hipMemcpy((dst), (src), (n) * sizeof(int), hipMemcpyDeviceToHost))
+  if (active_handles) D2H(active_handles, tb.active, H);
+  if (seq_lens) D2H(seq_lens, tb.seq_len, H);
+  if (block_tables) D2H(block_tables, tb.bt[scal[S_BTSEL]], H * dm.max_bp);
+  if (free_stack) {
+    D2H(free_stack, tb.free_stack, (size_t)dm.num_pages);
+    for (int i = scal[S_FREETOP]; i < dm.num_pages; ++i) free_stack[i] = -1;  // popped entries are not part of the state
+  }
+  if (prefix_tables) D2H(prefix_tables, tb.prefix_table, R * dm.max_pp);
+  if (prefix_lens) D2H(prefix_lens, tb.prefix_len, R);
+  if (prefix_refcnt) D2H(prefix_refcnt, tb.refcnt, R);
+  if (branch_state) D2H(branch_state, tb.br_state, H);
+  if (req_counters) {
+    std::vector<int> a(R), b(R);
+    D2H(a.data(), tb.num_completed, R);
+    D2H(b.data(), tb.num_pruned, R);
+    for (size_t r = 0; r < R; ++r) { req_counters[2 * r] = a[r]; req_counters[2 * r + 1] = b[r]; }
+  }
+#undef D2H
+  return status;
+}
+
+sart_status sart_set_profiling(sart_cache* c, int32_t on) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  c->profiling = on != 0;
+  c->ev_valid = false;
+  return SART_OK;
+}
+
+sart_status sart_last_decode_ms(sart_cache* c, float* ms_attn, float* ms_total) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (!c->ev_valid) return fail(SART_E_STATE, "no profiled decode call yet");
+  HIP_TRY(hipEventSynchronize(c->ev[3]));
+  if (ms_attn) HIP_TRY(hipEventElapsedTime(ms_attn, c->ev[1], c->ev[2]));
+  if (ms_total) HIP_TRY(hipEventElapsedTime(ms_total, c->ev[0], c->ev[3]));
+  return SART_OK;
+}
+
+sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t prefix_chunk_pages) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (n_workgroups > c->max_wg) return fail(SART_E_INVALID, "at most %d workgroups", c->max_wg);
+  hipDeviceProp_t prop;
+  HIP_TRY(hipGetDeviceProperties(&prop, c->device));
+  c->n_wg = n_workgroups > 0 ? n_workgroups : (prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256);
+  c->chunk_pages = prefix_chunk_pages > 0 ? prefix_chunk_pages : 0;
+  return SART_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,523 @@
+// Cache bookkeeping kernels: table initialisation, token append, and the
+// terminate pass shared by pruning and completion / early stop.
+//
+// The paper (arXiv 2505.13326) states the rules these kernels implement:
+// Algorithm 1 (Prefill creates a request's Nb branches; Decode removes
+// completed branches, applies the prune predicate, tests for termination),
+// Section 3 Solution 1 (early stop once Q branches complete) and Section 4
+// (shared prefix KV, immediate release of a leaving branch's KV, prefix
+// released with the request's last branch).
+//
+// Every planning kernel is ONE workgroup of 1024 threads: the integer state
+// is a few thousand entries, and a single workgroup makes the order of every
+// pop and push a plain prefix sum, hence reproducible bit for bit.  The bulk
+// work (KV rows, block-table rows, free-stack pushes) is done by wide
+// kernels that read the plan.
+#include "sart_internal.h"
+
+namespace sart {
+
+// ---------------------------------------------------------------------------
+// block-wide exclusive scan (1024 threads = 16 waves)
+// ---------------------------------------------------------------------------
+__device__ inline int wave_incl_scan(int v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    int n = __shfl_up(v, off, 64);
+    if (lane >= off) v += n;
+  }
+  return v;
+}
+
+// Returns the exclusive prefix of v over the block and the block total.
+// lds must hold 17 ints.  All threads of the block must call it.
+__device__ inline int block_excl_scan(int v, int* lds, int& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nw = (blockDim.x + 63) >> 6;
+  int incl = wave_incl_scan(v);
+  __syncthreads();
+  if (lane == 63) lds[wave] = incl;
+  __syncthreads();
+  if (wave == 0) {
+    int t = lane < nw ? lds[lane] : 0;
+    int ti = wave_incl_scan(t);
+    if (lane < nw) lds[lane] = ti - t;
+    if (lane == nw - 1) lds[16] = ti;
+  }
+  __syncthreads();
+  total = lds[16];
+  return incl - v + lds[wave];
+}
+
+__device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// First error of a call wins and stays until the host reads it.
+__device__ inline void record_error(int* scal, int code, int call_seq) {
+  if (scal[S_ERR] == 0) {
+    scal[S_ERR] = code;
+    scal[S_ERRCALL] = call_seq;
+  }
+  scal[S_CALLOK] = 0;
+}
+
+// ---------------------------------------------------------------------------
+// A0: initial tables
+// ---------------------------------------------------------------------------
+__global__ void k_init_tables(Ctx c, const int* free_order) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long nth = (long long)gridDim.x * blockDim.x;
+  // page free_order[0] is popped first, so it sits on top of the stack
+  for (long long i = tid; i < dm.num_pages; i += nth) {
+    int j = dm.num_pages - 1 - (int)i;
+    tb.free_stack[i] = free_order ? free_order[j] : j;
+  }
+  for (long long i = tid; i < dm.max_req; i += nth) {
+    tb.req_used[i] = 0; tb.prefix_len[i] = 0; tb.refcnt[i] = 0; tb.num_completed[i] = 0;
+    tb.num_pruned[i] = 0; tb.branch_appended[i] = 0; tb.req_first[i] = 0; tb.req_push_off[i] = -1;
+    tb.req_touched[i] = 0;
+  }
+  for (long long i = tid; i < (long long)dm.max_req * dm.max_pp; i += nth) tb.prefix_table[i] = -1;
+  for (long long i = tid; i < dm.H; i += nth) {
+    tb.br_state[i] = SART_BRANCH_UNUSED; tb.active_idx_of[i] = -1; tb.active[i] = -1; tb.seq_len[i] = 0;
+  }
+  for (long long i = tid; i < (long long)dm.H * dm.max_bp; i += nth) { tb.bt[0][i] = -1; tb.bt[1][i] = -1; }
+  if (tid < S_COUNT) tb.scal[tid] = tid == S_FREETOP ? dm.num_pages : (tid == S_CALLOK ? 1 : 0);
+}
+
+void launch_init_tables(const Ctx& c, const int* free_order_dev, hipStream_t s) {
+  hipLaunchKernelGGL(k_init_tables, dim3(1024), dim3(256), 0, s, c, free_order_dev);
+}
+
+// ---------------------------------------------------------------------------
+// A1/A2: append plan.  Validates the whole list, pops pages by prefix sum,
+// creates requests, updates lengths.  Sequence i takes
+// free_stack[top-1-(off_i+k)] as its k-th new page: exactly the pages a
+// sequential pop loop in list order would hand out.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kPlanThreads)
+k_append_plan(Ctx c, AppendArgs a) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  int* scal = tb.scal;
+  __shared__ int lds[17];
+  __shared__ int s_err;     // (list index << 2) | status of the first failing sequence
+  const int tid = threadIdx.x;
+  const int nA = scal[S_NACTIVE];
+  const int top = scal[S_FREETOP];
+  if (tid == 0) s_err = 0x7fffffff;
+  __syncthreads();
+  if (!a.ids && a.n_seqs != nA) {
+    if (tid == 0) record_error(scal, SART_E_INVALID, a.call_seq);
+    return;
+  }
+  // pass 1: validate, compute pages needed, stash id / start length
+  int carry = 0, carry_new = 0;
+  for (int base = 0; base < a.n_seqs; base += kPlanThreads) {
+    const int i = base + tid;
+    int need = 0, creates = 0;
+    if (i < a.n_seqs) {
+      const int id = a.ids ? a.ids[i] : tb.active[i];
+      const int n = a.ntok ? a.ntok[i] : 1;
+      int err = 0, len = 0, cap = 0;
+      if (a.kind == SART_SEQ_PREFIX) {
+        if (tb.req_used[id] && (tb.refcnt[id] == 0 || tb.branch_appended[id])) err = SART_E_STATE;
+        len = tb.prefix_len[id];
+        cap = dm.max_pp;
+        creates = !tb.req_used[id];
+      } else {
+        if (tb.br_state[id] != SART_BRANCH_ACTIVE) err = SART_E_STATE;
+        else len = tb.seq_len[tb.active_idx_of[id]];
+        cap = dm.max_bp;
+      }
+      const int have = ceil_div(len, dm.pt), want = ceil_div(len + n, dm.pt);
+      if (!err && want > cap) err = SART_E_INVALID;
+      if (err) atomicMin(&s_err, (i << 2) | err);
+      need = want - have;
+      tb.ap_id[i] = id;
+      tb.ap_start[i] = len;
+    }
+    int tot, tot_new;
+    const int ex = block_excl_scan(need, lds, tot);
+    const int ex_new = block_excl_scan(creates, lds, tot_new);
+    if (i < a.n_seqs) { tb.tmp_a[i] = carry + ex; tb.tmp_b[i] = carry_new + ex_new; }
+    carry += tot;
+    carry_new += tot_new;
+  }
+  __syncthreads();
+  if (s_err != 0x7fffffff) {
+    if (tid == 0) record_error(scal, s_err & 3, a.call_seq);
+    return;
+  }
+  if (carry > top) {
+    if (tid == 0) record_error(scal, SART_E_OOM_PAGES, a.call_seq);
+    return;
+  }
+  // pass 2: apply
+  int* bt = tb.bt[scal[S_BTSEL]];
+  for (int i = tid; i < a.n_seqs; i += kPlanThreads) {
+    const int id = tb.ap_id[i];
+    const int n = a.ntok ? a.ntok[i] : 1;
+    const int len = tb.ap_start[i];
+    const int have = ceil_div(len, dm.pt), want = ceil_div(len + n, dm.pt);
+    const int off = tb.tmp_a[i];
+    int* table;
+    if (a.kind == SART_SEQ_PREFIX) {
+      table = tb.prefix_table + (long long)id * dm.max_pp;
+      tb.prefix_len[id] = len + n;
+      if (!tb.req_used[id]) {
+        tb.req_used[id] = 1;
+        tb.refcnt[id] = dm.Nb;
+        const int first = nA + tb.tmp_b[i] * dm.Nb;
+        for (int j = 0; j < dm.Nb; ++j) {
+          const int b = id * dm.Nb + j;
+          tb.br_state[b] = SART_BRANCH_ACTIVE;
+          tb.active[first + j] = b;
+          tb.seq_len[first + j] = 0;
+          tb.active_idx_of[b] = first + j;
+        }
+      }
+    } else {
+      const int row = tb.active_idx_of[id];
+      table = bt + (long long)row * dm.max_bp;
+      tb.seq_len[row] = len + n;
+      if (n > 0) tb.branch_appended[id / dm.Nb] = 1;
+    }
+    for (int k = 0; k < want - have; ++k) table[have + k] = tb.free_stack[top - 1 - (off + k)];
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const int na_new = nA + carry_new * dm.Nb;
+    scal[S_NACTIVE] = na_new;
+    scal[S_FREETOP] = top - carry;
+    const int sel = scal[S_BTSEL];
+    if (scal[S_BTHI0 + sel] < na_new) scal[S_BTHI0 + sel] = na_new;
+    scal[S_CALLOK] = 1;
+  }
+}
+
+// One wave copies one (token, kv head) row of K and V into its page slot.
+template <typename T>
+__global__ void __launch_bounds__(256)
+k_append_write(Ctx c, AppendArgs a) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  if (!tb.scal[S_CALLOK]) return;
+  const int lane = threadIdx.x & 63;
+  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
+  const long long units = a.total_rows * dm.Hkv;
+  const int* bt = tb.bt[tb.scal[S_BTSEL]];
+  T* pool = (T*)c.pool;
+  for (long long u = wave; u < units; u += nwaves) {
+    const long long row = u / dm.Hkv;
+    const int head = (int)(u % dm.Hkv);
+    // sequence owning this row: last i with tok_off[i] <= row
+    int i;
+    if (a.tok_off) {
+      int lo = 0, hi = a.n_seqs - 1;
+      while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if ((long long)a.tok_off[mid] <= row) lo = mid; else hi = mid - 1;
+      }
+      i = lo;
+    } else {
+      i = (int)row;
+    }
+    const int t = (int)(row - (a.tok_off ? a.tok_off[i] : i));
+    const int id = tb.ap_id[i];
+    const int pos = tb.ap_start[i] + t;
+    const int* table = a.kind == SART_SEQ_PREFIX ? tb.prefix_table + (long long)id * dm.max_pp
+                                                 : bt + (long long)tb.active_idx_of[id] * dm.max_bp;
+    const int page = table[pos / dm.pt], slot = pos % dm.pt;
+    const long long kb = tile_base(dm, page, head), vb = kb + dm.tile_elems;
+    const T* ksrc = (const T*)a.k + (row * dm.Hkv + head) * dm.d;
+    const T* vsrc = (const T*)a.v + (row * dm.Hkv + head) * dm.d;
+    for (int d = lane; d < dm.d; d += 64) {
+      pool[kb + k_elem_off(dm.layout, dm.d, slot, d)] = ksrc[d];
+      pool[vb + v_elem_off(dm.layout, dm.d, slot, d)] = vsrc[d];
+    }
+  }
+}
+
+void launch_append(const Ctx& c, const AppendArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_append_plan, dim3(1), dim3(kPlanThreads), 0, s, c, a);
+  if (a.total_rows <= 0) return;
+  const long long units = a.total_rows * c.dm.Hkv;
+  long long blocks = (units + 3) / 4;
+  if (blocks > 8192) blocks = 8192;
+  if (c.dm.dtype == SART_F32)
+    hipLaunchKernelGGL(k_append_write<float>, dim3((unsigned)blocks), dim3(256), 0, s, c, a);
+  else
+    hipLaunchKernelGGL(k_append_write<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, s, c, a);
+}
+
+// ---------------------------------------------------------------------------
+// Terminate pass, planning half (device function run by the single planning
+// workgroup after victims were marked in new_state[]).
+//  (1) victims in ascending active index push their private pages in
+//      ascending logical order;
+//  (2) then requests that lost their last branch, in ascending request id,
+//      push their prefix pages;
+//  (3) survivors keep their relative order.
+// The pushes themselves and the block-table rows are moved by k_terminate_move.
+// ---------------------------------------------------------------------------
+__device__ void terminate_plan(const Ctx& c, int* lds) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  int* scal = tb.scal;
+  const int tid = threadIdx.x;
+  const int nA = scal[S_NACTIVE];
+  const int top = scal[S_FREETOP];
+  for (int r = tid; r < dm.max_req; r += kPlanThreads) { tb.req_touched[r] = 0; tb.req_push_off[r] = -1; }
+  __syncthreads();
+  // scans over active rows: pages pushed by victims, new index of survivors
+  int carry_p = 0, carry_s = 0;
+  for (int base = 0; base < nA; base += kPlanThreads) {
+    const int a = base + tid;
+    int np = 0, keep = 0;
+    if (a < nA) {
+      if (tb.new_state[a]) np = ceil_div(tb.seq_len[a], dm.pt); else keep = 1;
+    }
+    int tp, ts;
+    const int exp_ = block_excl_scan(np, lds, tp);
+    const int exs = block_excl_scan(keep, lds, ts);
+    if (a < nA) {
+      tb.mv_push_off[a] = tb.new_state[a] ? carry_p + exp_ : -1;
+      tb.mv_new_idx[a] = tb.new_state[a] ? -1 : carry_s + exs;
+    }
+    carry_p += tp;
+    carry_s += ts;
+  }
+  const int na_new = carry_s, priv_pages = carry_p;
+  // victims: state, reference counts
+  for (int a = tid; a < nA; a += kPlanThreads) {
+    if (!tb.new_state[a]) continue;
+    const int b = tb.active[a], r = b / dm.Nb;
+    tb.br_state[b] = tb.new_state[a];
+    tb.active_idx_of[b] = -1;
+    atomicSub(&tb.refcnt[r], 1);
+    tb.req_touched[r] = 1;
+  }
+  __syncthreads();
+  // requests whose last branch left: prefix pushes in ascending request id
+  int carry_r = 0;
+  for (int base = 0; base < dm.max_req; base += kPlanThreads) {
+    const int r = base + tid;
+    int np = 0, dead = 0;
+    if (r < dm.max_req && tb.req_touched[r] && tb.refcnt[r] == 0) {
+      dead = 1;
+      np = ceil_div(tb.prefix_len[r], dm.pt);
+    }
+    int tr;
+    const int ex = block_excl_scan(np, lds, tr);
+    if (dead) tb.req_push_off[r] = carry_r + ex;
+    carry_r += tr;
+  }
+  // compact the small active-order arrays through scratch
+  for (int a = tid; a < nA; a += kPlanThreads) {
+    const int ni = tb.mv_new_idx[a];
+    if (ni >= 0) { tb.tmp_a[ni] = tb.active[a]; tb.tmp_b[ni] = tb.seq_len[a]; }
+  }
+  __syncthreads();
+  for (int a = tid; a < nA; a += kPlanThreads) {
+    if (a < na_new) {
+      const int b = tb.tmp_a[a];
+      tb.active[a] = b;
+      tb.seq_len[a] = tb.tmp_b[a];
+      tb.active_idx_of[b] = a;
+    } else {
+      tb.active[a] = -1;
+      tb.seq_len[a] = 0;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const int old_sel = scal[S_BTSEL], new_sel = old_sel ^ 1;
+    scal[S_T_NA_OLD] = nA;
+    scal[S_T_NA_NEW] = na_new;
+    scal[S_T_TOP_OLD] = top;
+    scal[S_T_PRIV_PAGES] = priv_pages;
+    scal[S_T_BT_OLD] = old_sel;
+    scal[S_T_CLEAR_HI] = scal[S_BTHI0 + new_sel];
+    scal[S_BTHI0 + new_sel] = na_new;
+    scal[S_BTSEL] = new_sel;
+    scal[S_NACTIVE] = na_new;
+    scal[S_FREETOP] = top + priv_pages + carry_r;
+    scal[S_CALLOK] = 1;
+  }
+}
+
+// Terminate pass, bulk half: one workgroup per old row / dead request.
+__global__ void __launch_bounds__(256)
+k_terminate_move(Ctx c) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  const int* scal = tb.scal;
+  if (!scal[S_CALLOK]) return;
+  const int na_old = scal[S_T_NA_OLD], na_new = scal[S_T_NA_NEW], top = scal[S_T_TOP_OLD];
+  const int priv = scal[S_T_PRIV_PAGES], clear_hi = scal[S_T_CLEAR_HI];
+  const int* bt_old = tb.bt[scal[S_T_BT_OLD]];
+  int* bt_new = tb.bt[scal[S_T_BT_OLD] ^ 1];
+  const int rows_hi = na_old > clear_hi ? na_old : clear_hi;
+  const int units = rows_hi + dm.max_req;
+  for (int u = blockIdx.x; u < units; u += gridDim.x) {
+    if (u < rows_hi) {
+      // (a) old row u: push its pages or move it to its new place
+      if (u < na_old) {
+        const int* src = bt_old + (long long)u * dm.max_bp;
+        const int off = tb.mv_push_off[u];
+        if (off >= 0) {
+          for (int p = threadIdx.x; p < dm.max_bp; p += blockDim.x) {
+            const int page = src[p];
+            if (page >= 0) tb.free_stack[top + off + p] = page;
+          }
+        } else {
+          int* dst = bt_new + (long long)tb.mv_new_idx[u] * dm.max_bp;
+          for (int p = threadIdx.x; p < dm.max_bp; p += blockDim.x) dst[p] = src[p];
+        }
+      }
+      // (b) row u of the new buffer beyond the survivors goes back to -1
+      if (u >= na_new && u < clear_hi) {
+        int* dst = bt_new + (long long)u * dm.max_bp;
+        for (int p = threadIdx.x; p < dm.max_bp; p += blockDim.x) dst[p] = -1;
+      }
+    } else {
+      const int r = u - rows_hi;
+      const int off = tb.req_push_off[r];
+      if (off >= 0) {
+        int* ptab = tb.prefix_table + (long long)r * dm.max_pp;
+        for (int p = threadIdx.x; p < dm.max_pp; p += blockDim.x) {
+          const int page = ptab[p];
+          if (page >= 0) { tb.free_stack[top + priv + off + p] = page; ptab[p] = -1; }
+        }
+      }
+    }
+  }
+}
+
+static void launch_move(const Ctx& c, hipStream_t s) {
+  int units = c.dm.H + c.dm.max_req;
+  int blocks = units < 2048 ? units : 2048;
+  hipLaunchKernelGGL(k_terminate_move, dim3(blocks), dim3(256), 0, s, c);
+}
+
+// first active index of every live request (a request's branches are
+// contiguous in the active list: created together, compaction is stable)
+__device__ inline void find_request_starts(const Ctx& c, int nA) {
+  const Tables& tb = c.tb;
+  for (int a = threadIdx.x; a < nA; a += kPlanThreads) {
+    const int r = tb.active[a] / c.dm.Nb;
+    if (a == 0 || tb.active[a - 1] / c.dm.Nb != r) tb.req_first[r] = a;
+  }
+}
+
+__device__ inline bool key_less(float sa, int ha, float sb, int hb) {
+  if (sa != sa) sa = __builtin_inff();
+  if (sb != sb) sb = __builtin_inff();
+  if (sa < sb) return true;
+  if (sa > sb) return false;
+  return ha < hb;
+}
+
+// ---------------------------------------------------------------------------
+// A7: prune.  Victim selection per request, then the terminate plan.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kPlanThreads)
+k_prune_plan(Ctx c, PruneArgs a) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  int* scal = tb.scal;
+  __shared__ int lds[17];
+  const int tid = threadIdx.x;
+  const int nA = scal[S_NACTIVE];
+  if (a.n_scores < nA) {
+    if (tid == 0) record_error(scal, SART_E_INVALID, a.call_seq);
+    return;
+  }
+  find_request_starts(c, nA);
+  __syncthreads();
+  for (int i = tid; i < nA; i += kPlanThreads) {
+    const int b = tb.active[i], r = b / dm.Nb;
+    const int first = tb.req_first[r], live = tb.refcnt[r];
+    const float sc = a.scores[i];
+    int room = 0x7fffffff;
+    if (a.maxp) { room = a.maxp[r] - tb.num_pruned[r]; if (room < 0) room = 0; }
+    int victim;
+    if (a.mode == SART_PRUNE_THRESHOLD) {
+      // Algorithm 1's predicate walked in ascending active index: the branches
+      // before this one that qualify use up the room first.
+      const float th = a.thr[r];
+      int earlier = 0;
+      for (int j = first; j < i; ++j) earlier += a.scores[j] < th;
+      victim = (sc < th) && earlier < room;
+    } else {
+      int rank = 0;
+      for (int j = first; j < first + live; ++j)
+        rank += key_less(a.scores[j], tb.active[j], sc, b);
+      int kk = a.k_per_req ? a.k_per_req[r] : a.k;
+      kk = kk < 0 ? 0 : (kk > live ? live : kk);
+      int nv = a.mode == SART_PRUNE_DROP_LOWEST_K ? kk : live - kk;
+      if (nv > room) nv = room;
+      victim = rank < nv;
+    }
+    tb.new_state[i] = victim ? SART_BRANCH_PRUNED : 0;
+  }
+  __syncthreads();
+  for (int i = tid; i < nA; i += kPlanThreads)
+    if (tb.new_state[i]) atomicAdd(&tb.num_pruned[tb.active[i] / dm.Nb], 1);
+  __syncthreads();
+  terminate_plan(c, lds);
+}
+
+void launch_prune(const Ctx& c, const PruneArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_prune_plan, dim3(1), dim3(kPlanThreads), 0, s, c, a);
+  launch_move(c, s);
+}
+
+// ---------------------------------------------------------------------------
+// A8: completion + early stop, then the terminate plan.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kPlanThreads)
+k_finish_plan(Ctx c, int n, const int* handles, int call_seq) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  int* scal = tb.scal;
+  __shared__ int lds[17];
+  __shared__ int s_bad;
+  const int tid = threadIdx.x;
+  const int nA = scal[S_NACTIVE];
+  if (tid == 0) s_bad = 0;
+  __syncthreads();
+  for (int i = tid; i < n; i += kPlanThreads)
+    if (tb.br_state[handles[i]] != SART_BRANCH_ACTIVE) s_bad = 1;
+  __syncthreads();
+  if (s_bad) {
+    if (tid == 0) record_error(scal, SART_E_STATE, call_seq);
+    return;
+  }
+  for (int a = tid; a < nA; a += kPlanThreads) tb.new_state[a] = 0;
+  __syncthreads();
+  for (int i = tid; i < n; i += kPlanThreads) {
+    const int b = handles[i];
+    tb.new_state[tb.active_idx_of[b]] = SART_BRANCH_COMPLETED;
+    atomicAdd(&tb.num_completed[b / dm.Nb], 1);
+  }
+  __syncthreads();
+  if (dm.Q >= 1 && dm.Q <= dm.Nb) {
+    for (int a = tid; a < nA; a += kPlanThreads)
+      if (!tb.new_state[a] && tb.num_completed[tb.active[a] / dm.Nb] >= dm.Q)
+        tb.new_state[a] = SART_BRANCH_EARLY_STOPPED;
+  }
+  __syncthreads();
+  terminate_plan(c, lds);
+}
+
+void launch_finish(const Ctx& c, int n, const int* handles_dev, int call_seq, hipStream_t s) {
+  hipLaunchKernelGGL(k_finish_plan, dim3(1), dim3(kPlanThreads), 0, s, c, n, handles_dev, call_seq);
+  launch_move(c, s);
+}
+
+}  // namespace sart

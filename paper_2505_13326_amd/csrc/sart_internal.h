@@ -1,0 +1,152 @@
+// Internal declarations shared by the HIP sources of libsart (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sart.h"
+
+namespace sart {
+
+constexpr int kWave = 64;
+constexpr int kPlanThreads = 1024;     // single-workgroup planning kernels
+constexpr int kAttnWaves = 8;          // waves per attention workgroup
+constexpr int kAttnThreads = kAttnWaves * kWave;
+constexpr int kStagePages = 4;         // prefix pages staged in LDS per pipeline stage
+constexpr int kMaxGroup = 16;          // query heads per KV head the MFMA tile holds
+
+// Indices into the device scalar block.
+enum Scalar {
+  S_NACTIVE = 0,
+  S_FREETOP,
+  S_BTSEL,        // which of the two block-table buffers is current
+  S_ERR,          // sticky status of the first failed call
+  S_ERRCALL,      // sequence number of that call
+  S_CALLOK,       // the call now running passed its device-side validation
+  S_BTHI0,        // rows of block-table buffer 0 that may hold non -1 entries
+  S_BTHI1,
+  // plan of the terminate pass (written by the plan kernel, read by the move kernel)
+  S_T_NA_OLD,
+  S_T_NA_NEW,
+  S_T_TOP_OLD,
+  S_T_PRIV_PAGES, // pages pushed by branches; prefix pushes start after them
+  S_T_BT_OLD,     // buffer index holding the rows to move
+  S_T_CLEAR_HI,   // rows [na_new, clear_hi) of the new buffer must be reset to -1
+  // plan of the decode pass
+  S_D_NA,
+  S_D_UNITS,      // private (page, kv head) units in total
+  S_D_PER_WAVE,   // units per private wave
+  S_D_NITEMS,     // prefix workgroup items
+  S_D_NLIVE,      // live requests with a non-empty prompt
+  S_D_CHUNK,      // prefix chunk in pages
+  S_D_NPC,        // prefix chunks per (row, kv head) slot stride
+  S_COUNT = 32
+};
+
+struct Dims {
+  int Hq, Hkv, G, d, pt, num_pages, max_req, Nb, Q, max_bp, max_pp, H, dtype, layout, esize;
+  long long tile_elems;   // pt * d: elements of one K (or V) tile
+  long long page_elems;   // Hkv * 2 * tile_elems
+};
+
+struct Tables {
+  int* scal;
+  int* free_stack;
+  // per request
+  int* req_used;
+  int* prefix_len;
+  int* prefix_table;     // [max_req][max_pp]
+  int* refcnt;
+  int* num_completed;
+  int* num_pruned;
+  int* branch_appended;
+  // per branch handle
+  int* br_state;
+  int* active_idx_of;    // handle -> active index, -1 when not active
+  // active order
+  int* active;           // handles
+  int* seq_len;
+  int* bt[2];            // [H][max_bp] ping-pong block tables
+  // scratch of the planning kernels
+  int* new_state;        // [H]
+  int* mv_push_off;      // [H]  -1 for survivors
+  int* mv_new_idx;       // [H]
+  int* tmp_a;            // [H]
+  int* tmp_b;            // [H]
+  int* req_first;        // [max_req] first active index of the request
+  int* req_push_off;     // [max_req] -1 unless the request died in this pass
+  int* req_touched;      // [max_req]
+  // append plan
+  int* ap_id;            // [H] resolved sequence ids
+  int* ap_start;         // [H] length before the append
+  // decode plan
+  int* page_cum;         // [H+1] exclusive scan of private pages over active rows
+  int* live_req;         // [max_req] live requests with prompt, active order
+  int* live_item_start;  // [max_req+1] exclusive scan of prefix items
+};
+
+struct Ctx {
+  Dims dm;
+  Tables tb;
+  void* pool;
+};
+
+// ---- layout: element offsets inside one K or V tile ------------------------
+// NATURAL: [token][d].   MFMA16: see sart.h.
+__host__ __device__ inline long long k_elem_off(int layout, int d_dim, int token, int d) {
+  if (layout == SART_LAYOUT_NATURAL) return (long long)token * d_dim + d;
+  return ((long long)(d >> 3) * 16 + token) * 8 + (d & 7);
+}
+__host__ __device__ inline long long v_elem_off(int layout, int d_dim, int token, int d) {
+  if (layout == SART_LAYOUT_NATURAL) return (long long)token * d_dim + d;
+  int chunk = (d >> 5) * 64 + (token >> 2) * 16 + (d & 15);
+  int e = (token & 3) + (((d >> 4) & 1) << 2);
+  return (long long)chunk * 8 + e;
+}
+// element offset of the K tile of (page, kv head); the V tile follows it
+__host__ __device__ inline long long tile_base(const Dims& dm, int page, int head) {
+  return (long long)page * dm.page_elems + (long long)head * 2 * dm.tile_elems;
+}
+
+// ---- kernels' launchers (defined in the .hip files) ------------------------
+struct AppendArgs {
+  int kind, n_seqs;
+  const int* ids;      // device or null
+  const int* ntok;     // device or null
+  const int* tok_off;  // device or null (null: one token per sequence)
+  long long total_rows;
+  const void* k;
+  const void* v;
+  int call_seq;
+};
+void launch_append(const Ctx& c, const AppendArgs& a, hipStream_t s);
+
+struct PruneArgs {
+  int mode, k;
+  const int* k_per_req;  // device or null
+  const float* thr;      // device or null
+  const int* maxp;       // device or null
+  const float* scores;
+  int n_scores;
+  int call_seq;
+};
+void launch_prune(const Ctx& c, const PruneArgs& a, hipStream_t s);
+void launch_finish(const Ctx& c, int n, const int* handles_dev, int call_seq, hipStream_t s);
+
+struct DecodeArgs {
+  const void* q;
+  float* out;
+  int n_rows;
+  float scale_log2;     // scale * log2(e)
+  int n_wg;             // persistent attention workgroups
+  int chunk_pages;      // <= 0: choose on the device
+  float* partials;      // scratch
+  long long partial_cap; // partial slots available
+  int call_seq;
+  hipEvent_t ev[4];     // optional profiling events (null: none)
+};
+void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s);
+
+void launch_init_tables(const Ctx& c, const int* free_order_dev, hipStream_t s);
+
+}  // namespace sart
