@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the SART decode hot path on one MI355X.
+
+A step = one pass of the hot path over the batch: append one token of K/V to
+every active branch (sart_append_tokens), then the decode attention of all
+active branches (sart_decode_attention: partition, shared-prompt + private
+split-K attention, merge).  Inputs are resident in HBM before timing starts.
+The default workload is the benchmark's config 2 (7B-like GQA, 16 requests x 8
+branches, prompt 512, lognormal private lengths); prune / finish are timed
+once after the step loop and reported in microseconds.
+
+Prints ONE JSON line (see the keys below).  --gpus > 1 is refused: this build
+is single-GPU by design.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# HBM traffic of the dominant kernel per launch measured offline with
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def _request_arrays(wl, cfg, r, L):
+    import numpy as np
+    pk, pv = wl.prefix_kv(cfg, r)
+    ids = [r * cfg.nb + j for j in range(cfg.nb)]
+    ns = [int(L[r, j]) for j in range(cfg.nb)]
+    kv = [wl.branch_kv(cfg, b, n) for b, n in zip(ids, ns)]
+    return r, pk, pv, ids, ns, np.concatenate([x[0] for x in kv]), np.concatenate([x[1] for x in kv])
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--free-order", default="scattered", choices=["scattered", "identity"])
+    ap.add_argument("--workgroups", type=int, default=0, help="attention workgroups (0 = library default)")
+    ap.add_argument("--chunk-pages", type=int, default=0, help="prompt chunk in pages (0 = chosen on device)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (requests are independent and would shard with no "
+              "collective; see DESIGN.md); --gpus > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2505_13326_amd as sart
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = wl.CONFIGS[int(args.workload[3:])]
+    K, W = args.steps, args.warmup
+    L = wl.lengths(cfg)
+    growth = K + W + 2 * K + 64           # timed + profiled passes append one token per step
+    num_pages = wl.pages_needed(cfg, L, growth_tokens=growth) + 64
+    max_bp = (cfg.length_cap + growth) // cfg.page_tokens + 2
+    fo = wl.free_order(cfg, num_pages) if args.free_order == "scattered" else None
+    cache = sart.SartCache(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+                           page_tokens=cfg.page_tokens, num_pages=num_pages, max_requests=cfg.n_requests,
+                           branches_per_request=cfg.nb, finish_quota=cfg.quota, max_pages_per_branch=max_bp,
+                           max_prefix_pages=max(1, cfg.prompt_len // cfg.page_tokens), dtype=cfg.dtype,
+                           free_order=fo)
+    if args.workgroups or args.chunk_pages:
+        cache.set_decode_launch(args.workgroups, args.chunk_pages)
+
+    # ---- CPU baseline cache (oracle) on a bounded sample of the same workload ------------
+    do_cpu = not args.no_cpu_baseline
+    n_cpu = args.cpu_sample_requests or {2: cfg.n_requests, 4: 4, 5: 1}[cfg.cfg_id]
+    n_cpu = min(n_cpu, cfg.n_requests)
+    ocache = None
+    if do_cpu:
+        import oracle as orc
+        Ls = L[:n_cpu]
+        ocache = orc.OracleCache(
+            n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, page_tokens=cfg.page_tokens,
+            num_pages=int(np.sum((Ls + 15) // 16)) + n_cpu * (cfg.prompt_len // 16 + 1) + 8, max_requests=cfg.n_requests,
+            branches_per_request=cfg.nb, finish_quota=cfg.quota, max_pages_per_branch=max_bp,
+            max_prefix_pages=max(1, cfg.prompt_len // cfg.page_tokens), dtype=cfg.dtype)
+
+    t0 = time.time()
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        for r, pk, pv, ids, ns, bk, bv in ex.map(lambda r: _request_arrays(wl, cfg, r, L), range(cfg.n_requests)):
+            cache.append_tokens(sart.SEQ_PREFIX, [r], [cfg.prompt_len], pk, pv)
+            cache.append_tokens(sart.SEQ_BRANCH, ids, ns, bk, bv)
+            if ocache is not None and r < n_cpu:
+                assert ocache.append(0, [r], [cfg.prompt_len], pk, pv) == 0
+                assert ocache.append(1, ids, ns, bk, bv) == 0
+    assert cache.sync_status() == 0
+    st = cache.get_state()
+    nA = int(st["n_active"][0])
+    assert nA == cfg.n_handles
+    t_build = time.time() - t0
+
+    # ---- per-step inputs, resident on the device --------------------------------------
+    def dev(x):
+        t = torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).view(torch.bfloat16) if cfg.dtype == "bf16" \
+            else torch.from_numpy(np.ascontiguousarray(x))
+        return t.cuda()
+    n_in = 4
+    qs = [dev(wl.query(cfg, s)) for s in range(n_in)]
+    kvs = [tuple(dev(x) for x in wl.step_kv(cfg, s)) for s in range(n_in)]
+    out = torch.empty((nA, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+
+    def step(i):
+        k, v = kvs[i % n_in]
+        cache.append_tokens(sart.SEQ_BRANCH, None, None, k, v)
+        cache.decode_attention(qs[i % n_in], out=out)
+
+    def tokens_now():
+        s = cache.get_state()
+        n = int(s["n_active"][0])
+        return int(s["seq_lens"][:n].sum()), cfg.n_requests * cfg.prompt_len
+
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    priv0, pre = tokens_now()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert cache.sync_status() == 0
+    ms_step = dt / K * 1e3
+    # private tokens read at timed step i (1-based): priv0 + i*nA
+    mean_tokens = priv0 + nA * (K + 1) / 2 + pre
+    kv_bytes = mean_tokens * cfg.token_bytes
+    io_bytes = nA * cfg.n_q_heads * cfg.head_dim * (cfg.elem_bytes + 4)     # q read + out write
+    alg_bytes = kv_bytes + io_bytes
+    logical_bytes = (priv0 + nA * (K + 1) / 2 + nA * cfg.prompt_len) * cfg.token_bytes
+    value = kv_bytes / (dt / K) / 1e9
+
+    # ---- dominant kernel timed with HIP events on its own stream -----------------------
+    cache.set_profiling(True)
+    attn_ms, total_ms = [], []
+    priv1, _ = tokens_now()
+    for i in range(K):
+        step(i)
+        a, t = cache.last_decode_ms()
+        attn_ms.append(a)
+        total_ms.append(t)
+    cache.set_profiling(False)
+    attn_avg = float(np.mean(attn_ms))
+    alg_bytes_prof = (priv1 + nA * (K + 1) / 2 + pre) * cfg.token_bytes + io_bytes
+    achieved = alg_bytes_prof / (attn_avg * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "k_attn_mfma", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                "algorithmic_bytes_per_launch": int(alg_bytes_prof), "kernel_ms_avg": round(attn_avg, 4),
+                "kernel_ms_p10_p50_p90": [round(float(np.percentile(attn_ms, p)), 4) for p in (10, 50, 90)],
+                "decode_call_ms_avg": round(float(np.mean(total_ms)), 4)}
+
+    # ---- maintenance calls, once each (they change the batch, so after the step loop) --
+    sc = torch.from_numpy(wl.scores(cfg, 0)).cuda()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    cache.prune_branches(sart.DROP_LOWEST_K, sc, k=1)
+    torch.cuda.synchronize()
+    prune_us = (time.perf_counter() - t0) * 1e6
+    s2 = cache.get_state()
+    n2 = int(s2["n_active"][0])
+    fin = s2["active_handles"][:n2][::max(1, cfg.nb - 1)][:cfg.n_requests]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    cache.finish_branch(fin)
+    torch.cuda.synchronize()
+    finish_us = (time.perf_counter() - t0) * 1e6
+    assert cache.sync_status() == 0
+
+    # ---- CPU baseline: the oracle as it stands, same workload (bounded sample) ---------
+    cpu = None
+    if do_cpu:
+        import oracle as orc
+        so = ocache.state()
+        nO = int(so["n_active"][0])
+        act = so["active_handles"][:nO]
+        q0 = wl.query(cfg, 0)[act]
+        t0 = time.perf_counter()
+        ocache.attention(q0)
+        t_cpu = time.perf_counter() - t0
+        o_bytes = (int(so["seq_lens"][:nO].sum()) + n_cpu * cfg.prompt_len) * cfg.token_bytes
+        cpu = {"value": round(o_bytes / t_cpu / 1e9, 4), "unit": "GB/s", "cores": orc.num_threads(), "kind": "oracle",
+               "sample": f"float64 oracle attention of requests 0..{n_cpu - 1} of {cfg.n_requests} "
+                         f"({nO} branches, {o_bytes / 1e6:.0f} MB of KV, one decode step, {t_cpu:.2f} s wall)",
+               "branch_steps_per_s": round(nO / t_cpu, 2)}
+
+    line = {
+        "metric": "decode-attention achieved KV GB/s (fraction of HBM peak); branch-steps/s",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload} {cfg.name}: {cfg.n_requests} requests x {cfg.nb} branches, "
+                               f"Hq{cfg.n_q_heads}/Hkv{cfg.n_kv_heads} d{cfg.head_dim} {cfg.dtype}, prompt "
+                               f"{cfg.prompt_len}, private lengths {cfg.length_dist}{cfg.length_params} cap "
+                               f"{cfg.length_cap}, page 16, free order {args.free_order}",
+                   "active_branches": nA, "kv_bytes_per_step": int(kv_bytes), "step": "append 1 token/branch + decode attention"},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "branch_steps_per_s": round(nA / (dt / K), 1),
+        "logical_kv_gbs": round(logical_bytes / (dt / K) / 1e9, 1),
+        "prune_us": round(prune_us, 1), "finish_us": round(finish_us, 1),
+        "build_state_s": round(t_build, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
