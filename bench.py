@@ -45,10 +45,16 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg5", "copy"],
+                    help="copy = a plain 1 GiB device copy, the known-size kernel that calibrates the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--free-order", default="scattered", choices=["scattered", "identity"])
     ap.add_argument("--workgroups", type=int, default=0, help="attention workgroups (0 = library default)")
     ap.add_argument("--chunk-pages", type=int, default=0, help="prompt chunk in pages (0 = chosen on device)")
+    ap.add_argument("--prompt-mode", type=int, default=-1, help="0 = prompt staged in LDS and shared, 1 = read inline, -1 = library default")
+    ap.add_argument("--skew", type=int, default=None, help="per-mille of work moved from odd to even workgroups (default: library's)")
+    ap.add_argument("--pool", type=int, default=None, help="per-mille of the work handed out dynamically (default: library's)")
+    ap.add_argument("--prompt-len", type=int, default=-1, help="override the workload's prompt length (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
     args = ap.parse_args()
@@ -64,7 +70,24 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.workload == "copy":
+        n = 1 << 30
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.warmup):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        print(json.dumps({"metric": "device copy", "bytes_read": n, "bytes_written": n, "steps": args.steps,
+                          "ms_per_step": round(dt * 1e3, 4), "value": round(2 * n / dt / 1e9, 1), "unit": "GB/s"}))
+        return
     cfg = wl.CONFIGS[int(args.workload[3:])]
+    if args.prompt_len >= 0:
+        cfg = wl.scaled(cfg, prompt_len=args.prompt_len)
     K, W = args.steps, args.warmup
     L = wl.lengths(cfg)
     growth = K + W + 2 * K + 64           # timed + profiled passes append one token per step
@@ -76,8 +99,9 @@ def main():
                            branches_per_request=cfg.nb, finish_quota=cfg.quota, max_pages_per_branch=max_bp,
                            max_prefix_pages=max(1, cfg.prompt_len // cfg.page_tokens), dtype=cfg.dtype,
                            free_order=fo)
-    if args.workgroups or args.chunk_pages:
-        cache.set_decode_launch(args.workgroups, args.chunk_pages)
+    if args.workgroups or args.chunk_pages or args.prompt_mode >= 0 or args.skew is not None or args.pool is not None:
+        cache.set_decode_launch(args.workgroups, args.chunk_pages, args.prompt_mode,
+                                50 if args.skew is None else args.skew, 0 if args.pool is None else args.pool)
 
     # ---- CPU baseline cache (oracle) on a bounded sample of the same workload ------------
     do_cpu = not args.no_cpu_baseline

@@ -18,7 +18,7 @@ DROP_LOWEST_K, KEEP_TOP_K, THRESHOLD = 0, 1, 2
 LAYOUT_NATURAL, LAYOUT_MFMA16 = 0, 1
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_DIR, "libsart.so")
+_LIB_PATH = os.environ.get("SART_LIB") or os.path.join(_DIR, "libsart.so")  # SART_LIB: a developer build
 _lib = None
 
 _ip = C.POINTER(C.c_int32)
@@ -61,7 +61,7 @@ _SIGNATURES = {
     "sart_get_state": (C.c_int, [C.c_void_p] + [_ip] * 11),
     "sart_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_last_decode_ms": (C.c_int, [C.c_void_p, _fp, _fp]),
-    "sart_set_decode_launch": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
+    "sart_set_decode_launch": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "sart_last_error": (C.c_char_p, []),
 }
 
@@ -256,5 +256,7 @@ class SartCache:
         self._check(self.lib.sart_last_decode_ms(self.h, C.byref(a), C.byref(t)))
         return a.value, t.value
 
-    def set_decode_launch(self, n_workgroups=0, prefix_chunk_pages=0):
-        self._check(self.lib.sart_set_decode_launch(self.h, int(n_workgroups), int(prefix_chunk_pages)))
+    def set_decode_launch(self, n_workgroups=0, prefix_chunk_pages=0, prompt_mode=-1, skew_permille=50,
+                          pool_permille=0):
+        self._check(self.lib.sart_set_decode_launch(self.h, int(n_workgroups), int(prefix_chunk_pages),
+                                                    int(prompt_mode), int(skew_permille), int(pool_permille)))

@@ -33,6 +33,11 @@ sart_status fail(sart_status st, const char* fmt, ...) {
   } while (0)
 
 constexpr int kStageSlots = 8;
+// share of the mean range moved from odd-XCD workgroups to even-XCD ones (measured on MI355X)
+constexpr int kDefaultSkewPermille = 50;
+// share of the unit line handed out dynamically at the end of the attention kernel
+constexpr int kDefaultPoolPermille = 0;
+constexpr int kMaxPoolPermille = 500;
 
 struct StageSlot {
   int* host = nullptr;  // pinned
@@ -55,9 +60,8 @@ struct sart_cache {
   hipStream_t last_stream = nullptr;
   float* partials = nullptr;
   long long partial_cap = 0;
-  int n_wg = 0;
+  PlanCfg plan{0, 0, 0, 0, 0};         // launch shape of the decode plan
   int max_wg = 0;
-  int chunk_pages = 0;
   bool profiling = false;
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   bool ev_valid = false;
@@ -176,6 +180,11 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   ALLOC(tb.req_first, R); ALLOC(tb.req_push_off, R); ALLOC(tb.req_touched, R);
   ALLOC(tb.ap_id, H); ALLOC(tb.ap_start, H);
   ALLOC(tb.page_cum, H + 1); ALLOC(tb.live_req, R); ALLOC(tb.live_item_start, R + 1);
+  {
+    const size_t max_items = R * dm.Hkv * ((dm.max_pp + kStagePages - 1) / kStagePages) *
+                             ((dm.Nb + kAttnWaves - 1) / kAttnWaves);
+    ALLOC(tb.item_desc, 8 * max_items);
+  }
 
   if (d->kv_pool) {
     c->ctx.pool = d->kv_pool;
@@ -192,15 +201,20 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   hipDeviceProp_t prop;
   HIP_TRY(hipGetDeviceProperties(&prop, c->device));
   const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  c->max_wg = cus * 8;
-  c->n_wg = cus;
-  c->chunk_pages = 0;
+  c->max_wg = cus * 16;
+  c->plan.n_wg = cus;                // one 4-wave workgroup per CU
+  c->plan.chunk_pages = 0;
+  c->plan.inline_prefix = 1;         // measured faster than the LDS-staged prompt phase on every config
+  c->plan.skew_permille = kDefaultSkewPermille;
+  c->plan.pool_permille = kDefaultPoolPermille;
+  const size_t max_chunks = (size_t)dm.num_pages * dm.Hkv * kMaxPoolPermille / 1000 / 4 + 1;
+  ALLOC(tb.wave_row, (size_t)c->max_wg * kAttnWaves + max_chunks);
   // partial slots: one per private wave, one per (row, kv head) crossing, and
   // the prompt chunks of every (row, kv head) at the smallest chunk size
   const long long S = (long long)H * dm.Hkv;
   const long long npc_max = (dm.max_pp + kStagePages - 1) / kStagePages;
-  c->partial_cap = (long long)c->max_wg * kAttnWaves + S * (1 + npc_max);
-  const long long pf = (long long)dm.G * dm.d + 2 * dm.G;
+  c->partial_cap = (long long)c->max_wg * kAttnWaves + (long long)max_chunks + S * (1 + npc_max);
+  const long long pf = (long long)dm.G * dm.d + ((2 * dm.G + 3) & ~3);
   ALLOC(c->partials, (size_t)(c->partial_cap * pf));
 #undef ALLOC
 
@@ -220,6 +234,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
     HIP_TRY(hipMemcpy(order_dev, d->initial_free_order, (size_t)dm.num_pages * sizeof(int), hipMemcpyHostToDevice));
   }
   launch_init_tables(c->ctx, order_dev, nullptr);
+  launch_plan(c->ctx, c->plan, nullptr);
   HIP_TRY(hipMemsetAsync(c->ctx.pool, 0, pool_bytes, nullptr));
   HIP_TRY(hipStreamSynchronize(nullptr));
   if (order_dev) HIP_TRY(hipFree(order_dev));
@@ -294,10 +309,10 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
     }
     rc = stage_upload(c, s, off, st);
     if (rc != SART_OK) return rc;
-    launch_append(c->ctx, a, st);
+    launch_append(c->ctx, c->plan, a, st);
     HIP_TRY(hipEventRecord(s->done, st));
   } else {
-    launch_append(c->ctx, a, st);
+    launch_append(c->ctx, c->plan, a, st);
   }
   HIP_TRY(hipGetLastError());
   return SART_OK;
@@ -316,7 +331,8 @@ sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, f
   DecodeArgs a{};
   a.q = q; a.out = out; a.n_rows = n_rows;
   a.scale_log2 = scale * 1.44269504088896340736f;
-  a.n_wg = c->n_wg; a.chunk_pages = c->chunk_pages;
+  a.n_wg = c->plan.n_wg;
+  a.inline_prefix = c->plan.inline_prefix;
   a.partials = c->partials; a.partial_cap = c->partial_cap;
   a.call_seq = ++c->call_seq;
   for (int i = 0; i < 4; ++i) a.ev[i] = c->profiling ? c->ev[i] : nullptr;
@@ -357,10 +373,10 @@ sart_status sart_prune_branches(sart_cache* c, const sart_prune_policy* pol, con
     }
     rc = stage_upload(c, s, off, st);
     if (rc != SART_OK) return rc;
-    launch_prune(c->ctx, a, st);
+    launch_prune(c->ctx, c->plan, a, st);
     HIP_TRY(hipEventRecord(s->done, st));
   } else {
-    launch_prune(c->ctx, a, st);
+    launch_prune(c->ctx, c->plan, a, st);
   }
   HIP_TRY(hipGetLastError());
   return SART_OK;
@@ -388,7 +404,7 @@ sart_status sart_finish_branch(sart_cache* c, int32_t n, const int32_t* handles,
   if (n) memcpy(s->host, handles, (size_t)n * sizeof(int));
   rc = stage_upload(c, s, n, st);
   if (rc != SART_OK) return rc;
-  launch_finish(c->ctx, n, s->dev, ++c->call_seq, st);
+  launch_finish(c->ctx, c->plan, n, s->dev, ++c->call_seq, st);
   HIP_TRY(hipEventRecord(s->done, st));
   HIP_TRY(hipGetLastError());
   return SART_OK;
@@ -463,13 +479,23 @@ sart_status sart_last_decode_ms(sart_cache* c, float* ms_attn, float* ms_total) 
   return SART_OK;
 }
 
-sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t prefix_chunk_pages) {
+sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t prefix_chunk_pages,
+                                   int32_t prompt_mode, int32_t skew_permille, int32_t pool_permille) {
   if (!c) return fail(SART_E_INVALID, "null cache");
+  if (prompt_mode < -1 || prompt_mode > 1) return fail(SART_E_INVALID, "prompt_mode must be -1, 0 or 1");
+  if (skew_permille < -500 || skew_permille > 500) return fail(SART_E_INVALID, "skew_permille out of range");
+  if (prompt_mode >= 0) c->plan.inline_prefix = c->ctx.dm.layout == SART_LAYOUT_MFMA16 ? prompt_mode : 1;
+  if (pool_permille < 0 || pool_permille > kMaxPoolPermille) return fail(SART_E_INVALID, "pool_permille out of range");
+  c->plan.skew_permille = skew_permille;
+  c->plan.pool_permille = pool_permille;
   if (n_workgroups > c->max_wg) return fail(SART_E_INVALID, "at most %d workgroups", c->max_wg);
   hipDeviceProp_t prop;
   HIP_TRY(hipGetDeviceProperties(&prop, c->device));
-  c->n_wg = n_workgroups > 0 ? n_workgroups : (prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256);
-  c->chunk_pages = prefix_chunk_pages > 0 ? prefix_chunk_pages : 0;
+  const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  c->plan.n_wg = n_workgroups > 0 ? n_workgroups : cus;
+  c->plan.chunk_pages = prefix_chunk_pages > 0 ? prefix_chunk_pages : 0;
+  launch_plan(c->ctx, c->plan, c->last_stream);   // the plan follows the launch shape
+  HIP_TRY(hipGetLastError());
   return SART_OK;
 }
 

@@ -22,7 +22,7 @@
 //   * Shared prompt pages are staged in LDS once per (request, kv head,
 //     chunk) workgroup and reused by the request's branches (one wave each)
 //     and all query heads of the group.
-#include "sart_internal.h"
+#include "sart_device.h"
 
 namespace sart {
 
@@ -31,145 +31,20 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-__device__ inline int ceil_div_i(int a, int b) { return (a + b - 1) / b; }
+#ifdef SART_TRACE
+// Developer build only: per-wave timestamps (100 MHz wall clock) at phase
+// boundaries of the attention kernel, read back with sart_debug_trace.
+__device__ unsigned long long g_trace[16384 * 8];
+#define SART_STAMP(k)                                                                              \
+  do {                                                                                             \
+    if ((threadIdx.x & 63) == 0) g_trace[((size_t)blockIdx.x * kAttnWaves + (threadIdx.x >> 6)) * 8 + (k)] = wall_clock64(); \
+  } while (0)
+#else
+#define SART_STAMP(k) do { } while (0)
+#endif
 
-__device__ inline int wave_incl_scan_i(int v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    int n = __shfl_up(v, off, 64);
-    if (lane >= off) v += n;
-  }
-  return v;
-}
-__device__ inline int block_excl_scan_i(int v, int* lds, int& total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int nw = (blockDim.x + 63) >> 6;
-  int incl = wave_incl_scan_i(v);
-  __syncthreads();
-  if (lane == 63) lds[wave] = incl;
-  __syncthreads();
-  if (wave == 0) {
-    int t = lane < nw ? lds[lane] : 0;
-    int ti = wave_incl_scan_i(t);
-    if (lane < nw) lds[lane] = ti - t;
-    if (lane == nw - 1) lds[16] = ti;
-  }
-  __syncthreads();
-  total = lds[16];
-  return incl - v + lds[wave];
-}
-
-// floats of one partial: o[G][d], then m[G], l[G]
-__host__ __device__ inline long long partial_floats(int G, int d) { return (long long)G * d + 2 * G; }
-
-// ---------------------------------------------------------------------------
-// A3: partition plan (one workgroup).
-//   page_cum[a]      exclusive scan of the pages each active row contributes
-//                    (private pages; plus the prompt's pages when the prompt
-//                    is read inline by the generic kernel)
-//   units            page_cum[nA] * Hkv, cut into ranges of per_wave units
-//   prefix items     one per (live request, kv head, prompt chunk, group of
-//                    kAttnWaves branches)
-// ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kPlanThreads)
-k_decode_plan(Ctx c, DecodeArgs a, int inline_prefix) {
-  const Dims& dm = c.dm;
-  const Tables& tb = c.tb;
-  int* scal = tb.scal;
-  __shared__ int lds[17];
-  __shared__ int s_npc;
-  const int tid = threadIdx.x;
-  const int nA = scal[S_NACTIVE];
-  if (a.n_rows < nA) {
-    if (tid == 0) {
-      if (scal[S_ERR] == 0) { scal[S_ERR] = SART_E_INVALID; scal[S_ERRCALL] = a.call_seq; }
-      scal[S_CALLOK] = 0;
-    }
-    return;
-  }
-  if (tid == 0) s_npc = 0;
-  // first active index of each live request
-  for (int i = tid; i < nA; i += kPlanThreads) {
-    const int r = tb.active[i] / dm.Nb;
-    if (i == 0 || tb.active[i - 1] / dm.Nb != r) tb.req_first[r] = i;
-  }
-  int carry = 0;
-  for (int base = 0; base < nA; base += kPlanThreads) {
-    const int i = base + tid;
-    int np = 0;
-    if (i < nA) {
-      np = ceil_div_i(tb.seq_len[i], dm.pt);
-      if (inline_prefix) np += ceil_div_i(tb.prefix_len[tb.active[i] / dm.Nb], dm.pt);
-    }
-    int tot;
-    const int ex = block_excl_scan_i(np, lds, tot);
-    if (i < nA) tb.page_cum[i] = carry + ex;
-    carry += tot;
-  }
-  if (tid == 0) tb.page_cum[nA] = carry;
-  const long long units = (long long)carry * dm.Hkv;
-  const int n_waves = a.n_wg * kAttnWaves;
-  int per_wave = (int)((units + n_waves - 1) / n_waves);
-  if (per_wave < 1) per_wave = 1;
-
-  int n_items = 0, n_live = 0, chunk = 0;
-  if (!inline_prefix) {
-    // pass 1: total prompt work, to size the chunk so that the items about fill the grid
-    int w_carry = 0;
-    for (int base = 0; base < nA; base += kPlanThreads) {
-      const int i = base + tid;
-      int w = 0;
-      if (i < nA) {
-        const int r = tb.active[i] / dm.Nb;
-        if (tb.req_first[r] == i)
-          w = ceil_div_i(tb.prefix_len[r], dm.pt) * ceil_div_i(tb.refcnt[r], kAttnWaves) * dm.Hkv;
-      }
-      int tot;
-      block_excl_scan_i(w, lds, tot);
-      w_carry += tot;
-    }
-    chunk = a.chunk_pages;
-    if (chunk <= 0) chunk = ceil_div_i(w_carry, a.n_wg > 0 ? a.n_wg : 1);
-    chunk = ceil_div_i(chunk < 1 ? 1 : chunk, kStagePages) * kStagePages;
-    // pass 2: the live-request list and its item offsets
-    int l_carry = 0, i_carry = 0;
-    for (int base = 0; base < nA; base += kPlanThreads) {
-      const int i = base + tid;
-      int is_live = 0, items = 0, r = 0;
-      if (i < nA) {
-        r = tb.active[i] / dm.Nb;
-        const int pp = ceil_div_i(tb.prefix_len[r], dm.pt);
-        if (tb.req_first[r] == i && pp > 0) {
-          is_live = 1;
-          const int nck = ceil_div_i(pp, chunk);
-          items = dm.Hkv * nck * ceil_div_i(tb.refcnt[r], kAttnWaves);
-          atomicMax(&s_npc, nck);
-        }
-      }
-      int tl, ti;
-      const int exl = block_excl_scan_i(is_live, lds, tl);
-      const int exi = block_excl_scan_i(items, lds, ti);
-      if (is_live) { tb.live_req[l_carry + exl] = r; tb.live_item_start[l_carry + exl] = i_carry + exi; }
-      l_carry += tl;
-      i_carry += ti;
-    }
-    n_live = l_carry;
-    n_items = i_carry;
-    if (tid == 0) tb.live_item_start[n_live] = n_items;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    scal[S_D_NA] = nA;
-    scal[S_D_UNITS] = (int)units;
-    scal[S_D_PER_WAVE] = per_wave;
-    scal[S_D_NITEMS] = n_items;
-    scal[S_D_NLIVE] = n_live;
-    scal[S_D_CHUNK] = chunk;
-    scal[S_D_NPC] = s_npc;
-    scal[S_CALLOK] = 1;
-  }
-}
+// floats of one partial: o[G][d], then m[G], l[G], padded to a 16-byte multiple
+__host__ __device__ inline long long partial_floats(int G, int d) { return (long long)G * d + ((2 * G + 3) & ~3); }
 
 // ---------------------------------------------------------------------------
 // Online-softmax state of one wave for one (row, kv head): the 16 x d tile
@@ -189,9 +64,32 @@ struct WaveState {
   }
 };
 
+// max over the four 16-lane rows of a wave for every column (lane & 15), on
+// the vector ALU: v_permlane32_swap / v_permlane16_swap exchange half-waves and
+// odd/even rows between two registers; feeding the same value twice and taking
+// the max of both results is the pairwise max whichever half is swapped.
+__device__ inline float max_over_rows(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const unsigned v = __float_as_uint(x);
+  const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ inline float sum_over_rows(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const unsigned v = __float_as_uint(x);
+  const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 // One 16-token page: kq[i] / vq[i] are the 16-byte chunks this lane loaded
-// (chunk i*64 + lane of the K resp. V tile), qreg the Q^T operand.
-template <int D>
+// (chunk i*64 + lane of the K resp. V tile), qreg the Q^T operand.  FULL: all
+// 16 tokens are valid (no masking code).  Scores are kept in the log2 domain:
+// p = 2^(s*c - m) with c = scale*log2(e).
+template <int D, bool FULL>
 __device__ inline void process_page(WaveState<D>& st, const uint4* kq, const uint4* vq, const uint4* qreg,
                                     int nvalid, float scale_log2) {
   const int g = (threadIdx.x & 63) >> 4;
@@ -200,17 +98,14 @@ __device__ inline void process_page(WaveState<D>& st, const uint4* kq, const uin
   for (int i = 0; i < D / 32; ++i)
     s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kq[i]),
                                                 __builtin_bit_cast(bf16x8, qreg[i]), s, 0, 0, 0);
-  float sv[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) sv[j] = s[j] * scale_log2;
   uint4 vloc[D / 32];
 #pragma unroll
   for (int i = 0; i < D / 32; ++i) vloc[i] = vq[i];
-  if (nvalid < 16) {  // wave-uniform: only the last page of a sequence
+  if (!FULL) {
     const int t0 = 4 * g;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-      if (t0 + j >= nvalid) sv[j] = -__builtin_inff();
+      if (t0 + j >= nvalid) s[j] = -__builtin_inff();
     const unsigned m01 = (t0 + 0 < nvalid ? 0x0000ffffu : 0u) | (t0 + 1 < nvalid ? 0xffff0000u : 0u);
     const unsigned m23 = (t0 + 2 < nvalid ? 0x0000ffffu : 0u) | (t0 + 3 < nvalid ? 0xffff0000u : 0u);
 #pragma unroll
@@ -218,15 +113,14 @@ __device__ inline void process_page(WaveState<D>& st, const uint4* kq, const uin
       vloc[i].x &= m01; vloc[i].y &= m23; vloc[i].z &= m01; vloc[i].w &= m23;
     }
   }
-  float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-  const float m_new = fmaxf(st.m, mx);          // finite: a page holds >= 1 valid token
-  const float alpha = exp2f(st.m - m_new);      // 0 on the first page (m = -inf)
+  float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+  mx = max_over_rows(mx) * scale_log2;           // scale > 0: max commutes with the scaling
+  const float m_new = fmaxf(st.m, mx);           // finite: a page holds >= 1 valid token
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // 0 on the first page (m = -inf)
   st.m = m_new;
   f32x4 p;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) p[j] = exp2f(sv[j] - m_new);
+  for (int j = 0; j < 4; ++j) p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[j], scale_log2, -m_new));
   st.l = st.l * alpha + (p[0] + p[1]) + (p[2] + p[3]);
   if (__any(alpha != 1.0f)) {
 #pragma unroll
@@ -255,9 +149,7 @@ __device__ inline void load_q(uint4* qreg, const uint16_t* q, const Dims& dm, in
 template <int D>
 __device__ inline void store_partial(const WaveState<D>& st, float* partials, long long slot, const Dims& dm) {
   const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
-  float l = st.l;
-  l += __shfl_xor(l, 16, 64);
-  l += __shfl_xor(l, 32, 64);
+  const float l = sum_over_rows(st.l);
   if (r >= dm.G) return;
   float* base = partials + slot * partial_floats(dm.G, D);
 #pragma unroll
@@ -270,170 +162,246 @@ __device__ inline void store_partial(const WaveState<D>& st, float* partials, lo
 
 // ---------------------------------------------------------------------------
 // A4 + A5: persistent attention kernel (bf16, SART_LAYOUT_MFMA16, 16-token pages).
+// One 4-wave workgroup per CU, one wave per SIMD: two waves on a SIMD do not
+// share it fairly (the older one streams about 1.5x faster, measured), which a
+// static partition cannot absorb; memory-level parallelism comes from the
+// per-wave ring of page buffers instead.  Each workgroup has a shared-prompt phase (its
+// items of the plan, K/V staged through LDS, one wave per branch; empty when
+// the prompt is read inline) and a private phase (each wave streams its own
+// range of units).  Even workgroups run the prompt phase first, odd ones last,
+// so that the latency-bound prompt phases do not all idle HBM at once.
+// bt0 / bt1 are the two block-table buffers again, as noalias kernel arguments:
+// the compiler may then read page ids with scalar loads, which do not queue
+// behind the in-flight vector loads of K/V tiles.
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, bool INL>
 __global__ void __launch_bounds__(kAttnThreads)
-k_attn_mfma(Ctx c, DecodeArgs a) {
+k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restrict__ bt1,
+            const int* __restrict__ item_desc, const int* __restrict__ prefix_table) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
-  const int* scal = tb.scal;
-  if (!scal[S_CALLOK]) return;
+  int* scal = tb.scal;
   constexpr int KQ = D / 32;                       // 16-byte chunks per lane per tile
+  constexpr int kRing = 4;                         // pages in flight per wave on the private path
   constexpr int kTileBytes = 16 * D * 2;           // one K (or V) tile
   constexpr int kPageBytes = 2 * kTileBytes;       // K tile + V tile of one kv head
+  constexpr int kRound = kAttnThreads * 16;                // bytes one load round of the workgroup covers
+  constexpr int kCPT = (kPageBytes + kRound - 1) / kRound; // staged 16-byte chunks per thread per page
   __shared__ __attribute__((aligned(16))) unsigned char lds_kv[2][kStagePages][kPageBytes];
 
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nA = scal[S_D_NA];
+  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != (int)gridDim.x) {
+    // a row buffer smaller than the active list, or a launch that does not match the plan
+    if (blockIdx.x == 0 && threadIdx.x == 0) record_error(scal, SART_E_INVALID, a.call_seq);
+    return;
+  }
   const int chunk = scal[S_D_CHUNK], npc = scal[S_D_NPC];
-  const int n_items = scal[S_D_NITEMS], n_live = scal[S_D_NLIVE];
-  const int n_waves = gridDim.x * kAttnWaves;
+  const int n_items = scal[S_D_NITEMS];
   const long long S = (long long)nA * dm.Hkv;
-  const long long prefix_base = (long long)n_waves + S;
+  const long long prefix_base = (long long)scal[S_D_POOLBASE] + scal[S_D_NCHUNK] + S;
   const uint16_t* q = (const uint16_t*)a.q;
   const unsigned char* pool = (const unsigned char*)c.pool;
-  const int* bt = tb.bt[scal[S_BTSEL]];
+  const int* __restrict__ bt = scal[S_BTSEL] ? bt1 : bt0;
+  const bool prompt_first = (blockIdx.x & 1) == 0;
+  SART_STAMP(0);
   WaveState<D> st;
   uint4 qreg[KQ];
 
-  // ---- shared prompt items -------------------------------------------------
-  for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
-    int lo = 0, hi = n_live - 1;
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if (tb.live_item_start[mid] <= it) lo = mid; else hi = mid - 1;
-    }
-    const int r = tb.live_req[lo];
-    int local = it - tb.live_item_start[lo];
-    const int cnt = tb.refcnt[r], first = tb.req_first[r];
-    const int plen = tb.prefix_len[r];
-    const int pp = ceil_div_i(plen, 16);
-    const int nck = ceil_div_i(pp, chunk), ngr = ceil_div_i(cnt, kAttnWaves);
-    const int bg = local % ngr; local /= ngr;
-    const int ck = local % nck;
-    const int h = local / nck;
-    const int p0 = ck * chunk, p1 = min(pp, p0 + chunk);
-    const int slot_in_req = bg * kAttnWaves + wv;
-    const bool have_row = slot_in_req < cnt;
-    const int row = first + slot_in_req;
-    const int* ptab = tb.prefix_table + (long long)r * dm.max_pp;
-    if (have_row) { load_q<D>(qreg, q, dm, row, h); st.reset(); }
+  for (int phase = 0; phase < 2; ++phase) {
+    if ((phase == 0) == prompt_first) {
+      // ---- shared prompt items ---------------------------------------------
+      SART_STAMP(1);
+      for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+        const int4 d0 = *(const int4*)(item_desc + 8LL * it);
+        const int4 d1 = *(const int4*)(item_desc + 8LL * it + 4);
+        const int first = d0.x, cnt = d0.y, plen = d0.z, h = d0.w, ck = d1.x, bg = d1.y, r = d1.z;
+        const int pp = ceil_div(plen, 16);
+        const int p0 = ck * chunk, p1 = min(pp, p0 + chunk);
+        const int slot_in_req = bg * kAttnWaves + wv;
+        const bool have_row = slot_in_req < cnt;
+        const int row = first + slot_in_req;
+        const int* __restrict__ ptab = prefix_table + (long long)r * dm.max_pp;
+        if (have_row) { load_q<D>(qreg, q, dm, row, h); st.reset(); }
 
-    const int nst = ceil_div_i(p1 - p0, kStagePages);
-    const bool loader = threadIdx.x * 16 < kPageBytes;
-    uint4 greg[kStagePages];
-    auto g_load = [&](int stg) {
+        const int nst = ceil_div(p1 - p0, kStagePages);
+        uint4 greg[kStagePages][kCPT];
+        auto g_load = [&](int stg) {
 #pragma unroll
-      for (int k = 0; k < kStagePages; ++k) {
-        const int p = p0 + stg * kStagePages + k;
-        if (p < p1 && loader) {
-          const long long off = (tile_base(dm, ptab[p], h) * 2) + threadIdx.x * 16;
-          greg[k] = *(const uint4*)(pool + off);
-        }
-      }
-    };
-    auto l_store = [&](int stg) {
+          for (int k = 0; k < kStagePages; ++k) {
+            const int p = p0 + stg * kStagePages + k;
+            if (p < p1) {
+              const unsigned char* src = pool + tile_base(dm, ptab[p], h) * 2 + threadIdx.x * 16;
 #pragma unroll
-      for (int k = 0; k < kStagePages; ++k) {
-        const int p = p0 + stg * kStagePages + k;
-        if (p < p1 && loader) *(uint4*)(&lds_kv[stg & 1][k][threadIdx.x * 16]) = greg[k];
-      }
-    };
-    __syncthreads();   // the previous item's readers are done with both buffers
-    g_load(0);
-    l_store(0);
-    __syncthreads();
-    for (int stg = 0; stg < nst; ++stg) {
-      if (stg + 1 < nst) g_load(stg + 1);
-      if (have_row) {
-#pragma unroll
-        for (int k = 0; k < kStagePages; ++k) {
-          const int p = p0 + stg * kStagePages + k;
-          if (p < p1) {
-            uint4 kq[KQ], vq[KQ];
-#pragma unroll
-            for (int i = 0; i < KQ; ++i) {
-              kq[i] = *(const uint4*)(&lds_kv[stg & 1][k][i * 1024 + lane * 16]);
-              vq[i] = *(const uint4*)(&lds_kv[stg & 1][k][kTileBytes + i * 1024 + lane * 16]);
+              for (int j = 0; j < kCPT; ++j)
+                if (j * kRound + (int)threadIdx.x * 16 < kPageBytes) greg[k][j] = *(const uint4*)(src + j * kRound);
             }
-            const int nvalid = min(16, plen - p * 16);
-            process_page<D>(st, kq, vq, qreg, nvalid, a.scale_log2);
           }
-        }
-      }
-      if (stg + 1 < nst) l_store(stg + 1);
-      __syncthreads();
-    }
-    if (have_row)
-      store_partial<D>(st, a.partials, prefix_base + ((long long)row * dm.Hkv + h) * npc + ck, dm);
-  }
-
-  // ---- private pages: this wave's range of (page, kv head) units ------------
-  const long long units = (long long)tb.page_cum[nA] * dm.Hkv;
-  const int per = scal[S_D_PER_WAVE];
-  const long long w = (long long)blockIdx.x * kAttnWaves + wv;
-  long long u = w * per;
-  const long long u1 = min(units, u + per);
-  if (u >= u1) return;
-  // row containing unit u: last row with Hkv * page_cum[row] <= u and pages > 0
-  int row;
-  {
-    int lo = 0, hi = nA - 1;
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if ((long long)tb.page_cum[mid] * dm.Hkv <= u) lo = mid; else hi = mid - 1;
-    }
-    row = lo;
-  }
-  while (u < u1) {
-    int pages = tb.page_cum[row + 1] - tb.page_cum[row];
-    long long rem = u - (long long)tb.page_cum[row] * dm.Hkv;
-    while (pages == 0 || rem >= (long long)pages * dm.Hkv) {  // skip rows without private pages
-      ++row;
-      pages = tb.page_cum[row + 1] - tb.page_cum[row];
-      rem = u - (long long)tb.page_cum[row] * dm.Hkv;
-    }
-    const int h = (int)(rem / pages);
-    const int p0 = (int)(rem % pages);
-    const int n = (int)min((long long)(pages - p0), u1 - u);
-    const int len = tb.seq_len[row];
-    const int* table = bt + (long long)row * dm.max_bp;
-    load_q<D>(qreg, q, dm, row, h);
-    st.reset();
-    const long long head_off = (long long)h * kPageBytes + lane * 16;
-    const long long page_bytes = dm.page_elems * 2;
-
-    auto load_page = [&](uint4* kq, uint4* vq, int pid) {
-      const unsigned char* base = pool + (long long)pid * page_bytes + head_off;
+        };
+        auto l_store = [&](int stg) {
 #pragma unroll
-      for (int i = 0; i < KQ; ++i) {
-        kq[i] = *(const uint4*)(base + i * 1024);
-        vq[i] = *(const uint4*)(base + kTileBytes + i * 1024);
-      }
-    };
-    // pages are taken 64 at a time: one coalesced read of the block table,
-    // then page ids are broadcast from lanes
-    for (int b0 = 0; b0 < n; b0 += 64) {
-      const int nb = min(64, n - b0);
-      const int my_pid = lane < nb ? table[p0 + b0 + lane] : 0;
-      uint4 k0[KQ], v0[KQ], k1[KQ], v1[KQ];
-      load_page(k0, v0, __shfl(my_pid, 0, 64));
-      for (int i = 0; i < nb; i += 2) {
-        if (i + 1 < nb) load_page(k1, v1, __shfl(my_pid, i + 1, 64));
-        {
-          const int p = p0 + b0 + i;
-          process_page<D>(st, k0, v0, qreg, min(16, len - p * 16), a.scale_log2);
+          for (int k = 0; k < kStagePages; ++k) {
+            const int p = p0 + stg * kStagePages + k;
+            if (p < p1) {
+#pragma unroll
+              for (int j = 0; j < kCPT; ++j)
+                if (j * kRound + (int)threadIdx.x * 16 < kPageBytes)
+                  *(uint4*)(&lds_kv[stg & 1][k][j * kRound + threadIdx.x * 16]) = greg[k][j];
+            }
+          }
+        };
+        __syncthreads();   // the previous item's readers are done with both buffers
+        g_load(0);
+        l_store(0);
+        __syncthreads();
+        for (int stg = 0; stg < nst; ++stg) {
+          if (stg + 1 < nst) g_load(stg + 1);
+          if (have_row) {
+#pragma unroll
+            for (int k = 0; k < kStagePages; ++k) {
+              const int p = p0 + stg * kStagePages + k;
+              if (p < p1) {
+                uint4 kq[KQ], vq[KQ];
+#pragma unroll
+                for (int i = 0; i < KQ; ++i) {
+                  kq[i] = *(const uint4*)(&lds_kv[stg & 1][k][i * 1024 + lane * 16]);
+                  vq[i] = *(const uint4*)(&lds_kv[stg & 1][k][kTileBytes + i * 1024 + lane * 16]);
+                }
+                const int nvalid = min(16, plen - p * 16);
+                if (nvalid == 16) process_page<D, true>(st, kq, vq, qreg, 16, a.scale_log2);
+                else process_page<D, false>(st, kq, vq, qreg, nvalid, a.scale_log2);
+              }
+            }
+          }
+          if (stg + 1 < nst) l_store(stg + 1);
+          __syncthreads();
         }
-        if (i + 2 < nb) load_page(k0, v0, __shfl(my_pid, i + 2, 64));
-        if (i + 1 < nb) {
-          const int p = p0 + b0 + i + 1;
-          process_page<D>(st, k1, v1, qreg, min(16, len - p * 16), a.scale_log2);
-        }
+        if (have_row)
+          store_partial<D>(st, a.partials, prefix_base + ((long long)row * dm.Hkv + h) * npc + ck, dm);
       }
+      SART_STAMP(2);
+      continue;
     }
-    store_partial<D>(st, a.partials, w + (long long)row * dm.Hkv + h, dm);
-    u += n;
+
+    // ---- private pages: this wave's static range of (page, kv head) units, then
+    //      chunks of the shared pool until it is empty ---------------------------
+    const Cut cut = load_cut(scal);
+    long long w = (long long)blockIdx.x * kAttnWaves + wv;     // range number
+    SART_STAMP(3);
+    int n_pieces = 0;
+    bool own = true;                       // first pass: this wave's static range
+    for (;;) {
+      long long u = 0, u1 = 0;
+      if (!own || w < cut.pool_base) { u = range_start(cut, w); u1 = range_end(cut, w); }
+      // the next pool chunk is claimed before this range is processed, so the
+      // atomic's round trip hides behind the page loads
+      int next_chunk = 0;
+      if (lane == 0) next_chunk = atomicAdd(&scal[S_POOL_NEXT], 1);
+      next_chunk = __builtin_amdgcn_readfirstlane(next_chunk);
+      int row = u < u1 ? tb.wave_row[w] : 0;
+    while (u < u1) {
+      int pages = tb.page_cum[row + 1] - tb.page_cum[row];
+      long long rem = u - (long long)tb.page_cum[row] * dm.Hkv;
+      while (pages == 0 || rem >= (long long)pages * dm.Hkv) {  // skip rows without private pages
+        ++row;
+        pages = tb.page_cum[row + 1] - tb.page_cum[row];
+        rem = u - (long long)tb.page_cum[row] * dm.Hkv;
+      }
+      const int h = (int)(rem / pages);
+      const int p0 = (int)(rem % pages);
+      const int n = (int)min((long long)(pages - p0), u1 - u);
+      const int len = tb.seq_len[row];
+      load_q<D>(qreg, q, dm, row, h);
+      st.reset();
+      const long long head_off = (long long)h * kPageBytes + lane * 16;
+      const long long page_bytes = dm.page_elems * 2;
+
+      auto load_page = [&](uint4* kq, uint4* vq, int pid) {
+        const unsigned char* base = pool + (long long)pid * page_bytes + head_off;
+#pragma unroll
+        for (int i = 0; i < KQ; ++i) {
+          kq[i] = *(const uint4*)(base + i * 1024);
+          vq[i] = *(const uint4*)(base + kTileBytes + i * 1024);
+        }
+      };
+      // A piece is one run of pages of one table, or two when the prompt is
+      // read inline and the piece crosses from the prompt's pages into the
+      // row's own pages.  The online-softmax state carries over.
+      int pp = 0, plen = 0;
+      const int* __restrict__ ptab = prefix_table;
+      if (INL) {
+        const int req = tb.active[row] / dm.Nb;
+        plen = tb.prefix_len[req];
+        pp = ceil_div(plen, 16);
+        ptab = prefix_table + (long long)req * dm.max_pp;
+      }
+      const int* __restrict__ own = bt + (long long)row * dm.max_bp;
+      for (int run = 0; run < (INL ? 2 : 1); ++run) {
+        // pages [r0, r0 + rn) of `table`, the last of them holding n_last valid tokens
+        const int* __restrict__ table = own;
+        int r0 = p0, rn = n, n_last = min(16, len - (p0 + n - 1) * 16);
+        if (INL) {
+          if (run == 0) {
+            table = ptab;
+            rn = min(p0 + n, pp) - p0;
+            n_last = min(16, plen - (r0 + rn - 1) * 16);
+          } else {
+            r0 = max(p0, pp) - pp;
+            rn = p0 + n - pp - r0;
+            n_last = min(16, len - (r0 + rn - 1) * 16);
+          }
+          if (rn <= 0) continue;
+        }
+        // kRing register buffers in a software pipeline: kRing pages (8 KiB
+        // each) are in flight per wave.  The steady-state loop and its
+        // preheader have no conditional loads, so the compiler can wait for
+        // the oldest buffer only (s_waitcnt vmcnt(8*kRing-1 ...)) while the
+        // newer pages are still in flight; page ids are wave-uniform scalar
+        // reads of the table.
+        uint4 kb[kRing][KQ], vb[kRing][KQ];
+        int i = 0;
+        if (rn >= 2 * kRing) {
+#pragma unroll
+          for (int j = 0; j < kRing; ++j) load_page(kb[j], vb[j], table[r0 + j]);
+          do {   // at the top: buffer j holds page i+j (all full pages), i + 2*kRing <= rn
+            int pid[kRing];
+#pragma unroll
+            for (int j = 0; j < kRing; ++j) pid[j] = table[r0 + i + kRing + j];
+#pragma unroll
+            for (int j = 0; j < kRing; ++j) {
+              process_page<D, true>(st, kb[j], vb[j], qreg, 16, a.scale_log2);
+              load_page(kb[j], vb[j], pid[j]);
+            }
+            i += kRing;
+          } while (i + 2 * kRing <= rn);
+#pragma unroll
+          for (int j = 0; j < kRing; ++j)
+            process_page<D, false>(st, kb[j], vb[j], qreg, i + j == rn - 1 ? n_last : 16, a.scale_log2);
+          i += kRing;
+        }
+        while (i < rn) {   // fewer than 2*kRing pages left: groups of up to kRing, requested up front
+          const int cnt = min(kRing, rn - i);
+#pragma unroll
+          for (int j = 0; j < kRing; ++j)
+            if (j < cnt) load_page(kb[j], vb[j], table[r0 + i + j]);
+#pragma unroll
+          for (int j = 0; j < kRing; ++j)
+            if (j < cnt) process_page<D, false>(st, kb[j], vb[j], qreg, i + j == rn - 1 ? n_last : 16, a.scale_log2);
+          i += cnt;
+        }
+      }
+      store_partial<D>(st, a.partials, w + (long long)row * dm.Hkv + h, dm);
+      u += n;
+      if (n_pieces < 2) SART_STAMP(4 + n_pieces);
+      ++n_pieces;
+    }
+      if (own) SART_STAMP(6);
+      if (next_chunk >= cut.n_chunks) break;
+      w = cut.pool_base + next_chunk;
+      own = false;
+    }
   }
+  SART_STAMP(7);
 }
 
 // ---------------------------------------------------------------------------
@@ -451,29 +419,26 @@ __global__ void __launch_bounds__(kAttnThreads)
 k_attn_generic(Ctx c, DecodeArgs a) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
-  const int* scal = tb.scal;
-  if (!scal[S_CALLOK]) return;
+  int* scal = tb.scal;
+  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != (int)gridDim.x) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) record_error(scal, SART_E_INVALID, a.call_seq);
+    return;
+  }
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int nA = scal[S_D_NA];
   const int* bt = tb.bt[scal[S_BTSEL]];
   const T* pool = (const T*)c.pool;
   const T* q = (const T*)a.q;
   const int D = dm.d, pt = dm.pt;
-  const long long units = (long long)tb.page_cum[nA] * dm.Hkv;
-  const int per = scal[S_D_PER_WAVE];
-  const long long w = (long long)blockIdx.x * kAttnWaves + wv;
-  long long u = w * per;
-  const long long u1 = min(units, u + per);
-  if (u >= u1) return;
-  int row;
-  {
-    int lo = 0, hi = nA - 1;
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if ((long long)tb.page_cum[mid] * dm.Hkv <= u) lo = mid; else hi = mid - 1;
-    }
-    row = lo;
-  }
+  const Cut cut = load_cut(scal);
+  long long w = (long long)blockIdx.x * kAttnWaves + wv;
+  bool own = true;
+  for (;;) {
+  long long u = 0, u1 = 0;
+  if (!own || w < cut.pool_base) { u = range_start(cut, w); u1 = range_end(cut, w); }
+  int next_chunk = 0;
+  if (lane == 0) next_chunk = atomicAdd(&scal[S_POOL_NEXT], 1);
+  next_chunk = __shfl(next_chunk, 0, 64);
+  int row = u < u1 ? tb.wave_row[w] : 0;
   while (u < u1) {
     int pages = tb.page_cum[row + 1] - tb.page_cum[row];
     long long rem = u - (long long)tb.page_cum[row] * dm.Hkv;
@@ -487,7 +452,7 @@ k_attn_generic(Ctx c, DecodeArgs a) {
     const int n = (int)min((long long)(pages - p0), u1 - u);
     const int req = tb.active[row] / dm.Nb;
     const int plen = tb.prefix_len[req], len = tb.seq_len[row];
-    const int pp = ceil_div_i(plen, pt);
+    const int pp = ceil_div(plen, pt);
     const int* ptab = tb.prefix_table + (long long)req * dm.max_pp;
     const int* table = bt + (long long)row * dm.max_bp;
     float* pbase = a.partials + (w + (long long)row * dm.Hkv + h) * partial_floats(dm.G, D);
@@ -544,70 +509,69 @@ k_attn_generic(Ctx c, DecodeArgs a) {
     }
     u += n;
   }
+  if (next_chunk >= cut.n_chunks) break;
+  w = cut.pool_base + next_chunk;
+  own = false;
+  }
 }
 
 // ---------------------------------------------------------------------------
-// A6: merge.  One wave per output row (active row, query head):
-//   m = max m_i,  l = sum l_i 2^(m_i - m),  out = sum o_i 2^(m_i - m) / l
-// over the prompt-chunk partials and the private pieces, in slot order.
+// A6: merge.  One workgroup per (active row, kv head); each thread owns four
+// consecutive output columns of one query head and folds the partials of that
+// head in slot order (prompt chunks, then private pieces) with the running
+// form of  m = max m_i,  l = sum l_i 2^(m_i - m),  out = sum o_i 2^(m_i - m) / l.
+// The loads of successive partials are independent, so they overlap.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_merge(Ctx c, DecodeArgs a, int inline_prefix, int n_attn_waves) {
+k_merge(Ctx c, DecodeArgs a, int inline_prefix) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   const int* scal = tb.scal;
-  if (!scal[S_CALLOK]) return;
-  const int lane = threadIdx.x & 63;
+  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != a.n_wg) return;
   const int nA = scal[S_D_NA];
-  const int chunk = scal[S_D_CHUNK], npc = scal[S_D_NPC], per = scal[S_D_PER_WAVE];
-  const int D = dm.d, G = dm.G;
+  const int chunk = scal[S_D_CHUNK], npc = scal[S_D_NPC];
+  const Cut cut = load_cut(scal);
+  if (blockIdx.x == 0 && threadIdx.x == 0) tb.scal[S_POOL_NEXT] = 0;   // the pool is full again for the next launch
+  const int D = dm.d, G = dm.G, D4 = D >> 2;
   const long long pf = partial_floats(G, D);
   const long long S = (long long)nA * dm.Hkv;
-  const long long prefix_base = (long long)n_attn_waves + S;
-  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
-  for (long long orow = wave; orow < (long long)nA * dm.Hq; orow += nwaves) {
-    const int row = (int)(orow / dm.Hq), qh = (int)(orow % dm.Hq);
-    const int h = qh / G, r = qh % G;
-    const long long seg = (long long)row * dm.Hkv + h;
+  const long long prefix_base = (long long)cut.pool_base + cut.n_chunks + S;
+  for (long long seg = blockIdx.x; seg < S; seg += gridDim.x) {
+    const int row = (int)(seg / dm.Hkv), h = (int)(seg % dm.Hkv);
     // slot ranges: [pa, pa+pn) prompt chunks, [sa, sa+sn) private pieces
     long long pa = 0, sa = 0;
     int pn = 0, sn = 0;
     if (!inline_prefix) {
-      const int pp = ceil_div_i(tb.prefix_len[tb.active[row] / dm.Nb], dm.pt);
-      pn = pp > 0 ? ceil_div_i(pp, chunk) : 0;
+      const int pp = ceil_div(tb.prefix_len[tb.active[row] / dm.Nb], dm.pt);
+      pn = pp > 0 ? ceil_div(pp, chunk) : 0;
       pa = prefix_base + seg * npc;
     }
     const int pages = tb.page_cum[row + 1] - tb.page_cum[row];
     if (pages > 0) {
       const long long us = (long long)tb.page_cum[row] * dm.Hkv + (long long)h * pages;
-      const long long w0 = us / per, w1 = (us + pages - 1) / per;
+      const long long w0 = range_of_unit(cut, us), w1 = range_of_unit(cut, us + pages - 1);
       sa = w0 + seg;
       sn = (int)(w1 - w0 + 1);
     }
-    float m = -__builtin_inff();
-    for (int i = 0; i < pn + sn; ++i) {
-      const long long slot = i < pn ? pa + i : sa + (i - pn);
-      m = fmaxf(m, a.partials[slot * pf + (long long)G * D + r]);
-    }
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    float l = 0.f;
-    for (int i = 0; i < pn + sn; ++i) {
-      const long long slot = i < pn ? pa + i : sa + (i - pn);
-      const float* pb = a.partials + slot * pf;
-      const float wgt = exp2f(pb[(long long)G * D + r] - m);
-      l += wgt * pb[(long long)G * D + G + r];
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc) {
-        const int d = lane + 64 * cc;
-        if (d < D) acc[cc] = fmaf(wgt, pb[(long long)r * D + d], acc[cc]);
+    for (int e = threadIdx.x; e < G * D4; e += blockDim.x) {
+      const int r = e / D4, d4 = e % D4;
+      float m = -__builtin_inff(), l = 0.f;
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+      for (int i = 0; i < pn + sn; ++i) {
+        const long long slot = i < pn ? pa + i : sa + (i - pn);
+        const float* pb = a.partials + slot * pf;
+        const float mi = pb[(long long)G * D + r];
+        const float li = pb[(long long)G * D + G + r];
+        const f32x4 oi = *(const f32x4*)(pb + (long long)r * D + 4 * d4);
+        const float mn = fmaxf(m, mi);
+        const float ws = __builtin_amdgcn_exp2f(m - mn), wi = __builtin_amdgcn_exp2f(mi - mn);
+        l = l * ws + li * wi;
+        acc = acc * ws + oi * wi;
+        m = mn;
       }
-    }
-    const float inv = l > 0.f ? 1.0f / l : 0.f;
-#pragma unroll
-    for (int cc = 0; cc < 4; ++cc) {
-      const int d = lane + 64 * cc;
-      if (d < D) a.out[orow * D + d] = acc[cc] * inv;
+      const float inv = l > 0.f ? 1.0f / l : 0.f;
+      *(f32x4*)(a.out + ((long long)row * dm.Hq + h * G + r) * D + 4 * d4) = acc * inv;
     }
   }
 }
@@ -615,26 +579,31 @@ k_merge(Ctx c, DecodeArgs a, int inline_prefix, int n_attn_waves) {
 void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s) {
   const Dims& dm = c.dm;
   const bool mfma = dm.layout == SART_LAYOUT_MFMA16;
-  const int inline_prefix = mfma ? 0 : 1;
   if (a.ev[0]) (void)hipEventRecord(a.ev[0], s);
-  hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(kPlanThreads), 0, s, c, a, inline_prefix);
   if (a.ev[1]) (void)hipEventRecord(a.ev[1], s);
   if (mfma) {
-    if (dm.d == 128)
-      hipLaunchKernelGGL(k_attn_mfma<128>, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a);
-    else
-      hipLaunchKernelGGL(k_attn_mfma<64>, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a);
+#define SART_LAUNCH_MFMA(DD, II)                                                                         \
+  hipLaunchKernelGGL((k_attn_mfma<DD, II>), dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], \
+                     c.tb.bt[1], c.tb.item_desc, c.tb.prefix_table)
+    if (dm.d == 128) { if (a.inline_prefix) SART_LAUNCH_MFMA(128, true); else SART_LAUNCH_MFMA(128, false); }
+    else             { if (a.inline_prefix) SART_LAUNCH_MFMA(64, true); else SART_LAUNCH_MFMA(64, false); }
+#undef SART_LAUNCH_MFMA
   } else if (dm.dtype == SART_F32) {
     hipLaunchKernelGGL(k_attn_generic<float>, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a);
   } else {
     hipLaunchKernelGGL(k_attn_generic<uint16_t>, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a);
   }
   if (a.ev[2]) (void)hipEventRecord(a.ev[2], s);
-  const long long out_rows = (long long)dm.H * dm.Hq;
-  long long blocks = (out_rows + 3) / 4;
-  if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(k_merge, dim3((unsigned)blocks), dim3(256), 0, s, c, a, inline_prefix, a.n_wg * kAttnWaves);
+  long long blocks = (long long)dm.H * dm.Hkv;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(k_merge, dim3((unsigned)blocks), dim3(256), 0, s, c, a, a.inline_prefix);
   if (a.ev[3]) (void)hipEventRecord(a.ev[3], s);
 }
 
 }  // namespace sart
+
+#ifdef SART_TRACE
+extern "C" int sart_debug_trace(unsigned long long* host_out, int n_waves) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(sart::g_trace), (size_t)n_waves * 8 * sizeof(unsigned long long));
+}
+#endif

@@ -13,53 +13,9 @@
 // pop and push a plain prefix sum, hence reproducible bit for bit.  The bulk
 // work (KV rows, block-table rows, free-stack pushes) is done by wide
 // kernels that read the plan.
-#include "sart_internal.h"
+#include "sart_device.h"
 
 namespace sart {
-
-// ---------------------------------------------------------------------------
-// block-wide exclusive scan (1024 threads = 16 waves)
-// ---------------------------------------------------------------------------
-__device__ inline int wave_incl_scan(int v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    int n = __shfl_up(v, off, 64);
-    if (lane >= off) v += n;
-  }
-  return v;
-}
-
-// Returns the exclusive prefix of v over the block and the block total.
-// lds must hold 17 ints.  All threads of the block must call it.
-__device__ inline int block_excl_scan(int v, int* lds, int& total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int nw = (blockDim.x + 63) >> 6;
-  int incl = wave_incl_scan(v);
-  __syncthreads();
-  if (lane == 63) lds[wave] = incl;
-  __syncthreads();
-  if (wave == 0) {
-    int t = lane < nw ? lds[lane] : 0;
-    int ti = wave_incl_scan(t);
-    if (lane < nw) lds[lane] = ti - t;
-    if (lane == nw - 1) lds[16] = ti;
-  }
-  __syncthreads();
-  total = lds[16];
-  return incl - v + lds[wave];
-}
-
-__device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
-
-// First error of a call wins and stays until the host reads it.
-__device__ inline void record_error(int* scal, int code, int call_seq) {
-  if (scal[S_ERR] == 0) {
-    scal[S_ERR] = code;
-    scal[S_ERRCALL] = call_seq;
-  }
-  scal[S_CALLOK] = 0;
-}
 
 // ---------------------------------------------------------------------------
 // A0: initial tables
@@ -98,7 +54,7 @@ void launch_init_tables(const Ctx& c, const int* free_order_dev, hipStream_t s) 
 // sequential pop loop in list order would hand out.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kPlanThreads)
-k_append_plan(Ctx c, AppendArgs a) {
+k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
@@ -196,6 +152,7 @@ k_append_plan(Ctx c, AppendArgs a) {
     if (scal[S_BTHI0 + sel] < na_new) scal[S_BTHI0 + sel] = na_new;
     scal[S_CALLOK] = 1;
   }
+  refresh_decode_plan(c, pc, lds);
 }
 
 // One wave copies one (token, kv head) row of K and V into its page slot.
@@ -242,8 +199,8 @@ k_append_write(Ctx c, AppendArgs a) {
   }
 }
 
-void launch_append(const Ctx& c, const AppendArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(k_append_plan, dim3(1), dim3(kPlanThreads), 0, s, c, a);
+void launch_append(const Ctx& c, const PlanCfg& pc, const AppendArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_append_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, a);
   if (a.total_rows <= 0) return;
   const long long units = a.total_rows * c.dm.Hkv;
   long long blocks = (units + 3) / 4;
@@ -264,7 +221,7 @@ void launch_append(const Ctx& c, const AppendArgs& a, hipStream_t s) {
 //  (3) survivors keep their relative order.
 // The pushes themselves and the block-table rows are moved by k_terminate_move.
 // ---------------------------------------------------------------------------
-__device__ void terminate_plan(const Ctx& c, int* lds) {
+__device__ void terminate_plan(const Ctx& c, const PlanCfg& pc, int* lds) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
@@ -348,6 +305,7 @@ __device__ void terminate_plan(const Ctx& c, int* lds) {
     scal[S_FREETOP] = top + priv_pages + carry_r;
     scal[S_CALLOK] = 1;
   }
+  refresh_decode_plan(c, pc, lds);
 }
 
 // Terminate pass, bulk half: one workgroup per old row / dead request.
@@ -426,7 +384,7 @@ __device__ inline bool key_less(float sa, int ha, float sb, int hb) {
 // A7: prune.  Victim selection per request, then the terminate plan.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kPlanThreads)
-k_prune_plan(Ctx c, PruneArgs a) {
+k_prune_plan(Ctx c, PlanCfg pc, PruneArgs a) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
@@ -469,11 +427,11 @@ k_prune_plan(Ctx c, PruneArgs a) {
   for (int i = tid; i < nA; i += kPlanThreads)
     if (tb.new_state[i]) atomicAdd(&tb.num_pruned[tb.active[i] / dm.Nb], 1);
   __syncthreads();
-  terminate_plan(c, lds);
+  terminate_plan(c, pc, lds);
 }
 
-void launch_prune(const Ctx& c, const PruneArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(k_prune_plan, dim3(1), dim3(kPlanThreads), 0, s, c, a);
+void launch_prune(const Ctx& c, const PlanCfg& pc, const PruneArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_prune_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, a);
   launch_move(c, s);
 }
 
@@ -481,7 +439,7 @@ void launch_prune(const Ctx& c, const PruneArgs& a, hipStream_t s) {
 // A8: completion + early stop, then the terminate plan.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kPlanThreads)
-k_finish_plan(Ctx c, int n, const int* handles, int call_seq) {
+k_finish_plan(Ctx c, PlanCfg pc, int n, const int* handles, int call_seq) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
@@ -512,12 +470,24 @@ k_finish_plan(Ctx c, int n, const int* handles, int call_seq) {
         tb.new_state[a] = SART_BRANCH_EARLY_STOPPED;
   }
   __syncthreads();
-  terminate_plan(c, lds);
+  terminate_plan(c, pc, lds);
 }
 
-void launch_finish(const Ctx& c, int n, const int* handles_dev, int call_seq, hipStream_t s) {
-  hipLaunchKernelGGL(k_finish_plan, dim3(1), dim3(kPlanThreads), 0, s, c, n, handles_dev, call_seq);
+void launch_finish(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, int call_seq, hipStream_t s) {
+  hipLaunchKernelGGL(k_finish_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, n, handles_dev, call_seq);
   launch_move(c, s);
+}
+
+// Stand-alone refresh of the decode plan (after sart_alloc_cache and when the
+// launch shape changes).
+__global__ void __launch_bounds__(kPlanThreads)
+k_decode_plan(Ctx c, PlanCfg pc) {
+  __shared__ int lds[17];
+  refresh_decode_plan(c, pc, lds);
+}
+
+void launch_plan(const Ctx& c, const PlanCfg& pc, hipStream_t s) {
+  hipLaunchKernelGGL(k_decode_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc);
 }
 
 }  // namespace sart

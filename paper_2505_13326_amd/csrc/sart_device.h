@@ -1,0 +1,206 @@
+// Device-side helpers shared by the planning kernels: block scans, the sticky
+// error word, and the decode plan (the partition of one decode step's work),
+// which every state-changing planning kernel refreshes before it ends so that
+// sart_decode_attention needs no planning launch of its own.
+#pragma once
+
+#include "sart_internal.h"
+
+namespace sart {
+
+__device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+__device__ inline int wave_incl_scan(int v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int n = __shfl_up(v, off, 64);
+    if (lane >= off) v += n;
+  }
+  return v;
+}
+
+// Exclusive prefix of v over the workgroup (up to 1024 threads) and the total.
+// lds holds 17 ints.  Every thread of the workgroup must call it.
+__device__ inline int block_excl_scan(int v, int* lds, int& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nw = (blockDim.x + 63) >> 6;
+  const int incl = wave_incl_scan(v);
+  __syncthreads();
+  if (lane == 63) lds[wave] = incl;
+  __syncthreads();
+  if (wave == 0) {
+    const int t = lane < nw ? lds[lane] : 0;
+    const int ti = wave_incl_scan(t);
+    if (lane < nw) lds[lane] = ti - t;
+    if (lane == nw - 1) lds[16] = ti;
+  }
+  __syncthreads();
+  total = lds[16];
+  return incl - v + lds[wave];
+}
+
+// First error of a call wins and stays until the host reads it.
+__device__ inline void record_error(int* scal, int code, int call_seq) {
+  if (scal[S_ERR] == 0) {
+    scal[S_ERR] = code;
+    scal[S_ERRCALL] = call_seq;
+  }
+  scal[S_CALLOK] = 0;
+}
+
+// ---------------------------------------------------------------------------
+// A3: the decode plan (run by one 1024-thread workgroup; ends with a barrier).
+//
+//   page_cum[a]   exclusive scan over active rows of the pages a row puts on
+//                 the unit line: its private pages, plus its prompt's pages
+//                 when the prompt is read inline (natural-layout caches).
+//   units         page_cum[nA] * Hkv (page, kv head) units, cut into one static
+//                 range per attention wave followed by the pool chunks (Cut);
+//                 wave_row[w] = active row holding the first unit of range w.
+//   items         shared-prompt work: one per (live request, kv head, prompt
+//                 chunk, group of kAttnWaves branches), eight ints each:
+//                 {first row, live branches, prompt tokens, kv head, chunk,
+//                 group, request, 0}.
+// The prompt chunk is sized so that the items about fill the grid once.
+// ---------------------------------------------------------------------------
+__device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int* lds) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  int* scal = tb.scal;
+  const int tid = threadIdx.x;
+  __shared__ int s_npc;
+  __syncthreads();                       // the caller's table updates are visible
+  const int nA = scal[S_NACTIVE];
+  if (tid == 0) s_npc = 0;
+  int carry = 0, w_carry = 0, l_carry = 0;
+  for (int base = 0; base < nA; base += kPlanThreads) {
+    const int i = base + tid;
+    int np = 0, w = 0, first = 0, r = 0;
+    if (i < nA) {
+      const int b = tb.active[i];
+      r = b / dm.Nb;
+      first = i == 0 || tb.active[i - 1] / dm.Nb != r;
+      np = ceil_div(tb.seq_len[i], dm.pt);
+      const int pp = ceil_div(tb.prefix_len[r], dm.pt);
+      if (pc.inline_prefix) np += pp;
+      else if (first && pp > 0) w = pp * ceil_div(tb.refcnt[r], kAttnWaves) * dm.Hkv;
+      if (first) tb.req_first[r] = i;
+    }
+    int tot, totw, totl;
+    const int ex = block_excl_scan(np, lds, tot);
+    block_excl_scan(w, lds, totw);
+    const int exl = block_excl_scan(w > 0, lds, totl);
+    if (i < nA) tb.page_cum[i] = carry + ex;
+    if (w > 0) tb.live_req[l_carry + exl] = r;
+    carry += tot;
+    w_carry += totw;
+    l_carry += totl;
+  }
+  if (tid == 0) tb.page_cum[nA] = carry;
+  const long long units = (long long)carry * dm.Hkv;
+  const int n_waves = pc.n_wg * kAttnWaves;
+  // the pool: about pool_permille of the line, in chunks sized for ~8 chunks per wave
+  Cut cut;
+  {
+    const long long target = units * pc.pool_permille / 1000;
+    long long cc = target / (8LL * n_waves);
+    cut.pool_c = (int)(cc < 4 ? 4 : (cc > 64 ? 64 : cc));
+    cut.n_chunks = (int)(target / cut.pool_c);
+    cut.u_main = units - (long long)cut.n_chunks * cut.pool_c;
+  }
+  int per_wave = (int)((cut.u_main + n_waves - 1) / n_waves);
+  if (per_wave < 1) per_wave = 1;
+  // even / odd workgroups (see range_start): pe + po = 2 * per_wave, po >= 1;
+  // a grid with an odd workgroup count has no partner for the last one, so no skew
+  cut.pe = cut.po = per_wave;
+  if ((pc.n_wg & 1) == 0) {
+    int sk = (int)(((long long)per_wave * pc.skew_permille) / 1000);
+    if (sk > per_wave - 1) sk = per_wave - 1;
+    if (sk < 1 - per_wave) sk = 1 - per_wave;
+    cut.pe = per_wave + sk;
+    cut.po = per_wave - sk;
+  }
+  cut.pool_base = cut.u_main > 0 ? (int)static_of_unit(cut, cut.u_main - 1) + 1 : 0;
+  const int n_live = l_carry;
+  int chunk = pc.chunk_pages;
+  if (chunk <= 0) chunk = ceil_div(w_carry, pc.n_wg);
+  chunk = ceil_div(chunk < 1 ? 1 : chunk, kStagePages) * kStagePages;
+  __syncthreads();                       // live_req, req_first, page_cum written
+  // item offsets per live request
+  int i_carry = 0;
+  for (int base = 0; base < n_live; base += kPlanThreads) {
+    const int k = base + tid;
+    int items = 0;
+    if (k < n_live) {
+      const int r = tb.live_req[k];
+      const int nck = ceil_div(ceil_div(tb.prefix_len[r], dm.pt), chunk);
+      items = dm.Hkv * nck * ceil_div(tb.refcnt[r], kAttnWaves);
+      atomicMax(&s_npc, nck);
+    }
+    int ti;
+    const int ex = block_excl_scan(items, lds, ti);
+    if (k < n_live) tb.live_item_start[k] = i_carry + ex;
+    i_carry += ti;
+  }
+  const int n_items = i_carry;
+  if (tid == 0) tb.live_item_start[n_live] = n_items;
+  __syncthreads();
+  // item descriptors
+  for (int it = tid; it < n_items; it += kPlanThreads) {
+    int lo = 0, hi = n_live - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (tb.live_item_start[mid] <= it) lo = mid; else hi = mid - 1;
+    }
+    const int r = tb.live_req[lo];
+    int local = it - tb.live_item_start[lo];
+    const int cnt = tb.refcnt[r], plen = tb.prefix_len[r];
+    const int nck = ceil_div(ceil_div(plen, dm.pt), chunk), ngr = ceil_div(cnt, kAttnWaves);
+    const int bg = local % ngr; local /= ngr;
+    int4* d = (int4*)(tb.item_desc + 8LL * it);
+    d[0] = make_int4(tb.req_first[r], cnt, plen, local / nck);
+    d[1] = make_int4(local % nck, bg, r, 0);
+  }
+  // first row of every wave's range
+  for (int w = tid; w < cut.pool_base + cut.n_chunks; w += kPlanThreads) {
+    const long long u = range_start(cut, w);
+    int row = 0;
+    if (u < units) {
+      int lo = 0, hi = nA - 1;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((long long)tb.page_cum[mid] * dm.Hkv <= u) lo = mid; else hi = mid - 1;
+      }
+      row = lo;
+    }
+    tb.wave_row[w] = row;
+  }
+  if (tid == 0) {
+    scal[S_D_NA] = nA;
+    scal[S_D_UNITS] = (int)units;
+    scal[S_D_PER_EVEN] = cut.pe;
+    scal[S_D_PER_ODD] = cut.po;
+    scal[S_D_UMAIN] = (int)cut.u_main;
+    scal[S_D_POOLC] = cut.pool_c;
+    scal[S_D_NCHUNK] = cut.n_chunks;
+    scal[S_D_POOLBASE] = cut.pool_base;
+    scal[S_POOL_NEXT] = 0;
+    scal[S_D_NITEMS] = n_items;
+    scal[S_D_NLIVE] = n_live;
+    scal[S_D_CHUNK] = chunk;
+    scal[S_D_NPC] = s_npc;
+    scal[S_D_NWG] = pc.n_wg;
+  }
+  __syncthreads();
+}
+
+// The cut of the current plan, as the attention and merge kernels read it.
+__device__ inline Cut load_cut(const int* scal) {
+  Cut k;
+  k.pe = scal[S_D_PER_EVEN]; k.po = scal[S_D_PER_ODD]; k.u_main = scal[S_D_UMAIN];
+  k.pool_c = scal[S_D_POOLC]; k.n_chunks = scal[S_D_NCHUNK]; k.pool_base = scal[S_D_POOLBASE];
+  return k;
+}
+
+}  // namespace sart

@@ -10,7 +10,7 @@ namespace sart {
 
 constexpr int kWave = 64;
 constexpr int kPlanThreads = 1024;     // single-workgroup planning kernels
-constexpr int kAttnWaves = 8;          // waves per attention workgroup
+constexpr int kAttnWaves = 4;          // waves per attention workgroup (one per SIMD, one workgroup per CU)
 constexpr int kAttnThreads = kAttnWaves * kWave;
 constexpr int kStagePages = 4;         // prefix pages staged in LDS per pipeline stage
 constexpr int kMaxGroup = 16;          // query heads per KV head the MFMA tile holds
@@ -35,11 +35,18 @@ enum Scalar {
   // plan of the decode pass
   S_D_NA,
   S_D_UNITS,      // private (page, kv head) units in total
-  S_D_PER_WAVE,   // units per private wave
+  S_D_PER_EVEN,   // units per wave of an even workgroup
+  S_D_PER_ODD,    // units per wave of an odd workgroup
   S_D_NITEMS,     // prefix workgroup items
   S_D_NLIVE,      // live requests with a non-empty prompt
   S_D_CHUNK,      // prefix chunk in pages
   S_D_NPC,        // prefix chunks per (row, kv head) slot stride
+  S_D_NWG,        // attention workgroups the plan was made for
+  S_D_UMAIN,      // units cut statically into per-wave ranges; the rest is the shared pool
+  S_D_POOLC,      // units per pool chunk
+  S_D_NCHUNK,     // pool chunks
+  S_D_POOLBASE,   // range number of pool chunk 0 (= number of non-empty static ranges)
+  S_POOL_NEXT,    // next pool chunk to hand out (reset by the merge kernel)
   S_COUNT = 32
 };
 
@@ -83,6 +90,18 @@ struct Tables {
   int* page_cum;         // [H+1] exclusive scan of private pages over active rows
   int* live_req;         // [max_req] live requests with prompt, active order
   int* live_item_start;  // [max_req+1] exclusive scan of prefix items
+  int* item_desc;        // [max items][8] shared-prompt work items
+  int* wave_row;         // [max attention waves] active row of each wave's first unit
+};
+
+// Launch shape the decode plan is made for (host-chosen, passed to every
+// planning kernel).
+struct PlanCfg {
+  int n_wg;           // persistent attention workgroups
+  int chunk_pages;    // prompt chunk in pages; <= 0: sized on the device
+  int inline_prefix;  // the prompt is read as the first pages of every row
+  int skew_permille;  // even workgroups take (1000+skew)/1000 of the mean range, odd ones the rest
+  int pool_permille;  // share of the unit line handed out dynamically in small chunks
 };
 
 struct Ctx {
@@ -90,6 +109,46 @@ struct Ctx {
   Tables tb;
   void* pool;
 };
+
+// ---- unit line -> wave ranges ------------------------------------------------
+// Workgroups are dispatched round-robin over the 8 XCDs, and on MI355X the odd
+// XCDs stream measurably slower than the even ones, so ranges come in pairs of
+// workgroups: the kAttnWaves waves of an even workgroup take pe units each,
+// those of the following odd workgroup po units each.
+// After the static ranges comes the pool: the last units of the line in small
+// chunks that waves take from a shared counter when their own range is done
+// (ranges of equal size do not take equal time: XCDs and memory channels are
+// not symmetric).  Static ranges and pool chunks are numbered on one axis,
+// ranges first; a piece's partial goes to slot (range number + segment number).
+struct Cut {
+  int pe, po;            // units per wave of even / odd workgroups
+  long long u_main;      // units covered by the static ranges
+  int pool_c, n_chunks;  // units per pool chunk, number of chunks
+  int pool_base;         // range number of pool chunk 0: static ranges from here on are empty
+};
+__host__ __device__ inline long long static_start(const Cut& k, long long w) {
+  const long long b = w / kAttnWaves, wv = w % kAttnWaves;
+  const long long pair = b >> 1;
+  return pair * kAttnWaves * (k.pe + k.po) + ((b & 1) ? (long long)kAttnWaves * k.pe + wv * k.po : wv * k.pe);
+}
+__host__ __device__ inline long long static_of_unit(const Cut& k, long long u) {
+  const long long span = (long long)kAttnWaves * (k.pe + k.po);
+  const long long pair = u / span, off = u % span;
+  if (off < (long long)kAttnWaves * k.pe) return pair * 2 * kAttnWaves + off / k.pe;
+  return pair * 2 * kAttnWaves + kAttnWaves + (off - (long long)kAttnWaves * k.pe) / k.po;
+}
+// [range_start, range_end) of range number x; static ranges x >= pool_base are empty
+__host__ __device__ inline long long range_start(const Cut& k, long long x) {
+  return x >= k.pool_base ? k.u_main + (x - k.pool_base) * k.pool_c : static_start(k, x);
+}
+__host__ __device__ inline long long range_end(const Cut& k, long long x) {
+  if (x >= k.pool_base) return range_start(k, x) + k.pool_c;
+  const long long e = static_start(k, x) + (((x / kAttnWaves) & 1) ? k.po : k.pe);
+  return e < k.u_main ? e : k.u_main;
+}
+__host__ __device__ inline long long range_of_unit(const Cut& k, long long u) {
+  return u >= k.u_main ? k.pool_base + (u - k.u_main) / k.pool_c : static_of_unit(k, u);
+}
 
 // ---- layout: element offsets inside one K or V tile ------------------------
 // NATURAL: [token][d].   MFMA16: see sart.h.
@@ -119,7 +178,7 @@ struct AppendArgs {
   const void* v;
   int call_seq;
 };
-void launch_append(const Ctx& c, const AppendArgs& a, hipStream_t s);
+void launch_append(const Ctx& c, const PlanCfg& pc, const AppendArgs& a, hipStream_t s);
 
 struct PruneArgs {
   int mode, k;
@@ -130,16 +189,17 @@ struct PruneArgs {
   int n_scores;
   int call_seq;
 };
-void launch_prune(const Ctx& c, const PruneArgs& a, hipStream_t s);
-void launch_finish(const Ctx& c, int n, const int* handles_dev, int call_seq, hipStream_t s);
+void launch_prune(const Ctx& c, const PlanCfg& pc, const PruneArgs& a, hipStream_t s);
+void launch_finish(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, int call_seq, hipStream_t s);
+void launch_plan(const Ctx& c, const PlanCfg& pc, hipStream_t s);
 
 struct DecodeArgs {
   const void* q;
   float* out;
   int n_rows;
   float scale_log2;     // scale * log2(e)
-  int n_wg;             // persistent attention workgroups
-  int chunk_pages;      // <= 0: choose on the device
+  int n_wg;             // persistent attention workgroups (the plan's)
+  int inline_prefix;    // the plan's prompt mode
   float* partials;      // scratch
   long long partial_cap; // partial slots available
   int call_seq;

@@ -118,14 +118,15 @@ def test_cfg1_tiny_decode_prune_decode():
     print(f"cfg1 max abs err {e1:.3g} / {e2:.3g}")
 
 
-@pytest.mark.parametrize("natural", [False, True], ids=["mfma16", "natural"])
+@pytest.mark.parametrize("mode", ["mfma16-lds", "mfma16-inline", "natural"])
 @pytest.mark.parametrize("shape", [(28, 4, 128), (40, 8, 128), (8, 2, 64), (16, 1, 128)],
                          ids=["g7", "g5", "g4d64", "g16"])
-def test_bf16_small_all_rows(shape, natural):
+def test_bf16_small_all_rows(shape, mode):
     """7B-like / 32B-like head geometry at a size the oracle finishes in
     seconds: several pages per branch, ragged tails, a prompt that is not a
     page multiple, one branch with a single token."""
     Hq, Hkv, d = shape
+    natural = mode == "natural"
     cfg = wl.scaled(wl.CONFIGS[2], n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, n_requests=3, nb=5, prompt_len=100,
                     length_params=(200, 0.8), length_cap=1500)
     L = wl.lengths(cfg)
@@ -133,10 +134,15 @@ def test_bf16_small_all_rows(shape, natural):
     o, g = _pair(cfg, wl.pages_needed(cfg, L) + 4, int(-(-L.max() // 16)) + 1,
                  free_order=wl.free_order(cfg, wl.pages_needed(cfg, L) + 4), force_natural_layout=natural)
     assert g.c.layout == (0 if natural else 1)
+    g.c.set_decode_launch(prompt_mode=1 if mode == "mfma16-inline" else 0)
     populate(cfg, [o, g], L)
     assert_state_equal(o.state(), g.state())
     err = compare_attention(cfg, o, g, wl.query(cfg, 0))
-    print(f"shape {shape} natural={natural}: max abs err {err:.3g}")
+    print(f"shape {shape} {mode}: max abs err {err:.3g}")
+    # other launch shapes cut the unit line elsewhere; the result must not depend on it
+    for n_wg, chunk, skew, pool in ((3, 4, 45, 0), (64, 8, 300, 500), (1000, 0, -200, 120), (256, 0, 0, 333)):
+        g.c.set_decode_launch(n_wg, chunk, 1 if mode == "mfma16-inline" else 0, skew, pool)
+        compare_attention(cfg, o, g, wl.query(cfg, 1))
 
 
 def test_edge_cases_empty_and_short_contexts():
@@ -182,7 +188,9 @@ def test_prune_keeps_survivor_outputs_and_prefix_sharing_on_gpu():
     assert_state_equal(o.state(), st)
     surv = st["active_handles"][:int(st["n_active"][0])]
     after = g.c.decode_attention(q[surv]).cpu().numpy()
-    np.testing.assert_allclose(after, before[surv], rtol=0, atol=2e-6)  # same data, same order; split points may move
+    # same data, same order; only the split points move, and with them the running max that the
+    # bf16-rounded softmax weights are taken against
+    np.testing.assert_allclose(after, before[surv], rtol=0, atol=2e-3)
     compare_attention(cfg, o, g, q)
     # duplicated-prefix cache
     cfg0 = wl.scaled(cfg, prompt_len=0)
