@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM traffic of the dominant kernel per launch measured offline with
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 1554848608}  # profiles/k_attn_mfma_cfg2_hbm_traffic.md
 
 
 def _request_arrays(wl, cfg, r, L):
