@@ -84,7 +84,8 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
         cap = dm.max_pp;
         creates = !tb.req_used[id];
       } else {
-        if (tb.br_state[id] != SART_BRANCH_ACTIVE) err = SART_E_STATE;
+        if (!a.ids) len = tb.seq_len[i];                 // the active list itself: row i, known active
+        else if (tb.br_state[id] != SART_BRANCH_ACTIVE) err = SART_E_STATE;
         else len = tb.seq_len[tb.active_idx_of[id]];
         cap = dm.max_bp;
       }

@@ -40,6 +40,34 @@ __device__ inline int block_excl_scan(int v, int* lds, int& total) {
   return incl - v + lds[wave];
 }
 
+// Three exclusive scans at once (same barriers as one).  lds holds 3*17 ints.
+__device__ inline void block_excl_scan3(int v0, int v1, int v2, int* lds, int* ex, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nw = (blockDim.x + 63) >> 6;
+  const int v[3] = {v0, v1, v2};
+  int incl[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) incl[k] = wave_incl_scan(v[k]);
+  __syncthreads();
+  if (lane == 63) {
+#pragma unroll
+    for (int k = 0; k < 3; ++k) lds[17 * k + wave] = incl[k];
+  }
+  __syncthreads();
+  if (wave < 3) {
+    const int t = lane < nw ? lds[17 * wave + lane] : 0;
+    const int ti = wave_incl_scan(t);
+    if (lane < nw) lds[17 * wave + lane] = ti - t;
+    if (lane == nw - 1) lds[17 * wave + 16] = ti;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    total[k] = lds[17 * k + 16];
+    ex[k] = incl[k] - v[k] + lds[17 * k + wave];
+  }
+}
+
 // First error of a call wins and stays until the host reads it.
 __device__ inline void record_error(int* scal, int code, int call_seq) {
   if (scal[S_ERR] == 0) {
@@ -64,12 +92,16 @@ __device__ inline void record_error(int* scal, int code, int call_seq) {
 //                 group, request, 0}.
 // The prompt chunk is sized so that the items about fill the grid once.
 // ---------------------------------------------------------------------------
+constexpr int kPlanLdsRows = 4096;   // active rows whose page_cum is searched from LDS
+
 __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int* lds) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
   const int tid = threadIdx.x;
   __shared__ int s_npc;
+  __shared__ int s_scan[3 * 17];
+  __shared__ int s_cum[kPlanLdsRows + 1];
   __syncthreads();                       // the caller's table updates are visible
   const int nA = scal[S_NACTIVE];
   if (tid == 0) s_npc = 0;
@@ -87,17 +119,21 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       else if (first && pp > 0) w = pp * ceil_div(tb.refcnt[r], kAttnWaves) * dm.Hkv;
       if (first) tb.req_first[r] = i;
     }
-    int tot, totw, totl;
-    const int ex = block_excl_scan(np, lds, tot);
-    block_excl_scan(w, lds, totw);
-    const int exl = block_excl_scan(w > 0, lds, totl);
-    if (i < nA) tb.page_cum[i] = carry + ex;
-    if (w > 0) tb.live_req[l_carry + exl] = r;
-    carry += tot;
-    w_carry += totw;
-    l_carry += totl;
+    int ex3[3], tot3[3];
+    block_excl_scan3(np, w, w > 0, s_scan, ex3, tot3);
+    if (i < nA) {
+      tb.page_cum[i] = carry + ex3[0];
+      if (i <= kPlanLdsRows) s_cum[i] = carry + ex3[0];
+    }
+    if (w > 0) tb.live_req[l_carry + ex3[2]] = r;
+    carry += tot3[0];
+    w_carry += tot3[1];
+    l_carry += tot3[2];
   }
-  if (tid == 0) tb.page_cum[nA] = carry;
+  if (tid == 0) {
+    tb.page_cum[nA] = carry;
+    if (nA <= kPlanLdsRows) s_cum[nA] = carry;
+  }
   const long long units = (long long)carry * dm.Hkv;
   const int n_waves = pc.n_wg * kAttnWaves;
   // the pool: about pool_permille of the line, in chunks sized for ~8 chunks per wave
@@ -167,10 +203,11 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     const long long u = range_start(cut, w);
     int row = 0;
     if (u < units) {
+      const int* cum = nA <= kPlanLdsRows ? s_cum : tb.page_cum;   // uniform choice
       int lo = 0, hi = nA - 1;
       while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
-        if ((long long)tb.page_cum[mid] * dm.Hkv <= u) lo = mid; else hi = mid - 1;
+        if ((long long)cum[mid] * dm.Hkv <= u) lo = mid; else hi = mid - 1;
       }
       row = lo;
     }
