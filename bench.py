@@ -102,7 +102,7 @@ def main():
     ap.add_argument("--chunk-pages", type=int, default=0, help="prompt chunk in pages (0 = chosen on device)")
     ap.add_argument("--prompt-mode", type=int, default=-1, help="0 = prompt staged in LDS and shared, 1 = read inline, -1 = library default")
     ap.add_argument("--skew", type=int, default=None, help="per-mille of work moved from odd to even workgroups (default: library's)")
-    ap.add_argument("--pool", type=int, default=None, help="per-mille of the work handed out dynamically (default: library's)")
+    ap.add_argument("--prompt-workgroups", type=int, default=-1, help="workgroups serving only the prompts (-1 = half the grid)")
     ap.add_argument("--prompt-len", type=int, default=-1, help="override the workload's prompt length (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
@@ -150,9 +150,9 @@ def main():
                            branches_per_request=cfg.nb, finish_quota=cfg.quota, max_pages_per_branch=max_bp,
                            max_prefix_pages=max(1, cfg.prompt_len // cfg.page_tokens), dtype=cfg.dtype,
                            free_order=fo)
-    if args.workgroups or args.chunk_pages or args.prompt_mode >= 0 or args.skew is not None or args.pool is not None:
-        cache.set_decode_launch(args.workgroups, args.chunk_pages, args.prompt_mode,
-                                50 if args.skew is None else args.skew, 0 if args.pool is None else args.pool)
+    if args.workgroups or args.chunk_pages or args.prompt_mode >= 0 or args.skew is not None or args.prompt_workgroups >= 0:
+        cache.set_decode_launch(args.workgroups, args.prompt_workgroups, args.chunk_pages, args.prompt_mode,
+                                50 if args.skew is None else args.skew)
 
     # ---- CPU baseline cache (oracle) on a bounded sample of the same workload ------------
     do_cpu = not args.no_cpu_baseline

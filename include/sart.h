@@ -224,29 +224,30 @@ sart_status sart_set_profiling(sart_cache* cache, int32_t on);
 sart_status sart_last_decode_ms(sart_cache* cache, float* ms_attn, float* ms_total);
 
 /* Tuning knobs of the decode launch (defaults are chosen for MI355X):
- *   n_workgroups        persistent attention grid (<= 0: one workgroup per CU);
- *   prefix_chunk_pages  prompt chunk of the LDS-staged mode (<= 0: sized on the
- *                       device from the active set);
- *   prompt_mode         how the shared prompt is read on SART_LAYOUT_MFMA16
- *                       caches: 1 = every branch reads the prompt pages itself,
- *                       ahead of its own pages, and L2 / Infinity Cache serve
- *                       the re-reads (default); 0 = each prompt chunk is staged
- *                       once in LDS per workgroup and reused by the request's
- *                       branches, one wave each; -1 = keep the current mode.
- *                       Natural-layout caches always use mode 1;
- *   skew_permille       work moved from odd to even workgroups, in 1/1000 of
- *                       the mean per-wave range (workgroups go round-robin to
- *                       the 8 XCDs, and the odd XCDs stream about 10% slower);
- *                       default 50, 0 = equal;
- *   pool_permille       share of the step's (page, kv head) units, 0..500 in
- *                       1/1000, that is not assigned to a wave up front but
- *                       handed out in small chunks from a shared counter to
- *                       the waves that finish first.  Default 0: on the measured
- *                       workloads each chunk's start-up latency costs more than
- *                       the balance gains. */
+ *   n_workgroups         persistent attention grid of 4-wave workgroups (<= 0:
+ *                        one per CU);
+ *   n_prompt_workgroups  how many of them, the last ones of the grid, serve only
+ *                        the shared prompts while the others stream the branches'
+ *                        own pages (<= 0, the default: every workgroup does both,
+ *                        own pages first, then its share of the prompts);
+ *   prefix_chunk_pages   prompt chunk of the LDS-staged mode (<= 0: sized on the
+ *                        device from the active set);
+ *   prompt_mode          how the shared prompt is read on SART_LAYOUT_MFMA16
+ *                        caches: 1 = every branch reads the prompt pages itself;
+ *                        the prompt reads of all branches lie on a line of their
+ *                        own, ordered (request, kv head, branch, page) so that the
+ *                        re-reads of a chunk are neighbours and hit in L2
+ *                        (default); 0 = each prompt chunk is staged once in LDS
+ *                        per workgroup and reused by the request's branches, one
+ *                        wave each; -1 = keep the current mode.  Natural-layout
+ *                        caches always use mode 1;
+ *   skew_permille        work moved from odd to even streaming workgroups, in
+ *                        1/1000 of the mean per-wave range (workgroups go round-
+ *                        robin to the 8 XCDs, and the odd XCDs stream about 10 %
+ *                        slower); default 50, 0 = equal. */
 sart_status sart_set_decode_launch(sart_cache* cache, int32_t n_workgroups,
-                                   int32_t prefix_chunk_pages, int32_t prompt_mode,
-                                   int32_t skew_permille, int32_t pool_permille);
+                                   int32_t n_prompt_workgroups, int32_t prefix_chunk_pages,
+                                   int32_t prompt_mode, int32_t skew_permille);
 
 /* Text of the last host-side error of this thread. */
 const char* sart_last_error(void);

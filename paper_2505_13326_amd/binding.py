@@ -256,7 +256,7 @@ class SartCache:
         self._check(self.lib.sart_last_decode_ms(self.h, C.byref(a), C.byref(t)))
         return a.value, t.value
 
-    def set_decode_launch(self, n_workgroups=0, prefix_chunk_pages=0, prompt_mode=-1, skew_permille=50,
-                          pool_permille=0):
-        self._check(self.lib.sart_set_decode_launch(self.h, int(n_workgroups), int(prefix_chunk_pages),
-                                                    int(prompt_mode), int(skew_permille), int(pool_permille)))
+    def set_decode_launch(self, n_workgroups=0, n_prompt_workgroups=-1, prefix_chunk_pages=0, prompt_mode=-1,
+                          skew_permille=50):
+        self._check(self.lib.sart_set_decode_launch(self.h, int(n_workgroups), int(n_prompt_workgroups),
+                                                    int(prefix_chunk_pages), int(prompt_mode), int(skew_permille)))

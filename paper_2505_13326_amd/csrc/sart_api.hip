@@ -35,9 +35,6 @@ sart_status fail(sart_status st, const char* fmt, ...) {
 constexpr int kStageSlots = 8;
 // share of the mean range moved from odd-XCD workgroups to even-XCD ones (measured on MI355X)
 constexpr int kDefaultSkewPermille = 50;
-// share of the unit line handed out dynamically at the end of the attention kernel
-constexpr int kDefaultPoolPermille = 0;
-constexpr int kMaxPoolPermille = 500;
 
 struct StageSlot {
   int* host = nullptr;  // pinned
@@ -202,18 +199,18 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   HIP_TRY(hipGetDeviceProperties(&prop, c->device));
   const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   c->max_wg = cus * 16;
-  c->plan.n_wg = cus;                // one 4-wave workgroup per CU
+  c->plan.n_wg = cus;                // one 4-wave workgroup per CU, one wave per SIMD
+  c->plan.n_wg_prompt = 0;           // every wave serves the own line, then the prompt line
   c->plan.chunk_pages = 0;
   c->plan.inline_prefix = 1;         // measured faster than the LDS-staged prompt phase on every config
   c->plan.skew_permille = kDefaultSkewPermille;
-  c->plan.pool_permille = kDefaultPoolPermille;
-  const size_t max_chunks = (size_t)dm.num_pages * dm.Hkv * kMaxPoolPermille / 1000 / 4 + 1;
-  ALLOC(tb.wave_row, (size_t)c->max_wg * kAttnWaves + max_chunks);
+  ALLOC(tb.wave_row, (size_t)2 * c->max_wg * kAttnWaves);
+  ALLOC(tb.req_pstart, R);
   // partial slots: one per private wave, one per (row, kv head) crossing, and
   // the prompt chunks of every (row, kv head) at the smallest chunk size
   const long long S = (long long)H * dm.Hkv;
   const long long npc_max = (dm.max_pp + kStagePages - 1) / kStagePages;
-  c->partial_cap = (long long)c->max_wg * kAttnWaves + (long long)max_chunks + S * (1 + npc_max);
+  c->partial_cap = (long long)c->max_wg * kAttnWaves + S * (2 + npc_max);
   const long long pf = (long long)dm.G * dm.d + ((2 * dm.G + 3) & ~3);
   ALLOC(c->partials, (size_t)(c->partial_cap * pf));
 #undef ALLOC
@@ -479,20 +476,22 @@ sart_status sart_last_decode_ms(sart_cache* c, float* ms_attn, float* ms_total) 
   return SART_OK;
 }
 
-sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t prefix_chunk_pages,
-                                   int32_t prompt_mode, int32_t skew_permille, int32_t pool_permille) {
+sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t n_prompt_workgroups,
+                                   int32_t prefix_chunk_pages, int32_t prompt_mode, int32_t skew_permille) {
   if (!c) return fail(SART_E_INVALID, "null cache");
   if (prompt_mode < -1 || prompt_mode > 1) return fail(SART_E_INVALID, "prompt_mode must be -1, 0 or 1");
   if (skew_permille < -500 || skew_permille > 500) return fail(SART_E_INVALID, "skew_permille out of range");
-  if (prompt_mode >= 0) c->plan.inline_prefix = c->ctx.dm.layout == SART_LAYOUT_MFMA16 ? prompt_mode : 1;
-  if (pool_permille < 0 || pool_permille > kMaxPoolPermille) return fail(SART_E_INVALID, "pool_permille out of range");
-  c->plan.skew_permille = skew_permille;
-  c->plan.pool_permille = pool_permille;
   if (n_workgroups > c->max_wg) return fail(SART_E_INVALID, "at most %d workgroups", c->max_wg);
   hipDeviceProp_t prop;
   HIP_TRY(hipGetDeviceProperties(&prop, c->device));
   const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  c->plan.n_wg = n_workgroups > 0 ? n_workgroups : cus;
+  const int n_wg = n_workgroups > 0 ? n_workgroups : cus;
+  const int n_pw = n_prompt_workgroups >= 0 ? n_prompt_workgroups : 0;
+  if (n_pw >= n_wg && n_pw > 0) return fail(SART_E_INVALID, "n_prompt_workgroups must leave a streaming workgroup");
+  if (prompt_mode >= 0) c->plan.inline_prefix = c->ctx.dm.layout == SART_LAYOUT_MFMA16 ? prompt_mode : 1;
+  c->plan.skew_permille = skew_permille;
+  c->plan.n_wg = n_wg;
+  c->plan.n_wg_prompt = n_pw;
   c->plan.chunk_pages = prefix_chunk_pages > 0 ? prefix_chunk_pages : 0;
   launch_plan(c->ctx, c->plan, c->last_stream);   // the plan follows the launch shape
   HIP_TRY(hipGetLastError());

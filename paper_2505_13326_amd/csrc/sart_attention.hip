@@ -174,7 +174,7 @@ __device__ inline void store_partial(const WaveState<D>& st, float* partials, lo
 // the compiler may then read page ids with scalar loads, which do not queue
 // behind the in-flight vector loads of K/V tiles.
 // ---------------------------------------------------------------------------
-template <int D, bool INL>
+template <int D>
 __global__ void __launch_bounds__(kAttnThreads)
 k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restrict__ bt1,
             const int* __restrict__ item_desc, const int* __restrict__ prefix_table) {
@@ -182,7 +182,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
   const Tables& tb = c.tb;
   int* scal = tb.scal;
   constexpr int KQ = D / 32;                       // 16-byte chunks per lane per tile
-  constexpr int kRing = 4;                         // pages in flight per wave on the private path
+  constexpr int kRing = 4;                         // pages in flight per wave while streaming
   constexpr int kTileBytes = 16 * D * 2;           // one K (or V) tile
   constexpr int kPageBytes = 2 * kTileBytes;       // K tile + V tile of one kv head
   constexpr int kRound = kAttnThreads * 16;                // bytes one load round of the workgroup covers
@@ -199,10 +199,16 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
   const int chunk = scal[S_D_CHUNK], npc = scal[S_D_NPC];
   const int n_items = scal[S_D_NITEMS];
   const long long S = (long long)nA * dm.Hkv;
-  const long long prefix_base = (long long)scal[S_D_POOLBASE] + scal[S_D_NCHUNK] + S;
+  const int n_waves = gridDim.x * kAttnWaves;
+  const long long prompt_slot_base = (long long)scal[S_D_NOWN] + S;                        // inline prompt pieces
+  const long long prefix_base = (long long)scal[S_D_NOWN] + scal[S_D_NPROMPT] + 2 * S;     // LDS prompt chunks
   const uint16_t* q = (const uint16_t*)a.q;
   const unsigned char* pool = (const unsigned char*)c.pool;
   const int* __restrict__ bt = scal[S_BTSEL] ? bt1 : bt0;
+  // workgroup role (see Cut): streaming workgroups come first in the grid
+  const int n_own_wg = scal[S_D_NOWN] / kAttnWaves;
+  const bool dedicated = n_own_wg < (int)gridDim.x;
+  const bool prompt_wg = (int)blockIdx.x >= n_own_wg;
   const bool prompt_first = (blockIdx.x & 1) == 0;
   SART_STAMP(0);
   WaveState<D> st;
@@ -210,9 +216,12 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
 
   for (int phase = 0; phase < 2; ++phase) {
     if ((phase == 0) == prompt_first) {
-      // ---- shared prompt items ---------------------------------------------
+      // ---- shared prompt items (LDS prompt mode) ----------------------------
       SART_STAMP(1);
-      for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+      if (dedicated && !prompt_wg) continue;
+      const int it0 = dedicated ? (int)blockIdx.x - n_own_wg : (int)blockIdx.x;
+      const int it_step = dedicated ? (int)gridDim.x - n_own_wg : (int)gridDim.x;
+      for (int it = it0; it < n_items; it += it_step) {
         const int4 d0 = *(const int4*)(item_desc + 8LL * it);
         const int4 d1 = *(const int4*)(item_desc + 8LL * it + 4);
         const int first = d0.x, cnt = d0.y, plen = d0.z, h = d0.w, ck = d1.x, bg = d1.y, r = d1.z;
@@ -283,75 +292,81 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
       continue;
     }
 
-    // ---- private pages: this wave's static range of (page, kv head) units, then
-    //      chunks of the shared pool until it is empty ---------------------------
+    // ---- streaming phase: this wave's range of the own line and / or of the
+    //      prompt line (inline prompt mode); one partial per piece ---------------
     const Cut cut = load_cut(scal);
-    long long w = (long long)blockIdx.x * kAttnWaves + wv;     // range number
+    const long long wave_id = (long long)blockIdx.x * kAttnWaves + wv;
     SART_STAMP(3);
-    int n_pieces = 0;
-    bool own = true;                       // first pass: this wave's static range
-    for (;;) {
-      long long u = 0, u1 = 0;
-      if (!own || w < cut.pool_base) { u = range_start(cut, w); u1 = range_end(cut, w); }
-      // the next pool chunk is claimed before this range is processed, so the
-      // atomic's round trip hides behind the page loads
-      int next_chunk = 0;
-      if (lane == 0) next_chunk = atomicAdd(&scal[S_POOL_NEXT], 1);
-      next_chunk = __builtin_amdgcn_readfirstlane(next_chunk);
-      int row = u < u1 ? tb.wave_row[w] : 0;
-    while (u < u1) {
-      int pages = tb.page_cum[row + 1] - tb.page_cum[row];
-      long long rem = u - (long long)tb.page_cum[row] * dm.Hkv;
-      while (pages == 0 || rem >= (long long)pages * dm.Hkv) {  // skip rows without private pages
-        ++row;
-        pages = tb.page_cum[row + 1] - tb.page_cum[row];
-        rem = u - (long long)tb.page_cum[row] * dm.Hkv;
+    const long long page_bytes = dm.page_elems * 2;
+    for (int line = 0; line < 2; ++line) {
+      long long x, u, u1;          // range number and its units on this line
+      int cursor;                  // own line: active row; prompt line: live request index
+      if (line == 0) {
+        if (wave_id >= cut.n_own) continue;
+        x = wave_id; u = own_start(cut, x); u1 = own_end(cut, x);
+        if (u >= u1) continue;
+        cursor = tb.wave_row[x];
+      } else {
+        if (wave_id < n_waves - cut.n_prompt) continue;
+        x = cut.n_own + prompt_range_of_wave(wave_id - (n_waves - cut.n_prompt), cut.n_prompt);
+        u = prompt_start(cut, x); u1 = prompt_end(cut, x);
+        if (u >= u1) continue;
+        cursor = tb.wave_row[n_waves + (x - cut.n_own)];
       }
-      const int h = (int)(rem / pages);
-      const int p0 = (int)(rem % pages);
-      const int n = (int)min((long long)(pages - p0), u1 - u);
-      const int len = tb.seq_len[row];
-      load_q<D>(qreg, q, dm, row, h);
-      st.reset();
-      const long long head_off = (long long)h * kPageBytes + lane * 16;
-      const long long page_bytes = dm.page_elems * 2;
-
-      auto load_page = [&](uint4* kq, uint4* vq, int pid) {
-        const unsigned char* base = pool + (long long)pid * page_bytes + head_off;
-#pragma unroll
-        for (int i = 0; i < KQ; ++i) {
-          kq[i] = *(const uint4*)(base + i * 1024);
-          vq[i] = *(const uint4*)(base + kTileBytes + i * 1024);
-        }
-      };
-      // A piece is one run of pages of one table, or two when the prompt is
-      // read inline and the piece crosses from the prompt's pages into the
-      // row's own pages.  The online-softmax state carries over.
-      int pp = 0, plen = 0;
-      const int* __restrict__ ptab = prefix_table;
-      if (INL) {
-        const int req = tb.active[row] / dm.Nb;
-        plen = tb.prefix_len[req];
-        pp = ceil_div(plen, 16);
-        ptab = prefix_table + (long long)req * dm.max_pp;
-      }
-      const int* __restrict__ own = bt + (long long)row * dm.max_bp;
-      for (int run = 0; run < (INL ? 2 : 1); ++run) {
-        // pages [r0, r0 + rn) of `table`, the last of them holding n_last valid tokens
-        const int* __restrict__ table = own;
-        int r0 = p0, rn = n, n_last = min(16, len - (p0 + n - 1) * 16);
-        if (INL) {
-          if (run == 0) {
-            table = ptab;
-            rn = min(p0 + n, pp) - p0;
-            n_last = min(16, plen - (r0 + rn - 1) * 16);
-          } else {
-            r0 = max(p0, pp) - pp;
-            rn = p0 + n - pp - r0;
-            n_last = min(16, len - (r0 + rn - 1) * 16);
+      while (u < u1) {
+        // ---- next piece: pages [r0, r0 + rn) of `table`, for query rows (row, h)
+        int row, h, r0, rn, n_last;
+        long long slot;
+        const int* __restrict__ table;
+        if (line == 0) {
+          int pages = tb.page_cum[cursor + 1] - tb.page_cum[cursor];
+          long long rem = u - (long long)tb.page_cum[cursor] * dm.Hkv;
+          while (pages == 0 || rem >= (long long)pages * dm.Hkv) {   // skip rows without private pages
+            ++cursor;
+            pages = tb.page_cum[cursor + 1] - tb.page_cum[cursor];
+            rem = u - (long long)tb.page_cum[cursor] * dm.Hkv;
           }
-          if (rn <= 0) continue;
+          row = cursor;
+          h = (int)(rem / pages);
+          r0 = (int)(rem % pages);
+          rn = (int)min((long long)(pages - r0), u1 - u);
+          n_last = min(16, tb.seq_len[row] - (r0 + rn - 1) * 16);
+          table = bt + (long long)row * dm.max_bp;
+          slot = x + (long long)row * dm.Hkv + h;
+        } else {
+          int r, cnt, pp, plen;
+          long long rem;
+          for (;;) {   // the live request whose block holds unit u
+            r = tb.live_req[cursor];
+            cnt = tb.refcnt[r];
+            plen = tb.prefix_len[r];
+            pp = ceil_div(plen, 16);
+            rem = u - (long long)tb.live_item_start[cursor] * dm.Hkv;
+            if (rem < (long long)dm.Hkv * cnt * pp) break;
+            ++cursor;
+          }
+          const int first = tb.req_first[r];
+          const long long block = (long long)cnt * pp;
+          h = (int)(rem / block);
+          const int j = (int)((rem % block) / pp);
+          r0 = (int)(rem % pp);
+          rn = (int)min((long long)(pp - r0), u1 - u);
+          n_last = min(16, plen - (r0 + rn - 1) * 16);
+          row = first + j;
+          table = prefix_table + (long long)r * dm.max_pp;
+          slot = prompt_slot_base + (x - cut.n_own) + (long long)first * dm.Hkv + (long long)h * cnt + j;
         }
+        load_q<D>(qreg, q, dm, row, h);
+        st.reset();
+        const long long head_off = (long long)h * kPageBytes + lane * 16;
+        auto load_page = [&](uint4* kq, uint4* vq, int pid) {
+          const unsigned char* base = pool + (long long)pid * page_bytes + head_off;
+#pragma unroll
+          for (int i = 0; i < KQ; ++i) {
+            kq[i] = *(const uint4*)(base + i * 1024);
+            vq[i] = *(const uint4*)(base + kTileBytes + i * 1024);
+          }
+        };
         // kRing register buffers in a software pipeline: kRing pages (8 KiB
         // each) are in flight per wave.  The steady-state loop and its
         // preheader have no conditional loads, so the compiler can wait for
@@ -389,17 +404,11 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
             if (j < cnt) process_page<D, false>(st, kb[j], vb[j], qreg, i + j == rn - 1 ? n_last : 16, a.scale_log2);
           i += cnt;
         }
+        store_partial<D>(st, a.partials, slot, dm);
+        u += rn;
       }
-      store_partial<D>(st, a.partials, w + (long long)row * dm.Hkv + h, dm);
-      u += n;
-      if (n_pieces < 2) SART_STAMP(4 + n_pieces);
-      ++n_pieces;
     }
-      if (own) SART_STAMP(6);
-      if (next_chunk >= cut.n_chunks) break;
-      w = cut.pool_base + next_chunk;
-      own = false;
-    }
+    SART_STAMP(6);
   }
   SART_STAMP(7);
 }
@@ -430,88 +439,119 @@ k_attn_generic(Ctx c, DecodeArgs a) {
   const T* q = (const T*)a.q;
   const int D = dm.d, pt = dm.pt;
   const Cut cut = load_cut(scal);
-  long long w = (long long)blockIdx.x * kAttnWaves + wv;
-  bool own = true;
-  for (;;) {
-  long long u = 0, u1 = 0;
-  if (!own || w < cut.pool_base) { u = range_start(cut, w); u1 = range_end(cut, w); }
-  int next_chunk = 0;
-  if (lane == 0) next_chunk = atomicAdd(&scal[S_POOL_NEXT], 1);
-  next_chunk = __shfl(next_chunk, 0, 64);
-  int row = u < u1 ? tb.wave_row[w] : 0;
-  while (u < u1) {
-    int pages = tb.page_cum[row + 1] - tb.page_cum[row];
-    long long rem = u - (long long)tb.page_cum[row] * dm.Hkv;
-    while (pages == 0 || rem >= (long long)pages * dm.Hkv) {
-      ++row;
-      pages = tb.page_cum[row + 1] - tb.page_cum[row];
-      rem = u - (long long)tb.page_cum[row] * dm.Hkv;
+  const int n_waves = gridDim.x * kAttnWaves;
+  const long long S = (long long)scal[S_D_NA] * dm.Hkv;
+  const long long prompt_slot_base = (long long)cut.n_own + S;
+  const long long wave_id = (long long)blockIdx.x * kAttnWaves + wv;
+  for (int line = 0; line < 2; ++line) {
+    long long x, u, u1;
+    int cursor;
+    if (line == 0) {
+      if (wave_id >= cut.n_own) continue;
+      x = wave_id; u = own_start(cut, x); u1 = own_end(cut, x);
+      if (u >= u1) continue;
+      cursor = tb.wave_row[x];
+    } else {
+      if (wave_id < n_waves - cut.n_prompt) continue;
+      x = cut.n_own + (wave_id - (n_waves - cut.n_prompt));
+      u = prompt_start(cut, x); u1 = prompt_end(cut, x);
+      if (u >= u1) continue;
+      cursor = tb.wave_row[n_waves + (x - cut.n_own)];
     }
-    const int h = (int)(rem / pages);
-    const int p0 = (int)(rem % pages);
-    const int n = (int)min((long long)(pages - p0), u1 - u);
-    const int req = tb.active[row] / dm.Nb;
-    const int plen = tb.prefix_len[req], len = tb.seq_len[row];
-    const int pp = ceil_div(plen, pt);
-    const int* ptab = tb.prefix_table + (long long)req * dm.max_pp;
-    const int* table = bt + (long long)row * dm.max_bp;
-    float* pbase = a.partials + (w + (long long)row * dm.Hkv + h) * partial_floats(dm.G, D);
-    for (int r = 0; r < dm.G; ++r) {
-      const T* qrow = q + ((long long)row * dm.Hq + h * dm.G + r) * D;
-      float m = -__builtin_inff(), l = 0.f;
-      float o[4] = {0.f, 0.f, 0.f, 0.f};   // d = lane + 64*c
-      for (int p = p0; p < p0 + n; ++p) {
-        const bool in_prompt = p < pp;
-        const int page = in_prompt ? ptab[p] : table[p - pp];
-        const int nvalid = in_prompt ? min(pt, plen - p * pt) : min(pt, len - (p - pp) * pt);
-        const long long kb = tile_base(dm, page, h), vb = kb + dm.tile_elems;
-        for (int t0 = 0; t0 < nvalid; t0 += 64) {
-          const int t = t0 + lane;
-          float s = -__builtin_inff();
-          if (t < nvalid) {
-            float dot = 0.f;
-            for (int d = 0; d < D; ++d) dot = fmaf(to_f32<T>(qrow[d]), to_f32<T>(pool[kb + (long long)t * D + d]), dot);
-            s = dot * a.scale_log2;
-          }
-          float mx = s;
+    while (u < u1) {
+      int row, h, r0, rn, tokens;
+      long long slot;
+      const int* table;
+      if (line == 0) {
+        int pages = tb.page_cum[cursor + 1] - tb.page_cum[cursor];
+        long long rem = u - (long long)tb.page_cum[cursor] * dm.Hkv;
+        while (pages == 0 || rem >= (long long)pages * dm.Hkv) {
+          ++cursor;
+          pages = tb.page_cum[cursor + 1] - tb.page_cum[cursor];
+          rem = u - (long long)tb.page_cum[cursor] * dm.Hkv;
+        }
+        row = cursor;
+        h = (int)(rem / pages);
+        r0 = (int)(rem % pages);
+        rn = (int)min((long long)(pages - r0), u1 - u);
+        tokens = tb.seq_len[row];
+        table = bt + (long long)row * dm.max_bp;
+        slot = x + (long long)row * dm.Hkv + h;
+      } else {
+        int r, cnt, pp;
+        long long rem;
+        for (;;) {
+          r = tb.live_req[cursor];
+          cnt = tb.refcnt[r];
+          tokens = tb.prefix_len[r];
+          pp = ceil_div(tokens, pt);
+          rem = u - (long long)tb.live_item_start[cursor] * dm.Hkv;
+          if (rem < (long long)dm.Hkv * cnt * pp) break;
+          ++cursor;
+        }
+        const int first = tb.req_first[r];
+        const long long block = (long long)cnt * pp;
+        h = (int)(rem / block);
+        const int j = (int)((rem % block) / pp);
+        r0 = (int)(rem % pp);
+        rn = (int)min((long long)(pp - r0), u1 - u);
+        row = first + j;
+        table = tb.prefix_table + (long long)r * dm.max_pp;
+        slot = prompt_slot_base + (x - cut.n_own) + (long long)first * dm.Hkv + (long long)h * cnt + j;
+      }
+      float* pbase = a.partials + slot * partial_floats(dm.G, D);
+      for (int r = 0; r < dm.G; ++r) {
+        const T* qrow = q + ((long long)row * dm.Hq + h * dm.G + r) * D;
+        float m = -__builtin_inff(), l = 0.f;
+        float o[4] = {0.f, 0.f, 0.f, 0.f};   // d = lane + 64*c
+        for (int p = r0; p < r0 + rn; ++p) {
+          const int page = table[p];
+          const int nvalid = min(pt, tokens - p * pt);
+          const long long kb = tile_base(dm, page, h), vb = kb + dm.tile_elems;
+          for (int t0 = 0; t0 < nvalid; t0 += 64) {
+            const int t = t0 + lane;
+            float s = -__builtin_inff();
+            if (t < nvalid) {
+              float dot = 0.f;
+              for (int d = 0; d < D; ++d) dot = fmaf(to_f32<T>(qrow[d]), to_f32<T>(pool[kb + (long long)t * D + d]), dot);
+              s = dot * a.scale_log2;
+            }
+            float mx = s;
 #pragma unroll
-          for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-          const float m_new = fmaxf(m, mx);
-          const float alpha = exp2f(m - m_new);
-          const float pw = t < nvalid ? exp2f(s - m_new) : 0.f;
-          float ps = pw;
+            for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+            const float m_new = fmaxf(m, mx);
+            const float alpha = exp2f(m - m_new);
+            const float pw = t < nvalid ? exp2f(s - m_new) : 0.f;
+            float ps = pw;
 #pragma unroll
-          for (int off = 32; off >= 1; off >>= 1) ps += __shfl_xor(ps, off, 64);
-          l = l * alpha + ps;
-          m = m_new;
+            for (int off = 32; off >= 1; off >>= 1) ps += __shfl_xor(ps, off, 64);
+            l = l * alpha + ps;
+            m = m_new;
 #pragma unroll
-          for (int cc = 0; cc < 4; ++cc) o[cc] *= alpha;
-          const int nt = min(64, nvalid - t0);
-          for (int j = 0; j < nt; ++j) {
-            const float pj = __shfl(pw, j, 64);
+            for (int cc = 0; cc < 4; ++cc) o[cc] *= alpha;
+            const int nt = min(64, nvalid - t0);
+            for (int j = 0; j < nt; ++j) {
+              const float pj = __shfl(pw, j, 64);
 #pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
-              const int d = lane + 64 * cc;
-              if (d < D) o[cc] = fmaf(pj, to_f32<T>(pool[vb + (long long)(t0 + j) * D + d]), o[cc]);
+              for (int cc = 0; cc < 4; ++cc) {
+                const int d = lane + 64 * cc;
+                if (d < D) o[cc] = fmaf(pj, to_f32<T>(pool[vb + (long long)(t0 + j) * D + d]), o[cc]);
+              }
             }
           }
         }
-      }
 #pragma unroll
-      for (int cc = 0; cc < 4; ++cc) {
-        const int d = lane + 64 * cc;
-        if (d < D) pbase[(long long)r * D + d] = o[cc];
+        for (int cc = 0; cc < 4; ++cc) {
+          const int d = lane + 64 * cc;
+          if (d < D) pbase[(long long)r * D + d] = o[cc];
+        }
+        if (lane == 0) {
+          pbase[(long long)dm.G * D + r] = m;
+          pbase[(long long)dm.G * D + dm.G + r] = l;
+        }
       }
-      if (lane == 0) {
-        pbase[(long long)dm.G * D + r] = m;
-        pbase[(long long)dm.G * D + dm.G + r] = l;
-      }
+      u += rn;
     }
-    u += n;
-  }
-  if (next_chunk >= cut.n_chunks) break;
-  w = cut.pool_base + next_chunk;
-  own = false;
   }
 }
 
@@ -531,25 +571,35 @@ k_merge(Ctx c, DecodeArgs a, int inline_prefix) {
   const int nA = scal[S_D_NA];
   const int chunk = scal[S_D_CHUNK], npc = scal[S_D_NPC];
   const Cut cut = load_cut(scal);
-  if (blockIdx.x == 0 && threadIdx.x == 0) tb.scal[S_POOL_NEXT] = 0;   // the pool is full again for the next launch
   const int D = dm.d, G = dm.G, D4 = D >> 2;
   const long long pf = partial_floats(G, D);
   const long long S = (long long)nA * dm.Hkv;
-  const long long prefix_base = (long long)cut.pool_base + cut.n_chunks + S;
+  const long long prompt_slot_base = (long long)cut.n_own + S;
+  const long long prefix_base = (long long)cut.n_own + cut.n_prompt + 2 * S;
   for (long long seg = blockIdx.x; seg < S; seg += gridDim.x) {
     const int row = (int)(seg / dm.Hkv), h = (int)(seg % dm.Hkv);
-    // slot ranges: [pa, pa+pn) prompt chunks, [sa, sa+sn) private pieces
+    // slot ranges: [pa, pa+pn) prompt pieces or chunks, [sa, sa+sn) own pieces
     long long pa = 0, sa = 0;
     int pn = 0, sn = 0;
-    if (!inline_prefix) {
-      const int pp = ceil_div(tb.prefix_len[tb.active[row] / dm.Nb], dm.pt);
-      pn = pp > 0 ? ceil_div(pp, chunk) : 0;
-      pa = prefix_base + seg * npc;
+    {
+      const int r = tb.active[row] / dm.Nb;
+      const int pp = ceil_div(tb.prefix_len[r], dm.pt);
+      if (pp > 0 && inline_prefix) {
+        const int first = tb.req_first[r], cnt = tb.refcnt[r], j = row - first;
+        const long long ps = (long long)first * dm.Hkv + (long long)h * cnt + j;
+        const long long us = (long long)tb.req_pstart[r] * dm.Hkv + ((long long)h * cnt + j) * pp;
+        const long long w0 = prompt_of_unit(cut, us), w1 = prompt_of_unit(cut, us + pp - 1);
+        pa = prompt_slot_base + (w0 - cut.n_own) + ps;
+        pn = (int)(w1 - w0 + 1);
+      } else if (pp > 0) {
+        pn = ceil_div(pp, chunk);
+        pa = prefix_base + seg * npc;
+      }
     }
     const int pages = tb.page_cum[row + 1] - tb.page_cum[row];
     if (pages > 0) {
       const long long us = (long long)tb.page_cum[row] * dm.Hkv + (long long)h * pages;
-      const long long w0 = range_of_unit(cut, us), w1 = range_of_unit(cut, us + pages - 1);
+      const long long w0 = own_of_unit(cut, us), w1 = own_of_unit(cut, us + pages - 1);
       sa = w0 + seg;
       sn = (int)(w1 - w0 + 1);
     }
@@ -582,12 +632,12 @@ void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s) {
   if (a.ev[0]) (void)hipEventRecord(a.ev[0], s);
   if (a.ev[1]) (void)hipEventRecord(a.ev[1], s);
   if (mfma) {
-#define SART_LAUNCH_MFMA(DD, II)                                                                         \
-  hipLaunchKernelGGL((k_attn_mfma<DD, II>), dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], \
-                     c.tb.bt[1], c.tb.item_desc, c.tb.prefix_table)
-    if (dm.d == 128) { if (a.inline_prefix) SART_LAUNCH_MFMA(128, true); else SART_LAUNCH_MFMA(128, false); }
-    else             { if (a.inline_prefix) SART_LAUNCH_MFMA(64, true); else SART_LAUNCH_MFMA(64, false); }
-#undef SART_LAUNCH_MFMA
+    if (dm.d == 128)
+      hipLaunchKernelGGL(k_attn_mfma<128>, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], c.tb.bt[1],
+                         c.tb.item_desc, c.tb.prefix_table);
+    else
+      hipLaunchKernelGGL(k_attn_mfma<64>, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], c.tb.bt[1],
+                         c.tb.item_desc, c.tb.prefix_table);
   } else if (dm.dtype == SART_F32) {
     hipLaunchKernelGGL(k_attn_generic<float>, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a);
   } else {

@@ -80,17 +80,22 @@ __device__ inline void record_error(int* scal, int code, int call_seq) {
 // ---------------------------------------------------------------------------
 // A3: the decode plan (run by one 1024-thread workgroup; ends with a barrier).
 //
-//   page_cum[a]   exclusive scan over active rows of the pages a row puts on
-//                 the unit line: its private pages, plus its prompt's pages
-//                 when the prompt is read inline (natural-layout caches).
-//   units         page_cum[nA] * Hkv (page, kv head) units, cut into one static
-//                 range per attention wave followed by the pool chunks (Cut);
-//                 wave_row[w] = active row holding the first unit of range w.
-//   items         shared-prompt work: one per (live request, kv head, prompt
-//                 chunk, group of kAttnWaves branches), eight ints each:
-//                 {first row, live branches, prompt tokens, kv head, chunk,
-//                 group, request, 0}.
-// The prompt chunk is sized so that the items about fill the grid once.
+//   page_cum[a]   exclusive scan over active rows of their private pages; the
+//                 own line has page_cum[nA] * Hkv units.
+//   prompt line   (inline prompt mode) request r's block starts at
+//                 req_pstart[r] * Hkv and holds Hkv * branches * prompt pages
+//                 units; live_req[k] lists the live requests with a prompt in
+//                 active order, live_item_start[k] their req_pstart.
+//   cut           the first workgroups' waves cut the own line, the last
+//                 n_wg_prompt workgroups' waves the prompt line, see Cut;
+//                 wave_row[w] = active row holding the
+//                 first unit of own range w, or the index k of the live request
+//                 holding the first unit of prompt range w.
+//   items         (LDS prompt mode) shared-prompt work: one per (live request,
+//                 kv head, prompt chunk, group of kAttnWaves branches), eight
+//                 ints each: {first row, live branches, prompt tokens, kv head,
+//                 chunk, group, request, 0}; the chunk is sized so that the
+//                 items about fill the prompt workgroups once.
 // ---------------------------------------------------------------------------
 constexpr int kPlanLdsRows = 4096;   // active rows whose page_cum is searched from LDS
 
@@ -102,9 +107,12 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   __shared__ int s_npc;
   __shared__ int s_scan[3 * 17];
   __shared__ int s_cum[kPlanLdsRows + 1];
+  (void)lds;
   __syncthreads();                       // the caller's table updates are visible
   const int nA = scal[S_NACTIVE];
   if (tid == 0) s_npc = 0;
+  // w: weight of a live request with a prompt, on its first row.  Inline mode:
+  // its (branch, page) count on the prompt line; LDS mode: its item pages.
   int carry = 0, w_carry = 0, l_carry = 0;
   for (int base = 0; base < nA; base += kPlanThreads) {
     const int i = base + tid;
@@ -114,10 +122,11 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       r = b / dm.Nb;
       first = i == 0 || tb.active[i - 1] / dm.Nb != r;
       np = ceil_div(tb.seq_len[i], dm.pt);
-      const int pp = ceil_div(tb.prefix_len[r], dm.pt);
-      if (pc.inline_prefix) np += pp;
-      else if (first && pp > 0) w = pp * ceil_div(tb.refcnt[r], kAttnWaves) * dm.Hkv;
-      if (first) tb.req_first[r] = i;
+      if (first) {
+        const int pp = ceil_div(tb.prefix_len[r], dm.pt);
+        w = pc.inline_prefix ? pp * tb.refcnt[r] : pp * ceil_div(tb.refcnt[r], kAttnWaves) * dm.Hkv;
+        tb.req_first[r] = i;
+      }
     }
     int ex3[3], tot3[3];
     block_excl_scan3(np, w, w > 0, s_scan, ex3, tot3);
@@ -125,7 +134,13 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       tb.page_cum[i] = carry + ex3[0];
       if (i <= kPlanLdsRows) s_cum[i] = carry + ex3[0];
     }
-    if (w > 0) tb.live_req[l_carry + ex3[2]] = r;
+    if (w > 0) {
+      tb.live_req[l_carry + ex3[2]] = r;
+      if (pc.inline_prefix) {
+        tb.req_pstart[r] = w_carry + ex3[1];
+        tb.live_item_start[l_carry + ex3[2]] = w_carry + ex3[1];
+      }
+    }
     carry += tot3[0];
     w_carry += tot3[1];
     l_carry += tot3[2];
@@ -134,95 +149,113 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     tb.page_cum[nA] = carry;
     if (nA <= kPlanLdsRows) s_cum[nA] = carry;
   }
-  const long long units = (long long)carry * dm.Hkv;
+  const int n_live = l_carry;
   const int n_waves = pc.n_wg * kAttnWaves;
-  // the pool: about pool_permille of the line, in chunks sized for ~8 chunks per wave
   Cut cut;
-  {
-    const long long target = units * pc.pool_permille / 1000;
-    long long cc = target / (8LL * n_waves);
-    cut.pool_c = (int)(cc < 4 ? 4 : (cc > 64 ? 64 : cc));
-    cut.n_chunks = (int)(target / cut.pool_c);
-    cut.u_main = units - (long long)cut.n_chunks * cut.pool_c;
-  }
-  int per_wave = (int)((cut.u_main + n_waves - 1) / n_waves);
+  cut.u_own = (long long)carry * dm.Hkv;
+  cut.u_prompt = pc.inline_prefix ? (long long)w_carry * dm.Hkv : 0;
+  // workgroup roles: the last n_wg_prompt workgroups serve the prompt line (or the
+  // LDS-staged prompt items); with none dedicated every wave serves both lines
+  const int wg_prompt = pc.n_wg_prompt < pc.n_wg ? pc.n_wg_prompt : pc.n_wg - 1;
+  cut.n_own = (pc.n_wg - wg_prompt) * kAttnWaves;
+  cut.n_prompt = cut.u_prompt > 0 ? (wg_prompt > 0 ? wg_prompt * kAttnWaves : n_waves) : 0;
+  cut.pb = cut.n_prompt > 0 ? (int)((cut.u_prompt + cut.n_prompt - 1) / cut.n_prompt) : 1;
+  if (cut.pb < 1) cut.pb = 1;
+  int per_wave = (int)((cut.u_own + cut.n_own - 1) / (cut.n_own > 0 ? cut.n_own : 1));
   if (per_wave < 1) per_wave = 1;
-  // even / odd workgroups (see range_start): pe + po = 2 * per_wave, po >= 1;
-  // a grid with an odd workgroup count has no partner for the last one, so no skew
+  // even / odd workgroups: pe + po = 2 * per_wave, po >= 1; an odd number of
+  // own workgroups leaves the last one without a partner, so no skew then
   cut.pe = cut.po = per_wave;
-  if ((pc.n_wg & 1) == 0) {
+  if (((cut.n_own / kAttnWaves) & 1) == 0) {
     int sk = (int)(((long long)per_wave * pc.skew_permille) / 1000);
     if (sk > per_wave - 1) sk = per_wave - 1;
     if (sk < 1 - per_wave) sk = 1 - per_wave;
     cut.pe = per_wave + sk;
     cut.po = per_wave - sk;
   }
-  cut.pool_base = cut.u_main > 0 ? (int)static_of_unit(cut, cut.u_main - 1) + 1 : 0;
-  const int n_live = l_carry;
   int chunk = pc.chunk_pages;
-  if (chunk <= 0) chunk = ceil_div(w_carry, pc.n_wg);
+  if (chunk <= 0) chunk = ceil_div(pc.inline_prefix ? 0 : w_carry, wg_prompt > 0 ? wg_prompt : pc.n_wg);
   chunk = ceil_div(chunk < 1 ? 1 : chunk, kStagePages) * kStagePages;
-  __syncthreads();                       // live_req, req_first, page_cum written
-  // item offsets per live request
-  int i_carry = 0;
-  for (int base = 0; base < n_live; base += kPlanThreads) {
-    const int k = base + tid;
-    int items = 0;
-    if (k < n_live) {
-      const int r = tb.live_req[k];
-      const int nck = ceil_div(ceil_div(tb.prefix_len[r], dm.pt), chunk);
-      items = dm.Hkv * nck * ceil_div(tb.refcnt[r], kAttnWaves);
-      atomicMax(&s_npc, nck);
+  __syncthreads();                       // live_req, req_first, page_cum, req_pstart written
+  int n_items = 0;
+  if (!pc.inline_prefix) {
+    // item offsets per live request
+    int i_carry = 0;
+    for (int base = 0; base < n_live; base += kPlanThreads) {
+      const int k = base + tid;
+      int items = 0;
+      if (k < n_live) {
+        const int r = tb.live_req[k];
+        const int nck = ceil_div(ceil_div(tb.prefix_len[r], dm.pt), chunk);
+        items = dm.Hkv * nck * ceil_div(tb.refcnt[r], kAttnWaves);
+        atomicMax(&s_npc, nck);
+      }
+      int ti;
+      const int ex = block_excl_scan(items, s_scan, ti);
+      if (k < n_live) tb.live_item_start[k] = i_carry + ex;
+      i_carry += ti;
     }
-    int ti;
-    const int ex = block_excl_scan(items, lds, ti);
-    if (k < n_live) tb.live_item_start[k] = i_carry + ex;
-    i_carry += ti;
-  }
-  const int n_items = i_carry;
-  if (tid == 0) tb.live_item_start[n_live] = n_items;
-  __syncthreads();
-  // item descriptors
-  for (int it = tid; it < n_items; it += kPlanThreads) {
-    int lo = 0, hi = n_live - 1;
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if (tb.live_item_start[mid] <= it) lo = mid; else hi = mid - 1;
-    }
-    const int r = tb.live_req[lo];
-    int local = it - tb.live_item_start[lo];
-    const int cnt = tb.refcnt[r], plen = tb.prefix_len[r];
-    const int nck = ceil_div(ceil_div(plen, dm.pt), chunk), ngr = ceil_div(cnt, kAttnWaves);
-    const int bg = local % ngr; local /= ngr;
-    int4* d = (int4*)(tb.item_desc + 8LL * it);
-    d[0] = make_int4(tb.req_first[r], cnt, plen, local / nck);
-    d[1] = make_int4(local % nck, bg, r, 0);
-  }
-  // first row of every wave's range
-  for (int w = tid; w < cut.pool_base + cut.n_chunks; w += kPlanThreads) {
-    const long long u = range_start(cut, w);
-    int row = 0;
-    if (u < units) {
-      const int* cum = nA <= kPlanLdsRows ? s_cum : tb.page_cum;   // uniform choice
-      int lo = 0, hi = nA - 1;
+    n_items = i_carry;
+    if (tid == 0) tb.live_item_start[n_live] = n_items;
+    __syncthreads();
+    for (int it = tid; it < n_items; it += kPlanThreads) {
+      int lo = 0, hi = n_live - 1;
       while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
-        if ((long long)cum[mid] * dm.Hkv <= u) lo = mid; else hi = mid - 1;
+        if (tb.live_item_start[mid] <= it) lo = mid; else hi = mid - 1;
       }
-      row = lo;
+      const int r = tb.live_req[lo];
+      int local = it - tb.live_item_start[lo];
+      const int cnt = tb.refcnt[r], plen = tb.prefix_len[r];
+      const int nck = ceil_div(ceil_div(plen, dm.pt), chunk), ngr = ceil_div(cnt, kAttnWaves);
+      const int bg = local % ngr; local /= ngr;
+      int4* d = (int4*)(tb.item_desc + 8LL * it);
+      d[0] = make_int4(tb.req_first[r], cnt, plen, local / nck);
+      d[1] = make_int4(local % nck, bg, r, 0);
     }
-    tb.wave_row[w] = row;
+  }
+  // first row / first live request of every range
+  for (int w = tid; w < n_waves; w += kPlanThreads) {
+    int v = 0;
+    if (w < cut.n_own) {
+      const long long u = own_start(cut, w);
+      if (u < cut.u_own) {
+        const int* cum = nA <= kPlanLdsRows ? s_cum : tb.page_cum;   // uniform choice
+        int lo = 0, hi = nA - 1;
+        while (lo < hi) {
+          const int mid = (lo + hi + 1) >> 1;
+          if ((long long)cum[mid] * dm.Hkv <= u) lo = mid; else hi = mid - 1;
+        }
+        v = lo;
+      }
+      tb.wave_row[w] = v;
+    }
+    if (w >= n_waves - cut.n_prompt) {
+      // index into wave_row of prompt range x is n_waves + (x - n_own): the two kinds of
+      // ranges may be served by the same waves when there is a single workgroup
+      const long long x = cut.n_own + (w - (n_waves - cut.n_prompt));
+      const long long u = prompt_start(cut, x);
+      int k = 0;
+      if (u < cut.u_prompt) {
+        int lo = 0, hi = n_live - 1;
+        while (lo < hi) {
+          const int mid = (lo + hi + 1) >> 1;
+          if ((long long)tb.live_item_start[mid] * dm.Hkv <= u) lo = mid; else hi = mid - 1;
+        }
+        k = lo;
+      }
+      tb.wave_row[n_waves + (x - cut.n_own)] = k;
+    }
   }
   if (tid == 0) {
     scal[S_D_NA] = nA;
-    scal[S_D_UNITS] = (int)units;
     scal[S_D_PER_EVEN] = cut.pe;
     scal[S_D_PER_ODD] = cut.po;
-    scal[S_D_UMAIN] = (int)cut.u_main;
-    scal[S_D_POOLC] = cut.pool_c;
-    scal[S_D_NCHUNK] = cut.n_chunks;
-    scal[S_D_POOLBASE] = cut.pool_base;
-    scal[S_POOL_NEXT] = 0;
+    scal[S_D_UOWN] = (int)cut.u_own;
+    scal[S_D_NOWN] = cut.n_own;
+    scal[S_D_UPROMPT] = (int)cut.u_prompt;
+    scal[S_D_NPROMPT] = cut.n_prompt;
+    scal[S_D_PB] = cut.pb;
     scal[S_D_NITEMS] = n_items;
     scal[S_D_NLIVE] = n_live;
     scal[S_D_CHUNK] = chunk;
@@ -235,8 +268,8 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
 // The cut of the current plan, as the attention and merge kernels read it.
 __device__ inline Cut load_cut(const int* scal) {
   Cut k;
-  k.pe = scal[S_D_PER_EVEN]; k.po = scal[S_D_PER_ODD]; k.u_main = scal[S_D_UMAIN];
-  k.pool_c = scal[S_D_POOLC]; k.n_chunks = scal[S_D_NCHUNK]; k.pool_base = scal[S_D_POOLBASE];
+  k.pe = scal[S_D_PER_EVEN]; k.po = scal[S_D_PER_ODD]; k.u_own = scal[S_D_UOWN]; k.n_own = scal[S_D_NOWN];
+  k.u_prompt = scal[S_D_UPROMPT]; k.n_prompt = scal[S_D_NPROMPT]; k.pb = scal[S_D_PB];
   return k;
 }
 

@@ -42,11 +42,11 @@ enum Scalar {
   S_D_CHUNK,      // prefix chunk in pages
   S_D_NPC,        // prefix chunks per (row, kv head) slot stride
   S_D_NWG,        // attention workgroups the plan was made for
-  S_D_UMAIN,      // units cut statically into per-wave ranges; the rest is the shared pool
-  S_D_POOLC,      // units per pool chunk
-  S_D_NCHUNK,     // pool chunks
-  S_D_POOLBASE,   // range number of pool chunk 0 (= number of non-empty static ranges)
-  S_POOL_NEXT,    // next pool chunk to hand out (reset by the merge kernel)
+  S_D_UOWN,       // units of the own region (branches' private pages)
+  S_D_NOWN,       // ranges (waves) serving the own region
+  S_D_UPROMPT,    // units of the prompt region (inline prompt mode), else 0
+  S_D_NPROMPT,    // ranges serving the prompt region
+  S_D_PB,         // units per prompt range
   S_COUNT = 32
 };
 
@@ -91,17 +91,18 @@ struct Tables {
   int* live_req;         // [max_req] live requests with prompt, active order
   int* live_item_start;  // [max_req+1] exclusive scan of prefix items
   int* item_desc;        // [max items][8] shared-prompt work items
-  int* wave_row;         // [max attention waves] active row of each wave's first unit
+  int* wave_row;         // [max attention waves] own ranges: active row of the first unit; prompt ranges: live request index
+  int* req_pstart;       // [max_req] start of the request's block on the prompt line, in (branch, page) units
 };
 
 // Launch shape the decode plan is made for (host-chosen, passed to every
 // planning kernel).
 struct PlanCfg {
-  int n_wg;           // persistent attention workgroups
+  int n_wg;           // persistent attention workgroups in total
   int chunk_pages;    // prompt chunk in pages; <= 0: sized on the device
   int inline_prefix;  // the prompt is read as the first pages of every row
   int skew_permille;  // even workgroups take (1000+skew)/1000 of the mean range, odd ones the rest
-  int pool_permille;  // share of the unit line handed out dynamically in small chunks
+  int n_wg_prompt;    // the last n_wg_prompt workgroups serve the shared prompts only (0: all do both)
 };
 
 struct Ctx {
@@ -110,44 +111,59 @@ struct Ctx {
   void* pool;
 };
 
-// ---- unit line -> wave ranges ------------------------------------------------
-// Workgroups are dispatched round-robin over the 8 XCDs, and on MI355X the odd
-// XCDs stream measurably slower than the even ones, so ranges come in pairs of
-// workgroups: the kAttnWaves waves of an even workgroup take pe units each,
-// those of the following odd workgroup po units each.
-// After the static ranges comes the pool: the last units of the line in small
-// chunks that waves take from a shared counter when their own range is done
-// (ranges of equal size do not take equal time: XCDs and memory channels are
-// not symmetric).  Static ranges and pool chunks are numbered on one axis,
-// ranges first; a piece's partial goes to slot (range number + segment number).
+// ---- unit lines -> wave ranges -------------------------------------------------
+// One decode step's work is a set of (page, kv head) units of 8 KiB (d = 128).
+//   own line     every active row's private pages, ordered (row, kv head, page);
+//   prompt line  (inline prompt mode) every live request's prompt pages once per
+//                branch, ordered (request, kv head, branch, page), so that the
+//                re-reads of one prompt chunk by the request's other branches are
+//                neighbours in space and time and hit in L2.
+// The waves of the first workgroups each take a contiguous range of the own
+// line; the waves of the last n_wg_prompt workgroups a range of the prompt line.
+// The grid is two workgroups per CU, so the prompt waves (mostly waiting on L2
+// hits) run in the second wave slot of the SIMDs whose first slot streams HBM.  Workgroups are dispatched round-robin over the 8 XCDs and
+// on MI355X the odd XCDs stream measurably slower than the even ones, so own
+// ranges come in pairs of workgroups: waves of an even workgroup take pe units,
+// those of the following odd workgroup po units.
 struct Cut {
-  int pe, po;            // units per wave of even / odd workgroups
-  long long u_main;      // units covered by the static ranges
-  int pool_c, n_chunks;  // units per pool chunk, number of chunks
-  int pool_base;         // range number of pool chunk 0: static ranges from here on are empty
+  int pe, po;            // units per own range of even / odd workgroups
+  long long u_own;       // units on the own line
+  int n_own;             // ranges [0, n_own) serve the own line
+  long long u_prompt;    // units on the prompt line
+  int n_prompt;          // ranges [n_own, n_own + n_prompt) serve the prompt line
+  int pb;                // units per prompt range
 };
-__host__ __device__ inline long long static_start(const Cut& k, long long w) {
+__host__ __device__ inline long long own_start(const Cut& k, long long w) {
   const long long b = w / kAttnWaves, wv = w % kAttnWaves;
   const long long pair = b >> 1;
   return pair * kAttnWaves * (k.pe + k.po) + ((b & 1) ? (long long)kAttnWaves * k.pe + wv * k.po : wv * k.pe);
 }
-__host__ __device__ inline long long static_of_unit(const Cut& k, long long u) {
+__host__ __device__ inline long long own_end(const Cut& k, long long w) {
+  const long long e = own_start(k, w) + (((w / kAttnWaves) & 1) ? k.po : k.pe);
+  return e < k.u_own ? e : k.u_own;
+}
+__host__ __device__ inline long long own_of_unit(const Cut& k, long long u) {
   const long long span = (long long)kAttnWaves * (k.pe + k.po);
   const long long pair = u / span, off = u % span;
   if (off < (long long)kAttnWaves * k.pe) return pair * 2 * kAttnWaves + off / k.pe;
   return pair * 2 * kAttnWaves + kAttnWaves + (off - (long long)kAttnWaves * k.pe) / k.po;
 }
-// [range_start, range_end) of range number x; static ranges x >= pool_base are empty
-__host__ __device__ inline long long range_start(const Cut& k, long long x) {
-  return x >= k.pool_base ? k.u_main + (x - k.pool_base) * k.pool_c : static_start(k, x);
+__host__ __device__ inline long long prompt_start(const Cut& k, long long w) { return (w - k.n_own) * k.pb; }
+__host__ __device__ inline long long prompt_end(const Cut& k, long long w) {
+  const long long e = prompt_start(k, w) + k.pb;
+  return e < k.u_prompt ? e : k.u_prompt;
 }
-__host__ __device__ inline long long range_end(const Cut& k, long long x) {
-  if (x >= k.pool_base) return range_start(k, x) + k.pool_c;
-  const long long e = static_start(k, x) + (((x / kAttnWaves) & 1) ? k.po : k.pe);
-  return e < k.u_main ? e : k.u_main;
-}
-__host__ __device__ inline long long range_of_unit(const Cut& k, long long u) {
-  return u >= k.u_main ? k.pool_base + (u - k.u_main) / k.pool_c : static_of_unit(k, u);
+__host__ __device__ inline long long prompt_of_unit(const Cut& k, long long u) { return k.n_own + u / k.pb; }
+// Which prompt range the i-th prompt wave serves.  Workgroup b runs on XCD b % 8,
+// and neighbouring prompt ranges re-read the same pages, so they go to
+// workgroups of one XCD (one L2): with n a multiple of 8 workgroups, the ranges
+// are dealt to XCD 0's workgroups first, then XCD 1's, ...
+__host__ __device__ inline long long prompt_range_of_wave(long long i, int n_prompt) {
+  const long long nwg = n_prompt / kAttnWaves;
+  if (nwg % 8) return i;
+  const long long b = i / kAttnWaves, wv = i % kAttnWaves;
+  const long long per_xcd = nwg / 8;
+  return ((b % 8) * per_xcd + b / 8) * kAttnWaves + wv;
 }
 
 // ---- layout: element offsets inside one K or V tile ------------------------

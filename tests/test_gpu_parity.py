@@ -140,8 +140,8 @@ def test_bf16_small_all_rows(shape, mode):
     err = compare_attention(cfg, o, g, wl.query(cfg, 0))
     print(f"shape {shape} {mode}: max abs err {err:.3g}")
     # other launch shapes cut the unit line elsewhere; the result must not depend on it
-    for n_wg, chunk, skew, pool in ((3, 4, 45, 0), (64, 8, 300, 500), (1000, 0, -200, 120), (256, 0, 0, 333)):
-        g.c.set_decode_launch(n_wg, chunk, 1 if mode == "mfma16-inline" else 0, skew, pool)
+    for n_wg, n_pw, chunk, skew in ((3, 1, 4, 45), (64, 0, 8, 300), (1000, 900, 0, -200), (256, -1, 0, 0), (1, 0, 0, 50)):
+        g.c.set_decode_launch(n_wg, n_pw, chunk, 1 if mode == "mfma16-inline" else 0, skew)
         compare_attention(cfg, o, g, wl.query(cfg, 1))
 
 
