@@ -262,3 +262,76 @@ def test_full_size_configs_sampled_rows(cfg_id, sample):
         assert_state_equal({k: v for k, v in o.state().items() if k in ("active_handles", "seq_lens", "branch_state", "req_counters")},
                            {k: v for k, v in g.state().items() if k in ("active_handles", "seq_lens", "branch_state", "req_counters")})
         compare("after prune")
+
+
+# ---------------------------------------------------------------------------
+# many branches: the planning kernels loop over the active list in chunks of
+# 1024 rows and search the unit line from LDS only up to 4096 rows
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("R,Nb,dtype", [(300, 8, "bf16"), (1300, 4, "bf16"), (700, 3, "f32")])
+def test_many_branches_state_and_attention(R, Nb, dtype):
+    rng = np.random.default_rng(R)
+    d, Hq, Hkv, pt = 64, 4, 2, 16
+    num_pages = R * Nb * 3 + R * 2 + 64
+    kw = dict(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, page_tokens=pt, num_pages=num_pages, max_requests=R,
+              branches_per_request=Nb, finish_quota=2, max_pages_per_branch=4, max_prefix_pages=2, dtype=dtype)
+    fo = rng.permutation(num_pages).astype(np.int32)
+    o, g = orc.OracleCache(free_order=fo, **kw), GpuEngine(free_order=fo, **kw)
+
+    def draw(n, heads):
+        x = rng.standard_normal((n, heads, d)).astype(np.float32)
+        return x if dtype == "f32" else wl.f32_to_bf16_bits(x)
+
+    P = rng.integers(0, 2 * pt + 1, size=R)
+    for r0 in range(0, R, 64):                      # prompts, 64 requests per call
+        ids = np.arange(r0, min(R, r0 + 64))
+        k, v = draw(int(P[ids].sum()), Hkv), draw(int(P[ids].sum()), Hkv)
+        for e in (o, g):
+            assert e.append(orc.SEQ_PREFIX, ids, P[ids], k, v) == orc.OK
+    L = rng.integers(0, 3 * pt, size=R * Nb)        # some branches stay empty
+    k, v = draw(int(L.sum()), Hkv), draw(int(L.sum()), Hkv)
+    for e in (o, g):
+        assert e.append(orc.SEQ_BRANCH, None, L, k, v) == orc.OK
+    assert_state_equal(o.state(), g.state())
+    q = draw(R * Nb, Hq)
+    rows = sorted(set(rng.integers(0, R * Nb, size=48).tolist() + [0, 1023, 1024, R * Nb - 1]))
+    compare_attention(wl.scaled(wl.CONFIGS[2], dtype=dtype), o, g, q, rows=rows)
+    # finish a scattered set (early stop cascades at 2 completions), prune by threshold, append, compare again
+    fin = rng.choice(R * Nb, size=R // 2, replace=False)
+    sc = rng.random(R * Nb).astype(np.float32)
+    for e in (o, g):
+        assert e.finish(fin) == orc.OK
+    assert_state_equal(o.state(), g.state())
+    nA = int(o.state()["n_active"][0])
+    for e in (o, g):
+        assert e.prune(orc.THRESHOLD, sc[:nA], threshold=np.full(R, 0.4, np.float32),
+                       max_pruned=np.full(R, Nb - 1, np.int32)) == orc.OK
+    st = g.state()
+    assert_state_equal(o.state(), st)
+    check_invariants(st, pt=pt, num_pages=num_pages, Nb=Nb, max_req=R)
+    nA = int(st["n_active"][0])
+    assert nA > 1024 or R * Nb < 3000
+    k, v = draw(nA, Hkv), draw(nA, Hkv)
+    for e in (o, g):
+        assert e.append(orc.SEQ_BRANCH, None, None, k, v) == orc.OK
+    assert_state_equal(o.state(), g.state())
+    act = st["active_handles"][:nA]
+    rows = sorted(set(rng.integers(0, nA, size=48).tolist() + [0, nA - 1]))
+    compare_attention(wl.scaled(wl.CONFIGS[2], dtype=dtype), o, g, q, rows=rows)
+
+
+def test_decode_is_deterministic_and_leaves_inputs_alone():
+    """Two identical calls give bit-identical outputs (fixed partition, fixed merge order)."""
+    import torch
+    cfg = wl.scaled(wl.CONFIGS[2], n_requests=4, nb=8, prompt_len=200, length_params=(300, 0.8), length_cap=2000)
+    L = wl.lengths(cfg)
+    g = GpuEngine(**dims(cfg, wl.pages_needed(cfg, L) + 4, 130))
+    populate(cfg, [g], L)
+    q = g.c._dev(wl.query(cfg, 0), (cfg.n_q_heads, cfg.head_dim))
+    q0 = q.clone()
+    a = g.c.decode_attention(q).clone()
+    b = g.c.decode_attention(q)
+    assert torch.equal(a, b) and torch.equal(q, q0)
+    st1 = g.state()
+    g.c.decode_attention(q)
+    assert_state_equal(st1, g.state())          # attention never changes the integer state
