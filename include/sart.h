@@ -217,9 +217,12 @@ sart_status sart_get_state(sart_cache* cache, int32_t* n_active,
 
 /* Launch statistics of the last sart_decode_attention on this cache, measured
  * with HIP events on the stream the kernels ran on (for bench harnesses).
- * Enable with sart_set_profiling(cache, 1); then each decode call records
- * events around its dominant kernel.  ms_attn: that kernel; ms_total: the
- * whole call's device work.  Waits for the events. */
+ * sart_set_profiling(cache, n): n = 0 off; n = 1 each decode call records
+ * events around its dominant (attention) kernel; n > 1 the call launches that
+ * kernel n times back to back between the events (it is idempotent), which
+ * amortises the events' own dispatch overhead; ms_attn is then the average per
+ * launch.  ms_total: the whole call's device work.  sart_last_decode_ms waits
+ * for the events. */
 sart_status sart_set_profiling(sart_cache* cache, int32_t on);
 sart_status sart_last_decode_ms(sart_cache* cache, float* ms_attn, float* ms_total);
 

@@ -248,8 +248,8 @@ class SartCache:
         return n.value
 
     # -- measurement / tuning -------------------------------------------------
-    def set_profiling(self, on: bool):
-        self._check(self.lib.sart_set_profiling(self.h, 1 if on else 0))
+    def set_profiling(self, repeats: int):
+        self._check(self.lib.sart_set_profiling(self.h, int(repeats)))
 
     def last_decode_ms(self):
         a, t = C.c_float(0), C.c_float(0)

@@ -59,7 +59,7 @@ struct sart_cache {
   long long partial_cap = 0;
   PlanCfg plan{0, 0, 0, 0, 0};         // launch shape of the decode plan
   int max_wg = 0;
-  bool profiling = false;
+  int profiling = 0;                   // 0 off, n >= 1: events around n attention launches
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   bool ev_valid = false;
 };
@@ -333,8 +333,9 @@ sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, f
   a.partials = c->partials; a.partial_cap = c->partial_cap;
   a.call_seq = ++c->call_seq;
   for (int i = 0; i < 4; ++i) a.ev[i] = c->profiling ? c->ev[i] : nullptr;
+  a.repeats = c->profiling;
   launch_decode(c->ctx, a, st);
-  c->ev_valid = c->profiling;
+  c->ev_valid = c->profiling > 0;
   HIP_TRY(hipGetLastError());
   return SART_OK;
 }
@@ -462,7 +463,8 @@ sart_status sart_get_state(sart_cache* c, int32_t* n_active, int32_t* active_han
 
 sart_status sart_set_profiling(sart_cache* c, int32_t on) {
   if (!c) return fail(SART_E_INVALID, "null cache");
-  c->profiling = on != 0;
+  if (on < 0 || on > 1000) return fail(SART_E_INVALID, "profiling repeats out of range");
+  c->profiling = on;
   c->ev_valid = false;
   return SART_OK;
 }
@@ -471,7 +473,10 @@ sart_status sart_last_decode_ms(sart_cache* c, float* ms_attn, float* ms_total) 
   if (!c) return fail(SART_E_INVALID, "null cache");
   if (!c->ev_valid) return fail(SART_E_STATE, "no profiled decode call yet");
   HIP_TRY(hipEventSynchronize(c->ev[3]));
-  if (ms_attn) HIP_TRY(hipEventElapsedTime(ms_attn, c->ev[1], c->ev[2]));
+  if (ms_attn) {
+    HIP_TRY(hipEventElapsedTime(ms_attn, c->ev[1], c->ev[2]));
+    *ms_attn /= (float)(c->profiling > 1 ? c->profiling : 1);
+  }
   if (ms_total) HIP_TRY(hipEventElapsedTime(ms_total, c->ev[0], c->ev[3]));
   return SART_OK;
 }

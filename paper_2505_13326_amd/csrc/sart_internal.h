@@ -220,6 +220,7 @@ struct DecodeArgs {
   long long partial_cap; // partial slots available
   int call_seq;
   hipEvent_t ev[4];     // optional profiling events (null: none)
+  int repeats;          // profiling: attention launches between ev[1] and ev[2]
 };
 void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s);
 
