@@ -210,7 +210,8 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   // the prompt chunks of every (row, kv head) at the smallest chunk size
   const long long S = (long long)H * dm.Hkv;
   const long long npc_max = (dm.max_pp + kStagePages - 1) / kStagePages;
-  c->partial_cap = (long long)c->max_wg * kAttnWaves + S * (2 + npc_max);
+  // own pieces (ranges + segments), then prompt blocks (at least 4 pages each) or LDS prompt chunks
+  c->partial_cap = (long long)c->max_wg * kAttnWaves + S * (1 + npc_max + 1);
   const long long pf = (long long)dm.G * dm.d + ((2 * dm.G + 3) & ~3);
   ALLOC(c->partials, (size_t)(c->partial_cap * pf));
 #undef ALLOC

@@ -201,7 +201,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
   const long long S = (long long)nA * dm.Hkv;
   const int n_waves = gridDim.x * kAttnWaves;
   const long long prompt_slot_base = (long long)scal[S_D_NOWN] + S;                        // inline prompt pieces
-  const long long prefix_base = (long long)scal[S_D_NOWN] + scal[S_D_NPROMPT] + 2 * S;     // LDS prompt chunks
+  const long long prefix_base = (long long)scal[S_D_NOWN] + S;                             // LDS prompt chunks (the other mode)
   const uint16_t* q = (const uint16_t*)a.q;
   const unsigned char* pool = (const unsigned char*)c.pool;
   const int* __restrict__ bt = scal[S_BTSEL] ? bt1 : bt0;
@@ -298,7 +298,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
     const long long wave_id = (long long)blockIdx.x * kAttnWaves + wv;
     SART_STAMP(3);
     const long long page_bytes = dm.page_elems * 2;
-    for (int line = 0; line < 2; ++line) {
+    for (int line = 1; line >= 0; --line) {   // prompt line first: all waves start it together, so neighbours share pages in time
       long long x, u, u1;          // range number and its units on this line
       int cursor;                  // own line: active row; prompt line: live request index
       if (line == 0) {
@@ -308,10 +308,10 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         cursor = tb.wave_row[x];
       } else {
         if (wave_id < n_waves - cut.n_prompt) continue;
-        x = cut.n_own + prompt_range_of_wave(wave_id - (n_waves - cut.n_prompt), cut.n_prompt);
-        u = prompt_start(cut, x); u1 = prompt_end(cut, x);
+        const long long i = wave_id - (n_waves - cut.n_prompt);
+        x = 0; u = prompt_range_of_wave(i, cut.n_prompt); u1 = cut.n_blocks;   // u counts prompt blocks here
         if (u >= u1) continue;
-        cursor = tb.wave_row[n_waves + (x - cut.n_own)];
+        cursor = tb.wave_row[n_waves + i];
       }
       while (u < u1) {
         // ---- next piece: pages [r0, r0 + rn) of `table`, for query rows (row, h)
@@ -334,27 +334,19 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
           table = bt + (long long)row * dm.max_bp;
           slot = x + (long long)row * dm.Hkv + h;
         } else {
-          int r, cnt, pp, plen;
-          long long rem;
-          for (;;) {   // the live request whose block holds unit u
-            r = tb.live_req[cursor];
-            cnt = tb.refcnt[r];
-            plen = tb.prefix_len[r];
-            pp = ceil_div(plen, 16);
-            rem = u - (long long)tb.live_item_start[cursor] * dm.Hkv;
-            if (rem < (long long)dm.Hkv * cnt * pp) break;
-            ++cursor;
-          }
-          const int first = tb.req_first[r];
-          const long long block = (long long)cnt * pp;
-          h = (int)(rem / block);
-          const int j = (int)((rem % block) / pp);
-          r0 = (int)(rem % pp);
-          rn = (int)min((long long)(pp - r0), u1 - u);
+          while (u >= tb.live_item_start[cursor + 1]) ++cursor;   // the live request owning block u
+          const int r = tb.live_req[cursor];
+          const int cnt = tb.refcnt[r], plen = tb.prefix_len[r];
+          const int pp = ceil_div(plen, 16), nck = ceil_div(pp, cut.pb);
+          const int local = (int)(u - tb.live_item_start[cursor]);
+          const int j = local % cnt, ck = (local / cnt) % nck;
+          h = local / (cnt * nck);
+          r0 = ck * cut.pb;
+          rn = min(cut.pb, pp - r0);
           n_last = min(16, plen - (r0 + rn - 1) * 16);
-          row = first + j;
+          row = tb.req_first[r] + j;
           table = prefix_table + (long long)r * dm.max_pp;
-          slot = prompt_slot_base + (x - cut.n_own) + (long long)first * dm.Hkv + (long long)h * cnt + j;
+          slot = prompt_slot_base + u;
         }
         load_q<D>(qreg, q, dm, row, h);
         st.reset();
@@ -405,7 +397,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
           i += cnt;
         }
         store_partial<D>(st, a.partials, slot, dm);
-        u += rn;
+        u += line == 0 ? rn : cut.n_prompt;
       }
     }
     SART_STAMP(6);
@@ -443,7 +435,7 @@ k_attn_generic(Ctx c, DecodeArgs a) {
   const long long S = (long long)scal[S_D_NA] * dm.Hkv;
   const long long prompt_slot_base = (long long)cut.n_own + S;
   const long long wave_id = (long long)blockIdx.x * kAttnWaves + wv;
-  for (int line = 0; line < 2; ++line) {
+  for (int line = 1; line >= 0; --line) {   // prompt blocks first, as in the matrix-core kernel
     long long x, u, u1;
     int cursor;
     if (line == 0) {
@@ -453,10 +445,10 @@ k_attn_generic(Ctx c, DecodeArgs a) {
       cursor = tb.wave_row[x];
     } else {
       if (wave_id < n_waves - cut.n_prompt) continue;
-      x = cut.n_own + (wave_id - (n_waves - cut.n_prompt));
-      u = prompt_start(cut, x); u1 = prompt_end(cut, x);
+      const long long i = wave_id - (n_waves - cut.n_prompt);
+      x = 0; u = prompt_range_of_wave(i, cut.n_prompt); u1 = cut.n_blocks;   // u counts prompt blocks here
       if (u >= u1) continue;
-      cursor = tb.wave_row[n_waves + (x - cut.n_own)];
+      cursor = tb.wave_row[n_waves + i];
     }
     while (u < u1) {
       int row, h, r0, rn, tokens;
@@ -478,26 +470,19 @@ k_attn_generic(Ctx c, DecodeArgs a) {
         table = bt + (long long)row * dm.max_bp;
         slot = x + (long long)row * dm.Hkv + h;
       } else {
-        int r, cnt, pp;
-        long long rem;
-        for (;;) {
-          r = tb.live_req[cursor];
-          cnt = tb.refcnt[r];
-          tokens = tb.prefix_len[r];
-          pp = ceil_div(tokens, pt);
-          rem = u - (long long)tb.live_item_start[cursor] * dm.Hkv;
-          if (rem < (long long)dm.Hkv * cnt * pp) break;
-          ++cursor;
-        }
-        const int first = tb.req_first[r];
-        const long long block = (long long)cnt * pp;
-        h = (int)(rem / block);
-        const int j = (int)((rem % block) / pp);
-        r0 = (int)(rem % pp);
-        rn = (int)min((long long)(pp - r0), u1 - u);
-        row = first + j;
+        while (u >= tb.live_item_start[cursor + 1]) ++cursor;
+        const int r = tb.live_req[cursor];
+        const int cnt = tb.refcnt[r];
+        tokens = tb.prefix_len[r];
+        const int pp = ceil_div(tokens, pt), nck = ceil_div(pp, cut.pb);
+        const int local = (int)(u - tb.live_item_start[cursor]);
+        const int j = local % cnt, ck = (local / cnt) % nck;
+        h = local / (cnt * nck);
+        r0 = ck * cut.pb;
+        rn = min(cut.pb, pp - r0);
+        row = tb.req_first[r] + j;
         table = tb.prefix_table + (long long)r * dm.max_pp;
-        slot = prompt_slot_base + (x - cut.n_own) + (long long)first * dm.Hkv + (long long)h * cnt + j;
+        slot = prompt_slot_base + u;
       }
       float* pbase = a.partials + slot * partial_floats(dm.G, D);
       for (int r = 0; r < dm.G; ++r) {
@@ -550,7 +535,7 @@ k_attn_generic(Ctx c, DecodeArgs a) {
           pbase[(long long)dm.G * D + dm.G + r] = l;
         }
       }
-      u += rn;
+      u += line == 0 ? rn : cut.n_prompt;
     }
   }
 }
@@ -575,22 +560,21 @@ k_merge(Ctx c, DecodeArgs a, int inline_prefix) {
   const long long pf = partial_floats(G, D);
   const long long S = (long long)nA * dm.Hkv;
   const long long prompt_slot_base = (long long)cut.n_own + S;
-  const long long prefix_base = (long long)cut.n_own + cut.n_prompt + 2 * S;
+  const long long prefix_base = (long long)cut.n_own + S;
   for (long long seg = blockIdx.x; seg < S; seg += gridDim.x) {
     const int row = (int)(seg / dm.Hkv), h = (int)(seg % dm.Hkv);
     // slot ranges: [pa, pa+pn) prompt pieces or chunks, [sa, sa+sn) own pieces
-    long long pa = 0, sa = 0;
+    long long pa = 0, sa = 0, pstride = 1;
     int pn = 0, sn = 0;
     {
       const int r = tb.active[row] / dm.Nb;
       const int pp = ceil_div(tb.prefix_len[r], dm.pt);
       if (pp > 0 && inline_prefix) {
-        const int first = tb.req_first[r], cnt = tb.refcnt[r], j = row - first;
-        const long long ps = (long long)first * dm.Hkv + (long long)h * cnt + j;
-        const long long us = (long long)tb.req_pstart[r] * dm.Hkv + ((long long)h * cnt + j) * pp;
-        const long long w0 = prompt_of_unit(cut, us), w1 = prompt_of_unit(cut, us + pp - 1);
-        pa = prompt_slot_base + (w0 - cut.n_own) + ps;
-        pn = (int)(w1 - w0 + 1);
+        // one block per prompt chunk: req_pstart + ((head * chunks + chunk) * branches + branch)
+        const int cnt = tb.refcnt[r], j = row - tb.req_first[r];
+        pn = ceil_div(pp, cut.pb);
+        pstride = cnt;
+        pa = prompt_slot_base + tb.req_pstart[r] + (long long)h * pn * cnt + j;
       } else if (pp > 0) {
         pn = ceil_div(pp, chunk);
         pa = prefix_base + seg * npc;
@@ -609,7 +593,7 @@ k_merge(Ctx c, DecodeArgs a, int inline_prefix) {
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
       for (int i = 0; i < pn + sn; ++i) {
-        const long long slot = i < pn ? pa + i : sa + (i - pn);
+        const long long slot = i < pn ? pa + i * pstride : sa + (i - pn);
         const float* pb = a.partials + slot * pf;
         const float mi = pb[(long long)G * D + r];
         const float li = pb[(long long)G * D + G + r];

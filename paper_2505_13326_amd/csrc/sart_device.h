@@ -82,15 +82,14 @@ __device__ inline void record_error(int* scal, int code, int call_seq) {
 //
 //   page_cum[a]   exclusive scan over active rows of their private pages; the
 //                 own line has page_cum[nA] * Hkv units.
-//   prompt line   (inline prompt mode) request r's block starts at
-//                 req_pstart[r] * Hkv and holds Hkv * branches * prompt pages
-//                 units; live_req[k] lists the live requests with a prompt in
-//                 active order, live_item_start[k] their req_pstart.
-//   cut           the first workgroups' waves cut the own line, the last
-//                 n_wg_prompt workgroups' waves the prompt line, see Cut;
-//                 wave_row[w] = active row holding the
-//                 first unit of own range w, or the index k of the live request
-//                 holding the first unit of prompt range w.
+//   prompt blocks (inline prompt mode) blocks of pb pages, pb sized so that the
+//                 blocks about fill the prompt waves once; request r owns blocks
+//                 req_pstart[r] + ((head * chunks + chunk) * branches + branch);
+//                 live_req[k] lists the live requests with a prompt in active
+//                 order, live_item_start[k] their first block.
+//   cut           see Cut; wave_row[w] = active row holding the first unit of own
+//                 range w; wave_row[n_waves + i] = index k of the live request
+//                 owning the first block of prompt wave i.
 //   items         (LDS prompt mode) shared-prompt work: one per (live request,
 //                 kv head, prompt chunk, group of kAttnWaves branches), eight
 //                 ints each: {first row, live branches, prompt tokens, kv head,
@@ -136,10 +135,6 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     }
     if (w > 0) {
       tb.live_req[l_carry + ex3[2]] = r;
-      if (pc.inline_prefix) {
-        tb.req_pstart[r] = w_carry + ex3[1];
-        tb.live_item_start[l_carry + ex3[2]] = w_carry + ex3[1];
-      }
     }
     carry += tot3[0];
     w_carry += tot3[1];
@@ -153,14 +148,15 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   const int n_waves = pc.n_wg * kAttnWaves;
   Cut cut;
   cut.u_own = (long long)carry * dm.Hkv;
-  cut.u_prompt = pc.inline_prefix ? (long long)w_carry * dm.Hkv : 0;
+  const long long u_prompt = pc.inline_prefix ? (long long)w_carry * dm.Hkv : 0;   // prompt units of the step
   // workgroup roles: the last n_wg_prompt workgroups serve the prompt line (or the
   // LDS-staged prompt items); with none dedicated every wave serves both lines
   const int wg_prompt = pc.n_wg_prompt < pc.n_wg ? pc.n_wg_prompt : pc.n_wg - 1;
   cut.n_own = (pc.n_wg - wg_prompt) * kAttnWaves;
-  cut.n_prompt = cut.u_prompt > 0 ? (wg_prompt > 0 ? wg_prompt * kAttnWaves : n_waves) : 0;
-  cut.pb = cut.n_prompt > 0 ? (int)((cut.u_prompt + cut.n_prompt - 1) / cut.n_prompt) : 1;
-  if (cut.pb < 1) cut.pb = 1;
+  cut.n_prompt = u_prompt > 0 ? (wg_prompt > 0 ? wg_prompt * kAttnWaves : n_waves) : 0;
+  cut.pb = cut.n_prompt > 0 ? (int)((u_prompt + cut.n_prompt - 1) / cut.n_prompt) : 1;
+  cut.pb = ceil_div(cut.pb < 1 ? 1 : cut.pb, 4) * 4;        // whole rings of page buffers
+  cut.n_blocks = 0;
   int per_wave = (int)((cut.u_own + cut.n_own - 1) / (cut.n_own > 0 ? cut.n_own : 1));
   if (per_wave < 1) per_wave = 1;
   // even / odd workgroups: pe + po = 2 * per_wave, po >= 1; an odd number of
@@ -178,7 +174,25 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   chunk = ceil_div(chunk < 1 ? 1 : chunk, kStagePages) * kStagePages;
   __syncthreads();                       // live_req, req_first, page_cum, req_pstart written
   int n_items = 0;
-  if (!pc.inline_prefix) {
+  if (pc.inline_prefix) {
+    // first prompt block of every live request
+    int b_carry = 0;
+    for (int base = 0; base < n_live; base += kPlanThreads) {
+      const int k = base + tid;
+      int blocks = 0, r = 0;
+      if (k < n_live) {
+        r = tb.live_req[k];
+        blocks = dm.Hkv * ceil_div(ceil_div(tb.prefix_len[r], dm.pt), cut.pb) * tb.refcnt[r];
+      }
+      int tot;
+      const int ex = block_excl_scan(blocks, s_scan, tot);
+      if (k < n_live) { tb.live_item_start[k] = b_carry + ex; tb.req_pstart[r] = b_carry + ex; }
+      b_carry += tot;
+    }
+    cut.n_blocks = b_carry;
+    if (tid == 0) tb.live_item_start[n_live] = b_carry;
+    __syncthreads();
+  } else {
     // item offsets per live request
     int i_carry = 0;
     for (int base = 0; base < n_live; base += kPlanThreads) {
@@ -231,20 +245,19 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       tb.wave_row[w] = v;
     }
     if (w >= n_waves - cut.n_prompt) {
-      // index into wave_row of prompt range x is n_waves + (x - n_own): the two kinds of
-      // ranges may be served by the same waves when there is a single workgroup
-      const long long x = cut.n_own + (w - (n_waves - cut.n_prompt));
-      const long long u = prompt_start(cut, x);
+      // the live request owning the first block of prompt wave i (kept after the own-range entries)
+      const int i = w - (n_waves - cut.n_prompt);
+      const long long b = prompt_range_of_wave(i, cut.n_prompt);
       int k = 0;
-      if (u < cut.u_prompt) {
+      if (b < cut.n_blocks) {
         int lo = 0, hi = n_live - 1;
         while (lo < hi) {
           const int mid = (lo + hi + 1) >> 1;
-          if ((long long)tb.live_item_start[mid] * dm.Hkv <= u) lo = mid; else hi = mid - 1;
+          if (tb.live_item_start[mid] <= b) lo = mid; else hi = mid - 1;
         }
         k = lo;
       }
-      tb.wave_row[n_waves + (x - cut.n_own)] = k;
+      tb.wave_row[n_waves + i] = k;
     }
   }
   if (tid == 0) {
@@ -253,9 +266,9 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     scal[S_D_PER_ODD] = cut.po;
     scal[S_D_UOWN] = (int)cut.u_own;
     scal[S_D_NOWN] = cut.n_own;
-    scal[S_D_UPROMPT] = (int)cut.u_prompt;
     scal[S_D_NPROMPT] = cut.n_prompt;
     scal[S_D_PB] = cut.pb;
+    scal[S_D_NBLOCKS] = cut.n_blocks;
     scal[S_D_NITEMS] = n_items;
     scal[S_D_NLIVE] = n_live;
     scal[S_D_CHUNK] = chunk;
@@ -269,7 +282,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
 __device__ inline Cut load_cut(const int* scal) {
   Cut k;
   k.pe = scal[S_D_PER_EVEN]; k.po = scal[S_D_PER_ODD]; k.u_own = scal[S_D_UOWN]; k.n_own = scal[S_D_NOWN];
-  k.u_prompt = scal[S_D_UPROMPT]; k.n_prompt = scal[S_D_NPROMPT]; k.pb = scal[S_D_PB];
+  k.n_prompt = scal[S_D_NPROMPT]; k.pb = scal[S_D_PB]; k.n_blocks = scal[S_D_NBLOCKS];
   return k;
 }
 

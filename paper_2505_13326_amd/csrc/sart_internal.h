@@ -44,9 +44,9 @@ enum Scalar {
   S_D_NWG,        // attention workgroups the plan was made for
   S_D_UOWN,       // units of the own region (branches' private pages)
   S_D_NOWN,       // ranges (waves) serving the own region
-  S_D_UPROMPT,    // units of the prompt region (inline prompt mode), else 0
-  S_D_NPROMPT,    // ranges serving the prompt region
-  S_D_PB,         // units per prompt range
+  S_D_NPROMPT,    // waves serving the prompt blocks (the last ones of the grid, or all)
+  S_D_PB,         // pages per prompt block
+  S_D_NBLOCKS,    // prompt blocks
   S_COUNT = 32
 };
 
@@ -92,7 +92,7 @@ struct Tables {
   int* live_item_start;  // [max_req+1] exclusive scan of prefix items
   int* item_desc;        // [max items][8] shared-prompt work items
   int* wave_row;         // [max attention waves] own ranges: active row of the first unit; prompt ranges: live request index
-  int* req_pstart;       // [max_req] start of the request's block on the prompt line, in (branch, page) units
+  int* req_pstart;       // [max_req] first prompt block of the request
 };
 
 // Launch shape the decode plan is made for (host-chosen, passed to every
@@ -111,27 +111,29 @@ struct Ctx {
   void* pool;
 };
 
-// ---- unit lines -> wave ranges -------------------------------------------------
-// One decode step's work is a set of (page, kv head) units of 8 KiB (d = 128).
-//   own line     every active row's private pages, ordered (row, kv head, page);
-//   prompt line  (inline prompt mode) every live request's prompt pages once per
-//                branch, ordered (request, kv head, branch, page), so that the
-//                re-reads of one prompt chunk by the request's other branches are
-//                neighbours in space and time and hit in L2.
-// The waves of the first workgroups each take a contiguous range of the own
-// line; the waves of the last n_wg_prompt workgroups a range of the prompt line.
-// The grid is two workgroups per CU, so the prompt waves (mostly waiting on L2
-// hits) run in the second wave slot of the SIMDs whose first slot streams HBM.  Workgroups are dispatched round-robin over the 8 XCDs and
-// on MI355X the odd XCDs stream measurably slower than the even ones, so own
-// ranges come in pairs of workgroups: waves of an even workgroup take pe units,
-// those of the following odd workgroup po units.
+// ---- work of one decode step -> waves ------------------------------------------
+// The work is a set of (page, kv head) units of 8 KiB (d = 128).
+//   own line      every active row's private pages, ordered (row, kv head, page),
+//                 cut into one contiguous range per wave (a range may cross rows;
+//                 a long row is split over many waves).
+//   prompt blocks (inline prompt mode) every live request's prompt is read once
+//                 per branch, in blocks of pb pages ordered (request, kv head,
+//                 chunk, branch): the blocks of the request's branches for one
+//                 chunk are neighbours, go to waves of one workgroup (or of
+//                 workgroups on one XCD) and are read at the same time, at the
+//                 start of the kernel, so all but the first reader hit in cache.
+// Every wave serves its prompt block(s), then its own-line range.  Workgroups are
+// dispatched round-robin over the 8 XCDs and on MI355X the odd XCDs stream
+// measurably slower than the even ones, so own ranges come in pairs of
+// workgroups: waves of an even workgroup take pe units, those of the following
+// odd workgroup po units.
 struct Cut {
   int pe, po;            // units per own range of even / odd workgroups
   long long u_own;       // units on the own line
   int n_own;             // ranges [0, n_own) serve the own line
-  long long u_prompt;    // units on the prompt line
-  int n_prompt;          // ranges [n_own, n_own + n_prompt) serve the prompt line
-  int pb;                // units per prompt range
+  int n_prompt;          // waves serving prompt blocks: the last n_prompt of the grid
+  int pb;                // pages per prompt block
+  int n_blocks;          // prompt blocks; block b's partial goes to slot n_own + S + b
 };
 __host__ __device__ inline long long own_start(const Cut& k, long long w) {
   const long long b = w / kAttnWaves, wv = w % kAttnWaves;
@@ -148,16 +150,10 @@ __host__ __device__ inline long long own_of_unit(const Cut& k, long long u) {
   if (off < (long long)kAttnWaves * k.pe) return pair * 2 * kAttnWaves + off / k.pe;
   return pair * 2 * kAttnWaves + kAttnWaves + (off - (long long)kAttnWaves * k.pe) / k.po;
 }
-__host__ __device__ inline long long prompt_start(const Cut& k, long long w) { return (w - k.n_own) * k.pb; }
-__host__ __device__ inline long long prompt_end(const Cut& k, long long w) {
-  const long long e = prompt_start(k, w) + k.pb;
-  return e < k.u_prompt ? e : k.u_prompt;
-}
-__host__ __device__ inline long long prompt_of_unit(const Cut& k, long long u) { return k.n_own + u / k.pb; }
-// Which prompt range the i-th prompt wave serves.  Workgroup b runs on XCD b % 8,
-// and neighbouring prompt ranges re-read the same pages, so they go to
-// workgroups of one XCD (one L2): with n a multiple of 8 workgroups, the ranges
-// are dealt to XCD 0's workgroups first, then XCD 1's, ...
+// Which prompt block the i-th prompt wave serves first (then every n_prompt-th
+// after it).  Workgroup b runs on XCD b % 8, and neighbouring blocks read the
+// same pages, so they go to workgroups of one XCD (one L2): with a multiple of
+// 8 workgroups, the blocks are dealt to XCD 0's workgroups first, then XCD 1's, ...
 __host__ __device__ inline long long prompt_range_of_wave(long long i, int n_prompt) {
   const long long nwg = n_prompt / kAttnWaves;
   if (nwg % 8) return i;
