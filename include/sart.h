@@ -236,10 +236,11 @@ sart_status sart_last_decode_ms(sart_cache* cache, float* ms_attn, float* ms_tot
  *   prefix_chunk_pages   prompt chunk of the LDS-staged mode (<= 0: sized on the
  *                        device from the active set);
  *   prompt_mode          how the shared prompt is read on SART_LAYOUT_MFMA16
- *                        caches: 1 = every branch reads the prompt pages itself;
- *                        the prompt reads of all branches lie on a line of their
- *                        own, ordered (request, kv head, branch, page) so that the
- *                        re-reads of a chunk are neighbours and hit in L2
+ *                        caches: 1 = every branch reads the prompt pages itself,
+ *                        in blocks of pages ordered (request, kv head, chunk,
+ *                        branch) that every wave serves before its own range, so
+ *                        that the re-reads of a chunk by the request's branches
+ *                        are neighbours in time and place and hit in L2
  *                        (default); 0 = each prompt chunk is staged once in LDS
  *                        per workgroup and reused by the request's branches, one
  *                        wave each; -1 = keep the current mode.  Natural-layout
