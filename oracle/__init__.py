@@ -43,6 +43,7 @@ def _load():
         L.orc_destroy.argtypes = [vp]
         L.orc_append.argtypes = [vp, C.c_int, C.c_int, ip, ip, vp, vp]
         L.orc_attention.argtypes = [vp, vp, C.c_int, C.c_double, ip, C.c_int, dp, dp]
+        L.orc_prefill_attention.argtypes = [vp, C.c_int, vp, C.c_int, C.c_double, dp, dp]
         L.orc_finish.argtypes = [vp, C.c_int, ip]
         L.orc_prune.argtypes = [vp, C.c_int, C.c_int, ip, fp, ip, fp, C.c_int]
         L.orc_request_done.argtypes = [vp, C.c_int]
@@ -122,6 +123,20 @@ class OracleCache:
                                   ws.ctypes.data_as(C.POINTER(C.c_double)))
         if rc != OK:
             raise ValueError(f"orc_attention status {rc}")
+        return (out, ws) if want_wsum else out
+
+    def prefill_attention(self, request, q, scale=0.0, want_wsum=False):
+        """Causal attention of the last len(q) prompt tokens of `request` (Algorithm 1, Prefill).
+        Returns a status code on error, else out [n_q, Hq, d] float64 (and the weight sums)."""
+        q = self._raw(q, (self.Hq, self.d))
+        n_q = q.shape[0]
+        out = np.zeros((n_q, self.Hq, self.d), dtype=np.float64)
+        ws = np.zeros((n_q, self.Hq), dtype=np.float64)
+        rc = self.L.orc_prefill_attention(self.h, int(request), q.ctypes.data, n_q, float(scale),
+                                          out.ctypes.data_as(C.POINTER(C.c_double)),
+                                          ws.ctypes.data_as(C.POINTER(C.c_double)))
+        if rc != OK:
+            return rc
         return (out, ws) if want_wsum else out
 
     def finish(self, handles) -> int:

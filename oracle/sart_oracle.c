@@ -306,6 +306,56 @@ int orc_attention(const orc* o, const void* q, int n_rows, double scale, const i
 }
 
 /*
+ * Prefill attention (Algorithm 1, Prefill; Section 4 calls the prefill phase
+ * the same as in plain LLM inference, so this is ordinary causal
+ * self-attention over the prompt).  The queries are the last n_q prompt tokens
+ * of request r: query i sits at prompt position p = P_r - n_q + i and attends
+ * to prompt tokens 0..p (itself included), read through the prefix table:
+ *   s_t = scale * q_i . K[t],  w_t = exp(s_t - max) / sum,  out_i = sum_t w_t V[t].
+ * With n_q < P_r this is one chunk of a chunked prefill (append a chunk of the
+ * prompt, then attend with that chunk's queries).
+ * q: [n_q][Hq][d] in the cache dtype; out: [n_q][Hq][d] double; wsum optional.
+ */
+int orc_prefill_attention(const orc* o, int r, const void* q, int n_q, double scale, double* out, double* wsum) {
+  if (r < 0 || r >= o->max_req || n_q < 0) return ORC_E_INVALID;
+  if (!o->req_used[r] || o->refcnt[r] == 0) return ORC_E_STATE;
+  const int P = o->prefix_len[r];
+  if (n_q > P) return ORC_E_INVALID;
+  if (scale <= 0) scale = 1.0 / sqrt((double)o->d);
+  const int G = o->Hq / o->Hkv, d = o->d;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+  for (int i = 0; i < n_q; ++i) {
+    for (int h = 0; h < o->Hq; ++h) {
+      const int g = h / G, T = P - n_q + i + 1;      /* tokens 0..p */
+      const unsigned char* qrow = (const unsigned char*)q + ((size_t)i * o->Hq + h) * d * o->esize;
+      double* orow = out + ((size_t)i * o->Hq + h) * d;
+      for (int c = 0; c < d; ++c) orow[c] = 0.0;
+      double* s = (double*)malloc((size_t)T * sizeof(double));
+      double smax = -INFINITY;
+      for (int t = 0; t < T; ++t) {
+        const unsigned char* kp = token_ptr(o, o->prefix_table[(size_t)r * o->max_pp + t / o->pt], t % o->pt, g, 0);
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c) dot += widen(o, qrow, c) * widen(o, kp, c);
+        s[t] = scale * dot;
+        if (s[t] > smax) smax = s[t];
+      }
+      double Z = 0.0;
+      for (int t = 0; t < T; ++t) { s[t] = exp(s[t] - smax); Z += s[t]; }
+      double ws = 0.0;
+      for (int t = 0; t < T; ++t) {
+        const unsigned char* vp = token_ptr(o, o->prefix_table[(size_t)r * o->max_pp + t / o->pt], t % o->pt, g, 1);
+        const double w = s[t] / Z;
+        ws += w;
+        for (int c = 0; c < d; ++c) orow[c] += w * widen(o, vp, c);
+      }
+      if (wsum) wsum[(size_t)i * o->Hq + h] = ws;
+      free(s);
+    }
+  }
+  return ORC_OK;
+}
+
+/*
  * Remove a set of active branches (Section 4, immediate release).
  * new_state[a] != 0 marks active index a as leaving with that state.
  *  (1) in ascending active index: push the branch's private pages in ascending

@@ -119,8 +119,8 @@ def test_cfg1_tiny_decode_prune_decode():
 
 
 @pytest.mark.parametrize("mode", ["mfma16-lds", "mfma16-inline", "natural"])
-@pytest.mark.parametrize("shape", [(28, 4, 128), (40, 8, 128), (8, 2, 64), (16, 1, 128)],
-                         ids=["g7", "g5", "g4d64", "g16"])
+@pytest.mark.parametrize("shape", [(28, 4, 128), (40, 8, 128), (8, 2, 64), (16, 1, 128), (64, 8, 128)],
+                         ids=["g7", "g5", "g4d64", "g16", "g8-70b"])
 def test_bf16_small_all_rows(shape, mode):
     """7B-like / 32B-like head geometry at a size the oracle finishes in
     seconds: several pages per branch, ragged tails, a prompt that is not a
