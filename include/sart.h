@@ -168,6 +168,27 @@ sart_status sart_decode_attention(sart_cache* cache, int32_t layer,
                                   const void* q, float* out, int32_t n_rows,
                                   float scale, void* stream);
 
+/* Prefill attention (Algorithm 1, Prefill; Section 4 takes the prefill phase
+ * from plain LLM inference): causal self-attention over prompts already in the
+ * cache.  For each listed request the queries are its LAST n_q[i] prompt tokens:
+ * query j of the request sits at prompt position p = P - n_q[i] + j and reads
+ * prompt tokens 0..p (itself included) through the request's prefix table;
+ * out = softmax(q K^T * scale) V per query head, KV head = head / (Hq / Hkv).
+ * n_q[i] = P: the whole prompt at once; smaller: one chunk of a chunked prefill
+ * (append the chunk with sart_append_tokens(SART_SEQ_PREFIX), then attend with
+ * the chunk's queries).  Decode branches of the request are not involved.
+ *   request_ids, n_q   host arrays [n_seqs]; ids in [0, max_requests), n_q >= 0;
+ *   q                  device, [sum n_q][Hq][head_dim], kv_dtype, rows in list order;
+ *   out                device, [sum n_q][Hq][head_dim], float32;
+ *   scale              <= 0: 1 / sqrt(head_dim).
+ * Errors: host-checkable faults return a status and enqueue nothing.  A request
+ * that is not live (SART_E_STATE) or holds fewer than n_q[i] prompt tokens
+ * (SART_E_INVALID) is found on the device: then nothing is written to out and
+ * the status is sticky until sart_sync_status / sart_get_state reads it.
+ * Asynchronous on `stream`; q and out are not retained after the stream work. */
+sart_status sart_prefill_attention(sart_cache* cache, int32_t layer, int32_t n_seqs, const int32_t* request_ids,
+                                   const int32_t* n_q, const void* q, float* out, float scale, void* stream);
+
 /* A7.  Prunes branches by score (Algorithm 1, Decode: "Prune the branch").
  * scores: DEVICE float [n_scores], active order, n_scores >= active count.
  * Per request, over its active branches:

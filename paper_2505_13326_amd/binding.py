@@ -55,6 +55,8 @@ _SIGNATURES = {
                                      C.c_int32, C.c_void_p]),
     "sart_decode_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float,
                                         C.c_void_p]),
+    "sart_prefill_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, _ip, _ip, C.c_void_p, C.c_void_p, C.c_float,
+                                         C.c_void_p]),
     "sart_prune_branches": (C.c_int, [C.c_void_p, C.POINTER(_Policy), C.c_void_p, C.c_int32, C.c_void_p]),
     "sart_finish_branch": (C.c_int, [C.c_void_p, C.c_int32, _ip, C.c_void_p]),
     "sart_sync_status": (C.c_int, [C.c_void_p]),
@@ -186,6 +188,23 @@ class SartCache:
         assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
         self._check(self.lib.sart_decode_attention(self.h, 0, C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()),
                                                    q.shape[0], float(scale), _stream_handle(stream)))
+        return out
+
+    def prefill_attention(self, request_ids, n_q, q, out=None, scale=0.0, stream=None, status=False):
+        """sart_prefill_attention.  q: [sum n_q, Hq, d], rows in list order; returns out float32 (device)."""
+        import torch
+        ids, nq = _i32(request_ids), _i32(n_q)
+        assert len(ids) == len(nq)
+        q = self._dev(q, (self.Hq, self.d))
+        assert q.shape[0] == int(np.maximum(nq, 0).sum())
+        if out is None:
+            out = torch.zeros((q.shape[0], self.Hq, self.d), dtype=torch.float32, device=q.device)
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
+        rc = self.lib.sart_prefill_attention(self.h, 0, len(ids), _ptr(ids), _ptr(nq), C.c_void_p(q.data_ptr()),
+                                             C.c_void_p(out.data_ptr()), float(scale), _stream_handle(stream))
+        if status:
+            return rc
+        self._check(rc)
         return out
 
     def prune_branches(self, mode, scores, k=0, k_per_request=None, threshold=None, max_pruned=None, stream=None,

@@ -217,7 +217,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
 #undef ALLOC
 
   // staging slots for small host arrays (ids, counts, offsets, policy arrays)
-  c->stage_ints = 3 * H + 3 * R + 16;
+  c->stage_ints = 3 * H + 4 * R + 16;
   for (int i = 0; i < kStageSlots; ++i) {
     HIP_TRY(hipHostMalloc((void**)&c->stage[i].host, c->stage_ints * sizeof(int), hipHostMallocDefault));
     HIP_TRY(hipMalloc((void**)&c->stage[i].dev, c->stage_ints * sizeof(int)));
@@ -337,6 +337,54 @@ sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, f
   a.repeats = c->profiling;
   launch_decode(c->ctx, a, st);
   c->ev_valid = c->profiling > 0;
+  HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
+
+sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs, const int32_t* request_ids,
+                                   const int32_t* n_q, const void* q, float* out, float scale, void* stream) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (layer != 0) return fail(SART_E_INVALID, "layer must be 0");
+  const Dims& dm = c->ctx.dm;
+  if (n_seqs < 0 || n_seqs > dm.max_req) return fail(SART_E_INVALID, "n_seqs out of range");
+  if (n_seqs > 0 && (!request_ids || !n_q)) return fail(SART_E_INVALID, "null request_ids or n_q");
+  long long total = 0, tiles = 0;
+  const int rows_per_tile = 16 * 4 * kAttnWaves;            // the matrix-core kernel's workgroup tile
+  for (int i = 0; i < n_seqs; ++i) {
+    if (request_ids[i] < 0 || request_ids[i] >= dm.max_req)
+      return fail(SART_E_INVALID, "request %d out of range at %d", request_ids[i], i);
+    if (n_q[i] < 0 || n_q[i] > dm.max_pp * dm.pt) return fail(SART_E_INVALID, "n_q out of range at %d", i);
+    total += n_q[i];
+    tiles += (long long)dm.Hkv * (((long long)n_q[i] * dm.G + rows_per_tile - 1) / rows_per_tile);
+  }
+  if (total > 0x7fffffffLL / dm.Hq || tiles > 0x7fffffffLL) return fail(SART_E_INVALID, "too many queries in one call");
+  if (total > 0 && (!q || !out)) return fail(SART_E_INVALID, "null q or out");
+  if (n_seqs == 0) return SART_OK;
+  if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)dm.d);
+  hipStream_t st = (hipStream_t)stream;
+  note_stream(c, stream);
+  StageSlot* s;
+  sart_status rc = stage_begin(c, &s);
+  if (rc != SART_OK) return rc;
+  PrefillArgs a{};
+  a.n_seqs = n_seqs; a.q = q; a.out = out; a.call_seq = ++c->call_seq;
+  a.scale_log2 = scale * 1.44269504088896340736f;
+  a.total_q = (int)total; a.n_tiles = (int)tiles;
+  int* hbuf = s->host;
+  int qo = 0, to = 0;
+  for (int i = 0; i < n_seqs; ++i) {
+    hbuf[i] = request_ids[i];
+    hbuf[n_seqs + i] = n_q[i];
+    hbuf[2 * n_seqs + i] = qo;
+    hbuf[3 * n_seqs + i] = to;
+    qo += n_q[i];
+    to += dm.Hkv * (int)(((long long)n_q[i] * dm.G + rows_per_tile - 1) / rows_per_tile);
+  }
+  a.ids = s->dev; a.nq = s->dev + n_seqs; a.q_off = s->dev + 2 * n_seqs; a.tile_start = s->dev + 3 * n_seqs;
+  rc = stage_upload(c, s, (size_t)4 * n_seqs, st);
+  if (rc != SART_OK) return rc;
+  launch_prefill(c->ctx, a, st);
+  HIP_TRY(hipEventRecord(s->done, st));
   HIP_TRY(hipGetLastError());
   return SART_OK;
 }

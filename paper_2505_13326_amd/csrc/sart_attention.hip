@@ -22,14 +22,9 @@
 //   * Shared prompt pages are staged in LDS once per (request, kv head,
 //     chunk) workgroup and reused by the request's branches (one wave each)
 //     and all query heads of the group.
-#include "sart_device.h"
+#include "sart_attn_tile.h"
 
 namespace sart {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #ifdef SART_TRACE
 // Developer build only: per-wave timestamps (100 MHz wall clock) at phase
@@ -45,95 +40,6 @@ __device__ unsigned long long g_trace[16384 * 8];
 
 // floats of one partial: o[G][d], then m[G], l[G], padded to a 16-byte multiple
 __host__ __device__ inline long long partial_floats(int G, int d) { return (long long)G * d + ((2 * G + 3) & ~3); }
-
-// ---------------------------------------------------------------------------
-// Online-softmax state of one wave for one (row, kv head): the 16 x d tile
-// O^T as matrix-core accumulators, running max m and per-lane partial sum l.
-// Lane (r = lane & 15, g = lane >> 4) holds head r, tokens 4g..4g+3 of a page
-// and output columns d = 16*blk + 4g + j.
-// ---------------------------------------------------------------------------
-template <int D>
-struct WaveState {
-  f32x4 o[D / 16];
-  float m, l;
-  __device__ inline void reset() {
-#pragma unroll
-    for (int b = 0; b < D / 16; ++b) o[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-    m = -__builtin_inff();
-    l = 0.f;
-  }
-};
-
-// max over the four 16-lane rows of a wave for every column (lane & 15), on
-// the vector ALU: v_permlane32_swap / v_permlane16_swap exchange half-waves and
-// odd/even rows between two registers; feeding the same value twice and taking
-// the max of both results is the pairwise max whichever half is swapped.
-__device__ inline float max_over_rows(float x) {
-  const unsigned u = __float_as_uint(x);
-  const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
-  const unsigned v = __float_as_uint(x);
-  const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
-}
-__device__ inline float sum_over_rows(float x) {
-  const unsigned u = __float_as_uint(x);
-  const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
-  const unsigned v = __float_as_uint(x);
-  const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
-}
-
-// One 16-token page: kq[i] / vq[i] are the 16-byte chunks this lane loaded
-// (chunk i*64 + lane of the K resp. V tile), qreg the Q^T operand.  FULL: all
-// 16 tokens are valid (no masking code).  Scores are kept in the log2 domain:
-// p = 2^(s*c - m) with c = scale*log2(e).
-template <int D, bool FULL>
-__device__ inline void process_page(WaveState<D>& st, const uint4* kq, const uint4* vq, const uint4* qreg,
-                                    int nvalid, float scale_log2) {
-  const int g = (threadIdx.x & 63) >> 4;
-  f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int i = 0; i < D / 32; ++i)
-    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kq[i]),
-                                                __builtin_bit_cast(bf16x8, qreg[i]), s, 0, 0, 0);
-  uint4 vloc[D / 32];
-#pragma unroll
-  for (int i = 0; i < D / 32; ++i) vloc[i] = vq[i];
-  if (!FULL) {
-    const int t0 = 4 * g;
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (t0 + j >= nvalid) s[j] = -__builtin_inff();
-    const unsigned m01 = (t0 + 0 < nvalid ? 0x0000ffffu : 0u) | (t0 + 1 < nvalid ? 0xffff0000u : 0u);
-    const unsigned m23 = (t0 + 2 < nvalid ? 0x0000ffffu : 0u) | (t0 + 3 < nvalid ? 0xffff0000u : 0u);
-#pragma unroll
-    for (int i = 0; i < D / 32; ++i) {
-      vloc[i].x &= m01; vloc[i].y &= m23; vloc[i].z &= m01; vloc[i].w &= m23;
-    }
-  }
-  float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-  mx = max_over_rows(mx) * scale_log2;           // scale > 0: max commutes with the scaling
-  const float m_new = fmaxf(st.m, mx);           // finite: a page holds >= 1 valid token
-  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // 0 on the first page (m = -inf)
-  st.m = m_new;
-  f32x4 p;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[j], scale_log2, -m_new));
-  st.l = st.l * alpha + (p[0] + p[1]) + (p[2] + p[3]);
-  if (__any(alpha != 1.0f)) {
-#pragma unroll
-    for (int b = 0; b < D / 16; ++b) st.o[b] *= alpha;
-  }
-  const s16x4 pb = __builtin_bit_cast(s16x4, __builtin_convertvector(p, bf16x4));
-#pragma unroll
-  for (int i = 0; i < D / 32; ++i) {
-    const uint2 lo = {vloc[i].x, vloc[i].y}, hi = {vloc[i].z, vloc[i].w};
-    st.o[2 * i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, lo), pb, st.o[2 * i], 0, 0, 0);
-    st.o[2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, hi), pb, st.o[2 * i + 1], 0, 0, 0);
-  }
-}
 
 template <int D>
 __device__ inline void load_q(uint4* qreg, const uint16_t* q, const Dims& dm, int row, int head) {
@@ -277,8 +183,8 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
                   vq[i] = *(const uint4*)(&lds_kv[stg & 1][k][kTileBytes + i * 1024 + lane * 16]);
                 }
                 const int nvalid = min(16, plen - p * 16);
-                if (nvalid == 16) process_page<D, true>(st, kq, vq, qreg, 16, a.scale_log2);
-                else process_page<D, false>(st, kq, vq, qreg, nvalid, a.scale_log2);
+                if (nvalid == 16) process_page<D, true>(st, kq, vq, qreg, 16, 16, a.scale_log2);
+                else process_page<D, false>(st, kq, vq, qreg, nvalid, nvalid, a.scale_log2);
               }
             }
           }
@@ -376,14 +282,14 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
             for (int j = 0; j < kRing; ++j) pid[j] = table[r0 + i + kRing + j];
 #pragma unroll
             for (int j = 0; j < kRing; ++j) {
-              process_page<D, true>(st, kb[j], vb[j], qreg, 16, a.scale_log2);
+              process_page<D, true>(st, kb[j], vb[j], qreg, 16, 16, a.scale_log2);
               load_page(kb[j], vb[j], pid[j]);
             }
             i += kRing;
           } while (i + 2 * kRing <= rn);
 #pragma unroll
           for (int j = 0; j < kRing; ++j)
-            process_page<D, false>(st, kb[j], vb[j], qreg, i + j == rn - 1 ? n_last : 16, a.scale_log2);
+            { const int nv = i + j == rn - 1 ? n_last : 16; process_page<D, false>(st, kb[j], vb[j], qreg, nv, nv, a.scale_log2); }
           i += kRing;
         }
         while (i < rn) {   // fewer than 2*kRing pages left: groups of up to kRing, requested up front
@@ -393,7 +299,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
             if (j < cnt) load_page(kb[j], vb[j], table[r0 + i + j]);
 #pragma unroll
           for (int j = 0; j < kRing; ++j)
-            if (j < cnt) process_page<D, false>(st, kb[j], vb[j], qreg, i + j == rn - 1 ? n_last : 16, a.scale_log2);
+            if (j < cnt) { const int nv = i + j == rn - 1 ? n_last : 16; process_page<D, false>(st, kb[j], vb[j], qreg, nv, nv, a.scale_log2); }
           i += cnt;
         }
         store_partial<D>(st, a.partials, slot, dm);
@@ -411,10 +317,6 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
 // is read inline as the first pages of every row.  Used for fp32 caches and
 // for shapes the matrix-core tile does not cover; not a tuned path.
 // ---------------------------------------------------------------------------
-template <typename T> __device__ inline float to_f32(T x);
-template <> __device__ inline float to_f32<float>(float x) { return x; }
-template <> __device__ inline float to_f32<uint16_t>(uint16_t x) { return __uint_as_float((unsigned)x << 16); }
-
 template <typename T>
 __global__ void __launch_bounds__(kAttnThreads)
 k_attn_generic(Ctx c, DecodeArgs a) {
@@ -489,42 +391,7 @@ k_attn_generic(Ctx c, DecodeArgs a) {
         const T* qrow = q + ((long long)row * dm.Hq + h * dm.G + r) * D;
         float m = -__builtin_inff(), l = 0.f;
         float o[4] = {0.f, 0.f, 0.f, 0.f};   // d = lane + 64*c
-        for (int p = r0; p < r0 + rn; ++p) {
-          const int page = table[p];
-          const int nvalid = min(pt, tokens - p * pt);
-          const long long kb = tile_base(dm, page, h), vb = kb + dm.tile_elems;
-          for (int t0 = 0; t0 < nvalid; t0 += 64) {
-            const int t = t0 + lane;
-            float s = -__builtin_inff();
-            if (t < nvalid) {
-              float dot = 0.f;
-              for (int d = 0; d < D; ++d) dot = fmaf(to_f32<T>(qrow[d]), to_f32<T>(pool[kb + (long long)t * D + d]), dot);
-              s = dot * a.scale_log2;
-            }
-            float mx = s;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-            const float m_new = fmaxf(m, mx);
-            const float alpha = exp2f(m - m_new);
-            const float pw = t < nvalid ? exp2f(s - m_new) : 0.f;
-            float ps = pw;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) ps += __shfl_xor(ps, off, 64);
-            l = l * alpha + ps;
-            m = m_new;
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) o[cc] *= alpha;
-            const int nt = min(64, nvalid - t0);
-            for (int j = 0; j < nt; ++j) {
-              const float pj = __shfl(pw, j, 64);
-#pragma unroll
-              for (int cc = 0; cc < 4; ++cc) {
-                const int d = lane + 64 * cc;
-                if (d < D) o[cc] = fmaf(pj, to_f32<T>(pool[vb + (long long)(t0 + j) * D + d]), o[cc]);
-              }
-            }
-          }
-        }
+        generic_row<T>(dm, pool, table, r0, rn, tokens, h, qrow, a.scale_log2, m, l, o);
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) {
           const int d = lane + 64 * cc;

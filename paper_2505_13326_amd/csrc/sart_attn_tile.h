@@ -1,0 +1,161 @@
+// Tiles shared by the attention kernels (gfx950).  Matrix-core tile: one
+// 16-token page of K and V against 16 query rows, with the online-softmax state
+// of those rows.  Vector-ALU row routine for the untuned generic path.
+#pragma once
+
+#include "sart_device.h"
+
+namespace sart {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// Online-softmax state of one wave for one (row, kv head): the 16 x d tile
+// O^T as matrix-core accumulators, running max m and per-lane partial sum l.
+// Lane (r = lane & 15, g = lane >> 4) holds head r, tokens 4g..4g+3 of a page
+// and output columns d = 16*blk + 4g + j.
+// ---------------------------------------------------------------------------
+template <int D>
+struct WaveState {
+  f32x4 o[D / 16];
+  float m, l;
+  __device__ inline void reset() {
+#pragma unroll
+    for (int b = 0; b < D / 16; ++b) o[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    m = -__builtin_inff();
+    l = 0.f;
+  }
+};
+
+// max over the four 16-lane rows of a wave for every column (lane & 15), on
+// the vector ALU: v_permlane32_swap / v_permlane16_swap exchange half-waves and
+// odd/even rows between two registers; feeding the same value twice and taking
+// the max of both results is the pairwise max whichever half is swapped.
+__device__ inline float max_over_rows(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const unsigned v = __float_as_uint(x);
+  const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ inline float sum_over_rows(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const unsigned v = __float_as_uint(x);
+  const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// One 16-token page: kq[i] / vq[i] are the 16-byte chunks this lane loaded
+// (chunk i*64 + lane of the K resp. V tile), qreg the Q^T operand.  FULL: all
+// 16 tokens are valid (no masking code).  Scores are kept in the log2 domain:
+// p = 2^(s*c - m) with c = scale*log2(e).
+// Not FULL: tokens >= nvalid of the page do not exist (their K/V bytes may be
+// anything): their scores are masked and their V rows zeroed; nvalid is
+// wave-uniform.  nvalid_row (per lane, by its query row lane & 15; <= nvalid)
+// masks further scores of that row only: the causal bound of prefill.
+template <int D, bool FULL>
+__device__ inline void process_page(WaveState<D>& st, const uint4* kq, const uint4* vq, const uint4* qreg,
+                                    int nvalid, int nvalid_row, float scale_log2) {
+  const int g = (threadIdx.x & 63) >> 4;
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i)
+    s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kq[i]),
+                                                __builtin_bit_cast(bf16x8, qreg[i]), s, 0, 0, 0);
+  uint4 vloc[D / 32];
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i) vloc[i] = vq[i];
+  if (!FULL) {
+    const int t0 = 4 * g;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (t0 + j >= nvalid_row) s[j] = -__builtin_inff();
+    const unsigned m01 = (t0 + 0 < nvalid ? 0x0000ffffu : 0u) | (t0 + 1 < nvalid ? 0xffff0000u : 0u);
+    const unsigned m23 = (t0 + 2 < nvalid ? 0x0000ffffu : 0u) | (t0 + 3 < nvalid ? 0xffff0000u : 0u);
+#pragma unroll
+    for (int i = 0; i < D / 32; ++i) {
+      vloc[i].x &= m01; vloc[i].y &= m23; vloc[i].z &= m01; vloc[i].w &= m23;
+    }
+  }
+  float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+  mx = max_over_rows(mx) * scale_log2;           // scale > 0: max commutes with the scaling
+  const float m_new = fmaxf(st.m, mx);           // finite: a page holds >= 1 valid token
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // 0 on the first page (m = -inf)
+  st.m = m_new;
+  f32x4 p;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[j], scale_log2, -m_new));
+  st.l = st.l * alpha + (p[0] + p[1]) + (p[2] + p[3]);
+  if (__any(alpha != 1.0f)) {
+#pragma unroll
+    for (int b = 0; b < D / 16; ++b) st.o[b] *= alpha;
+  }
+  const s16x4 pb = __builtin_bit_cast(s16x4, __builtin_convertvector(p, bf16x4));
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i) {
+    const uint2 lo = {vloc[i].x, vloc[i].y}, hi = {vloc[i].z, vloc[i].w};
+    st.o[2 * i] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, lo), pb, st.o[2 * i], 0, 0, 0);
+    st.o[2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, hi), pb, st.o[2 * i + 1], 0, 0, 0);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Vector-ALU path (any dtype, SART_LAYOUT_NATURAL, any page size, head dim <=
+// 256): one wave folds pages [r0, r0 + rn) of `table` into the online-softmax
+// state (m, l, o) of one query row; `tokens` = tokens of the sequence the
+// table describes (the last page may be partly filled).  Lane holds output
+// columns d = lane + 64 c.  Not a tuned path.
+// ---------------------------------------------------------------------------
+template <typename T> __device__ inline float to_f32(T x);
+template <> __device__ inline float to_f32<float>(float x) { return x; }
+template <> __device__ inline float to_f32<uint16_t>(uint16_t x) { return __uint_as_float((unsigned)x << 16); }
+
+template <typename T>
+__device__ inline void generic_row(const Dims& dm, const T* pool, const int* table, int r0, int rn, int tokens, int h,
+                                   const T* qrow, float scale_log2, float& m, float& l, float (&o)[4]) {
+  const int lane = threadIdx.x & 63, D = dm.d, pt = dm.pt;
+  for (int p = r0; p < r0 + rn; ++p) {
+    const int page = table[p];
+    const int nvalid = min(pt, tokens - p * pt);
+    const long long kb = tile_base(dm, page, h), vb = kb + dm.tile_elems;
+    for (int t0 = 0; t0 < nvalid; t0 += 64) {
+      const int t = t0 + lane;
+      float s = -__builtin_inff();
+      if (t < nvalid) {
+        float dot = 0.f;
+        for (int d = 0; d < D; ++d) dot = fmaf(to_f32<T>(qrow[d]), to_f32<T>(pool[kb + (long long)t * D + d]), dot);
+        s = dot * scale_log2;
+      }
+      float mx = s;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+      const float m_new = fmaxf(m, mx);
+      const float alpha = exp2f(m - m_new);
+      const float pw = t < nvalid ? exp2f(s - m_new) : 0.f;
+      float ps = pw;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) ps += __shfl_xor(ps, off, 64);
+      l = l * alpha + ps;
+      m = m_new;
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) o[cc] *= alpha;
+      const int nt = min(64, nvalid - t0);
+      for (int j = 0; j < nt; ++j) {
+        const float pj = __shfl(pw, j, 64);
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+          const int d = lane + 64 * cc;
+          if (d < D) o[cc] = fmaf(pj, to_f32<T>(pool[vb + (long long)(t0 + j) * D + d]), o[cc]);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace sart

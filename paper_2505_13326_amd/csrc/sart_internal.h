@@ -220,6 +220,21 @@ struct DecodeArgs {
 };
 void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s);
 
+struct PrefillArgs {
+  int n_seqs;
+  const int* ids;         // device: request of every listed sequence
+  const int* nq;          // device: queries per sequence (its last nq prompt tokens)
+  const int* q_off;       // device: first row of the sequence in q / out
+  const int* tile_start;  // device: first workgroup tile of the sequence (matrix-core kernel)
+  const void* q;
+  float* out;
+  float scale_log2;
+  int call_seq;
+  int n_tiles;
+  int total_q;
+};
+void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s);
+
 void launch_init_tables(const Ctx& c, const int* free_order_dev, hipStream_t s);
 
 }  // namespace sart

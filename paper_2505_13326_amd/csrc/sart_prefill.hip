@@ -1,0 +1,205 @@
+// Prefill attention over a request's prompt (Algorithm 1, Prefill; arXiv
+// 2505.13326).  The paper treats the prefill phase as that of plain LLM
+// inference (Section 4), so what is computed is causal self-attention: the
+// query of the prompt token at position p reads prompt tokens 0..p through the
+// request's prefix table.  A call names requests and, for each, how many of its
+// last prompt tokens are the queries (all of them: whole prefill; fewer: one
+// chunk of a chunked prefill, after that chunk's K/V was appended).
+//
+// Design for MI355X (gfx950).  Unlike decode this is a dense contraction with
+// reuse: a K/V page serves every later query.  The rows of one kv head -
+// (query, head of the GQA group), query-major - are cut into tiles of 256; a
+// 4-wave workgroup takes a tile, each wave 64 rows as four 16-row blocks of the
+// same matrix-core tile the decode kernel uses (S^T = K Q^T, 16x16x32 bf16;
+// O^T += V^T P^T, 16x16x16 bf16; online softmax on the vector ALUs), so a page
+// loaded into registers once is used by four blocks, and the four waves of a
+// workgroup walk the same pages together (the first load of a page brings it to
+// the CU's cache for the others).  A wave reads its pages double-buffered, with
+// unconditional loads.  Blocks skip pages that lie wholly after their rows'
+// positions and mask scores only on the pages that straddle them.  No split
+// over the sequence: one wave sees a row's whole context, so there is no merge.
+#include "sart_attn_tile.h"
+
+namespace sart {
+
+constexpr int kPfBlocks = 4;                                  // 16-row blocks per wave
+constexpr int kPfRowsPerWave = 16 * kPfBlocks;
+constexpr int kPfRowsPerWg = kPfRowsPerWave * kAttnWaves;
+
+// Device-side validation of the call (one workgroup): every listed request must
+// be live and hold at least as many prompt tokens as it has queries.
+__global__ void __launch_bounds__(256)
+k_prefill_check(Ctx c, PrefillArgs a) {
+  const Tables& tb = c.tb;
+  __shared__ int s_err;
+  if (threadIdx.x == 0) s_err = 0x7fffffff;
+  __syncthreads();
+  for (int i = threadIdx.x; i < a.n_seqs; i += blockDim.x) {
+    const int r = a.ids[i];
+    int err = 0;
+    if (!tb.req_used[r] || tb.refcnt[r] == 0) err = SART_E_STATE;
+    else if (a.nq[i] > tb.prefix_len[r]) err = SART_E_INVALID;
+    if (err) atomicMin(&s_err, (i << 2) | err);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (s_err != 0x7fffffff) record_error(tb.scal, s_err & 3, a.call_seq);
+    else tb.scal[S_CALLOK] = 1;
+  }
+}
+
+// index of the last entry of the ascending array v[0..n) that is <= x (v[0] <= x)
+__device__ inline int last_le(const int* v, int n, int x) {
+  int lo = 0, hi = n - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (v[mid] <= x) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+template <int D>
+__global__ void __launch_bounds__(kAttnThreads)
+k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  if (!tb.scal[S_CALLOK]) return;
+  constexpr int KQ = D / 32;
+  constexpr int kTileBytes = 16 * D * 2, kPageBytes = 2 * kTileBytes;
+  const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r16 = lane & 15, g4 = lane >> 4;
+  // tile -> (sequence, kv head, row tile); a sequence's later rows (longer contexts) come first
+  const int tile = blockIdx.x;
+  const int i = last_le(a.tile_start, a.n_seqs, tile);
+  const int req = a.ids[i], nq = a.nq[i], plen = tb.prefix_len[req];
+  const int n_rows = nq * dm.G;
+  const int tiles_per_head = ceil_div(n_rows, kPfRowsPerWg);
+  const int local = tile - a.tile_start[i];
+  const int h = local / tiles_per_head;
+  const int rt = tiles_per_head - 1 - local % tiles_per_head;
+  const int row_w0 = rt * kPfRowsPerWg + wv * kPfRowsPerWave;
+  if (row_w0 >= n_rows) return;
+  const int p_first = plen - nq;                           // prompt position of the call's first query
+  const long long q_row0 = a.q_off[i];
+  const uint16_t* q = (const uint16_t*)a.q;
+  const unsigned char* pool = (const unsigned char*)c.pool;
+  const int* __restrict__ table = prefix_table + (long long)req * dm.max_pp;
+  const long long page_bytes = dm.page_elems * 2;
+  const long long head_off = (long long)h * kPageBytes + lane * 16;
+
+  // per 16-row block: this lane's row, its position, the block's position range
+  WaveState<D> st[kPfBlocks];
+  uint4 qreg[kPfBlocks][KQ];
+  int pos[kPfBlocks], lo_pos[kPfBlocks], hi_pos[kPfBlocks];
+  long long out_row[kPfBlocks];                            // element offset of this lane's output row, -1: no row
+#pragma unroll
+  for (int b = 0; b < kPfBlocks; ++b) {
+    const int row0 = row_w0 + 16 * b;
+    const int row = row0 + r16;
+    const bool have = row < n_rows;
+    const int rc = have ? row : n_rows - 1;               // rows past the end shadow the last one, and are not stored
+    const int ql = rc / dm.G, g = rc % dm.G;
+    pos[b] = p_first + ql;
+    lo_pos[b] = row0 < n_rows ? p_first + row0 / dm.G : -1;
+    hi_pos[b] = row0 < n_rows ? p_first + min(row0 + 15, n_rows - 1) / dm.G : -1;
+    const long long qrow = ((q_row0 + ql) * dm.Hq + h * dm.G + g) * D;
+    out_row[b] = have ? qrow : -1;
+#pragma unroll
+    for (int k = 0; k < KQ; ++k) qreg[b][k] = *(const uint4*)(q + qrow + k * 32 + g4 * 8);
+    st[b].reset();
+  }
+  const int last_pos = p_first + min(row_w0 + kPfRowsPerWave - 1, n_rows - 1) / dm.G;
+  const int n_pages = last_pos / 16 + 1;
+
+  auto load_page = [&](uint4* kq, uint4* vq, int pid) {
+    const unsigned char* base = pool + (long long)pid * page_bytes + head_off;
+#pragma unroll
+    for (int k = 0; k < KQ; ++k) {
+      kq[k] = *(const uint4*)(base + k * 1024);
+      vq[k] = *(const uint4*)(base + kTileBytes + k * 1024);
+    }
+  };
+  auto process = [&](int pg, const uint4* kq, const uint4* vq) {
+    const int t0 = pg * 16;
+    const int nvalid = min(16, plen - t0);                 // tokens the page holds
+#pragma unroll
+    for (int b = 0; b < kPfBlocks; ++b) {
+      if (t0 > hi_pos[b]) continue;                        // the page lies after every row of the block
+      if (t0 + 15 <= lo_pos[b]) process_page<D, true>(st[b], kq, vq, qreg[b], 16, 16, a.scale_log2);
+      else process_page<D, false>(st[b], kq, vq, qreg[b], nvalid, min(nvalid, pos[b] + 1 - t0), a.scale_log2);
+    }
+  };
+  // two register page buffers; every load is unconditional (past the end the last page again)
+  uint4 ka[KQ], va[KQ], kb[KQ], vb[KQ];
+  load_page(ka, va, table[0]);
+  for (int pg = 0; pg < n_pages; pg += 2) {
+    load_page(kb, vb, table[min(pg + 1, n_pages - 1)]);
+    process(pg, ka, va);
+    load_page(ka, va, table[min(pg + 2, n_pages - 1)]);
+    if (pg + 1 < n_pages) process(pg + 1, kb, vb);
+  }
+#pragma unroll
+  for (int b = 0; b < kPfBlocks; ++b) {
+    const float l = sum_over_rows(st[b].l);
+    if (out_row[b] < 0) continue;
+    const float inv = 1.0f / l;                            // every row sees at least its own token
+    float* o = a.out + out_row[b];
+#pragma unroll
+    for (int k = 0; k < D / 16; ++k) *(f32x4*)(o + k * 16 + 4 * g4) = st[b].o[k] * inv;
+  }
+}
+
+// Any dtype, SART_LAYOUT_NATURAL: one wave per (query, kv head), the heads of
+// the group one after the other on the vector ALUs.  Not a tuned path.
+template <typename T>
+__global__ void __launch_bounds__(kAttnThreads)
+k_prefill_generic(Ctx c, PrefillArgs a) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  if (!tb.scal[S_CALLOK]) return;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const T* pool = (const T*)c.pool;
+  const T* q = (const T*)a.q;
+  const int D = dm.d;
+  const long long units = (long long)a.total_q * dm.Hkv;
+  for (long long u = (long long)blockIdx.x * kAttnWaves + wv; u < units; u += (long long)gridDim.x * kAttnWaves) {
+    const int gq = (int)(u / dm.Hkv), h = (int)(u % dm.Hkv);
+    const int i = last_le(a.q_off, a.n_seqs, gq);
+    const int req = a.ids[i];
+    const int tokens = tb.prefix_len[req] - a.nq[i] + (gq - a.q_off[i]) + 1;     // prompt tokens 0..p
+    const int* table = tb.prefix_table + (long long)req * dm.max_pp;
+    for (int r = 0; r < dm.G; ++r) {
+      const long long row = ((long long)gq * dm.Hq + h * dm.G + r) * D;
+      float m = -__builtin_inff(), l = 0.f;
+      float o[4] = {0.f, 0.f, 0.f, 0.f};
+      generic_row<T>(dm, pool, table, 0, ceil_div(tokens, dm.pt), tokens, h, q + row, a.scale_log2, m, l, o);
+      const float inv = 1.0f / l;
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) {
+        const int d = lane + 64 * cc;
+        if (d < D) a.out[row + d] = o[cc] * inv;
+      }
+    }
+  }
+}
+
+void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s) {
+  const Dims& dm = c.dm;
+  hipLaunchKernelGGL(k_prefill_check, dim3(1), dim3(256), 0, s, c, a);
+  if (a.total_q <= 0) return;
+  if (dm.layout == SART_LAYOUT_MFMA16) {
+    if (dm.d == 128)
+      hipLaunchKernelGGL(k_prefill_mfma<128>, dim3(a.n_tiles), dim3(kAttnThreads), 0, s, c, a, c.tb.prefix_table);
+    else
+      hipLaunchKernelGGL(k_prefill_mfma<64>, dim3(a.n_tiles), dim3(kAttnThreads), 0, s, c, a, c.tb.prefix_table);
+  } else {
+    long long blocks = ((long long)a.total_q * dm.Hkv + kAttnWaves - 1) / kAttnWaves;
+    if (blocks > 65536) blocks = 65536;
+    if (dm.dtype == SART_F32)
+      hipLaunchKernelGGL(k_prefill_generic<float>, dim3((unsigned)blocks), dim3(kAttnThreads), 0, s, c, a);
+    else
+      hipLaunchKernelGGL(k_prefill_generic<uint16_t>, dim3((unsigned)blocks), dim3(kAttnThreads), 0, s, c, a);
+  }
+}
+
+}  // namespace sart

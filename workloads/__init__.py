@@ -26,7 +26,7 @@ import numpy as np
 BASE_SEED = 2505133260
 
 # stream kinds
-_S_LENGTHS, _S_TARGETS, _S_SCORES, _S_PREFIX, _S_BRANCH, _S_QUERY, _S_STEP_KV, _S_PERM = range(8)
+_S_LENGTHS, _S_TARGETS, _S_SCORES, _S_PREFIX, _S_BRANCH, _S_QUERY, _S_STEP_KV, _S_PERM, _S_PREFIX_Q = range(9)
 
 
 def _rng(cfg_id: int, kind: int, index: int = 0) -> np.random.Generator:
@@ -159,6 +159,14 @@ def prefix_kv(cfg: Config, request: int, n_tokens: int | None = None):
     g = _rng(cfg.cfg_id, _S_PREFIX, request)
     kv = _normal(cfg, g, (2, n, cfg.n_kv_heads, cfg.head_dim))
     return kv[0], kv[1]
+
+
+def prefix_query(cfg: Config, request: int, n_tokens: int | None = None) -> np.ndarray:
+    """Queries of a request's prompt tokens (prefill): [P, Hq, d]; a prefix of
+    the same stream for a shorter prompt."""
+    n = cfg.prompt_len if n_tokens is None else n_tokens
+    g = _rng(cfg.cfg_id, _S_PREFIX_Q, request)
+    return _normal(cfg, g, (n, cfg.n_q_heads, cfg.head_dim))
 
 
 def branch_kv(cfg: Config, handle: int, n_tokens: int):
