@@ -40,6 +40,74 @@ def _request_arrays(wl, cfg, r, L):
     return r, pk, pv, ids, ns, np.concatenate([x[0] for x in kv]), np.concatenate([x[1] for x in kv])
 
 
+def bench_prefill(args, cfg, sart, wl, np, torch):
+    """Prefill attention (Algorithm 1, Prefill) over the prompts of a configuration: one library call attends
+    every request's whole prompt (causal).  The prompts' K/V are appended beforehand (not timed: they are the
+    model's output, not this library's work).  value = algorithmic causal flops / time."""
+    R, P = cfg.n_requests, cfg.prompt_len
+    pp = -(-P // cfg.page_tokens)
+    num_pages = R * pp + 8
+    cache = sart.SartCache(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+                           page_tokens=cfg.page_tokens, num_pages=num_pages, max_requests=R, branches_per_request=cfg.nb,
+                           max_pages_per_branch=4, max_prefix_pages=pp, dtype=cfg.dtype,
+                           free_order=wl.free_order(cfg, num_pages) if args.free_order == "scattered" else None)
+
+    def dev(x):
+        return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).view(torch.bfloat16).cuda()
+    qs = []
+    for r in range(R):
+        k, v = wl.prefix_kv(cfg, r)
+        cache.append_tokens(sart.SEQ_PREFIX, [r], [P], k, v)
+        qs.append(wl.prefix_query(cfg, r))
+    q = dev(np.concatenate(qs))
+    out = torch.empty((R * P, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+    ids, nq = list(range(R)), [P] * R
+    assert cache.sync_status() == 0
+    K, W = args.steps, args.warmup
+    for _ in range(W):
+        cache.prefill_attention(ids, nq, q, out=out)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record()
+    for _ in range(K):
+        cache.prefill_attention(ids, nq, q, out=out)
+    ev[1].record()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / K
+    k_ms = ev[0].elapsed_time(ev[1]) / K
+    assert cache.sync_status() == 0
+    flops = R * 4.0 * cfg.head_dim * cfg.n_q_heads * P * (P + 1) / 2
+    kv_bytes = R * P * cfg.token_bytes
+    roofline = {"bound": "mfma", "kernel": "k_prefill_mfma", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
+                "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / (k_ms * 1e-3) / 1e12 / 2500.0, 4), "traffic": None,
+                "algorithmic_flops_per_launch": int(flops), "kernel_ms_avg": round(k_ms, 4),
+                "note": "events on the call's stream around all timed calls (validation kernel included)"}
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        n = args.cpu_sample_requests or 1
+        oc = orc.OracleCache(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+                             page_tokens=cfg.page_tokens, num_pages=n * pp + 4, max_requests=R, branches_per_request=cfg.nb,
+                             finish_quota=0, max_pages_per_branch=4, max_prefix_pages=pp, dtype=cfg.dtype)
+        for r in range(n):
+            k, v = wl.prefix_kv(cfg, r)
+            assert oc.append(0, [r], [P], k, v) == 0
+        t1 = time.perf_counter()
+        for r in range(n):
+            oc.prefill_attention(r, qs[r])
+        dt_cpu = time.perf_counter() - t1
+        cpu = {"value": round(n * flops / R / dt_cpu / 1e12, 5), "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+               "sample": f"whole prompts of {n} of {R} requests, float64", "seconds": round(dt_cpu, 2)}
+    print(json.dumps({
+        "metric": "prefill attention, algorithmic causal flops per second", "value": round(flops / dt / 1e12, 2),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(dt * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"prompts of config {cfg.cfg_id}: {R} requests x {P} tokens, Hq {cfg.n_q_heads} / Hkv "
+                               f"{cfg.n_kv_heads}, d {cfg.head_dim}, one call", "kv_bytes": kv_bytes},
+        "roofline": roofline, "cpu_baseline": cpu}))
+
+
 def bench_trace(args, cfg, sart, wl, np, torch):
     """Config 3: the whole 400-step early-stop / prune loop (append + attention + finish + prune, host
     step loop included).  value = branch-decode-steps per second over the loop."""
@@ -94,9 +162,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "copy"],
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "copy", "prefill4", "prefill5"],
                     help="copy = a plain 1 GiB device copy, the known-size kernel that calibrates the "
-                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters; prefillN = prefill attention over the prompts "
+                         "of config N")
     ap.add_argument("--free-order", default="scattered", choices=["scattered", "identity"])
     ap.add_argument("--workgroups", type=int, default=0, help="attention workgroups (0 = library default)")
     ap.add_argument("--chunk-pages", type=int, default=0, help="prompt chunk in pages (0 = chosen on device)")
@@ -136,9 +205,11 @@ def main():
         print(json.dumps({"metric": "device copy", "bytes_read": n, "bytes_written": n, "steps": args.steps,
                           "ms_per_step": round(dt * 1e3, 4), "value": round(2 * n / dt / 1e9, 1), "unit": "GB/s"}))
         return
-    cfg = wl.CONFIGS[int(args.workload[3:])]
+    cfg = wl.CONFIGS[int(args.workload[-1])]
     if args.prompt_len >= 0:
         cfg = wl.scaled(cfg, prompt_len=args.prompt_len)
+    if args.workload.startswith("prefill"):
+        return bench_prefill(args, cfg, sart, wl, np, torch)
     if cfg.cfg_id == 3:
         return bench_trace(args, cfg, sart, wl, np, torch)
     K, W = args.steps, args.warmup

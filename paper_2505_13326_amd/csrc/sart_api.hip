@@ -349,7 +349,7 @@ sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs,
   if (n_seqs < 0 || n_seqs > dm.max_req) return fail(SART_E_INVALID, "n_seqs out of range");
   if (n_seqs > 0 && (!request_ids || !n_q)) return fail(SART_E_INVALID, "null request_ids or n_q");
   long long total = 0, tiles = 0;
-  const int rows_per_tile = 16 * 4 * kAttnWaves;            // the matrix-core kernel's workgroup tile
+  const int rows_per_tile = kPfTileRows;                    // the matrix-core kernel's workgroup tile
   for (int i = 0; i < n_seqs; ++i) {
     if (request_ids[i] < 0 || request_ids[i] >= dm.max_req)
       return fail(SART_E_INVALID, "request %d out of range at %d", request_ids[i], i);

@@ -13,6 +13,8 @@ constexpr int kPlanThreads = 1024;     // single-workgroup planning kernels
 constexpr int kAttnWaves = 4;          // waves per attention workgroup (one per SIMD, one workgroup per CU)
 constexpr int kAttnThreads = kAttnWaves * kWave;
 constexpr int kStagePages = 4;         // prefix pages staged in LDS per pipeline stage
+constexpr int kPfBlocks = 2;           // prefill: 16-row blocks per wave (two waves per SIMD fit the registers)
+constexpr int kPfTileRows = 16 * kPfBlocks * kAttnWaves;   // prefill: rows of one workgroup tile
 constexpr int kMaxGroup = 16;          // query heads per KV head the MFMA tile holds
 
 // Indices into the device scalar block.

@@ -8,23 +8,28 @@
 //
 // Design for MI355X (gfx950).  Unlike decode this is a dense contraction with
 // reuse: a K/V page serves every later query.  The rows of one kv head -
-// (query, head of the GQA group), query-major - are cut into tiles of 256; a
-// 4-wave workgroup takes a tile, each wave 64 rows as four 16-row blocks of the
-// same matrix-core tile the decode kernel uses (S^T = K Q^T, 16x16x32 bf16;
-// O^T += V^T P^T, 16x16x16 bf16; online softmax on the vector ALUs), so a page
-// loaded into registers once is used by four blocks, and the four waves of a
-// workgroup walk the same pages together (the first load of a page brings it to
-// the CU's cache for the others).  A wave reads its pages double-buffered, with
-// unconditional loads.  Blocks skip pages that lie wholly after their rows'
-// positions and mask scores only on the pages that straddle them.  No split
-// over the sequence: one wave sees a row's whole context, so there is no merge.
+// (query, head of the GQA group), query-major - are cut into tiles of
+// kPfTileRows; a 4-wave workgroup takes a tile, each wave kPfBlocks 16-row
+// blocks of the matrix-core tile the decode kernel uses (S^T = K Q^T and
+// O^T += V^T P^T as 16x16x32 bf16 products; online softmax on the vector ALUs).
+// Pages are taken two at a time (32 tokens): one running-max update per 32
+// tokens.  A page pair loaded into registers is used by all blocks of the wave,
+// and the four waves of a workgroup walk the same pages together (the first
+// load of a page brings it to the CU's cache for the others).  Work goes phase
+// by phase over the wave's blocks - scores of all blocks, softmax updates,
+// O^T products - so K's registers are free for the next pair's loads after the
+// first phase and V's after the last; every load is unconditional.  Two blocks
+// per wave keep a wave under 256 registers, so two waves share a SIMD and one's
+// vector work overlaps the other's matrix-core work.  Blocks skip pairs that lie
+// wholly after their rows' positions and mask scores only on the pairs that
+// straddle them.  No split over the sequence: one wave sees a row's whole
+// context, so there is no merge.
 #include "sart_attn_tile.h"
 
 namespace sart {
 
-constexpr int kPfBlocks = 4;                                  // 16-row blocks per wave
 constexpr int kPfRowsPerWave = 16 * kPfBlocks;
-constexpr int kPfRowsPerWg = kPfRowsPerWave * kAttnWaves;
+constexpr int kPfRowsPerWg = kPfRowsPerWave * kAttnWaves;       // = kPfTileRows
 
 // Device-side validation of the call (one workgroup): every listed request must
 // be live and hold at least as many prompt tokens as it has queries.
@@ -59,7 +64,7 @@ __device__ inline int last_le(const int* v, int n, int x) {
 }
 
 template <int D>
-__global__ void __launch_bounds__(kAttnThreads)
+__global__ void __launch_bounds__(kAttnThreads, 2)
 k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
@@ -111,32 +116,53 @@ k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   const int last_pos = p_first + min(row_w0 + kPfRowsPerWave - 1, n_rows - 1) / dm.G;
   const int n_pages = last_pos / 16 + 1;
 
-  auto load_page = [&](uint4* kq, uint4* vq, int pid) {
-    const unsigned char* base = pool + (long long)pid * page_bytes + head_off;
+  // Pages are taken two at a time (32 tokens); an odd last page is paired with itself, masked.
+  // One register buffer per operand: K of the next pair is requested as soon as the scores of all
+  // blocks are done, V after the last O^T product, so each load has half a turn to arrive.  Every
+  // load is unconditional (past the end the last pair again).
+  const int n_pairs = (n_pages + 1) >> 1;
+  uint4 k0[KQ], k1[KQ], v0[KQ], v1[KQ];
+  auto load_k = [&](int pr) {
+    const unsigned char* b0 = pool + (long long)table[2 * pr] * page_bytes + head_off;
+    const unsigned char* b1 = pool + (long long)table[min(2 * pr + 1, n_pages - 1)] * page_bytes + head_off;
 #pragma unroll
-    for (int k = 0; k < KQ; ++k) {
-      kq[k] = *(const uint4*)(base + k * 1024);
-      vq[k] = *(const uint4*)(base + kTileBytes + k * 1024);
-    }
+    for (int k = 0; k < KQ; ++k) { k0[k] = *(const uint4*)(b0 + k * 1024); k1[k] = *(const uint4*)(b1 + k * 1024); }
   };
-  auto process = [&](int pg, const uint4* kq, const uint4* vq) {
-    const int t0 = pg * 16;
-    const int nvalid = min(16, plen - t0);                 // tokens the page holds
+  auto load_v = [&](int pr) {
+    const unsigned char* b0 = pool + (long long)table[2 * pr] * page_bytes + head_off + kTileBytes;
+    const unsigned char* b1 = pool + (long long)table[min(2 * pr + 1, n_pages - 1)] * page_bytes + head_off + kTileBytes;
 #pragma unroll
-    for (int b = 0; b < kPfBlocks; ++b) {
-      if (t0 > hi_pos[b]) continue;                        // the page lies after every row of the block
-      if (t0 + 15 <= lo_pos[b]) process_page<D, true>(st[b], kq, vq, qreg[b], 16, 16, a.scale_log2);
-      else process_page<D, false>(st[b], kq, vq, qreg[b], nvalid, min(nvalid, pos[b] + 1 - t0), a.scale_log2);
-    }
+    for (int k = 0; k < KQ; ++k) { v0[k] = *(const uint4*)(b0 + k * 1024); v1[k] = *(const uint4*)(b1 + k * 1024); }
   };
-  // two register page buffers; every load is unconditional (past the end the last page again)
-  uint4 ka[KQ], va[KQ], kb[KQ], vb[KQ];
-  load_page(ka, va, table[0]);
-  for (int pg = 0; pg < n_pages; pg += 2) {
-    load_page(kb, vb, table[min(pg + 1, n_pages - 1)]);
-    process(pg, ka, va);
-    load_page(ka, va, table[min(pg + 2, n_pages - 1)]);
-    if (pg + 1 < n_pages) process(pg + 1, kb, vb);
+  load_k(0);
+  load_v(0);
+  for (int pr = 0; pr < n_pairs; ++pr) {
+    const int t0 = pr * 32;
+    const int nxt = min(pr + 1, n_pairs - 1);
+    if (t0 + 31 <= lo_pos[0]) {
+      // every row of the wave sees the whole pair: phase by phase over the wave's independent blocks
+      f32x4 s0[kPfBlocks], s1[kPfBlocks];
+      bf16x8 pp[kPfBlocks];
+#pragma unroll
+      for (int b = 0; b < kPfBlocks; ++b) pair_scores<D, 1>(k0, k1, qreg[b], s0[b], s1[b]);
+      load_k(nxt);
+#pragma unroll
+      for (int b = 0; b < kPfBlocks; ++b) pp[b] = pair_softmax<D, true>(st[b], s0[b], s1[b], 32, a.scale_log2);
+#pragma unroll
+      for (int b = 0; b < kPfBlocks; ++b) pair_pv<D, true>(st[b], v0, v1, pp[b], 32);
+      load_v(nxt);
+    } else {
+      // pairs that straddle some row's position: block by block, scores masked per row
+      const int nvalid = min(32, min(plen, n_pages * 16) - t0);      // tokens the pair holds
+#pragma unroll
+      for (int b = 0; b < kPfBlocks; ++b) {
+        if (t0 > hi_pos[b]) continue;                        // the pair lies after every row of the block
+        if (t0 + 31 <= lo_pos[b]) process_pair<D, true, 1>(st[b], k0, v0, k1, v1, qreg[b], 32, 32, a.scale_log2);
+        else process_pair<D, false, 1>(st[b], k0, v0, k1, v1, qreg[b], nvalid, min(nvalid, pos[b] + 1 - t0), a.scale_log2);
+      }
+      load_k(nxt);
+      load_v(nxt);
+    }
   }
 #pragma unroll
   for (int b = 0; b < kPfBlocks; ++b) {
