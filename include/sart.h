@@ -62,6 +62,9 @@ typedef enum {
 
 typedef enum { SART_F32 = 0, SART_BF16 = 1 } sart_dtype;
 
+#define SART_ALL_ACTIVE(rows) (-(rows))   /* n_seqs of sart_append_tokens: every active branch (count read on the
+                                             device); k and v hold `rows` >= 1 rows */
+
 typedef enum { SART_SEQ_PREFIX = 0, SART_SEQ_BRANCH = 1 } sart_seq_kind;
 
 /* Branch life cycle (Algorithm 1: a branch leaves the batch by completing,
@@ -145,7 +148,15 @@ int32_t sart_cache_layout(const sart_cache* cache); /* sart_kv_layout */
  *     of that request (SART_E_STATE after).  ids must not be NULL.
  *   SART_SEQ_BRANCH: ids are branch handles, all ACTIVE (else SART_E_STATE);
  *     ids == NULL means every active branch in active order and then n_seqs
- *     must equal the active count (else SART_E_INVALID).
+ *     must equal the active count (else SART_E_INVALID), or be
+ *     SART_ALL_ACTIVE(rows) = -rows: one token for every active branch, however
+ *     many there are when the call executes (ids and n_tokens NULL; k and v
+ *     hold `rows` rows, the library reads the first active-count of them; more
+ *     active branches than rows: SART_E_INVALID, nothing changes).  That
+ *     form stages no host data and bakes no count into the launch, so a decode
+ *     step recorded into a HIP graph (this call, then sart_decode_attention
+ *     with n_rows = capacity of q and out) can be replayed while branches are
+ *     pruned or finished between replays.
  *   n_tokens == NULL means one token per sequence.
  * Pages are popped from the free stack sequence by sequence in list order,
  * each sequence taking its new pages in ascending logical page order.

@@ -163,11 +163,21 @@ class SartCache:
         return x.contiguous()
 
     # -- the five calls -----------------------------------------------------
-    def append_tokens(self, kind, ids, n_tokens, k, v, stream=None, status=False):
-        """sart_append_tokens.  k, v: [sum n, Hkv, d] device tensors (or numpy, copied to the device)."""
+    def append_tokens(self, kind, ids, n_tokens, k, v, stream=None, status=False, all_active=False):
+        """sart_append_tokens.  k, v: [sum n, Hkv, d] device tensors (or numpy, copied to the device).
+        all_active: SART_ALL_ACTIVE (one token per active branch, count read on the device; k, v hold
+        at least that many rows)."""
         ids_a, nt_a = _i32(ids), _i32(n_tokens)
         k = self._dev(k, (self.Hkv, self.d))
         v = self._dev(v, (self.Hkv, self.d))
+        if all_active:
+            assert ids is None and n_tokens is None and k.shape == v.shape and k.shape[0] >= 1
+            rc = self.lib.sart_append_tokens(self.h, kind, -int(k.shape[0]), None, None, C.c_void_p(k.data_ptr()),
+                                             C.c_void_p(v.data_ptr()), 0, _stream_handle(stream))
+            if status:
+                return rc if rc != OK else self.sync_status()
+            self._check(rc)
+            return OK
         n_seqs = len(ids_a) if ids_a is not None else (len(nt_a) if nt_a is not None else k.shape[0])
         total = int(nt_a.sum()) if nt_a is not None else n_seqs
         if k.shape[0] != total or v.shape[0] != total:

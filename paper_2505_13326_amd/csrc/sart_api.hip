@@ -265,6 +265,17 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
   const Dims& dm = c->ctx.dm;
   if (layer != 0) return fail(SART_E_INVALID, "layer must be 0");
   if (kind != SART_SEQ_PREFIX && kind != SART_SEQ_BRANCH) return fail(SART_E_INVALID, "unknown sequence kind");
+  if (n_seqs < 0 && kind == SART_SEQ_BRANCH && !ids && !n_tokens) {   // SART_ALL_ACTIVE(rows)
+    if (!k || !v) return fail(SART_E_INVALID, "null k or v");
+    hipStream_t st = (hipStream_t)stream;
+    note_stream(c, stream);
+    AppendArgs a{};
+    a.kind = kind; a.n_seqs = n_seqs; a.total_rows = n_seqs < -dm.H ? dm.H : -n_seqs; a.k = k; a.v = v;
+    a.call_seq = ++c->call_seq;
+    launch_append(c->ctx, c->plan, a, st);
+    HIP_TRY(hipGetLastError());
+    return SART_OK;
+  }
   if (n_seqs < 0) return fail(SART_E_INVALID, "negative n_seqs");
   if (kind == SART_SEQ_PREFIX && !ids && n_seqs > 0) return fail(SART_E_INVALID, "prefix append needs request ids");
   const int limit = kind == SART_SEQ_PREFIX ? dm.max_req : dm.H;

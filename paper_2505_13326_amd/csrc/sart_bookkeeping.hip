@@ -65,9 +65,16 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
   const int top = scal[S_FREETOP];
   if (tid == 0) s_err = 0x7fffffff;
   __syncthreads();
-  if (!a.ids && a.n_seqs != nA) {
+  if (!a.ids && a.n_seqs >= 0 && a.n_seqs != nA) {
     if (tid == 0) record_error(scal, SART_E_INVALID, a.call_seq);
     return;
+  }
+  if (a.n_seqs < 0) {                     // "all active branches, however many there are now"; -n_seqs rows given
+    if (nA > -a.n_seqs) {
+      if (tid == 0) record_error(scal, SART_E_INVALID, a.call_seq);
+      return;
+    }
+    a.n_seqs = nA;
   }
   // pass 1: validate, compute pages needed, stash id / start length
   int carry = 0, carry_new = 0;
@@ -166,7 +173,8 @@ k_append_write(Ctx c, AppendArgs a) {
   const int lane = threadIdx.x & 63;
   const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
-  const long long units = a.total_rows * dm.Hkv;
+  // n_seqs < 0: one row per active branch (a branch append leaves the active list as it is)
+  const long long units = (a.n_seqs < 0 ? (long long)tb.scal[S_NACTIVE] : a.total_rows) * dm.Hkv;
   const int* bt = tb.bt[tb.scal[S_BTSEL]];
   T* pool = (T*)c.pool;
   for (long long u = wave; u < units; u += nwaves) {

@@ -1,0 +1,97 @@
+"""A decode step recorded once into a HIP graph and replayed while the batch
+changes under it (the step loop of Algorithm 1, Decode, without a host
+round-trip per call): append one token to every active branch, attend.  The
+plan of the step lives on the device and the all-active append bakes no count
+into the launch, so the same graph serves after branches were finished or
+pruned (eagerly) between replays.  Every replay is checked against the oracle."""
+import numpy as np
+import pytest
+
+import oracle as orc
+import workloads as wl
+from gpu_common import GpuEngine, TOL, dims, populate
+from helpers import assert_state_equal
+
+pytestmark = pytest.mark.gpu
+
+
+def test_decode_step_graph_replays_across_finish_and_prune():
+    import torch
+    cfg = wl.scaled(wl.CONFIGS[2], n_requests=4, nb=8, prompt_len=100, length_params=(150, 0.8), length_cap=900)
+    L = wl.lengths(cfg)
+    steps = 24
+    pages = wl.pages_needed(cfg, L, growth_tokens=steps) + 8
+    kw = dims(cfg, pages, int(-(-(L.max() + steps) // 16)) + 1)
+    fo = wl.free_order(cfg, pages)
+    o = orc.OracleCache(free_order=fo, **kw)
+    g = GpuEngine(free_order=fo, **kw)
+    populate(cfg, [o, g], L)
+    H = cfg.n_handles
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).view(torch.bfloat16).cuda()
+    kbuf = torch.zeros((H, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    vbuf = torch.zeros_like(kbuf)
+    qbuf = torch.zeros((H, cfg.n_q_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros((H, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+
+    def active():
+        st = o.state()
+        return st["active_handles"][:int(st["n_active"][0])]
+
+    def load_inputs(s, act):
+        k, v = wl.step_kv(cfg, s)
+        n = len(act)
+        kbuf[:n].copy_(dev(k[act])); vbuf[:n].copy_(dev(v[act])); qbuf[:n].copy_(dev(wl.query(cfg, s)[act]))
+        return k[act], v[act], wl.query(cfg, s)[act]
+
+    def check(s, act, k, v, q):
+        assert o.append(orc.SEQ_BRANCH, None, None, k, v) == orc.OK
+        assert g.c.sync_status() == 0
+        assert_state_equal(o.state(), g.state())
+        ref = o.attention(q)
+        got = out[:len(act)].cpu().numpy().astype(np.float64)
+        err = float(np.abs(got - ref).max())
+        assert np.all(np.isfinite(got)) and err <= TOL["bf16"], f"step {s}: max abs err {err}"
+
+    # step 1 eagerly on a side stream (also the warm-up the capture needs), then record step 2
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    act = active()
+    k, v, q = load_inputs(1, act)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        g.c.append_tokens(orc.SEQ_BRANCH, None, None, kbuf, vbuf, all_active=True)
+        g.c.decode_attention(qbuf, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    check(1, act, k, v, q)
+
+    graph = torch.cuda.CUDAGraph()
+    k, v, q = load_inputs(2, act)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        g.c.append_tokens(orc.SEQ_BRANCH, None, None, kbuf, vbuf, all_active=True)
+        g.c.decode_attention(qbuf, out=out)
+    graph.replay()                      # capture records, replay runs: this is step 2
+    torch.cuda.synchronize()
+    check(2, act, k, v, q)
+
+    for s in range(3, steps + 1):
+        if s == 8:                      # eager maintenance between replays: the batch shrinks
+            fin = [int(act[1]), int(act[10]), int(act[-1])]
+            assert o.finish(fin) == orc.OK and g.finish(fin) == orc.OK
+        if s == 14:
+            sc = wl.scores(cfg, 0)[act]
+            assert o.prune(orc.DROP_LOWEST_K, sc, k=2) == orc.OK and g.prune(orc.DROP_LOWEST_K, sc, k=2) == orc.OK
+        act = active()
+        k, v, q = load_inputs(s, act)
+        out.fill_(7.0)                  # eager work between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        check(s, act, k, v, q)
+    assert len(act) < H                 # the batch did change under the graph
+
+    # the row capacity of an all-active append is checked on the device
+    small = kbuf[: len(act) - 1]
+    g.c.append_tokens(orc.SEQ_BRANCH, None, None, small, vbuf[: len(act) - 1], all_active=True)
+    assert g.c.sync_status() == orc.E_INVALID
+    assert_state_equal(o.state(), g.state())
