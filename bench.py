@@ -175,6 +175,8 @@ def main():
     ap.add_argument("--prompt-len", type=int, default=-1, help="override the workload's prompt length (experiments)")
     ap.add_argument("--kernel-repeats", type=int, default=8,
                     help="launches of the attention kernel between the two HIP events of the profiled pass")
+    ap.add_argument("--layers", type=int, default=1, help="layers sharing the tables; a step appends to and attends over "
+                    "every layer (same values in every layer)")
     ap.add_argument("--graph", action="store_true", help="replay the step (append + attention) from a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
@@ -214,6 +216,7 @@ def main():
     if cfg.cfg_id == 3:
         return bench_trace(args, cfg, sart, wl, np, torch)
     K, W = args.steps, args.warmup
+    NL = max(1, args.layers)
     L = wl.lengths(cfg)
     growth = K + W + 2 * K + 64           # timed + profiled passes append one token per step
     num_pages = wl.pages_needed(cfg, L, growth_tokens=growth) + 64
@@ -223,7 +226,7 @@ def main():
                            page_tokens=cfg.page_tokens, num_pages=num_pages, max_requests=cfg.n_requests,
                            branches_per_request=cfg.nb, finish_quota=cfg.quota, max_pages_per_branch=max_bp,
                            max_prefix_pages=max(1, cfg.prompt_len // cfg.page_tokens), dtype=cfg.dtype,
-                           free_order=fo)
+                           free_order=fo, n_layers=NL)
     if args.workgroups or args.chunk_pages or args.prompt_mode >= 0 or args.skew is not None or args.prompt_workgroups >= 0:
         cache.set_decode_launch(args.workgroups, args.prompt_workgroups, args.chunk_pages, args.prompt_mode,
                                 50 if args.skew is None else args.skew)
@@ -245,8 +248,15 @@ def main():
     t0 = time.time()
     with ThreadPoolExecutor(max_workers=8) as ex:
         for r, pk, pv, ids, ns, bk, bv in ex.map(lambda r: _request_arrays(wl, cfg, r, L), range(cfg.n_requests)):
-            cache.append_tokens(sart.SEQ_PREFIX, [r], [cfg.prompt_len], pk, pv)
-            cache.append_tokens(sart.SEQ_BRANCH, ids, ns, bk, bv)
+            if NL == 1:
+                cache.append_tokens(sart.SEQ_PREFIX, [r], [cfg.prompt_len], pk, pv)
+                cache.append_tokens(sart.SEQ_BRANCH, ids, ns, bk, bv)
+            else:   # every layer gets the same values (uploaded once): the timing does not depend on them
+                dpk, dpv, dbk, dbv = (cache._dev(x, (cfg.n_kv_heads, cfg.head_dim)) for x in (pk, pv, bk, bv))
+                for l in range(NL):
+                    cache.append_tokens(sart.SEQ_PREFIX, [r], [cfg.prompt_len], dpk, dpv, layer=l)
+                for l in range(NL):
+                    cache.append_tokens(sart.SEQ_BRANCH, ids, ns, dbk, dbv, layer=l)
             if ocache is not None and r < n_cpu:
                 assert ocache.append(0, [r], [cfg.prompt_len], pk, pv) == 0
                 assert ocache.append(1, ids, ns, bk, bv) == 0
@@ -268,8 +278,9 @@ def main():
 
     def step(i):
         k, v = kvs[i % n_in]
-        cache.append_tokens(sart.SEQ_BRANCH, None, None, k, v)
-        cache.decode_attention(qs[i % n_in], out=out)
+        for l in range(NL):          # a model's forward: every layer appends its K/V of the token, then attends
+            cache.append_tokens(sart.SEQ_BRANCH, None, None, k, v, layer=l)
+            cache.decode_attention(qs[i % n_in], out=out, layer=l)
 
     if args.graph:
         # the step (all-active append + attention) recorded once per input set and replayed
@@ -315,7 +326,7 @@ def main():
     io_bytes = nA * cfg.n_q_heads * cfg.head_dim * (cfg.elem_bytes + 4)     # q read + out write
     alg_bytes = kv_bytes + io_bytes
     logical_bytes = (priv0 + nA * (K + 1) / 2 + nA * cfg.prompt_len) * cfg.token_bytes
-    value = kv_bytes / (dt / K) / 1e9
+    value = NL * kv_bytes / (dt / K) / 1e9
 
     # ---- dominant kernel timed with HIP events on its own stream -----------------------
     cache.set_profiling(args.kernel_repeats)
@@ -381,7 +392,8 @@ def main():
                                f"Hq{cfg.n_q_heads}/Hkv{cfg.n_kv_heads} d{cfg.head_dim} {cfg.dtype}, prompt "
                                f"{cfg.prompt_len}, private lengths {cfg.length_dist}{cfg.length_params} cap "
                                f"{cfg.length_cap}, page 16, free order {args.free_order}",
-                   "active_branches": nA, "kv_bytes_per_step": int(kv_bytes), "step": "append 1 token/branch + decode attention"},
+                   "active_branches": nA, "layers": NL, "kv_bytes_per_step": int(NL * kv_bytes),
+                   "step": "append 1 token/branch + decode attention" + (f", for each of {NL} layers" if NL > 1 else "")},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "branch_steps_per_s": round(nA / (dt / K), 1),
         "logical_kv_gbs": round(logical_bytes / (dt / K) / 1e9, 1),

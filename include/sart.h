@@ -97,7 +97,7 @@ typedef enum {
 typedef enum { SART_LAYOUT_NATURAL = 0, SART_LAYOUT_MFMA16 = 1 } sart_kv_layout;
 
 typedef struct {
-  int32_t n_layers;             /* must be 1                                     */
+  int32_t n_layers;             /* >= 1: layers sharing the tables (see below)   */
   int32_t n_q_heads;            /* Hq                                            */
   int32_t n_kv_heads;           /* Hkv, divides Hq                               */
   int32_t head_dim;             /* d, multiple of 8, <= 256                      */
@@ -158,6 +158,14 @@ int32_t sart_cache_layout(const sart_cache* cache); /* sart_kv_layout */
  *     with n_rows = capacity of q and out) can be replayed while branches are
  *     pruned or finished between replays.
  *   n_tokens == NULL means one token per sequence.
+ * Layers.  All layers of a model share one set of tables (a token has the
+ * same page and slot in every layer); the pool is [layer][page][kv head][K|V].
+ * An append to layer 0 is the one that allocates pages and advances lengths.
+ * An append to a layer > 0 writes that layer's K/V of the same tokens: it must
+ * repeat the step's layer-0 append (same kind, list, counts; SART_E_INVALID at
+ * once otherwise) and come before any other state-changing call; it changes no
+ * state, and is skipped on the device if that layer-0 append failed there.
+ * sart_decode_attention and sart_prefill_attention read the layer they name.
  * Pages are popped from the free stack sequence by sequence in list order,
  * each sequence taking its new pages in ascending logical page order.
  * Fewer free pages than needed: SART_E_OOM_PAGES, nothing changes. */

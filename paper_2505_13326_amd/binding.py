@@ -110,7 +110,7 @@ class SartCache:
 
     def __init__(self, *, n_q_heads, n_kv_heads, head_dim, page_tokens=16, num_pages, max_requests,
                  branches_per_request, finish_quota=0, max_pages_per_branch, max_prefix_pages, dtype="bf16",
-                 free_order=None, kv_pool=None, force_natural_layout=False):
+                 free_order=None, kv_pool=None, force_natural_layout=False, n_layers=1):
         import torch
         self.lib = load_library()
         self.Hq, self.Hkv, self.d, self.pt = n_q_heads, n_kv_heads, head_dim, page_tokens
@@ -118,7 +118,8 @@ class SartCache:
         self.Q, self.max_bp, self.max_pp = finish_quota, max_pages_per_branch, max_prefix_pages
         self.dtype = dtype
         self.torch_dtype = torch.float32 if dtype == "f32" else torch.bfloat16
-        d = _Desc(1, n_q_heads, n_kv_heads, head_dim, page_tokens, num_pages, max_requests, branches_per_request,
+        self.n_layers = n_layers
+        d = _Desc(n_layers, n_q_heads, n_kv_heads, head_dim, page_tokens, num_pages, max_requests, branches_per_request,
                   finish_quota, max_pages_per_branch, max_prefix_pages, F32 if dtype == "f32" else BF16,
                   1 if force_natural_layout else 0, None, 0, None)
         self.pool_bytes = int(self.lib.sart_pool_bytes(C.byref(d)))
@@ -163,7 +164,7 @@ class SartCache:
         return x.contiguous()
 
     # -- the five calls -----------------------------------------------------
-    def append_tokens(self, kind, ids, n_tokens, k, v, stream=None, status=False, all_active=False):
+    def append_tokens(self, kind, ids, n_tokens, k, v, stream=None, status=False, all_active=False, layer=0):
         """sart_append_tokens.  k, v: [sum n, Hkv, d] device tensors (or numpy, copied to the device).
         all_active: SART_ALL_ACTIVE (one token per active branch, count read on the device; k, v hold
         at least that many rows)."""
@@ -173,7 +174,7 @@ class SartCache:
         if all_active:
             assert ids is None and n_tokens is None and k.shape == v.shape and k.shape[0] >= 1
             rc = self.lib.sart_append_tokens(self.h, kind, -int(k.shape[0]), None, None, C.c_void_p(k.data_ptr()),
-                                             C.c_void_p(v.data_ptr()), 0, _stream_handle(stream))
+                                             C.c_void_p(v.data_ptr()), int(layer), _stream_handle(stream))
             if status:
                 return rc if rc != OK else self.sync_status()
             self._check(rc)
@@ -183,24 +184,24 @@ class SartCache:
         if k.shape[0] != total or v.shape[0] != total:
             raise ValueError(f"k/v rows {k.shape[0]} != tokens {total}")
         rc = self.lib.sart_append_tokens(self.h, kind, n_seqs, _ptr(ids_a), _ptr(nt_a), C.c_void_p(k.data_ptr()),
-                                         C.c_void_p(v.data_ptr()), 0, _stream_handle(stream))
+                                         C.c_void_p(v.data_ptr()), int(layer), _stream_handle(stream))
         if status:
             return rc if rc != OK else self.sync_status()
         self._check(rc)
         return OK
 
-    def decode_attention(self, q, out=None, scale=0.0, stream=None):
+    def decode_attention(self, q, out=None, scale=0.0, stream=None, layer=0):
         """sart_decode_attention.  q: [n_rows, Hq, d]; returns out [n_rows, Hq, d] float32 (device)."""
         import torch
         q = self._dev(q, (self.Hq, self.d))
         if out is None:
             out = torch.zeros((q.shape[0], self.Hq, self.d), dtype=torch.float32, device=q.device)
         assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
-        self._check(self.lib.sart_decode_attention(self.h, 0, C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()),
+        self._check(self.lib.sart_decode_attention(self.h, int(layer), C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()),
                                                    q.shape[0], float(scale), _stream_handle(stream)))
         return out
 
-    def prefill_attention(self, request_ids, n_q, q, out=None, scale=0.0, stream=None, status=False):
+    def prefill_attention(self, request_ids, n_q, q, out=None, scale=0.0, stream=None, status=False, layer=0):
         """sart_prefill_attention.  q: [sum n_q, Hq, d], rows in list order; returns out float32 (device)."""
         import torch
         ids, nq = _i32(request_ids), _i32(n_q)
@@ -210,7 +211,7 @@ class SartCache:
         if out is None:
             out = torch.zeros((q.shape[0], self.Hq, self.d), dtype=torch.float32, device=q.device)
         assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
-        rc = self.lib.sart_prefill_attention(self.h, 0, len(ids), _ptr(ids), _ptr(nq), C.c_void_p(q.data_ptr()),
+        rc = self.lib.sart_prefill_attention(self.h, int(layer), len(ids), _ptr(ids), _ptr(nq), C.c_void_p(q.data_ptr()),
                                              C.c_void_p(out.data_ptr()), float(scale), _stream_handle(stream))
         if status:
             return rc

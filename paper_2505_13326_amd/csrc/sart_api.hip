@@ -54,6 +54,10 @@ struct sart_cache {
   size_t stage_ints = 0;
   int next_slot = 0;
   int call_seq = 0;
+  size_t layer_bytes = 0;              // pool bytes of one layer
+  // the last layer-0 append, which the same step's appends to the other layers must repeat
+  int last_kind = -1, last_n_seqs = 0, last_has_ids = 0;
+  long long last_total = 0;
   hipStream_t last_stream = nullptr;
   float* partials = nullptr;
   long long partial_cap = 0;
@@ -93,7 +97,7 @@ sart_status stage_upload(sart_cache* c, StageSlot* s, size_t n_ints, hipStream_t
 
 sart_status check_desc(const sart_cache_desc* d) {
   if (!d) return fail(SART_E_INVALID, "null description");
-  if (d->n_layers != 1) return fail(SART_E_INVALID, "n_layers must be 1");
+  if (d->n_layers < 1 || d->n_layers > 1024) return fail(SART_E_INVALID, "n_layers must be in [1, 1024]");
   if (d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->n_q_heads % d->n_kv_heads)
     return fail(SART_E_INVALID, "n_q_heads must be a positive multiple of n_kv_heads");
   if (d->head_dim <= 0 || d->head_dim % 8 || d->head_dim > 256)
@@ -127,7 +131,14 @@ const char* sart_last_error(void) { return g_err; }
 size_t sart_pool_bytes(const sart_cache_desc* d) {
   if (!d) return 0;
   const size_t es = d->kv_dtype == SART_F32 ? 4 : 2;
-  return (size_t)d->num_pages * d->page_tokens * 2 * d->n_kv_heads * d->head_dim * es;
+  return (size_t)(d->n_layers > 0 ? d->n_layers : 1) * d->num_pages * d->page_tokens * 2 * d->n_kv_heads * d->head_dim * es;
+}
+
+// The layer's slice of the pool: [layer][page][kv head][K tile | V tile].
+static Ctx layer_ctx(const sart_cache* c, int layer) {
+  Ctx x = c->ctx;
+  x.pool = (char*)c->ctx.pool + (size_t)layer * c->layer_bytes;
+  return x;
 }
 
 sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
@@ -148,6 +159,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   }
   sart_cache* c = new sart_cache();
   c->desc = *d;
+  c->layer_bytes = pool_bytes / d->n_layers;
   c->desc.initial_free_order = nullptr;
   HIP_TRY(hipGetDevice(&c->device));
   Dims& dm = c->ctx.dm;
@@ -263,7 +275,7 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
                                void* stream) {
   if (!c) return fail(SART_E_INVALID, "null cache");
   const Dims& dm = c->ctx.dm;
-  if (layer != 0) return fail(SART_E_INVALID, "layer must be 0");
+  if (layer < 0 || layer >= c->desc.n_layers) return fail(SART_E_INVALID, "layer out of range");
   if (kind != SART_SEQ_PREFIX && kind != SART_SEQ_BRANCH) return fail(SART_E_INVALID, "unknown sequence kind");
   if (n_seqs < 0 && kind == SART_SEQ_BRANCH && !ids && !n_tokens) {   // SART_ALL_ACTIVE(rows)
     if (!k || !v) return fail(SART_E_INVALID, "null k or v");
@@ -272,7 +284,11 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
     AppendArgs a{};
     a.kind = kind; a.n_seqs = n_seqs; a.total_rows = n_seqs < -dm.H ? dm.H : -n_seqs; a.k = k; a.v = v;
     a.call_seq = ++c->call_seq;
-    launch_append(c->ctx, c->plan, a, st);
+    a.write_only = layer > 0;
+    if (layer == 0) { c->last_kind = kind; c->last_n_seqs = n_seqs; c->last_has_ids = 0; c->last_total = -1; }
+    else if (c->last_kind != kind || c->last_n_seqs != n_seqs || c->last_total != -1)
+      return fail(SART_E_INVALID, "an append to layer %d must repeat the step's layer-0 append", layer);
+    launch_append(layer_ctx(c, layer), c->plan, a, st);
     HIP_TRY(hipGetLastError());
     return SART_OK;
   }
@@ -303,6 +319,11 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
   note_stream(c, stream);
   AppendArgs a{};
   a.kind = kind; a.n_seqs = n_seqs; a.total_rows = total; a.k = k; a.v = v; a.call_seq = ++c->call_seq;
+  a.write_only = layer > 0;
+  if (layer == 0) { c->last_kind = kind; c->last_n_seqs = n_seqs; c->last_has_ids = ids != nullptr; c->last_total = total; }
+  else if (c->last_kind != kind || c->last_n_seqs != n_seqs || c->last_has_ids != (ids != nullptr) || c->last_total != total)
+    return fail(SART_E_INVALID, "an append to layer %d must repeat the step's layer-0 append", layer);
+  const Ctx lctx = layer_ctx(c, layer);
   if (ids || n_tokens) {
     StageSlot* s;
     sart_status rc = stage_begin(c, &s);
@@ -318,10 +339,10 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
     }
     rc = stage_upload(c, s, off, st);
     if (rc != SART_OK) return rc;
-    launch_append(c->ctx, c->plan, a, st);
+    launch_append(lctx, c->plan, a, st);
     HIP_TRY(hipEventRecord(s->done, st));
   } else {
-    launch_append(c->ctx, c->plan, a, st);
+    launch_append(lctx, c->plan, a, st);
   }
   HIP_TRY(hipGetLastError());
   return SART_OK;
@@ -330,7 +351,7 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
 sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows,
                                   float scale, void* stream) {
   if (!c) return fail(SART_E_INVALID, "null cache");
-  if (layer != 0) return fail(SART_E_INVALID, "layer must be 0");
+  if (layer < 0 || layer >= c->desc.n_layers) return fail(SART_E_INVALID, "layer out of range");
   if (n_rows < 0) return fail(SART_E_INVALID, "negative n_rows");
   if (n_rows > 0 && (!q || !out)) return fail(SART_E_INVALID, "null q or out");
   const Dims& dm = c->ctx.dm;
@@ -346,7 +367,7 @@ sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, f
   a.call_seq = ++c->call_seq;
   for (int i = 0; i < 4; ++i) a.ev[i] = c->profiling ? c->ev[i] : nullptr;
   a.repeats = c->profiling;
-  launch_decode(c->ctx, a, st);
+  launch_decode(layer_ctx(c, layer), a, st);
   c->ev_valid = c->profiling > 0;
   HIP_TRY(hipGetLastError());
   return SART_OK;
@@ -355,7 +376,7 @@ sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, f
 sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs, const int32_t* request_ids,
                                    const int32_t* n_q, const void* q, float* out, float scale, void* stream) {
   if (!c) return fail(SART_E_INVALID, "null cache");
-  if (layer != 0) return fail(SART_E_INVALID, "layer must be 0");
+  if (layer < 0 || layer >= c->desc.n_layers) return fail(SART_E_INVALID, "layer out of range");
   const Dims& dm = c->ctx.dm;
   if (n_seqs < 0 || n_seqs > dm.max_req) return fail(SART_E_INVALID, "n_seqs out of range");
   if (n_seqs > 0 && (!request_ids || !n_q)) return fail(SART_E_INVALID, "null request_ids or n_q");
@@ -394,7 +415,7 @@ sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs,
   a.ids = s->dev; a.nq = s->dev + n_seqs; a.q_off = s->dev + 2 * n_seqs; a.tile_start = s->dev + 3 * n_seqs;
   rc = stage_upload(c, s, (size_t)4 * n_seqs, st);
   if (rc != SART_OK) return rc;
-  launch_prefill(c->ctx, a, st);
+  launch_prefill(layer_ctx(c, layer), a, st);
   HIP_TRY(hipEventRecord(s->done, st));
   HIP_TRY(hipGetLastError());
   return SART_OK;

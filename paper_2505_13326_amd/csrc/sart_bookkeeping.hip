@@ -63,7 +63,7 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
   const int tid = threadIdx.x;
   const int nA = scal[S_NACTIVE];
   const int top = scal[S_FREETOP];
-  if (tid == 0) s_err = 0x7fffffff;
+  if (tid == 0) { s_err = 0x7fffffff; scal[S_APPENDOK] = 0; }
   __syncthreads();
   if (!a.ids && a.n_seqs >= 0 && a.n_seqs != nA) {
     if (tid == 0) record_error(scal, SART_E_INVALID, a.call_seq);
@@ -159,6 +159,7 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
     const int sel = scal[S_BTSEL];
     if (scal[S_BTHI0 + sel] < na_new) scal[S_BTHI0 + sel] = na_new;
     scal[S_CALLOK] = 1;
+    scal[S_APPENDOK] = 1;
   }
   refresh_decode_plan(c, pc, lds);
 }
@@ -169,7 +170,7 @@ __global__ void __launch_bounds__(256)
 k_append_write(Ctx c, AppendArgs a) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
-  if (!tb.scal[S_CALLOK]) return;
+  if (!tb.scal[a.write_only ? S_APPENDOK : S_CALLOK]) return;
   const int lane = threadIdx.x & 63;
   const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
@@ -209,7 +210,7 @@ k_append_write(Ctx c, AppendArgs a) {
 }
 
 void launch_append(const Ctx& c, const PlanCfg& pc, const AppendArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(k_append_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, a);
+  if (!a.write_only) hipLaunchKernelGGL(k_append_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, a);
   if (a.total_rows <= 0) return;
   const long long units = a.total_rows * c.dm.Hkv;
   long long blocks = (units + 3) / 4;
@@ -400,6 +401,7 @@ k_prune_plan(Ctx c, PlanCfg pc, PruneArgs a) {
   __shared__ int lds[17];
   const int tid = threadIdx.x;
   const int nA = scal[S_NACTIVE];
+  if (tid == 0) scal[S_APPENDOK] = 0;      // rows of the last append may move: no more writes to other layers
   if (a.n_scores < nA) {
     if (tid == 0) record_error(scal, SART_E_INVALID, a.call_seq);
     return;
@@ -456,7 +458,7 @@ k_finish_plan(Ctx c, PlanCfg pc, int n, const int* handles, int call_seq) {
   __shared__ int s_bad;
   const int tid = threadIdx.x;
   const int nA = scal[S_NACTIVE];
-  if (tid == 0) s_bad = 0;
+  if (tid == 0) { s_bad = 0; scal[S_APPENDOK] = 0; }
   __syncthreads();
   for (int i = tid; i < n; i += kPlanThreads)
     if (tb.br_state[handles[i]] != SART_BRANCH_ACTIVE) s_bad = 1;

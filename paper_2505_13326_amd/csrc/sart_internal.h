@@ -36,7 +36,7 @@ enum Scalar {
   S_T_CLEAR_HI,   // rows [na_new, clear_hi) of the new buffer must be reset to -1
   // plan of the decode pass
   S_D_NA,
-  S_D_UNITS,      // private (page, kv head) units in total
+  S_APPENDOK,     // the last layer-0 append passed its validation and no call changed the state since
   S_D_PER_EVEN,   // units per wave of an even workgroup
   S_D_PER_ODD,    // units per wave of an odd workgroup
   S_D_NITEMS,     // prefix workgroup items
@@ -191,6 +191,7 @@ struct AppendArgs {
   const void* k;
   const void* v;
   int call_seq;
+  int write_only;      // layer > 0: write the rows of the last layer-0 append again, into this layer's pool
 };
 void launch_append(const Ctx& c, const PlanCfg& pc, const AppendArgs& a, hipStream_t s);
 
