@@ -45,6 +45,9 @@ def _load():
         L.orc_attention.argtypes = [vp, vp, C.c_int, C.c_double, ip, C.c_int, dp, dp]
         L.orc_prefill_attention.argtypes = [vp, C.c_int, vp, C.c_int, C.c_double, dp, dp]
         L.orc_finish.argtypes = [vp, C.c_int, ip]
+        L.orc_set_fp8.argtypes = [vp, C.c_double, C.c_double]
+        L.orc_fp8_roundtrip.argtypes = [vp, C.c_int, C.c_double, vp, vp]
+        L.orc_fp8_roundtrip.restype = None
         L.orc_prune.argtypes = [vp, C.c_int, C.c_int, ip, fp, ip, fp, C.c_int]
         L.orc_request_done.argtypes = [vp, C.c_int]
         L.orc_get_state.argtypes = [vp] + [ip] * 11
@@ -62,17 +65,27 @@ def _i32(a):
     return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
 
 
+def fp8_roundtrip(bits, scale=1.0):
+    """The oracle's E4M3 codec on bf16 bit patterns: (codes uint8, read-back values float64)."""
+    b = np.ascontiguousarray(bits, np.uint16)
+    codes = np.zeros(b.size, np.uint8)
+    vals = np.zeros(b.size, np.float64)
+    _load().orc_fp8_roundtrip(b.ctypes.data, b.size, float(scale), codes.ctypes.data, vals.ctypes.data)
+    return codes.reshape(b.shape), vals.reshape(b.shape)
+
+
 def num_threads() -> int:
     return int(_load().orc_num_threads())
 
 
 class OracleCache:
-    """Plain CPU paged cache + attention.  dtype: 'f32' (float32 arrays) or
-    'bf16' (uint16 bit arrays)."""
+    """Plain CPU paged cache + attention.  dtype: 'f32' (float32 arrays),
+    'bf16' (uint16 bit arrays) or 'fp8' (uint16 bf16 bit arrays in, the cache
+    keeps 8-bit floats)."""
 
     def __init__(self, *, n_q_heads, n_kv_heads, head_dim, page_tokens, num_pages, max_requests,
                  branches_per_request, finish_quota, max_pages_per_branch, max_prefix_pages, dtype,
-                 free_order=None):
+                 free_order=None, k_scale=1.0, v_scale=1.0):
         self.L = _load()
         self.Hq, self.Hkv, self.d, self.pt = n_q_heads, n_kv_heads, head_dim, page_tokens
         self.num_pages, self.max_req, self.Nb = num_pages, max_requests, branches_per_request
@@ -85,6 +98,9 @@ class OracleCache:
                                    max_prefix_pages, 0 if dtype == "f32" else 1, _iptr(fo))
         if not self.h:
             raise ValueError("orc_create rejected the description")
+        if dtype == "fp8":      # bf16 in and out, K and V kept as 8-bit floats (E4M3) of x / scale
+            if self.L.orc_set_fp8(self.h, float(k_scale), float(v_scale)) != OK:
+                raise ValueError("orc_set_fp8 rejected the scales")
 
     def close(self):
         if self.h:

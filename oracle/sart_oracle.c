@@ -55,6 +55,8 @@ enum { DT_F32 = 0, DT_BF16 = 1 };
 typedef struct {
   int Hq, Hkv, d, pt, num_pages, max_req, Nb, Q, max_bp, max_pp, dtype;
   size_t esize;
+  int fp8;              /* 1: the cache keeps K and V as 8-bit floats (inputs stay bf16) */
+  double kv_scale[2];   /* fp8: stored code = round(x / scale); K, V */
   unsigned char* pool;
   int* free_stack;
   int free_top;
@@ -132,6 +134,61 @@ static unsigned char* token_ptr(const orc* o, int page, int slot, int head, int 
   return o->pool + e * o->esize;
 }
 
+/*
+ * 8-bit float cache (an extension beyond the paper, which keeps KV in the
+ * model's dtype): OCP FP8 E4M3 - 1 sign, 4 exponent bits (bias 7), 3 mantissa
+ * bits, subnormals, no infinities, S.1111.111 = NaN, largest finite 448.
+ * value(code): e == 0: m/8 * 2^-6; else (1 + m/8) * 2^(e-7).
+ * A value is stored as the nearest code of x / scale (ties to the even code,
+ * |x / scale| clamped to 448 first) and read back as value(code) * scale.
+ */
+static double e4m3_value(unsigned code) {
+  const unsigned e = (code >> 3) & 15, m = code & 7;
+  const double mag = e == 0 ? ldexp(m / 8.0, -6) : ldexp(1.0 + m / 8.0, (int)e - 7);
+  return (code & 0x80) ? -mag : mag;
+}
+static unsigned e4m3_nearest(double x) {
+  const unsigned sign = signbit(x) ? 0x80u : 0u;
+  double a = fabs(x);
+  if (a > 448.0) a = 448.0;
+  /* codes 0..126 are the finite magnitudes in ascending order: take the nearest, ties to the even code */
+  unsigned best = 0;
+  double best_err = a;
+  for (unsigned c = 1; c <= 126; ++c) {
+    const double err = fabs(e4m3_value(c) - a);
+    if (err < best_err || (err == best_err && (c & 1) == 0)) { best = c; best_err = err; }
+  }
+  return sign | best;
+}
+static double bf16_bits_value(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return (double)f;
+}
+static uint16_t value_bf16_bits(double v) {   /* exact for every E4M3 value */
+  float f = (float)v;
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  return (uint16_t)(u >> 16);
+}
+/* the codec by itself, for tests: bf16 bits in, codes and read-back values out */
+void orc_fp8_roundtrip(const uint16_t* in, int n, double scale, unsigned char* codes, double* values) {
+  for (int i = 0; i < n; ++i) {
+    const unsigned c = e4m3_nearest(bf16_bits_value(in[i]) / scale);
+    if (codes) codes[i] = (unsigned char)c;
+    if (values) values[i] = e4m3_value(c) * scale;
+  }
+}
+/* switches a bf16 cache to 8-bit float storage (before the first append) */
+int orc_set_fp8(orc* o, double k_scale, double v_scale) {
+  if (o->dtype != DT_BF16 || !(k_scale > 0) || !(v_scale > 0)) return ORC_E_INVALID;
+  o->fp8 = 1;
+  o->kv_scale[0] = k_scale;
+  o->kv_scale[1] = v_scale;
+  return ORC_OK;
+}
+
 static double widen(const orc* o, const unsigned char* p, int c) {
   if (o->dtype == DT_F32) {
     float f;
@@ -144,6 +201,12 @@ static double widen(const orc* o, const unsigned char* p, int c) {
   float f;
   memcpy(&f, &u, 4);
   return (double)f;
+}
+
+/* a cached element as the attention reads it: the stored value, times the scale of an 8-bit float cache */
+static double cached(const orc* o, const unsigned char* p, int c, int which) {
+  const double x = widen(o, p, c);
+  return o->fp8 ? x * o->kv_scale[which] : x;
 }
 
 static int is_dup(const int* ids, int n, int limit) {
@@ -229,8 +292,18 @@ int orc_append(orc* o, int kind, int n_seqs, const int* ids, const int* n_tokens
       int page = table[pos / o->pt], slot = pos % o->pt;
       for (int h = 0; h < o->Hkv; ++h) {
         size_t src = tok * row + (size_t)h * o->d * o->esize;
-        memcpy(token_ptr(o, page, slot, h, 0), (const unsigned char*)k + src, o->d * o->esize);
-        memcpy(token_ptr(o, page, slot, h, 1), (const unsigned char*)v + src, o->d * o->esize);
+        if (!o->fp8) {
+          memcpy(token_ptr(o, page, slot, h, 0), (const unsigned char*)k + src, o->d * o->esize);
+          memcpy(token_ptr(o, page, slot, h, 1), (const unsigned char*)v + src, o->d * o->esize);
+        } else {
+          /* keep value(code) as bf16 bits (exact): the scale is applied when the element is read */
+          for (int w = 0; w < 2; ++w) {
+            const uint16_t* in = (const uint16_t*)((const unsigned char*)(w ? v : k) + src);
+            uint16_t* dst = (uint16_t*)token_ptr(o, page, slot, h, w);
+            for (int c = 0; c < o->d; ++c)
+              dst[c] = value_bf16_bits(e4m3_value(e4m3_nearest(bf16_bits_value(in[c]) / o->kv_scale[w])));
+          }
+        }
       }
       *len = pos + 1;
     }
@@ -282,7 +355,7 @@ int orc_attention(const orc* o, const void* q, int n_rows, double scale, const i
         int slot = t < P ? t % o->pt : (t - P) % o->pt;
         const unsigned char* kp = token_ptr(o, page, slot, g, 0);
         double dot = 0.0;
-        for (int c = 0; c < d; ++c) dot += widen(o, qrow, c) * widen(o, kp, c);
+        for (int c = 0; c < d; ++c) dot += widen(o, qrow, c) * cached(o, kp, c, 0);
         s[t] = scale * dot;
         if (s[t] > smax) smax = s[t];
       }
@@ -296,7 +369,7 @@ int orc_attention(const orc* o, const void* q, int n_rows, double scale, const i
         const unsigned char* vp = token_ptr(o, page, slot, g, 1);
         double w = s[t] / Z;
         ws += w;
-        for (int c = 0; c < d; ++c) orow[c] += w * widen(o, vp, c);
+        for (int c = 0; c < d; ++c) orow[c] += w * cached(o, vp, c, 1);
       }
       if (wsum) wsum[(size_t)i * o->Hq + h] = ws;
       free(s);
@@ -335,7 +408,7 @@ int orc_prefill_attention(const orc* o, int r, const void* q, int n_q, double sc
       for (int t = 0; t < T; ++t) {
         const unsigned char* kp = token_ptr(o, o->prefix_table[(size_t)r * o->max_pp + t / o->pt], t % o->pt, g, 0);
         double dot = 0.0;
-        for (int c = 0; c < d; ++c) dot += widen(o, qrow, c) * widen(o, kp, c);
+        for (int c = 0; c < d; ++c) dot += widen(o, qrow, c) * cached(o, kp, c, 0);
         s[t] = scale * dot;
         if (s[t] > smax) smax = s[t];
       }
@@ -346,7 +419,7 @@ int orc_prefill_attention(const orc* o, int r, const void* q, int n_q, double sc
         const unsigned char* vp = token_ptr(o, o->prefix_table[(size_t)r * o->max_pp + t / o->pt], t % o->pt, g, 1);
         const double w = s[t] / Z;
         ws += w;
-        for (int c = 0; c < d; ++c) orow[c] += w * widen(o, vp, c);
+        for (int c = 0; c < d; ++c) orow[c] += w * cached(o, vp, c, 1);
       }
       if (wsum) wsum[(size_t)i * o->Hq + h] = ws;
       free(s);
