@@ -175,6 +175,8 @@ def main():
     ap.add_argument("--prompt-len", type=int, default=-1, help="override the workload's prompt length (experiments)")
     ap.add_argument("--kernel-repeats", type=int, default=8,
                     help="launches of the attention kernel between the two HIP events of the profiled pass")
+    ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"], help="fp8: the cache keeps K and V as 8-bit floats "
+                    "(E4M3; bf16 crosses the boundary): half the bytes per cached token")
     ap.add_argument("--layers", type=int, default=1, help="layers sharing the tables; a step appends to and attends over "
                     "every layer (same values in every layer)")
     ap.add_argument("--graph", action="store_true", help="replay the step (append + attention) from a HIP graph")
@@ -225,14 +227,14 @@ def main():
     cache = sart.SartCache(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
                            page_tokens=cfg.page_tokens, num_pages=num_pages, max_requests=cfg.n_requests,
                            branches_per_request=cfg.nb, finish_quota=cfg.quota, max_pages_per_branch=max_bp,
-                           max_prefix_pages=max(1, cfg.prompt_len // cfg.page_tokens), dtype=cfg.dtype,
-                           free_order=fo, n_layers=NL)
+                           max_prefix_pages=max(1, cfg.prompt_len // cfg.page_tokens),
+                           dtype="fp8" if args.kv_dtype == "fp8" else cfg.dtype, free_order=fo, n_layers=NL)
     if args.workgroups or args.chunk_pages or args.prompt_mode >= 0 or args.skew is not None or args.prompt_workgroups >= 0:
         cache.set_decode_launch(args.workgroups, args.prompt_workgroups, args.chunk_pages, args.prompt_mode,
                                 50 if args.skew is None else args.skew)
 
     # ---- CPU baseline cache (oracle) on a bounded sample of the same workload ------------
-    do_cpu = not args.no_cpu_baseline
+    do_cpu = not args.no_cpu_baseline and args.kv_dtype == "bf16"     # the CPU baseline is timed on the bf16 cache
     n_cpu = args.cpu_sample_requests or {2: cfg.n_requests, 4: 4, 5: 1}[cfg.cfg_id]
     n_cpu = min(n_cpu, cfg.n_requests)
     ocache = None
@@ -322,10 +324,11 @@ def main():
     ms_step = dt / K * 1e3
     # private tokens read at timed step i (1-based): priv0 + i*nA
     mean_tokens = priv0 + nA * (K + 1) / 2 + pre
-    kv_bytes = mean_tokens * cfg.token_bytes
+    tok_bytes = cfg.token_bytes // (2 if args.kv_dtype == "fp8" else 1)     # an 8-bit float cache keeps half the bytes
+    kv_bytes = mean_tokens * tok_bytes
     io_bytes = nA * cfg.n_q_heads * cfg.head_dim * (cfg.elem_bytes + 4)     # q read + out write
     alg_bytes = kv_bytes + io_bytes
-    logical_bytes = (priv0 + nA * (K + 1) / 2 + nA * cfg.prompt_len) * cfg.token_bytes
+    logical_bytes = (priv0 + nA * (K + 1) / 2 + nA * cfg.prompt_len) * tok_bytes
     value = NL * kv_bytes / (dt / K) / 1e9
 
     # ---- dominant kernel timed with HIP events on its own stream -----------------------
@@ -340,11 +343,11 @@ def main():
         total_ms.append(t)
     cache.set_profiling(0)
     attn_avg = float(np.mean(attn_ms))
-    alg_bytes_prof = (priv1 + nA * (n_prof + 1) / 2 + pre) * cfg.token_bytes + io_bytes
+    alg_bytes_prof = (priv1 + nA * (n_prof + 1) / 2 + pre) * tok_bytes + io_bytes
     achieved = alg_bytes_prof / (attn_avg * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "k_attn_mfma", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if args.kv_dtype == "bf16" else None,
                 "algorithmic_bytes_per_launch": int(alg_bytes_prof), "kernel_ms_avg": round(attn_avg, 4),
                 "kernel_ms_p10_p50_p90": [round(float(np.percentile(attn_ms, p)), 4) for p in (10, 50, 90)],
                 "launches_per_event_pair": args.kernel_repeats}
@@ -387,9 +390,9 @@ def main():
         "metric": "decode-attention achieved KV GB/s (fraction of HBM peak); branch-steps/s",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.dtype, "data": "synthetic",
+        "dtype": cfg.dtype if args.kv_dtype == "bf16" else "bf16 arithmetic on an fp8 (E4M3) cache", "data": "synthetic",
         "config": {"workload": f"{args.workload} {cfg.name}: {cfg.n_requests} requests x {cfg.nb} branches, "
-                               f"Hq{cfg.n_q_heads}/Hkv{cfg.n_kv_heads} d{cfg.head_dim} {cfg.dtype}, prompt "
+                               f"Hq{cfg.n_q_heads}/Hkv{cfg.n_kv_heads} d{cfg.head_dim} {cfg.dtype if args.kv_dtype == 'bf16' else 'fp8 cache'}, prompt "
                                f"{cfg.prompt_len}, private lengths {cfg.length_dist}{cfg.length_params} cap "
                                f"{cfg.length_cap}, page 16, free order {args.free_order}",
                    "active_branches": nA, "layers": NL, "kv_bytes_per_step": int(NL * kv_bytes),

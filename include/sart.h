@@ -60,7 +60,14 @@ typedef enum {
   SART_E_HIP = 4        /* a HIP runtime call failed; see sart_last_error      */
 } sart_status;
 
-typedef enum { SART_F32 = 0, SART_BF16 = 1 } sart_dtype;
+/* Element type of the cache.  SART_FP8_E4M3: Q, K, V cross the boundary as bf16;
+ * the pool keeps K and V as 8-bit floats (OCP E4M3: 4 exponent bits, bias 7, 3
+ * mantissa bits, largest finite 448): code = nearest(x / scale), ties to even,
+ * |x / scale| clamped to 448; read back as value(code) * scale, with one scale
+ * for K and one for V per cache (k_scale, v_scale).  Inputs must be finite.
+ * Half the bytes of bf16 per cached token.  Needs page_tokens 16, head_dim 64 or
+ * 128 and Hq/Hkv <= 16. */
+typedef enum { SART_F32 = 0, SART_BF16 = 1, SART_FP8_E4M3 = 2 } sart_dtype;
 
 #define SART_ALL_ACTIVE(rows) (-(rows))   /* n_seqs of sart_append_tokens: every active branch (count read on the
                                              device); k and v hold `rows` >= 1 rows */
@@ -92,9 +99,14 @@ typedef enum {
  *              V chunk (d/32)*64 + (token/4)*16 + d%16
  *                      holds V[4*(token/4)+0..3][32*(d/32) + d%16]     then
  *                            V[4*(token/4)+0..3][32*(d/32) + 16 + d%16]
+ *   MFMA16_FP8: the same for SART_FP8_E4M3, one byte per element, a 16-byte
+ *            chunk holding what two bf16 chunks hold:
+ *              K chunk (d/64)*64 + ((d/8)%4)*16 + token, byte 8*((d/32)%2) + d%8
+ *              V chunk (d/64)*64 + (token/4)*16 + d%16,
+ *                      byte 8*((d/32)%2) + 4*((d/16)%2) + token%4
  * The layout is chosen by sart_alloc_cache (MFMA16 whenever it applies unless
  * force_natural_layout is set) and reported by sart_cache_layout. */
-typedef enum { SART_LAYOUT_NATURAL = 0, SART_LAYOUT_MFMA16 = 1 } sart_kv_layout;
+typedef enum { SART_LAYOUT_NATURAL = 0, SART_LAYOUT_MFMA16 = 1, SART_LAYOUT_MFMA16_FP8 = 2 } sart_kv_layout;
 
 typedef struct {
   int32_t n_layers;             /* >= 1: layers sharing the tables (see below)   */
@@ -108,13 +120,15 @@ typedef struct {
   int32_t finish_quota;         /* Q; 0 or > Nb disables early stop              */
   int32_t max_pages_per_branch; /* private pages a branch may hold               */
   int32_t max_prefix_pages;     /* pages a request's prompt may hold             */
-  int32_t kv_dtype;             /* sart_dtype of Q, K, V                         */
+  int32_t kv_dtype;             /* sart_dtype of Q, K, V (see sart_dtype)        */
   int32_t force_natural_layout; /* nonzero: never pick SART_LAYOUT_MFMA16        */
   void* kv_pool;                /* DEVICE, caller owned, or NULL: library owns   */
   size_t kv_pool_bytes;         /* >= sart_pool_bytes(desc) when kv_pool != NULL */
   const int32_t* initial_free_order; /* HOST [num_pages] permutation, or NULL =
                                         identity.  Page initial_free_order[0] is
                                         handed out first.                        */
+  float k_scale;                /* SART_FP8_E4M3 only: scale of K, of V;         */
+  float v_scale;                /* <= 0 means 1                                  */
 } sart_cache_desc;
 
 typedef struct {

@@ -139,9 +139,15 @@ static unsigned char* token_ptr(const orc* o, int page, int slot, int head, int 
  * model's dtype): OCP FP8 E4M3 - 1 sign, 4 exponent bits (bias 7), 3 mantissa
  * bits, subnormals, no infinities, S.1111.111 = NaN, largest finite 448.
  * value(code): e == 0: m/8 * 2^-6; else (1 + m/8) * 2^(e-7).
- * A value is stored as the nearest code of x / scale (ties to the even code,
- * |x / scale| clamped to 448 first) and read back as value(code) * scale.
+ * A value is stored as the nearest code of y = x * (1 / scale), both the
+ * reciprocal and the product taken in float32 (the precision the cache's kernels
+ * work in, so that both sides decide every code alike), ties to the even code,
+ * |y| clamped to 448 first; it is read back as value(code) * scale.
  */
+static double fp8_prescale(double x, double scale) {
+  const float inv = 1.0f / (float)scale;
+  return (double)((float)x * inv);
+}
 static double e4m3_value(unsigned code) {
   const unsigned e = (code >> 3) & 15, m = code & 7;
   const double mag = e == 0 ? ldexp(m / 8.0, -6) : ldexp(1.0 + m / 8.0, (int)e - 7);
@@ -151,10 +157,16 @@ static unsigned e4m3_nearest(double x) {
   const unsigned sign = signbit(x) ? 0x80u : 0u;
   double a = fabs(x);
   if (a > 448.0) a = 448.0;
-  /* codes 0..126 are the finite magnitudes in ascending order: take the nearest, ties to the even code */
-  unsigned best = 0;
-  double best_err = a;
-  for (unsigned c = 1; c <= 126; ++c) {
+  /* codes 0..126 are the finite magnitudes in ascending order: take the nearest, ties to the even code.
+   * The nearest code's value is within a factor 2 of a, so only the codes of the binades next to a's
+   * need looking at (exponent field E = ilogb(a) + 7; everything below 2^-6 is the subnormal binade). */
+  int E = a > 0 ? ilogb(a) + 7 : 0;
+  if (E < 1) E = 1;
+  unsigned first = (unsigned)(E - 1) * 8, last = (unsigned)(E + 1) * 8 + 7;
+  if (last > 126) last = 126;
+  unsigned best = first;
+  double best_err = fabs(e4m3_value(first) - a);
+  for (unsigned c = first + 1; c <= last; ++c) {
     const double err = fabs(e4m3_value(c) - a);
     if (err < best_err || (err == best_err && (c & 1) == 0)) { best = c; best_err = err; }
   }
@@ -175,7 +187,7 @@ static uint16_t value_bf16_bits(double v) {   /* exact for every E4M3 value */
 /* the codec by itself, for tests: bf16 bits in, codes and read-back values out */
 void orc_fp8_roundtrip(const uint16_t* in, int n, double scale, unsigned char* codes, double* values) {
   for (int i = 0; i < n; ++i) {
-    const unsigned c = e4m3_nearest(bf16_bits_value(in[i]) / scale);
+    const unsigned c = e4m3_nearest(fp8_prescale(bf16_bits_value(in[i]), scale));
     if (codes) codes[i] = (unsigned char)c;
     if (values) values[i] = e4m3_value(c) * scale;
   }
@@ -301,7 +313,7 @@ int orc_append(orc* o, int kind, int n_seqs, const int* ids, const int* n_tokens
             const uint16_t* in = (const uint16_t*)((const unsigned char*)(w ? v : k) + src);
             uint16_t* dst = (uint16_t*)token_ptr(o, page, slot, h, w);
             for (int c = 0; c < o->d; ++c)
-              dst[c] = value_bf16_bits(e4m3_value(e4m3_nearest(bf16_bits_value(in[c]) / o->kv_scale[w])));
+              dst[c] = value_bf16_bits(e4m3_value(e4m3_nearest(fp8_prescale(bf16_bits_value(in[c]), o->kv_scale[w]))));
           }
         }
       }

@@ -11,11 +11,11 @@ import os
 import numpy as np
 
 OK, E_INVALID, E_OOM_PAGES, E_STATE, E_HIP = range(5)
-F32, BF16 = 0, 1
+F32, BF16, FP8_E4M3 = 0, 1, 2
 SEQ_PREFIX, SEQ_BRANCH = 0, 1
 UNUSED, ACTIVE, COMPLETED, PRUNED, EARLY_STOPPED = range(5)
 DROP_LOWEST_K, KEEP_TOP_K, THRESHOLD = 0, 1, 2
-LAYOUT_NATURAL, LAYOUT_MFMA16 = 0, 1
+LAYOUT_NATURAL, LAYOUT_MFMA16, LAYOUT_MFMA16_FP8 = 0, 1, 2
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("SART_LIB") or os.path.join(_DIR, "libsart.so")  # SART_LIB: a developer build
@@ -38,7 +38,8 @@ class _Desc(C.Structure):
                 ("finish_quota", C.c_int32), ("max_pages_per_branch", C.c_int32),
                 ("max_prefix_pages", C.c_int32), ("kv_dtype", C.c_int32),
                 ("force_natural_layout", C.c_int32), ("kv_pool", C.c_void_p),
-                ("kv_pool_bytes", C.c_size_t), ("initial_free_order", _ip)]
+                ("kv_pool_bytes", C.c_size_t), ("initial_free_order", _ip), ("k_scale", C.c_float),
+                ("v_scale", C.c_float)]
 
 
 class _Policy(C.Structure):
@@ -110,7 +111,7 @@ class SartCache:
 
     def __init__(self, *, n_q_heads, n_kv_heads, head_dim, page_tokens=16, num_pages, max_requests,
                  branches_per_request, finish_quota=0, max_pages_per_branch, max_prefix_pages, dtype="bf16",
-                 free_order=None, kv_pool=None, force_natural_layout=False, n_layers=1):
+                 free_order=None, kv_pool=None, force_natural_layout=False, n_layers=1, k_scale=1.0, v_scale=1.0):
         import torch
         self.lib = load_library()
         self.Hq, self.Hkv, self.d, self.pt = n_q_heads, n_kv_heads, head_dim, page_tokens
@@ -120,8 +121,8 @@ class SartCache:
         self.torch_dtype = torch.float32 if dtype == "f32" else torch.bfloat16
         self.n_layers = n_layers
         d = _Desc(n_layers, n_q_heads, n_kv_heads, head_dim, page_tokens, num_pages, max_requests, branches_per_request,
-                  finish_quota, max_pages_per_branch, max_prefix_pages, F32 if dtype == "f32" else BF16,
-                  1 if force_natural_layout else 0, None, 0, None)
+                  finish_quota, max_pages_per_branch, max_prefix_pages, {"f32": F32, "bf16": BF16, "fp8": FP8_E4M3}[dtype],
+                  1 if force_natural_layout else 0, None, 0, None, float(k_scale), float(v_scale))
         self.pool_bytes = int(self.lib.sart_pool_bytes(C.byref(d)))
         self._pool = kv_pool  # keep the tensor alive
         if kv_pool is not None:

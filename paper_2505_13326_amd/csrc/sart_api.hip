@@ -55,6 +55,7 @@ struct sart_cache {
   int next_slot = 0;
   int call_seq = 0;
   size_t layer_bytes = 0;              // pool bytes of one layer
+  float k_scale = 1.0f, v_scale = 1.0f; // 8-bit float caches: stored code * scale is the value
   // the last layer-0 append, which the same step's appends to the other layers must repeat
   int last_kind = -1, last_n_seqs = 0, last_has_ids = 0;
   long long last_total = 0;
@@ -106,7 +107,12 @@ sart_status check_desc(const sart_cache_desc* d) {
     return fail(SART_E_INVALID, "page_tokens, num_pages, max_requests, branches_per_request must be positive");
   if (d->max_pages_per_branch <= 0 || d->max_prefix_pages <= 0)
     return fail(SART_E_INVALID, "max_pages_per_branch and max_prefix_pages must be positive");
-  if (d->kv_dtype != SART_F32 && d->kv_dtype != SART_BF16) return fail(SART_E_INVALID, "unknown kv_dtype");
+  if (d->kv_dtype != SART_F32 && d->kv_dtype != SART_BF16 && d->kv_dtype != SART_FP8_E4M3)
+    return fail(SART_E_INVALID, "unknown kv_dtype");
+  if (d->kv_dtype == SART_FP8_E4M3 &&
+      (d->page_tokens != 16 || (d->head_dim != 64 && d->head_dim != 128) || d->n_q_heads / d->n_kv_heads > kMaxGroup ||
+       d->force_natural_layout))
+    return fail(SART_E_INVALID, "SART_FP8_E4M3 needs page_tokens 16, head_dim 64 or 128, Hq/Hkv <= 16, no forced layout");
   if ((long long)d->max_requests * d->branches_per_request > (1 << 22))
     return fail(SART_E_INVALID, "max_requests * branches_per_request too large");
   return SART_OK;
@@ -114,6 +120,7 @@ sart_status check_desc(const sart_cache_desc* d) {
 
 int pick_layout(const sart_cache_desc* d) {
   const int G = d->n_q_heads / d->n_kv_heads;
+  if (d->kv_dtype == SART_FP8_E4M3) return SART_LAYOUT_MFMA16_FP8;
   if (!d->force_natural_layout && d->kv_dtype == SART_BF16 && d->page_tokens == 16 &&
       (d->head_dim == 64 || d->head_dim == 128) && G <= kMaxGroup)
     return SART_LAYOUT_MFMA16;
@@ -130,7 +137,7 @@ const char* sart_last_error(void) { return g_err; }
 
 size_t sart_pool_bytes(const sart_cache_desc* d) {
   if (!d) return 0;
-  const size_t es = d->kv_dtype == SART_F32 ? 4 : 2;
+  const size_t es = d->kv_dtype == SART_F32 ? 4 : (d->kv_dtype == SART_FP8_E4M3 ? 1 : 2);
   return (size_t)(d->n_layers > 0 ? d->n_layers : 1) * d->num_pages * d->page_tokens * 2 * d->n_kv_heads * d->head_dim * es;
 }
 
@@ -167,7 +174,10 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   dm.pt = d->page_tokens; dm.num_pages = d->num_pages; dm.max_req = d->max_requests;
   dm.Nb = d->branches_per_request; dm.Q = d->finish_quota; dm.max_bp = d->max_pages_per_branch;
   dm.max_pp = d->max_prefix_pages; dm.H = dm.max_req * dm.Nb; dm.dtype = d->kv_dtype;
-  dm.layout = pick_layout(d); dm.esize = d->kv_dtype == SART_F32 ? 4 : 2;
+  dm.layout = pick_layout(d); dm.esize = d->kv_dtype == SART_F32 ? 4 : (d->kv_dtype == SART_FP8_E4M3 ? 1 : 2);
+  c->k_scale = d->kv_dtype == SART_FP8_E4M3 && d->k_scale > 0.f ? d->k_scale : 1.0f;
+  c->v_scale = d->kv_dtype == SART_FP8_E4M3 && d->v_scale > 0.f ? d->v_scale : 1.0f;
+  dm.k_inv_scale = 1.0f / c->k_scale; dm.v_inv_scale = 1.0f / c->v_scale;
   dm.tile_elems = (long long)dm.pt * dm.d;
   dm.page_elems = (long long)dm.Hkv * 2 * dm.tile_elems;
 
@@ -214,7 +224,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   c->plan.n_wg = cus;                // one 4-wave workgroup per CU, one wave per SIMD
   c->plan.n_wg_prompt = 0;           // every wave serves the own line, then the prompt line
   c->plan.chunk_pages = 0;
-  c->plan.inline_prefix = 1;         // measured faster than the LDS-staged prompt phase on every config
+  c->plan.inline_prefix = 1;         // (8-bit float and natural-layout caches: always) measured faster than the LDS-staged prompt phase on every config
   c->plan.skew_permille = kDefaultSkewPermille;
   ALLOC(tb.wave_row, (size_t)2 * c->max_wg * kAttnWaves);
   ALLOC(tb.req_pstart, R);
@@ -360,7 +370,8 @@ sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, f
   note_stream(c, stream);
   DecodeArgs a{};
   a.q = q; a.out = out; a.n_rows = n_rows;
-  a.scale_log2 = scale * 1.44269504088896340736f;
+  a.scale_log2 = scale * 1.44269504088896340736f * c->k_scale;
+  a.v_scale = c->v_scale;
   a.n_wg = c->plan.n_wg;
   a.inline_prefix = c->plan.inline_prefix;
   a.partials = c->partials; a.partial_cap = c->partial_cap;
@@ -400,7 +411,8 @@ sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs,
   if (rc != SART_OK) return rc;
   PrefillArgs a{};
   a.n_seqs = n_seqs; a.q = q; a.out = out; a.call_seq = ++c->call_seq;
-  a.scale_log2 = scale * 1.44269504088896340736f;
+  a.scale_log2 = scale * 1.44269504088896340736f * c->k_scale;
+  a.v_scale = c->v_scale;
   a.total_q = (int)total; a.n_tiles = (int)tiles;
   int* hbuf = s->host;
   int qo = 0, to = 0;
@@ -574,7 +586,7 @@ sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t 
   const int n_wg = n_workgroups > 0 ? n_workgroups : cus;
   const int n_pw = n_prompt_workgroups >= 0 ? n_prompt_workgroups : 0;
   if (n_pw >= n_wg && n_pw > 0) return fail(SART_E_INVALID, "n_prompt_workgroups must leave a streaming workgroup");
-  if (prompt_mode >= 0) c->plan.inline_prefix = c->ctx.dm.layout == SART_LAYOUT_MFMA16 ? prompt_mode : 1;
+  if (prompt_mode >= 0) c->plan.inline_prefix = c->ctx.dm.layout == SART_LAYOUT_MFMA16 ? prompt_mode : 1;   // other layouts: inline only
   c->plan.skew_permille = skew_permille;
   c->plan.n_wg = n_wg;
   c->plan.n_wg_prompt = n_pw;

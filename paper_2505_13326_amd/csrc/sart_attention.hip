@@ -80,16 +80,19 @@ __device__ inline void store_partial(const WaveState<D>& st, float* partials, lo
 // the compiler may then read page ids with scalar loads, which do not queue
 // behind the in-flight vector loads of K/V tiles.
 // ---------------------------------------------------------------------------
-template <int D>
+// FP8: an 8-bit float cache (SART_LAYOUT_MFMA16_FP8): half the bytes per tile, expanded
+// to bf16 operands in registers; its prompts are always read inline.
+template <int D, bool FP8>
 __global__ void __launch_bounds__(kAttnThreads)
 k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restrict__ bt1,
             const int* __restrict__ item_desc, const int* __restrict__ prefix_table) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
-  constexpr int KQ = D / 32;                       // 16-byte chunks per lane per tile
-  constexpr int kRing = 4;                         // pages in flight per wave while streaming
-  constexpr int kTileBytes = 16 * D * 2;           // one K (or V) tile
+  constexpr int KQ = D / 32;                       // 16-byte bf16 chunks per lane per tile
+  constexpr int KR = raw_chunks<D, FP8>();         // 16-byte chunks per lane per tile as stored
+  constexpr int kRing = 4;                         // pages in flight per wave while streaming (8 for an 8-bit float cache measured slower)
+  constexpr int kTileBytes = 16 * D * (FP8 ? 1 : 2);   // one K (or V) tile
   constexpr int kPageBytes = 2 * kTileBytes;       // K tile + V tile of one kv head
   constexpr int kRound = kAttnThreads * 16;                // bytes one load round of the workgroup covers
   constexpr int kCPT = (kPageBytes + kRound - 1) / kRound; // staged 16-byte chunks per thread per page
@@ -124,7 +127,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
     if ((phase == 0) == prompt_first) {
       // ---- shared prompt items (LDS prompt mode) ----------------------------
       SART_STAMP(1);
-      if (dedicated && !prompt_wg) continue;
+      if (FP8 || (dedicated && !prompt_wg)) continue;
       const int it0 = dedicated ? (int)blockIdx.x - n_own_wg : (int)blockIdx.x;
       const int it_step = dedicated ? (int)gridDim.x - n_own_wg : (int)gridDim.x;
       for (int it = it0; it < n_items; it += it_step) {
@@ -203,7 +206,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
     const Cut cut = load_cut(scal);
     const long long wave_id = (long long)blockIdx.x * kAttnWaves + wv;
     SART_STAMP(3);
-    const long long page_bytes = dm.page_elems * 2;
+    const long long page_bytes = dm.page_elems * (FP8 ? 1 : 2);
     for (int line = 1; line >= 0; --line) {   // prompt line first: all waves start it together, so neighbours share pages in time
       long long x, u, u1;          // range number and its units on this line
       int cursor;                  // own line: active row; prompt line: live request index
@@ -260,7 +263,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         auto load_page = [&](uint4* kq, uint4* vq, int pid) {
           const unsigned char* base = pool + (long long)pid * page_bytes + head_off;
 #pragma unroll
-          for (int i = 0; i < KQ; ++i) {
+          for (int i = 0; i < KR; ++i) {
             kq[i] = *(const uint4*)(base + i * 1024);
             vq[i] = *(const uint4*)(base + kTileBytes + i * 1024);
           }
@@ -271,7 +274,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         // the oldest buffer only (s_waitcnt vmcnt(8*kRing-1 ...)) while the
         // newer pages are still in flight; page ids are wave-uniform scalar
         // reads of the table.
-        uint4 kb[kRing][KQ], vb[kRing][KQ];
+        uint4 kb[kRing][KR], vb[kRing][KR];
         int i = 0;
         if (rn >= 2 * kRing) {
 #pragma unroll
@@ -282,14 +285,14 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
             for (int j = 0; j < kRing; ++j) pid[j] = table[r0 + i + kRing + j];
 #pragma unroll
             for (int j = 0; j < kRing; ++j) {
-              process_page<D, true>(st, kb[j], vb[j], qreg, 16, 16, a.scale_log2);
+              process_raw<D, FP8, true>(st, kb[j], vb[j], qreg, 16, 16, a.scale_log2);
               load_page(kb[j], vb[j], pid[j]);
             }
             i += kRing;
           } while (i + 2 * kRing <= rn);
 #pragma unroll
           for (int j = 0; j < kRing; ++j)
-            { const int nv = i + j == rn - 1 ? n_last : 16; process_page<D, false>(st, kb[j], vb[j], qreg, nv, nv, a.scale_log2); }
+            { const int nv = i + j == rn - 1 ? n_last : 16; process_raw<D, FP8, false>(st, kb[j], vb[j], qreg, nv, nv, a.scale_log2); }
           i += kRing;
         }
         while (i < rn) {   // fewer than 2*kRing pages left: groups of up to kRing, requested up front
@@ -299,7 +302,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
             if (j < cnt) load_page(kb[j], vb[j], table[r0 + i + j]);
 #pragma unroll
           for (int j = 0; j < kRing; ++j)
-            if (j < cnt) { const int nv = i + j == rn - 1 ? n_last : 16; process_page<D, false>(st, kb[j], vb[j], qreg, nv, nv, a.scale_log2); }
+            if (j < cnt) { const int nv = i + j == rn - 1 ? n_last : 16; process_raw<D, FP8, false>(st, kb[j], vb[j], qreg, nv, nv, a.scale_log2); }
           i += cnt;
         }
         store_partial<D>(st, a.partials, slot, dm);
@@ -472,26 +475,27 @@ k_merge(Ctx c, DecodeArgs a, int inline_prefix) {
         m = mn;
       }
       const float inv = l > 0.f ? 1.0f / l : 0.f;
-      *(f32x4*)(a.out + ((long long)row * dm.Hq + h * G + r) * D + 4 * d4) = acc * inv;
+      *(f32x4*)(a.out + ((long long)row * dm.Hq + h * G + r) * D + 4 * d4) = acc * (inv * a.v_scale);
     }
   }
 }
 
 void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s) {
   const Dims& dm = c.dm;
-  const bool mfma = dm.layout == SART_LAYOUT_MFMA16;
+  const bool mfma = dm.layout != SART_LAYOUT_NATURAL;
   if (a.ev[0]) (void)hipEventRecord(a.ev[0], s);
   if (a.ev[1]) (void)hipEventRecord(a.ev[1], s);
   // profiling with repeats > 1 launches the (idempotent) attention kernel that many times
   // back to back between the two events, so their dispatch overhead is amortised
   for (int rep = 0; rep < (a.repeats > 1 ? a.repeats : 1); ++rep) {
   if (mfma) {
-    if (dm.d == 128)
-      hipLaunchKernelGGL(k_attn_mfma<128>, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], c.tb.bt[1],
-                         c.tb.item_desc, c.tb.prefix_table);
-    else
-      hipLaunchKernelGGL(k_attn_mfma<64>, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], c.tb.bt[1],
-                         c.tb.item_desc, c.tb.prefix_table);
+    auto go = [&](auto kern) {
+      hipLaunchKernelGGL(kern, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], c.tb.bt[1], c.tb.item_desc,
+                         c.tb.prefix_table);
+    };
+    const bool fp8 = dm.layout == SART_LAYOUT_MFMA16_FP8;
+    if (dm.d == 128) { if (fp8) go(k_attn_mfma<128, true>); else go(k_attn_mfma<128, false>); }
+    else { if (fp8) go(k_attn_mfma<64, true>); else go(k_attn_mfma<64, false>); }
   } else if (dm.dtype == SART_F32) {
     hipLaunchKernelGGL(k_attn_generic<float>, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a);
   } else {

@@ -105,6 +105,40 @@ __device__ inline void process_page(WaveState<D>& st, const uint4* kq, const uin
   }
 }
 
+// 8-bit float caches (SART_LAYOUT_MFMA16_FP8): a 16-byte chunk of the tile holds
+// what two bf16 chunks hold.  expand_fp8 turns the D/64 raw chunks of a lane into
+// the D/32 bf16 chunks process_page expects (E4M3 values are exact in bf16; the
+// cache's scales are applied to the scores and to the output, not here).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ inline unsigned fp8x2_to_bf16x2(unsigned codes, bool high_half) {
+  return high_half ? __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes, 1.0f, true))
+                   : __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes, 1.0f, false));
+}
+template <int D>
+__device__ inline void expand_fp8(const uint4* raw, uint4* out) {
+#pragma unroll
+  for (int c = 0; c < D / 64; ++c) {
+    out[2 * c] = uint4{fp8x2_to_bf16x2(raw[c].x, false), fp8x2_to_bf16x2(raw[c].x, true),
+                       fp8x2_to_bf16x2(raw[c].y, false), fp8x2_to_bf16x2(raw[c].y, true)};
+    out[2 * c + 1] = uint4{fp8x2_to_bf16x2(raw[c].z, false), fp8x2_to_bf16x2(raw[c].z, true),
+                           fp8x2_to_bf16x2(raw[c].w, false), fp8x2_to_bf16x2(raw[c].w, true)};
+  }
+}
+// chunks a lane loads per K (or V) tile, and process_page on them as loaded
+template <int D, bool FP8> constexpr int raw_chunks() { return FP8 ? D / 64 : D / 32; }
+template <int D, bool FP8, bool FULL>
+__device__ inline void process_raw(WaveState<D>& st, const uint4* rk, const uint4* rv, const uint4* qreg,
+                                   int nvalid, int nvalid_row, float scale_log2) {
+  if constexpr (FP8) {
+    uint4 kq[D / 32], vq[D / 32];
+    expand_fp8<D>(rk, kq);
+    expand_fp8<D>(rv, vq);
+    process_page<D, FULL>(st, kq, vq, qreg, nvalid, nvalid_row, scale_log2);
+  } else {
+    process_page<D, FULL>(st, rk, rv, qreg, nvalid, nvalid_row, scale_log2);
+  }
+}
+
 // Two consecutive pages (32 tokens) at once, for the compute-bound prefill:
 // one running-max update per 32 tokens, and O^T += V^T P^T as 16x16x32
 // products.  The contraction index of that product is (lane >> 4, e): e < 4 is

@@ -202,6 +202,20 @@ k_append_write(Ctx c, AppendArgs a) {
     const long long kb = tile_base(dm, page, head), vb = kb + dm.tile_elems;
     const T* ksrc = (const T*)a.k + (row * dm.Hkv + head) * dm.d;
     const T* vsrc = (const T*)a.v + (row * dm.Hkv + head) * dm.d;
+    if (dm.dtype == SART_FP8_E4M3) {
+      // bf16 in, one byte out: nearest E4M3 code of x / scale (ties to even), magnitude clamped to 448
+      if constexpr (sizeof(T) == 2) {
+        unsigned char* pool8 = (unsigned char*)c.pool;
+        for (int d = lane; d < dm.d; d += 64) {
+          const float kf = __uint_as_float((unsigned)ksrc[d] << 16) * dm.k_inv_scale;
+          const float vf = __uint_as_float((unsigned)vsrc[d] << 16) * dm.v_inv_scale;
+          const int codes = __builtin_amdgcn_cvt_pk_fp8_f32(fminf(fmaxf(kf, -448.f), 448.f), fminf(fmaxf(vf, -448.f), 448.f), 0, false);
+          pool8[kb + k_elem_off(dm.layout, dm.d, slot, d)] = (unsigned char)(codes & 0xff);
+          pool8[vb + v_elem_off(dm.layout, dm.d, slot, d)] = (unsigned char)((codes >> 8) & 0xff);
+        }
+      }
+      continue;
+    }
     for (int d = lane; d < dm.d; d += 64) {
       pool[kb + k_elem_off(dm.layout, dm.d, slot, d)] = ksrc[d];
       pool[vb + v_elem_off(dm.layout, dm.d, slot, d)] = vsrc[d];

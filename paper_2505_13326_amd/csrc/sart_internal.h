@@ -56,6 +56,7 @@ struct Dims {
   int Hq, Hkv, G, d, pt, num_pages, max_req, Nb, Q, max_bp, max_pp, H, dtype, layout, esize;
   long long tile_elems;   // pt * d: elements of one K (or V) tile
   long long page_elems;   // Hkv * 2 * tile_elems
+  float k_inv_scale, v_inv_scale;   // 8-bit float caches: what K and V are multiplied by before rounding
 };
 
 struct Tables {
@@ -168,10 +169,14 @@ __host__ __device__ inline long long prompt_range_of_wave(long long i, int n_pro
 // NATURAL: [token][d].   MFMA16: see sart.h.
 __host__ __device__ inline long long k_elem_off(int layout, int d_dim, int token, int d) {
   if (layout == SART_LAYOUT_NATURAL) return (long long)token * d_dim + d;
+  if (layout == SART_LAYOUT_MFMA16_FP8)
+    return ((long long)(d >> 6) * 64 + ((d >> 3) & 3) * 16 + token) * 16 + ((d >> 5) & 1) * 8 + (d & 7);
   return ((long long)(d >> 3) * 16 + token) * 8 + (d & 7);
 }
 __host__ __device__ inline long long v_elem_off(int layout, int d_dim, int token, int d) {
   if (layout == SART_LAYOUT_NATURAL) return (long long)token * d_dim + d;
+  if (layout == SART_LAYOUT_MFMA16_FP8)
+    return ((long long)(d >> 6) * 64 + (token >> 2) * 16 + (d & 15)) * 16 + ((d >> 5) & 1) * 8 + ((d >> 4) & 1) * 4 + (token & 3);
   int chunk = (d >> 5) * 64 + (token >> 2) * 16 + (d & 15);
   int e = (token & 3) + (((d >> 4) & 1) << 2);
   return (long long)chunk * 8 + e;
@@ -218,6 +223,7 @@ struct DecodeArgs {
   float* partials;      // scratch
   long long partial_cap; // partial slots available
   int call_seq;
+  float v_scale;        // 8-bit float caches: what the output is multiplied by (1 otherwise)
   hipEvent_t ev[4];     // optional profiling events (null: none)
   int repeats;          // profiling: attention launches between ev[1] and ev[2]
 };
@@ -232,6 +238,7 @@ struct PrefillArgs {
   const void* q;
   float* out;
   float scale_log2;
+  float v_scale;          // 8-bit float caches: what the output is multiplied by (1 otherwise)
   int call_seq;
   int n_tiles;
   int total_q;

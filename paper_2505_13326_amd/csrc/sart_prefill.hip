@@ -63,14 +63,15 @@ __device__ inline int last_le(const int* v, int n, int x) {
   return lo;
 }
 
-template <int D>
+template <int D, bool FP8>
 __global__ void __launch_bounds__(kAttnThreads, 2)
 k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   if (!tb.scal[S_CALLOK]) return;
   constexpr int KQ = D / 32;
-  constexpr int kTileBytes = 16 * D * 2, kPageBytes = 2 * kTileBytes;
+  constexpr int KR = raw_chunks<D, FP8>();                 // 16-byte chunks per lane per tile as stored
+  constexpr int kTileBytes = 16 * D * (FP8 ? 1 : 2), kPageBytes = 2 * kTileBytes;
   const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r16 = lane & 15, g4 = lane >> 4;
   // tile -> (sequence, kv head, row tile); a sequence's later rows (longer contexts) come first
@@ -89,7 +90,7 @@ k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   const uint16_t* q = (const uint16_t*)a.q;
   const unsigned char* pool = (const unsigned char*)c.pool;
   const int* __restrict__ table = prefix_table + (long long)req * dm.max_pp;
-  const long long page_bytes = dm.page_elems * 2;
+  const long long page_bytes = dm.page_elems * (FP8 ? 1 : 2);
   const long long head_off = (long long)h * kPageBytes + lane * 16;
 
   // per 16-row block: this lane's row, its position, the block's position range
@@ -121,44 +122,61 @@ k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   // blocks are done, V after the last O^T product, so each load has half a turn to arrive.  Every
   // load is unconditional (past the end the last pair again).
   const int n_pairs = (n_pages + 1) >> 1;
-  uint4 k0[KQ], k1[KQ], v0[KQ], v1[KQ];
+  uint4 k0[KR], k1[KR], v0[KR], v1[KR];                       // as stored (an 8-bit float cache: half as many)
   auto load_k = [&](int pr) {
     const unsigned char* b0 = pool + (long long)table[2 * pr] * page_bytes + head_off;
     const unsigned char* b1 = pool + (long long)table[min(2 * pr + 1, n_pages - 1)] * page_bytes + head_off;
 #pragma unroll
-    for (int k = 0; k < KQ; ++k) { k0[k] = *(const uint4*)(b0 + k * 1024); k1[k] = *(const uint4*)(b1 + k * 1024); }
+    for (int k = 0; k < KR; ++k) { k0[k] = *(const uint4*)(b0 + k * 1024); k1[k] = *(const uint4*)(b1 + k * 1024); }
   };
   auto load_v = [&](int pr) {
     const unsigned char* b0 = pool + (long long)table[2 * pr] * page_bytes + head_off + kTileBytes;
     const unsigned char* b1 = pool + (long long)table[min(2 * pr + 1, n_pages - 1)] * page_bytes + head_off + kTileBytes;
 #pragma unroll
-    for (int k = 0; k < KQ; ++k) { v0[k] = *(const uint4*)(b0 + k * 1024); v1[k] = *(const uint4*)(b1 + k * 1024); }
+    for (int k = 0; k < KR; ++k) { v0[k] = *(const uint4*)(b0 + k * 1024); v1[k] = *(const uint4*)(b1 + k * 1024); }
+  };
+  // the bf16 operands of a tile: the registers as loaded, or their expansion
+  auto operands = [&](const uint4* raw, uint4* tmp) -> const uint4* {
+    if constexpr (FP8) { expand_fp8<D>(raw, tmp); return tmp; } else { return raw; }
   };
   load_k(0);
   load_v(0);
   for (int pr = 0; pr < n_pairs; ++pr) {
     const int t0 = pr * 32;
     const int nxt = min(pr + 1, n_pairs - 1);
+    uint4 tk0[FP8 ? KQ : 1], tk1[FP8 ? KQ : 1], tv0[FP8 ? KQ : 1], tv1[FP8 ? KQ : 1];
     if (t0 + 31 <= lo_pos[0]) {
       // every row of the wave sees the whole pair: phase by phase over the wave's independent blocks
       f32x4 s0[kPfBlocks], s1[kPfBlocks];
       bf16x8 pp[kPfBlocks];
+      {
+        const uint4* q0 = operands(k0, tk0);
+        const uint4* q1 = operands(k1, tk1);
 #pragma unroll
-      for (int b = 0; b < kPfBlocks; ++b) pair_scores<D, 1>(k0, k1, qreg[b], s0[b], s1[b]);
+        for (int b = 0; b < kPfBlocks; ++b) pair_scores<D, 1>(q0, q1, qreg[b], s0[b], s1[b]);
+      }
       load_k(nxt);
 #pragma unroll
       for (int b = 0; b < kPfBlocks; ++b) pp[b] = pair_softmax<D, true>(st[b], s0[b], s1[b], 32, a.scale_log2);
+      {
+        const uint4* w0 = operands(v0, tv0);
+        const uint4* w1 = operands(v1, tv1);
 #pragma unroll
-      for (int b = 0; b < kPfBlocks; ++b) pair_pv<D, true>(st[b], v0, v1, pp[b], 32);
+        for (int b = 0; b < kPfBlocks; ++b) pair_pv<D, true>(st[b], w0, w1, pp[b], 32);
+      }
       load_v(nxt);
     } else {
       // pairs that straddle some row's position: block by block, scores masked per row
       const int nvalid = min(32, min(plen, n_pages * 16) - t0);      // tokens the pair holds
+      const uint4* q0 = operands(k0, tk0);
+      const uint4* q1 = operands(k1, tk1);
+      const uint4* w0 = operands(v0, tv0);
+      const uint4* w1 = operands(v1, tv1);
 #pragma unroll
       for (int b = 0; b < kPfBlocks; ++b) {
         if (t0 > hi_pos[b]) continue;                        // the pair lies after every row of the block
-        if (t0 + 31 <= lo_pos[b]) process_pair<D, true, 1>(st[b], k0, v0, k1, v1, qreg[b], 32, 32, a.scale_log2);
-        else process_pair<D, false, 1>(st[b], k0, v0, k1, v1, qreg[b], nvalid, min(nvalid, pos[b] + 1 - t0), a.scale_log2);
+        if (t0 + 31 <= lo_pos[b]) process_pair<D, true, 1>(st[b], q0, w0, q1, w1, qreg[b], 32, 32, a.scale_log2);
+        else process_pair<D, false, 1>(st[b], q0, w0, q1, w1, qreg[b], nvalid, min(nvalid, pos[b] + 1 - t0), a.scale_log2);
       }
       load_k(nxt);
       load_v(nxt);
@@ -168,7 +186,7 @@ k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   for (int b = 0; b < kPfBlocks; ++b) {
     const float l = sum_over_rows(st[b].l);
     if (out_row[b] < 0) continue;
-    const float inv = 1.0f / l;                            // every row sees at least its own token
+    const float inv = a.v_scale / l;                       // every row sees at least its own token
     float* o = a.out + out_row[b];
 #pragma unroll
     for (int k = 0; k < D / 16; ++k) *(f32x4*)(o + k * 16 + 4 * g4) = st[b].o[k] * inv;
@@ -199,7 +217,7 @@ k_prefill_generic(Ctx c, PrefillArgs a) {
       float m = -__builtin_inff(), l = 0.f;
       float o[4] = {0.f, 0.f, 0.f, 0.f};
       generic_row<T>(dm, pool, table, 0, ceil_div(tokens, dm.pt), tokens, h, q + row, a.scale_log2, m, l, o);
-      const float inv = 1.0f / l;
+      const float inv = a.v_scale / l;
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc) {
         const int d = lane + 64 * cc;
@@ -213,11 +231,13 @@ void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s) {
   const Dims& dm = c.dm;
   hipLaunchKernelGGL(k_prefill_check, dim3(1), dim3(256), 0, s, c, a);
   if (a.total_q <= 0) return;
-  if (dm.layout == SART_LAYOUT_MFMA16) {
-    if (dm.d == 128)
-      hipLaunchKernelGGL(k_prefill_mfma<128>, dim3(a.n_tiles), dim3(kAttnThreads), 0, s, c, a, c.tb.prefix_table);
-    else
-      hipLaunchKernelGGL(k_prefill_mfma<64>, dim3(a.n_tiles), dim3(kAttnThreads), 0, s, c, a, c.tb.prefix_table);
+  if (dm.layout != SART_LAYOUT_NATURAL) {
+    auto go = [&](auto kern) {
+      hipLaunchKernelGGL(kern, dim3(a.n_tiles), dim3(kAttnThreads), 0, s, c, a, c.tb.prefix_table);
+    };
+    const bool fp8 = dm.layout == SART_LAYOUT_MFMA16_FP8;
+    if (dm.d == 128) { if (fp8) go(k_prefill_mfma<128, true>); else go(k_prefill_mfma<128, false>); }
+    else { if (fp8) go(k_prefill_mfma<64, true>); else go(k_prefill_mfma<64, false>); }
   } else {
     long long blocks = ((long long)a.total_q * dm.Hkv + kAttnWaves - 1) / kAttnWaves;
     if (blocks > 65536) blocks = 65536;
