@@ -19,9 +19,11 @@
 //     step are laid on one line and cut into equal ranges, one per wave
 //     (a range may cross branch boundaries); each piece yields a partial
 //     (m, l, o) that a merge kernel combines.
-//   * Shared prompt pages are staged in LDS once per (request, kv head,
-//     chunk) workgroup and reused by the request's branches (one wave each)
-//     and all query heads of the group.
+//   * Shared prompt pages are read once per branch, but in blocks ordered
+//     (request, kv head, chunk, branch) that every wave serves before its own
+//     range, so the re-reads of a chunk are neighbours in time and on one XCD
+//     and hit in its L2 (default).  The other mode stages each prompt chunk in
+//     LDS once per workgroup for the request's branches, one wave each.
 #include "sart_attn_tile.h"
 
 namespace sart {
@@ -67,15 +69,16 @@ __device__ inline void store_partial(const WaveState<D>& st, float* partials, lo
 }
 
 // ---------------------------------------------------------------------------
-// A4 + A5: persistent attention kernel (bf16, SART_LAYOUT_MFMA16, 16-token pages).
+// A4 + A5: persistent attention kernel (SART_LAYOUT_MFMA16 / _FP8, 16-token pages).
 // One 4-wave workgroup per CU, one wave per SIMD: two waves on a SIMD do not
 // share it fairly (the older one streams about 1.5x faster, measured), which a
 // static partition cannot absorb; memory-level parallelism comes from the
-// per-wave ring of page buffers instead.  Each workgroup has a shared-prompt phase (its
-// items of the plan, K/V staged through LDS, one wave per branch; empty when
-// the prompt is read inline) and a private phase (each wave streams its own
-// range of units).  Even workgroups run the prompt phase first, odd ones last,
-// so that the latency-bound prompt phases do not all idle HBM at once.
+// per-wave ring of page buffers instead.  Each workgroup has an LDS prompt phase
+// (its items of the plan, K/V staged through LDS, one wave per branch; empty when
+// the prompt is read inline, the default) and a streaming phase (each wave
+// streams its prompt blocks, then its range of the own line).  With LDS prompt
+// items, even workgroups run that phase first, odd ones last, so that the
+// latency-bound phases do not all idle HBM at once.
 // bt0 / bt1 are the two block-table buffers again, as noalias kernel arguments:
 // the compiler may then read page ids with scalar loads, which do not queue
 // behind the in-flight vector loads of K/V tiles.
