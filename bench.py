@@ -351,6 +351,36 @@ def main():
                 "algorithmic_bytes_per_launch": int(alg_bytes_prof), "kernel_ms_avg": round(attn_avg, 4),
                 "kernel_ms_p10_p50_p90": [round(float(np.percentile(attn_ms, p)), 4) for p in (10, 50, 90)],
                 "launches_per_event_pair": args.kernel_repeats}
+    # the whole sart_decode_attention call (attention kernel + merge), back to back without appends, wall clock
+    n_call = max(10, K // 2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n_call):
+        cache.decode_attention(qs[i % n_in], out=out)
+    torch.cuda.synchronize()
+    call_ms = (time.perf_counter() - t0) / n_call * 1e3
+    priv2, _ = tokens_now()
+    call_bytes = (priv2 + pre) * tok_bytes + io_bytes
+    roofline["decode_call_ms_avg"] = round(call_ms, 4)
+    roofline["decode_call_frac"] = round(call_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+
+    # ---- what plain reads reach on this machine: 8 KiB chunks of a 2 GiB buffer, in order and shuffled ----
+    probe = torch.ones(1 << 31, dtype=torch.uint8, device="cuda")
+    order = torch.randperm((1 << 31) // 8192, device="cuda", dtype=torch.int32, generator=torch.Generator(device="cuda").manual_seed(1))
+    rates = []
+    for od in (None, order):
+        for _ in range(3):
+            sart.read_probe(probe, od)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        evs[0].record()
+        for _ in range(10):
+            sart.read_probe(probe, od)
+        evs[1].record()
+        torch.cuda.synchronize()
+        rates.append((1 << 31) * 10 / (evs[0].elapsed_time(evs[1]) * 1e-3) / 1e9)
+    del probe, order
+    roofline["read_probe_gbs"] = {"sequential": round(rates[0], 1), "shuffled_8KiB": round(rates[1], 1)}
+    roofline["frac_of_read_probe"] = round(achieved / rates[1], 4)
 
     # ---- maintenance calls, once each (they change the batch, so after the step loop) --
     sc = torch.from_numpy(wl.scores(cfg, 0)).cuda()

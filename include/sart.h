@@ -280,6 +280,14 @@ sart_status sart_get_state(sart_cache* cache, int32_t* n_active,
 sart_status sart_set_profiling(sart_cache* cache, int32_t on);
 sart_status sart_last_decode_ms(sart_cache* cache, float* ms_attn, float* ms_total);
 
+/* Measurement aid, no part of the method: reads `bytes` (a multiple of 8 KiB is
+ * used) of a DEVICE buffer with plain coalesced loads, in 8 KiB chunks, in
+ * ascending order or in the order chunk_order gives (DEVICE, bytes / 8192
+ * entries, each a chunk number below that; NULL: ascending).  Asynchronous on
+ * `stream`; the caller times it.  bench.py reports the attention kernel's rate
+ * against this one's on the same box. */
+sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_order, void* stream);
+
 /* Tuning knobs of the decode launch (defaults are chosen for MI355X):
  *   n_workgroups         persistent attention grid of 4-wave workgroups (<= 0:
  *                        one per CU);

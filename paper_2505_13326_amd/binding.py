@@ -65,6 +65,7 @@ _SIGNATURES = {
     "sart_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_last_decode_ms": (C.c_int, [C.c_void_p, _fp, _fp]),
     "sart_set_decode_launch": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "sart_read_probe": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "sart_last_error": (C.c_char_p, []),
 }
 
@@ -90,6 +91,15 @@ def load_library():
             fn.restype, fn.argtypes = res, args
         _lib = lib
     return _lib
+
+
+def read_probe(buf, chunk_order=None, stream=None):
+    """sart_read_probe over a torch device tensor (measurement aid)."""
+    lib = load_library()
+    rc = lib.sart_read_probe(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                             None if chunk_order is None else C.c_void_p(chunk_order.data_ptr()), _stream_handle(stream))
+    if rc != OK:
+        raise SartError(rc, lib.sart_last_error().decode())
 
 
 def _i32(a):

@@ -9,7 +9,7 @@ _DIR = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_DIR)
 CSRC = os.path.join(_DIR, "csrc")
 LIB = os.path.join(_DIR, "libsart.so")
-SOURCES = ["sart_api.hip", "sart_bookkeeping.hip", "sart_attention.hip", "sart_prefill.hip"]
+SOURCES = ["sart_api.hip", "sart_bookkeeping.hip", "sart_attention.hip", "sart_prefill.hip", "sart_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(_ROOT, "include"), "-I", CSRC]

@@ -574,6 +574,13 @@ sart_status sart_last_decode_ms(sart_cache* c, float* ms_attn, float* ms_total) 
   return SART_OK;
 }
 
+sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_order, void* stream) {
+  if (!buf || bytes < 8192) return fail(SART_E_INVALID, "the probe needs a device buffer of at least 8 KiB");
+  launch_read_probe(buf, (long long)(bytes / 8192), chunk_order, (hipStream_t)stream);
+  HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
+
 sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t n_prompt_workgroups,
                                    int32_t prefix_chunk_pages, int32_t prompt_mode, int32_t skew_permille) {
   if (!c) return fail(SART_E_INVALID, "null cache");
