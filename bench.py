@@ -169,7 +169,7 @@ def main():
     ap.add_argument("--free-order", default="scattered", choices=["scattered", "identity"])
     ap.add_argument("--workgroups", type=int, default=0, help="attention workgroups (0 = library default)")
     ap.add_argument("--chunk-pages", type=int, default=0, help="prompt chunk in pages (0 = chosen on device)")
-    ap.add_argument("--prompt-mode", type=int, default=-1, help="0 = prompt staged in LDS and shared, 1 = read inline, -1 = library default")
+    ap.add_argument("--prompt-mode", type=int, default=-1, help="0 = prompt staged in LDS and shared, 1 = prompt blocks read by every branch, 2 = prompt blocks read once for all of a request's query rows, -1 = library default")
     ap.add_argument("--skew", type=int, default=None, help="per-mille of work moved from odd to even workgroups (default: library's)")
     ap.add_argument("--prompt-workgroups", type=int, default=-1, help="workgroups serving only the prompts (-1 = half the grid)")
     ap.add_argument("--prompt-len", type=int, default=-1, help="override the workload's prompt length (experiments)")

@@ -297,16 +297,21 @@ sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_
  *                        own pages first, then its share of the prompts);
  *   prefix_chunk_pages   prompt chunk of the LDS-staged mode (<= 0: sized on the
  *                        device from the active set);
- *   prompt_mode          how the shared prompt is read on SART_LAYOUT_MFMA16
- *                        caches: 1 = every branch reads the prompt pages itself,
- *                        in blocks of pages ordered (request, kv head, chunk,
- *                        branch) that every wave serves before its own range, so
- *                        that the re-reads of a chunk by the request's branches
- *                        are neighbours in time and place and hit in L2
- *                        (default); 0 = each prompt chunk is staged once in LDS
- *                        per workgroup and reused by the request's branches, one
- *                        wave each; -1 = keep the current mode.  Natural-layout
- *                        caches always use mode 1;
+ *   prompt_mode          how the shared prompt is read on the matrix-core
+ *                        layouts.  2 (default) = in blocks of prompt pages, each
+ *                        read once per tile of 16 query rows of the request
+ *                        (rows = (branch, head of the GQA group), branch-major:
+ *                        with G = 7 and 8 branches, 4 tiles instead of 8
+ *                        per-branch reads, every row of the matrix-core tile
+ *                        used); the items are ordered (request, kv head, chunk,
+ *                        tile) and every wave serves its item(s) before its own
+ *                        range, so the tiles' re-reads of a chunk are neighbours
+ *                        in time and place and hit in L2.  1 = the same with one
+ *                        block per (chunk, branch), G of 16 tile rows used.  0 =
+ *                        each prompt chunk is staged once in LDS per workgroup
+ *                        and reused by the request's branches, one wave each
+ *                        (not for SART_FP8_E4M3 caches: 1 is taken).  -1 = keep
+ *                        the current mode.  Natural-layout caches always use 1;
  *   skew_permille        work moved from odd to even streaming workgroups, in
  *                        1/1000 of the mean per-wave range (workgroups go round-
  *                        robin to the 8 XCDs, and the odd XCDs stream about 10 %

@@ -224,7 +224,9 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   c->plan.n_wg = cus;                // one 4-wave workgroup per CU, one wave per SIMD
   c->plan.n_wg_prompt = 0;           // every wave serves the own line, then the prompt line
   c->plan.chunk_pages = 0;
-  c->plan.inline_prefix = 1;         // (8-bit float and natural-layout caches: always) measured faster than the LDS-staged prompt phase on every config
+  // prompt blocks read once per tile of 16 query rows of the request (matrix-core layouts), per branch otherwise:
+  // measured faster than the LDS-staged prompt phase on every config
+  c->plan.inline_prefix = dm.layout == SART_LAYOUT_NATURAL ? 1 : 2;
   c->plan.skew_permille = kDefaultSkewPermille;
   ALLOC(tb.wave_row, (size_t)2 * c->max_wg * kAttnWaves);
   ALLOC(tb.req_pstart, R);
@@ -584,7 +586,7 @@ sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_
 sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t n_prompt_workgroups,
                                    int32_t prefix_chunk_pages, int32_t prompt_mode, int32_t skew_permille) {
   if (!c) return fail(SART_E_INVALID, "null cache");
-  if (prompt_mode < -1 || prompt_mode > 1) return fail(SART_E_INVALID, "prompt_mode must be -1, 0 or 1");
+  if (prompt_mode < -1 || prompt_mode > 2) return fail(SART_E_INVALID, "prompt_mode must be -1, 0, 1 or 2");
   if (skew_permille < -500 || skew_permille > 500) return fail(SART_E_INVALID, "skew_permille out of range");
   if (n_workgroups > c->max_wg) return fail(SART_E_INVALID, "at most %d workgroups", c->max_wg);
   hipDeviceProp_t prop;
@@ -593,7 +595,10 @@ sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t 
   const int n_wg = n_workgroups > 0 ? n_workgroups : cus;
   const int n_pw = n_prompt_workgroups >= 0 ? n_prompt_workgroups : 0;
   if (n_pw >= n_wg && n_pw > 0) return fail(SART_E_INVALID, "n_prompt_workgroups must leave a streaming workgroup");
-  if (prompt_mode >= 0) c->plan.inline_prefix = c->ctx.dm.layout == SART_LAYOUT_MFMA16 ? prompt_mode : 1;   // other layouts: inline only
+  if (prompt_mode >= 0) {
+    const int layout = c->ctx.dm.layout;   // natural layout: per-branch blocks only; 8-bit float: no LDS staging
+    c->plan.inline_prefix = layout == SART_LAYOUT_NATURAL ? 1 : (layout == SART_LAYOUT_MFMA16_FP8 && prompt_mode == 0 ? 1 : prompt_mode);
+  }
   c->plan.skew_permille = skew_permille;
   c->plan.n_wg = n_wg;
   c->plan.n_wg_prompt = n_pw;

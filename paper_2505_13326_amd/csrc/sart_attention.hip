@@ -210,7 +210,122 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
     const long long wave_id = (long long)blockIdx.x * kAttnWaves + wv;
     SART_STAMP(3);
     const long long page_bytes = dm.page_elems * (FP8 ? 1 : 2);
-    for (int line = 1; line >= 0; --line) {   // prompt line first: all waves start it together, so neighbours share pages in time
+    // Streams pages [r0, r0 + rn) of `table` (kv head h) through kRing register
+    // buffers in a software pipeline: kRing pages (8 KiB each) are in flight per
+    // wave.  The steady-state loop and its preheader have no conditional loads,
+    // so the compiler can wait for the oldest buffer only (s_waitcnt
+    // vmcnt(8*kRing-1 ...)) while the newer pages are still in flight; page ids
+    // are wave-uniform scalar reads of the table.  full(k, v): a page of 16
+    // valid tokens; part(k, v, nv): a page that may hold fewer (the last one).
+    auto stream_pages = [&](const int* __restrict__ table, int r0, int rn, int n_last, int h, auto&& full, auto&& part) {
+      const long long head_off = (long long)h * kPageBytes + lane * 16;
+      auto load_page = [&](uint4* kq, uint4* vq, int pid) {
+        const unsigned char* base = pool + (long long)pid * page_bytes + head_off;
+#pragma unroll
+        for (int i = 0; i < KR; ++i) {
+          kq[i] = *(const uint4*)(base + i * 1024);
+          vq[i] = *(const uint4*)(base + kTileBytes + i * 1024);
+        }
+      };
+      uint4 kb[kRing][KR], vb[kRing][KR];
+      int i = 0;
+      if (rn >= 2 * kRing) {
+#pragma unroll
+        for (int j = 0; j < kRing; ++j) load_page(kb[j], vb[j], table[r0 + j]);
+        do {   // at the top: buffer j holds page i+j (all full pages), i + 2*kRing <= rn
+          int pid[kRing];
+#pragma unroll
+          for (int j = 0; j < kRing; ++j) pid[j] = table[r0 + i + kRing + j];
+#pragma unroll
+          for (int j = 0; j < kRing; ++j) {
+            full(kb[j], vb[j]);
+            load_page(kb[j], vb[j], pid[j]);
+          }
+          i += kRing;
+        } while (i + 2 * kRing <= rn);
+#pragma unroll
+        for (int j = 0; j < kRing; ++j) part(kb[j], vb[j], i + j == rn - 1 ? n_last : 16);
+        i += kRing;
+      }
+      while (i < rn) {   // fewer than 2*kRing pages left: groups of up to kRing, requested up front
+        const int cnt = min(kRing, rn - i);
+#pragma unroll
+        for (int j = 0; j < kRing; ++j)
+          if (j < cnt) load_page(kb[j], vb[j], table[r0 + i + j]);
+#pragma unroll
+        for (int j = 0; j < kRing; ++j)
+          if (j < cnt) part(kb[j], vb[j], i + j == rn - 1 ? n_last : 16);
+        i += cnt;
+      }
+    };
+
+    // ---- shared-rows prompt mode: a work item is (request, kv head, chunk of pb prompt pages, tile of up
+    //      to 16 * kSharedBlocks query rows); its pages are read once and every page feeds the tile's
+    //      blocks (rows = (branch, head of the group), branch-major).  One partial per (branch, kv head,
+    //      chunk), in the slots the per-branch blocks would have used. -------------------------------
+    if (a.inline_prefix == 2 && wave_id >= n_waves - cut.n_prompt) {
+      const int r16 = lane & 15, g4 = lane >> 4;
+      const long long pf = partial_floats(dm.G, D);
+      int cursor = tb.wave_row[n_waves + (wave_id - (n_waves - cut.n_prompt))];
+      for (long long item = prompt_range_of_wave(wave_id - (n_waves - cut.n_prompt), cut.n_prompt); item < cut.n_pitems;
+           item += cut.n_prompt) {
+        while (item >= tb.live_item_start[cursor + 1]) ++cursor;   // the live request owning the item
+        const int r = tb.live_req[cursor];
+        const int cnt = tb.refcnt[r], plen = tb.prefix_len[r];
+        const int pp = ceil_div(plen, 16), nck = ceil_div(pp, cut.pb);
+        const int rows = cnt * dm.G, ntile = ceil_div(rows, 16 * kSharedBlocks);
+        const int local = (int)(item - tb.live_item_start[cursor]);
+        const int rt = local % ntile, ck = (local / ntile) % nck, h = local / (ntile * nck);
+        const int r0 = ck * cut.pb, rn = min(cut.pb, pp - r0);
+        const int n_last = min(16, plen - (r0 + rn - 1) * 16);
+        const int row0 = rt * 16 * kSharedBlocks;
+        const int nb = min(kSharedBlocks, ceil_div(rows - row0, 16));          // blocks with rows (wave-uniform)
+        const int first_row = tb.req_first[r];
+        WaveState<D> sb[kSharedBlocks];
+        uint4 qb[kSharedBlocks][KQ];
+        int br[kSharedBlocks], hd[kSharedBlocks];                              // this lane's branch and head per block, -1: no row
+#pragma unroll
+        for (int b = 0; b < kSharedBlocks; ++b) {
+          const int flat = row0 + 16 * b + r16;
+          const bool have = flat < rows;
+          const int fc = have ? flat : rows - 1;                               // lanes past the end shadow the last row
+          const int j = fc / dm.G, g = fc % dm.G;
+          br[b] = have ? j : -1;
+          hd[b] = g;
+          const uint16_t* qrow = q + ((long long)(first_row + j) * dm.Hq + h * dm.G + g) * D;
+#pragma unroll
+          for (int i = 0; i < KQ; ++i) qb[b][i] = *(const uint4*)(qrow + i * 32 + g4 * 8);
+          sb[b].reset();
+        }
+        stream_pages(prefix_table + (long long)r * dm.max_pp, r0, rn, n_last, h,
+                     [&](const uint4* kq, const uint4* vq) {
+#pragma unroll
+                       for (int b = 0; b < kSharedBlocks; ++b)
+                         if (b < nb) process_raw<D, FP8, true>(sb[b], kq, vq, qb[b], 16, 16, a.scale_log2);
+                     },
+                     [&](const uint4* kq, const uint4* vq, int nv) {
+#pragma unroll
+                       for (int b = 0; b < kSharedBlocks; ++b)
+                         if (b < nb) process_raw<D, FP8, false>(sb[b], kq, vq, qb[b], nv, nv, a.scale_log2);
+                     });
+        const long long slot0 = prompt_slot_base + tb.req_pstart[r] + ((long long)h * nck + ck) * cnt;
+#pragma unroll
+        for (int b = 0; b < kSharedBlocks; ++b) {
+          if (b >= nb) continue;
+          const float l = sum_over_rows(sb[b].l);
+          if (br[b] < 0) continue;
+          float* base = a.partials + (slot0 + br[b]) * pf;
+#pragma unroll
+          for (int k = 0; k < D / 16; ++k) *(f32x4*)(base + (long long)hd[b] * D + k * 16 + 4 * g4) = sb[b].o[k];
+          if (g4 == 0) {
+            base[(long long)dm.G * D + hd[b]] = sb[b].m;
+            base[(long long)dm.G * D + dm.G + hd[b]] = l;
+          }
+        }
+      }
+    }
+
+    for (int line = a.inline_prefix == 2 ? 0 : 1; line >= 0; --line) {   // prompt blocks first: all waves start them together, so neighbours share pages in time
       long long x, u, u1;          // range number and its units on this line
       int cursor;                  // own line: active row; prompt line: live request index
       if (line == 0) {
@@ -262,52 +377,9 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         }
         load_q<D>(qreg, q, dm, row, h);
         st.reset();
-        const long long head_off = (long long)h * kPageBytes + lane * 16;
-        auto load_page = [&](uint4* kq, uint4* vq, int pid) {
-          const unsigned char* base = pool + (long long)pid * page_bytes + head_off;
-#pragma unroll
-          for (int i = 0; i < KR; ++i) {
-            kq[i] = *(const uint4*)(base + i * 1024);
-            vq[i] = *(const uint4*)(base + kTileBytes + i * 1024);
-          }
-        };
-        // kRing register buffers in a software pipeline: kRing pages (8 KiB
-        // each) are in flight per wave.  The steady-state loop and its
-        // preheader have no conditional loads, so the compiler can wait for
-        // the oldest buffer only (s_waitcnt vmcnt(8*kRing-1 ...)) while the
-        // newer pages are still in flight; page ids are wave-uniform scalar
-        // reads of the table.
-        uint4 kb[kRing][KR], vb[kRing][KR];
-        int i = 0;
-        if (rn >= 2 * kRing) {
-#pragma unroll
-          for (int j = 0; j < kRing; ++j) load_page(kb[j], vb[j], table[r0 + j]);
-          do {   // at the top: buffer j holds page i+j (all full pages), i + 2*kRing <= rn
-            int pid[kRing];
-#pragma unroll
-            for (int j = 0; j < kRing; ++j) pid[j] = table[r0 + i + kRing + j];
-#pragma unroll
-            for (int j = 0; j < kRing; ++j) {
-              process_raw<D, FP8, true>(st, kb[j], vb[j], qreg, 16, 16, a.scale_log2);
-              load_page(kb[j], vb[j], pid[j]);
-            }
-            i += kRing;
-          } while (i + 2 * kRing <= rn);
-#pragma unroll
-          for (int j = 0; j < kRing; ++j)
-            { const int nv = i + j == rn - 1 ? n_last : 16; process_raw<D, FP8, false>(st, kb[j], vb[j], qreg, nv, nv, a.scale_log2); }
-          i += kRing;
-        }
-        while (i < rn) {   // fewer than 2*kRing pages left: groups of up to kRing, requested up front
-          const int cnt = min(kRing, rn - i);
-#pragma unroll
-          for (int j = 0; j < kRing; ++j)
-            if (j < cnt) load_page(kb[j], vb[j], table[r0 + i + j]);
-#pragma unroll
-          for (int j = 0; j < kRing; ++j)
-            if (j < cnt) { const int nv = i + j == rn - 1 ? n_last : 16; process_raw<D, FP8, false>(st, kb[j], vb[j], qreg, nv, nv, a.scale_log2); }
-          i += cnt;
-        }
+        stream_pages(table, r0, rn, n_last, h,
+                     [&](const uint4* kq, const uint4* vq) { process_raw<D, FP8, true>(st, kq, vq, qreg, 16, 16, a.scale_log2); },
+                     [&](const uint4* kq, const uint4* vq, int nv) { process_raw<D, FP8, false>(st, kq, vq, qreg, nv, nv, a.scale_log2); });
         store_partial<D>(st, a.partials, slot, dm);
         u += line == 0 ? rn : cut.n_prompt;
       }

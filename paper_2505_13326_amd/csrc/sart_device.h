@@ -123,7 +123,11 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       np = ceil_div(tb.seq_len[i], dm.pt);
       if (first) {
         const int pp = ceil_div(tb.prefix_len[r], dm.pt);
-        w = pc.inline_prefix ? pp * tb.refcnt[r] : pp * ceil_div(tb.refcnt[r], kAttnWaves) * dm.Hkv;
+        // pages a wave reads for the request's prompt, per kv head: once per branch, once per
+        // tile of 16 * kSharedBlocks query rows (shared rows), or (LDS mode) once per group of branches
+        w = pc.inline_prefix == 2 ? pp * ceil_div(tb.refcnt[r] * dm.G, 16 * kSharedBlocks)
+            : pc.inline_prefix   ? pp * tb.refcnt[r]
+                                 : pp * ceil_div(tb.refcnt[r], kAttnWaves) * dm.Hkv;
         tb.req_first[r] = i;
       }
     }
@@ -157,6 +161,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   cut.pb = cut.n_prompt > 0 ? (int)((u_prompt + cut.n_prompt - 1) / cut.n_prompt) : 1;
   cut.pb = ceil_div(cut.pb < 1 ? 1 : cut.pb, 4) * 4;        // whole rings of page buffers
   cut.n_blocks = 0;
+  cut.n_pitems = 0;
   int per_wave = (int)((cut.u_own + cut.n_own - 1) / (cut.n_own > 0 ? cut.n_own : 1));
   if (per_wave < 1) per_wave = 1;
   // even / odd workgroups: pe + po = 2 * per_wave, po >= 1; an odd number of
@@ -176,21 +181,27 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   int n_items = 0;
   if (pc.inline_prefix) {
     // first prompt block of every live request
-    int b_carry = 0;
+    // (partial slots) and first work item of every live request
+    int b_carry = 0, i_carry = 0;
     for (int base = 0; base < n_live; base += kPlanThreads) {
       const int k = base + tid;
-      int blocks = 0, r = 0;
+      int blocks = 0, items = 0, r = 0;
       if (k < n_live) {
         r = tb.live_req[k];
-        blocks = dm.Hkv * ceil_div(ceil_div(tb.prefix_len[r], dm.pt), cut.pb) * tb.refcnt[r];
+        const int nck = ceil_div(ceil_div(tb.prefix_len[r], dm.pt), cut.pb);
+        blocks = dm.Hkv * nck * tb.refcnt[r];
+        items = pc.inline_prefix == 2 ? dm.Hkv * nck * ceil_div(tb.refcnt[r] * dm.G, 16 * kSharedBlocks) : blocks;
       }
-      int tot;
+      int tot, tot_i;
       const int ex = block_excl_scan(blocks, s_scan, tot);
-      if (k < n_live) { tb.live_item_start[k] = b_carry + ex; tb.req_pstart[r] = b_carry + ex; }
+      const int ex_i = block_excl_scan(items, s_scan, tot_i);
+      if (k < n_live) { tb.live_item_start[k] = i_carry + ex_i; tb.req_pstart[r] = b_carry + ex; }
       b_carry += tot;
+      i_carry += tot_i;
     }
     cut.n_blocks = b_carry;
-    if (tid == 0) tb.live_item_start[n_live] = b_carry;
+    cut.n_pitems = i_carry;
+    if (tid == 0) tb.live_item_start[n_live] = i_carry;
     __syncthreads();
   } else {
     // item offsets per live request
@@ -249,7 +260,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       const int i = w - (n_waves - cut.n_prompt);
       const long long b = prompt_range_of_wave(i, cut.n_prompt);
       int k = 0;
-      if (b < cut.n_blocks) {
+      if (b < cut.n_pitems) {
         int lo = 0, hi = n_live - 1;
         while (lo < hi) {
           const int mid = (lo + hi + 1) >> 1;
@@ -269,6 +280,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     scal[S_D_NPROMPT] = cut.n_prompt;
     scal[S_D_PB] = cut.pb;
     scal[S_D_NBLOCKS] = cut.n_blocks;
+    scal[S_D_NPITEMS] = cut.n_pitems;
     scal[S_D_NITEMS] = n_items;
     scal[S_D_NLIVE] = n_live;
     scal[S_D_CHUNK] = chunk;
@@ -282,7 +294,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
 __device__ inline Cut load_cut(const int* scal) {
   Cut k;
   k.pe = scal[S_D_PER_EVEN]; k.po = scal[S_D_PER_ODD]; k.u_own = scal[S_D_UOWN]; k.n_own = scal[S_D_NOWN];
-  k.n_prompt = scal[S_D_NPROMPT]; k.pb = scal[S_D_PB]; k.n_blocks = scal[S_D_NBLOCKS];
+  k.n_prompt = scal[S_D_NPROMPT]; k.pb = scal[S_D_PB]; k.n_blocks = scal[S_D_NBLOCKS]; k.n_pitems = scal[S_D_NPITEMS];
   return k;
 }
 

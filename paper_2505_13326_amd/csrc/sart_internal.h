@@ -15,6 +15,9 @@ constexpr int kAttnThreads = kAttnWaves * kWave;
 constexpr int kStagePages = 4;         // prefix pages staged in LDS per pipeline stage
 constexpr int kPfBlocks = 2;           // prefill: 16-row blocks per wave (two waves per SIMD fit the registers)
 constexpr int kPfTileRows = 16 * kPfBlocks * kAttnWaves;   // prefill: rows of one workgroup tile
+constexpr int kSharedBlocks = 1;       // shared-rows prompt mode: 16-row blocks of a row tile (1: every wave gets a
+                                       // tile's worth of prompt work; 4 read the prompt less often but left
+                                       // three waves in four without prompt work, measured slower)
 constexpr int kMaxGroup = 16;          // query heads per KV head the MFMA tile holds
 
 // Indices into the device scalar block.
@@ -48,7 +51,8 @@ enum Scalar {
   S_D_NOWN,       // ranges (waves) serving the own region
   S_D_NPROMPT,    // waves serving the prompt blocks (the last ones of the grid, or all)
   S_D_PB,         // pages per prompt block
-  S_D_NBLOCKS,    // prompt blocks
+  S_D_NBLOCKS,    // prompt blocks (partial slots of the prompts)
+  S_D_NPITEMS,    // prompt work items of the streaming phase (= blocks unless rows are shared)
   S_COUNT = 32
 };
 
@@ -103,7 +107,8 @@ struct Tables {
 struct PlanCfg {
   int n_wg;           // persistent attention workgroups in total
   int chunk_pages;    // prompt chunk in pages; <= 0: sized on the device
-  int inline_prefix;  // the prompt is read as the first pages of every row
+  int inline_prefix;  // prompt mode: 0 staged in LDS, 1 blocks read by every branch, 2 blocks' pages read once for
+                      // all query rows of the request (shared rows)
   int skew_permille;  // even workgroups take (1000+skew)/1000 of the mean range, odd ones the rest
   int n_wg_prompt;    // the last n_wg_prompt workgroups serve the shared prompts only (0: all do both)
 };
@@ -137,6 +142,8 @@ struct Cut {
   int n_prompt;          // waves serving prompt blocks: the last n_prompt of the grid
   int pb;                // pages per prompt block
   int n_blocks;          // prompt blocks; block b's partial goes to slot n_own + S + b
+  int n_pitems;          // prompt work items: the blocks themselves, or (request, kv head, chunk, row tile)
+                         // items that each write the blocks of up to 64 query rows (shared-rows mode)
 };
 __host__ __device__ inline long long own_start(const Cut& k, long long w) {
   const long long b = w / kAttnWaves, wv = w % kAttnWaves;
