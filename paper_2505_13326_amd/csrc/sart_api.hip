@@ -230,6 +230,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   c->plan.skew_permille = kDefaultSkewPermille;
   ALLOC(tb.wave_row, (size_t)2 * c->max_wg * kAttnWaves);
   ALLOC(tb.req_pstart, R);
+  ALLOC(tb.wave_desc, (size_t)16 * c->max_wg * kAttnWaves);
   // partial slots: one per private wave, one per (row, kv head) crossing, and
   // the prompt chunks of every (row, kv head) at the smallest chunk size
   const long long S = (long long)H * dm.Hkv;

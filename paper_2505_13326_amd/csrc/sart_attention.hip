@@ -88,7 +88,7 @@ __device__ inline void store_partial(const WaveState<D>& st, float* partials, lo
 template <int D, bool FP8>
 __global__ void __launch_bounds__(kAttnThreads)
 k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restrict__ bt1,
-            const int* __restrict__ item_desc, const int* __restrict__ prefix_table) {
+            const int* __restrict__ item_desc, const int* __restrict__ prefix_table, const int* __restrict__ wave_desc) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
@@ -208,6 +208,10 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
     //      prompt line (inline prompt mode); one partial per piece ---------------
     const Cut cut = load_cut(scal);
     const long long wave_id = (long long)blockIdx.x * kAttnWaves + wv;
+    // where the wave starts, resolved by the planning kernel: one load instead of a chain of lookups
+    const int4 wd0 = ((const int4*)(wave_desc + 16LL * wave_id))[0];
+    const int4 wd2 = ((const int4*)(wave_desc + 16LL * wave_id))[2];
+    const int4 wd3 = ((const int4*)(wave_desc + 16LL * wave_id))[3];
     SART_STAMP(3);
     const long long page_bytes = dm.page_elems * (FP8 ? 1 : 2);
     // Streams pages [r0, r0 + rn) of `table` (kv head h) through kRing register
@@ -266,21 +270,26 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
     if (a.inline_prefix == 2 && wave_id >= n_waves - cut.n_prompt) {
       const int r16 = lane & 15, g4 = lane >> 4;
       const long long pf = partial_floats(dm.G, D);
-      int cursor = tb.wave_row[n_waves + (wave_id - (n_waves - cut.n_prompt))];
+      int cursor = wd3.z;
+      bool resolved = wd3.w != 0;                                  // the first item's request came with the descriptor
       for (long long item = prompt_range_of_wave(wave_id - (n_waves - cut.n_prompt), cut.n_prompt); item < cut.n_pitems;
            item += cut.n_prompt) {
-        while (item >= tb.live_item_start[cursor + 1]) ++cursor;   // the live request owning the item
-        const int r = tb.live_req[cursor];
-        const int cnt = tb.refcnt[r], plen = tb.prefix_len[r];
+        int r = wd2.x, cnt = wd2.y, plen = wd2.z, first_row = wd2.w, pstart = wd3.x, istart = wd3.y;
+        if (!resolved) {                                           // rare: more items than waves
+          while (item >= tb.live_item_start[cursor + 1]) ++cursor; // the live request owning the item
+          r = tb.live_req[cursor];
+          cnt = tb.refcnt[r]; plen = tb.prefix_len[r]; first_row = tb.req_first[r]; pstart = tb.req_pstart[r];
+          istart = tb.live_item_start[cursor];
+        }
+        resolved = false;
         const int pp = ceil_div(plen, 16), nck = ceil_div(pp, cut.pb);
         const int rows = cnt * dm.G, ntile = ceil_div(rows, 16 * kSharedBlocks);
-        const int local = (int)(item - tb.live_item_start[cursor]);
+        const int local = (int)(item - istart);
         const int rt = local % ntile, ck = (local / ntile) % nck, h = local / (ntile * nck);
         const int r0 = ck * cut.pb, rn = min(cut.pb, pp - r0);
         const int n_last = min(16, plen - (r0 + rn - 1) * 16);
         const int row0 = rt * 16 * kSharedBlocks;
         const int nb = min(kSharedBlocks, ceil_div(rows - row0, 16));          // blocks with rows (wave-uniform)
-        const int first_row = tb.req_first[r];
         WaveState<D> sb[kSharedBlocks];
         uint4 qb[kSharedBlocks][KQ];
         int br[kSharedBlocks], hd[kSharedBlocks];                              // this lane's branch and head per block, -1: no row
@@ -308,7 +317,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
                        for (int b = 0; b < kSharedBlocks; ++b)
                          if (b < nb) process_raw<D, FP8, false>(sb[b], kq, vq, qb[b], nv, nv, a.scale_log2);
                      });
-        const long long slot0 = prompt_slot_base + tb.req_pstart[r] + ((long long)h * nck + ck) * cnt;
+        const long long slot0 = prompt_slot_base + pstart + ((long long)h * nck + ck) * cnt;
 #pragma unroll
         for (int b = 0; b < kSharedBlocks; ++b) {
           if (b >= nb) continue;
@@ -328,11 +337,12 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
     for (int line = a.inline_prefix == 2 ? 0 : 1; line >= 0; --line) {   // prompt blocks first: all waves start them together, so neighbours share pages in time
       long long x, u, u1;          // range number and its units on this line
       int cursor;                  // own line: active row; prompt line: live request index
+      int c_cum = 0, c_pages = 0, c_seq = 0;   // own line: page_cum, private pages and tokens of row `cursor`
       if (line == 0) {
         if (wave_id >= cut.n_own) continue;
         x = wave_id; u = own_start(cut, x); u1 = own_end(cut, x);
         if (u >= u1) continue;
-        cursor = tb.wave_row[x];
+        cursor = wd0.x; c_cum = wd0.y; c_pages = wd0.z; c_seq = wd0.w;
       } else {
         if (wave_id < n_waves - cut.n_prompt) continue;
         const long long i = wave_id - (n_waves - cut.n_prompt);
@@ -346,18 +356,19 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         long long slot;
         const int* __restrict__ table;
         if (line == 0) {
-          int pages = tb.page_cum[cursor + 1] - tb.page_cum[cursor];
-          long long rem = u - (long long)tb.page_cum[cursor] * dm.Hkv;
-          while (pages == 0 || rem >= (long long)pages * dm.Hkv) {   // skip rows without private pages
+          long long rem = u - (long long)c_cum * dm.Hkv;
+          while (c_pages == 0 || rem >= (long long)c_pages * dm.Hkv) {   // next row (skipping rows without private pages)
             ++cursor;
-            pages = tb.page_cum[cursor + 1] - tb.page_cum[cursor];
-            rem = u - (long long)tb.page_cum[cursor] * dm.Hkv;
+            c_cum = tb.page_cum[cursor];
+            c_pages = tb.page_cum[cursor + 1] - c_cum;
+            c_seq = tb.seq_len[cursor];
+            rem = u - (long long)c_cum * dm.Hkv;
           }
           row = cursor;
-          h = (int)(rem / pages);
-          r0 = (int)(rem % pages);
-          rn = (int)min((long long)(pages - r0), u1 - u);
-          n_last = min(16, tb.seq_len[row] - (r0 + rn - 1) * 16);
+          h = (int)(rem / c_pages);
+          r0 = (int)(rem % c_pages);
+          rn = (int)min((long long)(c_pages - r0), u1 - u);
+          n_last = min(16, c_seq - (r0 + rn - 1) * 16);
           table = bt + (long long)row * dm.max_bp;
           slot = x + (long long)row * dm.Hkv + h;
         } else {
@@ -566,7 +577,7 @@ void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s) {
   if (mfma) {
     auto go = [&](auto kern) {
       hipLaunchKernelGGL(kern, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], c.tb.bt[1], c.tb.item_desc,
-                         c.tb.prefix_table);
+                         c.tb.prefix_table, c.tb.wave_desc);
     };
     const bool fp8 = dm.layout == SART_LAYOUT_MFMA16_FP8;
     if (dm.d == 128) { if (fp8) go(k_attn_mfma<128, true>); else go(k_attn_mfma<128, false>); }

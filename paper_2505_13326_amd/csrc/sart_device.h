@@ -96,7 +96,8 @@ __device__ inline void record_error(int* scal, int code, int call_seq) {
 //                 chunk, group, request, 0}; the chunk is sized so that the
 //                 items about fill the prompt workgroups once.
 // ---------------------------------------------------------------------------
-constexpr int kPlanLdsRows = 4096;   // active rows whose page_cum is searched from LDS
+constexpr int kPlanLdsRows = 4096;   // active rows whose page_cum and lengths the plan keeps in LDS
+constexpr int kPlanLdsLive = 1024;   // live requests whose fields the plan keeps in LDS
 
 __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int* lds) {
   const Dims& dm = c.dm;
@@ -106,6 +107,11 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   __shared__ int s_npc;
   __shared__ int s_scan[3 * 17];
   __shared__ int s_cum[kPlanLdsRows + 1];
+  __shared__ int s_seq[kPlanLdsRows];         // tokens of the active rows
+  // live requests with a prompt, by live index: request, live branches, prompt tokens, first active
+  // row, first partial slot, first work item (searched per wave)
+  __shared__ int s_lreq[kPlanLdsLive], s_lcnt[kPlanLdsLive], s_lplen[kPlanLdsLive], s_lfirst[kPlanLdsLive],
+      s_lpstart[kPlanLdsLive], s_item[kPlanLdsLive + 1];
   (void)lds;
   __syncthreads();                       // the caller's table updates are visible
   const int nA = scal[S_NACTIVE];
@@ -115,19 +121,23 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   int carry = 0, w_carry = 0, l_carry = 0;
   for (int base = 0; base < nA; base += kPlanThreads) {
     const int i = base + tid;
-    int np = 0, w = 0, first = 0, r = 0;
+    int np = 0, w = 0, first = 0, r = 0, cnt = 0, plen = 0;
     if (i < nA) {
       const int b = tb.active[i];
       r = b / dm.Nb;
       first = i == 0 || tb.active[i - 1] / dm.Nb != r;
-      np = ceil_div(tb.seq_len[i], dm.pt);
+      const int len = tb.seq_len[i];
+      if (i < kPlanLdsRows) s_seq[i] = len;
+      np = ceil_div(len, dm.pt);
       if (first) {
-        const int pp = ceil_div(tb.prefix_len[r], dm.pt);
+        plen = tb.prefix_len[r];
+        cnt = tb.refcnt[r];
+        const int pp = ceil_div(plen, dm.pt);
         // pages a wave reads for the request's prompt, per kv head: once per branch, once per
         // tile of 16 * kSharedBlocks query rows (shared rows), or (LDS mode) once per group of branches
-        w = pc.inline_prefix == 2 ? pp * ceil_div(tb.refcnt[r] * dm.G, 16 * kSharedBlocks)
-            : pc.inline_prefix   ? pp * tb.refcnt[r]
-                                 : pp * ceil_div(tb.refcnt[r], kAttnWaves) * dm.Hkv;
+        w = pc.inline_prefix == 2 ? pp * ceil_div(cnt * dm.G, 16 * kSharedBlocks)
+            : pc.inline_prefix   ? pp * cnt
+                                 : pp * ceil_div(cnt, kAttnWaves) * dm.Hkv;
         tb.req_first[r] = i;
       }
     }
@@ -138,7 +148,9 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       if (i <= kPlanLdsRows) s_cum[i] = carry + ex3[0];
     }
     if (w > 0) {
-      tb.live_req[l_carry + ex3[2]] = r;
+      const int k = l_carry + ex3[2];
+      tb.live_req[k] = r;
+      if (k < kPlanLdsLive) { s_lreq[k] = r; s_lcnt[k] = cnt; s_lplen[k] = plen; s_lfirst[k] = i; }
     }
     carry += tot3[0];
     w_carry += tot3[1];
@@ -187,21 +199,30 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       const int k = base + tid;
       int blocks = 0, items = 0, r = 0;
       if (k < n_live) {
-        r = tb.live_req[k];
-        const int nck = ceil_div(ceil_div(tb.prefix_len[r], dm.pt), cut.pb);
-        blocks = dm.Hkv * nck * tb.refcnt[r];
-        items = pc.inline_prefix == 2 ? dm.Hkv * nck * ceil_div(tb.refcnt[r] * dm.G, 16 * kSharedBlocks) : blocks;
+        const bool in_lds = k < kPlanLdsLive;
+        r = in_lds ? s_lreq[k] : tb.live_req[k];
+        const int plen = in_lds ? s_lplen[k] : tb.prefix_len[r], cnt = in_lds ? s_lcnt[k] : tb.refcnt[r];
+        const int nck = ceil_div(ceil_div(plen, dm.pt), cut.pb);
+        blocks = dm.Hkv * nck * cnt;
+        items = pc.inline_prefix == 2 ? dm.Hkv * nck * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : blocks;
       }
       int tot, tot_i;
       const int ex = block_excl_scan(blocks, s_scan, tot);
       const int ex_i = block_excl_scan(items, s_scan, tot_i);
-      if (k < n_live) { tb.live_item_start[k] = i_carry + ex_i; tb.req_pstart[r] = b_carry + ex; }
+      if (k < n_live) {
+        tb.live_item_start[k] = i_carry + ex_i;
+        tb.req_pstart[r] = b_carry + ex;
+        if (k < kPlanLdsLive) { s_item[k] = i_carry + ex_i; s_lpstart[k] = b_carry + ex; }
+      }
       b_carry += tot;
       i_carry += tot_i;
     }
     cut.n_blocks = b_carry;
     cut.n_pitems = i_carry;
-    if (tid == 0) tb.live_item_start[n_live] = i_carry;
+    if (tid == 0) {
+      tb.live_item_start[n_live] = i_carry;
+      if (n_live <= kPlanLdsLive) s_item[n_live] = i_carry;
+    }
     __syncthreads();
   } else {
     // item offsets per live request
@@ -239,9 +260,20 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       d[1] = make_int4(local % nck, bg, r, 0);
     }
   }
-  // first row / first live request of every range
+  // Where every wave starts.  wave_row (generic kernel): active row of an own
+  // range's first unit and, after those entries, the live request of a prompt
+  // wave's first work item.  wave_desc (matrix-core kernel), 16 ints per wave,
+  // holds what the wave would otherwise look up through a chain of dependent
+  // loads before its first tile load:
+  //   [0..3]   own range: active row of its first unit, page_cum of that row,
+  //            private pages of the row, tokens of the row
+  //   [8..15]  first prompt item (inline modes): request, its live branches,
+  //            prompt tokens, first active row, first partial slot of the
+  //            request, first work item of the request, live request index,
+  //            1 if the wave has an item
   for (int w = tid; w < n_waves; w += kPlanThreads) {
     int v = 0;
+    int4 d0 = make_int4(0, 0, 0, 0), d2 = d0, d3 = d0;
     if (w < cut.n_own) {
       const long long u = own_start(cut, w);
       if (u < cut.u_own) {
@@ -252,24 +284,38 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
           if ((long long)cum[mid] * dm.Hkv <= u) lo = mid; else hi = mid - 1;
         }
         v = lo;
+        d0 = make_int4(lo, cum[lo], cum[lo + 1] - cum[lo], lo < kPlanLdsRows ? s_seq[lo] : tb.seq_len[lo]);
       }
       tb.wave_row[w] = v;
     }
     if (w >= n_waves - cut.n_prompt) {
-      // the live request owning the first block of prompt wave i (kept after the own-range entries)
       const int i = w - (n_waves - cut.n_prompt);
       const long long b = prompt_range_of_wave(i, cut.n_prompt);
       int k = 0;
       if (b < cut.n_pitems) {
+        const bool in_lds = n_live <= kPlanLdsLive;                              // uniform choice
+        const int* its = in_lds ? s_item : tb.live_item_start;
         int lo = 0, hi = n_live - 1;
         while (lo < hi) {
           const int mid = (lo + hi + 1) >> 1;
-          if (tb.live_item_start[mid] <= b) lo = mid; else hi = mid - 1;
+          if (its[mid] <= b) lo = mid; else hi = mid - 1;
         }
         k = lo;
+        if (pc.inline_prefix) {
+          if (in_lds) {
+            d2 = make_int4(s_lreq[k], s_lcnt[k], s_lplen[k], s_lfirst[k]);
+            d3 = make_int4(s_lpstart[k], its[k], k, 1);
+          } else {
+            const int r = tb.live_req[k];
+            d2 = make_int4(r, tb.refcnt[r], tb.prefix_len[r], tb.req_first[r]);
+            d3 = make_int4(tb.req_pstart[r], its[k], k, 1);
+          }
+        }
       }
       tb.wave_row[n_waves + i] = k;
     }
+    int4* wd = (int4*)(tb.wave_desc + 16LL * w);
+    wd[0] = d0; wd[2] = d2; wd[3] = d3;
   }
   if (tid == 0) {
     scal[S_D_NA] = nA;

@@ -100,6 +100,7 @@ struct Tables {
   int* item_desc;        // [max items][8] shared-prompt work items
   int* wave_row;         // [max attention waves] own ranges: active row of the first unit; prompt ranges: live request index
   int* req_pstart;       // [max_req] first prompt block of the request
+  int* wave_desc;        // [max attention waves][16] where each wave starts (see refresh_decode_plan)
 };
 
 // Launch shape the decode plan is made for (host-chosen, passed to every
