@@ -260,24 +260,23 @@ class SartCache:
     def sync_status(self) -> int:
         return int(self.lib.sart_sync_status(self.h))
 
-    def get_state(self, with_status=False):
+    _STATE_FIELDS = ("n_active", "active_handles", "seq_lens", "block_tables", "free_stack", "free_top",
+                     "prefix_tables", "prefix_lens", "prefix_refcnt", "branch_state", "req_counters")
+
+    def get_state(self, with_status=False, fields=None):
+        """sart_get_state (synchronises).  fields: names to read back (default: all); a step loop that only
+        needs the active list should not copy the block tables."""
         H = self.max_req * self.Nb
-        st = {
-            "n_active": np.zeros(1, np.int32),
-            "active_handles": np.zeros(H, np.int32),
-            "seq_lens": np.zeros(H, np.int32),
-            "block_tables": np.zeros((H, self.max_bp), np.int32),
-            "free_stack": np.zeros(self.num_pages, np.int32),
-            "free_top": np.zeros(1, np.int32),
-            "prefix_tables": np.zeros((self.max_req, self.max_pp), np.int32),
-            "prefix_lens": np.zeros(self.max_req, np.int32),
-            "prefix_refcnt": np.zeros(self.max_req, np.int32),
-            "branch_state": np.zeros(H, np.int32),
-            "req_counters": np.zeros((self.max_req, 2), np.int32),
+        shapes = {
+            "n_active": 1, "active_handles": H, "seq_lens": H, "block_tables": (H, self.max_bp),
+            "free_stack": self.num_pages, "free_top": 1, "prefix_tables": (self.max_req, self.max_pp),
+            "prefix_lens": self.max_req, "prefix_refcnt": self.max_req, "branch_state": H,
+            "req_counters": (self.max_req, 2),
         }
-        rc = self.lib.sart_get_state(self.h, *[_ptr(st[k]) for k in (
-            "n_active", "active_handles", "seq_lens", "block_tables", "free_stack", "free_top",
-            "prefix_tables", "prefix_lens", "prefix_refcnt", "branch_state", "req_counters")])
+        want = self._STATE_FIELDS if fields is None else tuple(fields)
+        assert all(f in shapes for f in want)
+        st = {k: np.zeros(shapes[k], np.int32) for k in want}
+        rc = self.lib.sart_get_state(self.h, *[_ptr(st[k]) if k in st else None for k in self._STATE_FIELDS])
         if rc == E_HIP:
             self._check(rc)
         return (st, int(rc)) if with_status else st

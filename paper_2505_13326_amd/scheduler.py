@@ -92,7 +92,7 @@ def serve(cache, params: SartParams, *, arrivals, prompt_kv, targets, step_kv, q
     window_pages = params.window // pt + 2          # pages a branch can need within one window
 
     def state():
-        s = cache.get_state()
+        s = cache.get_state(fields=("n_active", "active_handles", "free_top", "req_counters"))
         n = int(s["n_active"][0])
         return s, n, s["active_handles"][:n].copy()
 

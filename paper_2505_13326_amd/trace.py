@@ -34,7 +34,7 @@ def run_trace(cache, *, targets, step_kv, query, n_steps, prune_every=0, prune_k
     Returns dict(branch_steps, active_per_step, done_step)."""
     import torch
     Nb, R = cache.Nb, cache.max_req
-    st = cache.get_state()
+    st = cache.get_state(fields=("n_active", "active_handles", "seq_lens", "req_counters"))
     nA = int(st["n_active"][0])
     act = st["active_handles"][:nA].copy()
     lens = np.zeros(R * Nb, np.int64)
@@ -49,7 +49,7 @@ def run_trace(cache, *, targets, step_kv, query, n_steps, prune_every=0, prune_k
 
     def refresh():
         nonlocal act, act_dev, completed, pruned
-        s = cache.get_state()
+        s = cache.get_state(fields=("n_active", "active_handles", "req_counters"))
         n = int(s["n_active"][0])
         act = s["active_handles"][:n].copy()
         act_dev = torch.from_numpy(act.astype(np.int64)).cuda()
