@@ -231,7 +231,7 @@ def main():
                            dtype="fp8" if args.kv_dtype == "fp8" else cfg.dtype, free_order=fo, n_layers=NL)
     if args.workgroups or args.chunk_pages or args.prompt_mode >= 0 or args.skew is not None or args.prompt_workgroups >= 0:
         cache.set_decode_launch(args.workgroups, args.prompt_workgroups, args.chunk_pages, args.prompt_mode,
-                                50 if args.skew is None else args.skew)
+                                sart.DEFAULT_SKEW_PERMILLE if args.skew is None else args.skew)
 
     # ---- CPU baseline cache (oracle) on a bounded sample of the same workload ------------
     do_cpu = not args.no_cpu_baseline and args.kv_dtype == "bf16"     # the CPU baseline is timed on the bf16 cache

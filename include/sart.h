@@ -315,7 +315,7 @@ sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_
  *   skew_permille        work moved from odd to even streaming workgroups, in
  *                        1/1000 of the mean per-wave range (workgroups go round-
  *                        robin to the 8 XCDs, and the odd XCDs stream about 10 %
- *                        slower); default 50, 0 = equal. */
+ *                        slower); default 80, 0 = equal. */
 sart_status sart_set_decode_launch(sart_cache* cache, int32_t n_workgroups,
                                    int32_t n_prompt_workgroups, int32_t prefix_chunk_pages,
                                    int32_t prompt_mode, int32_t skew_permille);

@@ -16,6 +16,7 @@ SEQ_PREFIX, SEQ_BRANCH = 0, 1
 UNUSED, ACTIVE, COMPLETED, PRUNED, EARLY_STOPPED = range(5)
 DROP_LOWEST_K, KEEP_TOP_K, THRESHOLD = 0, 1, 2
 LAYOUT_NATURAL, LAYOUT_MFMA16, LAYOUT_MFMA16_FP8 = 0, 1, 2
+DEFAULT_SKEW_PERMILLE = 80   # the library's default of sart_set_decode_launch's skew_permille
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("SART_LIB") or os.path.join(_DIR, "libsart.so")  # SART_LIB: a developer build
@@ -297,6 +298,6 @@ class SartCache:
         return a.value, t.value
 
     def set_decode_launch(self, n_workgroups=0, n_prompt_workgroups=-1, prefix_chunk_pages=0, prompt_mode=-1,
-                          skew_permille=50):
+                          skew_permille=DEFAULT_SKEW_PERMILLE):
         self._check(self.lib.sart_set_decode_launch(self.h, int(n_workgroups), int(n_prompt_workgroups),
                                                     int(prefix_chunk_pages), int(prompt_mode), int(skew_permille)))
