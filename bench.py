@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM traffic of the dominant kernel per launch measured offline with
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
-MEASURED_TRAFFIC_BYTES = {"cfg2": 1450629787, "cfg4": 10926094961}  # profiles/k_attn_mfma_hbm_traffic_and_sq_counters.md
+MEASURED_TRAFFIC_BYTES = {"cfg2": 1450509075, "cfg4": 10928159910}  # profiles/k_attn_mfma_hbm_traffic_and_sq_counters.md
 
 
 def _request_arrays(wl, cfg, r, L):
