@@ -218,6 +218,30 @@ __device__ inline void pair_pv(WaveState<D>& st, const uint4* vq0, const uint4* 
     st.o[2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, hi), pp, st.o[2 * i + 1], 0, 0, 0);
   }
 }
+// The same product with the V operands already in the product's layout: lo[i] / hi[i] hold, for
+// head-dim slab i, this lane's four tokens of the first page then of the second page, for
+// column d % 16 resp. 16 + d % 16 (what loading the two pages' chunks in 8-byte halves gives).
+template <int D, bool FULL>
+__device__ inline void pair_pv_lohi(WaveState<D>& st, const uint4* lo, const uint4* hi, bf16x8 pp, int nvalid) {
+  unsigned a01 = ~0u, a23 = ~0u, b01 = ~0u, b23 = ~0u;
+  if (!FULL) {
+    const int t0 = 4 * ((threadIdx.x & 63) >> 4);
+    a01 = (t0 + 0 < nvalid ? 0x0000ffffu : 0u) | (t0 + 1 < nvalid ? 0xffff0000u : 0u);
+    a23 = (t0 + 2 < nvalid ? 0x0000ffffu : 0u) | (t0 + 3 < nvalid ? 0xffff0000u : 0u);
+    b01 = (t0 + 16 < nvalid ? 0x0000ffffu : 0u) | (t0 + 17 < nvalid ? 0xffff0000u : 0u);
+    b23 = (t0 + 18 < nvalid ? 0x0000ffffu : 0u) | (t0 + 19 < nvalid ? 0xffff0000u : 0u);
+  }
+#pragma unroll
+  for (int i = 0; i < D / 32; ++i) {
+    uint4 l = lo[i], h = hi[i];
+    if (!FULL) {
+      l.x &= a01; l.y &= a23; l.z &= b01; l.w &= b23;
+      h.x &= a01; h.y &= a23; h.z &= b01; h.w &= b23;
+    }
+    st.o[2 * i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, l), pp, st.o[2 * i], 0, 0, 0);
+    st.o[2 * i + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, h), pp, st.o[2 * i + 1], 0, 0, 0);
+  }
+}
 template <int D, bool FULL, int QSTRIDE>
 __device__ inline void process_pair(WaveState<D>& st, const uint4* kq0, const uint4* vq0, const uint4* kq1,
                                     const uint4* vq1, const uint4* qv, int nvalid, int nvalid_row, float scale_log2) {

@@ -24,6 +24,8 @@
 // wholly after their rows' positions and mask scores only on the pairs that
 // straddle them.  No split over the sequence: one wave sees a row's whole
 // context, so there is no merge.
+#include <type_traits>
+
 #include "sart_attn_tile.h"
 
 namespace sart {
@@ -122,7 +124,9 @@ k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   // blocks are done, V after the last O^T product, so each load has half a turn to arrive.  Every
   // load is unconditional (past the end the last pair again).
   const int n_pairs = (n_pages + 1) >> 1;
-  uint4 k0[KR], k1[KR], v0[KR], v1[KR];                       // as stored (an 8-bit float cache: half as many)
+  // K as stored; V as stored (8-bit float caches) or, for bf16, loaded in 8-byte halves straight into
+  // the layout of the O^T product's operand (v0 = lo, v1 = hi of pair_pv_lohi): no register shuffling
+  uint4 k0[KR], k1[KR], v0[KR], v1[KR];
   auto load_k = [&](int pr) {
     const unsigned char* b0 = pool + (long long)table[2 * pr] * page_bytes + head_off;
     const unsigned char* b1 = pool + (long long)table[min(2 * pr + 1, n_pages - 1)] * page_bytes + head_off;
@@ -133,50 +137,68 @@ k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
     const unsigned char* b0 = pool + (long long)table[2 * pr] * page_bytes + head_off + kTileBytes;
     const unsigned char* b1 = pool + (long long)table[min(2 * pr + 1, n_pages - 1)] * page_bytes + head_off + kTileBytes;
 #pragma unroll
-    for (int k = 0; k < KR; ++k) { v0[k] = *(const uint4*)(b0 + k * 1024); v1[k] = *(const uint4*)(b1 + k * 1024); }
+    for (int k = 0; k < KR; ++k) {
+      if constexpr (FP8) {
+        v0[k] = *(const uint4*)(b0 + k * 1024);
+        v1[k] = *(const uint4*)(b1 + k * 1024);
+      } else {
+        const uint2 a_lo = *(const uint2*)(b0 + k * 1024), a_hi = *(const uint2*)(b0 + k * 1024 + 8);
+        const uint2 b_lo = *(const uint2*)(b1 + k * 1024), b_hi = *(const uint2*)(b1 + k * 1024 + 8);
+        v0[k] = uint4{a_lo.x, a_lo.y, b_lo.x, b_lo.y};
+        v1[k] = uint4{a_hi.x, a_hi.y, b_hi.x, b_hi.y};
+      }
+    }
   };
   // the bf16 operands of a tile: the registers as loaded, or their expansion
   auto operands = [&](const uint4* raw, uint4* tmp) -> const uint4* {
     if constexpr (FP8) { expand_fp8<D>(raw, tmp); return tmp; } else { return raw; }
+  };
+  // O^T += V^T P^T of one block, FULL or masked by the tokens the pair holds
+  auto pv = [&](WaveState<D>& stb, bf16x8 ppb, auto full, int nvalid) {
+    constexpr bool FULLV = decltype(full)::value;
+    if constexpr (FP8) {
+      uint4 tv0[KQ], tv1[KQ];
+      expand_fp8<D>(v0, tv0);
+      expand_fp8<D>(v1, tv1);
+      pair_pv<D, FULLV>(stb, tv0, tv1, ppb, nvalid);
+    } else {
+      pair_pv_lohi<D, FULLV>(stb, v0, v1, ppb, nvalid);
+    }
   };
   load_k(0);
   load_v(0);
   for (int pr = 0; pr < n_pairs; ++pr) {
     const int t0 = pr * 32;
     const int nxt = min(pr + 1, n_pairs - 1);
-    uint4 tk0[FP8 ? KQ : 1], tk1[FP8 ? KQ : 1], tv0[FP8 ? KQ : 1], tv1[FP8 ? KQ : 1];
+    uint4 tk0[FP8 ? KQ : 1], tk1[FP8 ? KQ : 1];
+    f32x4 s0[kPfBlocks], s1[kPfBlocks];
+    bf16x8 pp[kPfBlocks];
+    const uint4* q0 = operands(k0, tk0);
+    const uint4* q1 = operands(k1, tk1);
     if (t0 + 31 <= lo_pos[0]) {
       // every row of the wave sees the whole pair: phase by phase over the wave's independent blocks
-      f32x4 s0[kPfBlocks], s1[kPfBlocks];
-      bf16x8 pp[kPfBlocks];
-      {
-        const uint4* q0 = operands(k0, tk0);
-        const uint4* q1 = operands(k1, tk1);
 #pragma unroll
-        for (int b = 0; b < kPfBlocks; ++b) pair_scores<D, 1>(q0, q1, qreg[b], s0[b], s1[b]);
-      }
+      for (int b = 0; b < kPfBlocks; ++b) pair_scores<D, 1>(q0, q1, qreg[b], s0[b], s1[b]);
       load_k(nxt);
 #pragma unroll
       for (int b = 0; b < kPfBlocks; ++b) pp[b] = pair_softmax<D, true>(st[b], s0[b], s1[b], 32, a.scale_log2);
-      {
-        const uint4* w0 = operands(v0, tv0);
-        const uint4* w1 = operands(v1, tv1);
 #pragma unroll
-        for (int b = 0; b < kPfBlocks; ++b) pair_pv<D, true>(st[b], w0, w1, pp[b], 32);
-      }
+      for (int b = 0; b < kPfBlocks; ++b) pv(st[b], pp[b], std::true_type{}, 32);
       load_v(nxt);
     } else {
       // pairs that straddle some row's position: block by block, scores masked per row
       const int nvalid = min(32, min(plen, n_pages * 16) - t0);      // tokens the pair holds
-      const uint4* q0 = operands(k0, tk0);
-      const uint4* q1 = operands(k1, tk1);
-      const uint4* w0 = operands(v0, tv0);
-      const uint4* w1 = operands(v1, tv1);
 #pragma unroll
       for (int b = 0; b < kPfBlocks; ++b) {
         if (t0 > hi_pos[b]) continue;                        // the pair lies after every row of the block
-        if (t0 + 31 <= lo_pos[b]) process_pair<D, true, 1>(st[b], q0, w0, q1, w1, qreg[b], 32, 32, a.scale_log2);
-        else process_pair<D, false, 1>(st[b], q0, w0, q1, w1, qreg[b], nvalid, min(nvalid, pos[b] + 1 - t0), a.scale_log2);
+        pair_scores<D, 1>(q0, q1, qreg[b], s0[b], s1[b]);
+        if (t0 + 31 <= lo_pos[b]) {
+          pp[b] = pair_softmax<D, true>(st[b], s0[b], s1[b], 32, a.scale_log2);
+          pv(st[b], pp[b], std::true_type{}, 32);
+        } else {
+          pp[b] = pair_softmax<D, false>(st[b], s0[b], s1[b], min(nvalid, pos[b] + 1 - t0), a.scale_log2);
+          pv(st[b], pp[b], std::false_type{}, nvalid);
+        }
       }
       load_k(nxt);
       load_v(nxt);
