@@ -245,6 +245,15 @@ sart_status sart_prune_branches(sart_cache* cache, const sart_prune_policy* poli
 sart_status sart_finish_branch(sart_cache* cache, int32_t n,
                                const int32_t* handles /*HOST*/, void* stream);
 
+/* A8 without a host list: completes every active branch whose length (private
+ * tokens) has reached target_len[handle] (DEVICE, max_requests * Nb entries, by
+ * handle), exactly as sart_finish_branch would for the list of those branches
+ * in active order (quota, early stop, release, compaction included).  No branch
+ * qualifies: nothing changes.  Stages no host data, so a whole step - append
+ * (SART_ALL_ACTIVE), attention, this call - can be recorded into a HIP graph
+ * and replayed (Algorithm 1, Decode: completed branches leave the batch). */
+sart_status sart_finish_reached(sart_cache* cache, const int32_t* target_len /*DEVICE*/, void* stream);
+
 /* Waits for the cache's last-used stream, returns the sticky device status
  * and clears it. */
 sart_status sart_sync_status(sart_cache* cache);

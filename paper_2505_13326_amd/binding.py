@@ -61,6 +61,7 @@ _SIGNATURES = {
                                          C.c_void_p]),
     "sart_prune_branches": (C.c_int, [C.c_void_p, C.POINTER(_Policy), C.c_void_p, C.c_int32, C.c_void_p]),
     "sart_finish_branch": (C.c_int, [C.c_void_p, C.c_int32, _ip, C.c_void_p]),
+    "sart_finish_reached": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "sart_sync_status": (C.c_int, [C.c_void_p]),
     "sart_get_state": (C.c_int, [C.c_void_p] + [_ip] * 11),
     "sart_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
@@ -258,6 +259,13 @@ class SartCache:
         return OK
 
     # -- readback -------------------------------------------------------------
+    def finish_reached(self, target_len, stream=None):
+        """sart_finish_reached.  target_len: int32 device tensor [max_requests * Nb] by handle."""
+        import torch
+        assert target_len.is_cuda and target_len.dtype == torch.int32 and target_len.is_contiguous()
+        assert target_len.numel() == self.max_req * self.Nb
+        self._check(self.lib.sart_finish_reached(self.h, C.c_void_p(target_len.data_ptr()), _stream_handle(stream)))
+
     def sync_status(self) -> int:
         return int(self.lib.sart_sync_status(self.h))
 

@@ -498,8 +498,17 @@ sart_status sart_finish_branch(sart_cache* c, int32_t n, const int32_t* handles,
   if (n) memcpy(s->host, handles, (size_t)n * sizeof(int));
   rc = stage_upload(c, s, n, st);
   if (rc != SART_OK) return rc;
-  launch_finish(c->ctx, c->plan, n, s->dev, ++c->call_seq, st);
+  launch_finish(c->ctx, c->plan, n, s->dev, nullptr, ++c->call_seq, st);
   HIP_TRY(hipEventRecord(s->done, st));
+  HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
+
+sart_status sart_finish_reached(sart_cache* c, const int32_t* target_len, void* stream) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (!target_len) return fail(SART_E_INVALID, "null target_len");
+  note_stream(c, stream);
+  launch_finish(c->ctx, c->plan, 0, nullptr, target_len, ++c->call_seq, (hipStream_t)stream);
   HIP_TRY(hipGetLastError());
   return SART_OK;
 }

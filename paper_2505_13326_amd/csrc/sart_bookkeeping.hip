@@ -463,16 +463,19 @@ void launch_prune(const Ctx& c, const PlanCfg& pc, const PruneArgs& a, hipStream
 // ---------------------------------------------------------------------------
 // A8: completion + early stop, then the terminate plan.
 // ---------------------------------------------------------------------------
+// Who completes: the listed handles, or (targets != null, no list) every active
+// branch whose length has reached targets[handle]; in that form a step with no
+// such branch changes nothing and the move kernel that follows does nothing.
 __global__ void __launch_bounds__(kPlanThreads)
-k_finish_plan(Ctx c, PlanCfg pc, int n, const int* handles, int call_seq) {
+k_finish_plan(Ctx c, PlanCfg pc, int n, const int* handles, const int* targets, int call_seq) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
   __shared__ int lds[17];
-  __shared__ int s_bad;
+  __shared__ int s_bad, s_any;
   const int tid = threadIdx.x;
   const int nA = scal[S_NACTIVE];
-  if (tid == 0) { s_bad = 0; scal[S_APPENDOK] = 0; }
+  if (tid == 0) { s_bad = 0; s_any = 0; }
   __syncthreads();
   for (int i = tid; i < n; i += kPlanThreads)
     if (tb.br_state[handles[i]] != SART_BRANCH_ACTIVE) s_bad = 1;
@@ -483,6 +486,22 @@ k_finish_plan(Ctx c, PlanCfg pc, int n, const int* handles, int call_seq) {
   }
   for (int a = tid; a < nA; a += kPlanThreads) tb.new_state[a] = 0;
   __syncthreads();
+  if (targets) {
+    for (int a = tid; a < nA; a += kPlanThreads) {
+      const int b = tb.active[a];
+      if (tb.seq_len[a] >= targets[b]) {
+        tb.new_state[a] = SART_BRANCH_COMPLETED;
+        atomicAdd(&tb.num_completed[b / dm.Nb], 1);
+        s_any = 1;
+      }
+    }
+    __syncthreads();
+    if (!s_any) {
+      if (tid == 0) scal[S_CALLOK] = 0;     // not an error: nothing for the move kernel to do
+      return;
+    }
+  }
+  if (tid == 0) scal[S_APPENDOK] = 0;        // rows move: no more writes to other layers for the last append
   for (int i = tid; i < n; i += kPlanThreads) {
     const int b = handles[i];
     tb.new_state[tb.active_idx_of[b]] = SART_BRANCH_COMPLETED;
@@ -498,8 +517,9 @@ k_finish_plan(Ctx c, PlanCfg pc, int n, const int* handles, int call_seq) {
   terminate_plan(c, pc, lds);
 }
 
-void launch_finish(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, int call_seq, hipStream_t s) {
-  hipLaunchKernelGGL(k_finish_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, n, handles_dev, call_seq);
+void launch_finish(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, const int* targets_dev, int call_seq,
+                   hipStream_t s) {
+  hipLaunchKernelGGL(k_finish_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, n, handles_dev, targets_dev, call_seq);
   launch_move(c, s);
 }
 

@@ -218,7 +218,8 @@ struct PruneArgs {
   int call_seq;
 };
 void launch_prune(const Ctx& c, const PlanCfg& pc, const PruneArgs& a, hipStream_t s);
-void launch_finish(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, int call_seq, hipStream_t s);
+void launch_finish(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, const int* targets_dev, int call_seq,
+                   hipStream_t s);
 void launch_plan(const Ctx& c, const PlanCfg& pc, hipStream_t s);
 
 struct DecodeArgs {

@@ -1,9 +1,11 @@
 """A decode step recorded once into a HIP graph and replayed while the batch
 changes under it (the step loop of Algorithm 1, Decode, without a host
-round-trip per call): append one token to every active branch, attend.  The
-plan of the step lives on the device and the all-active append bakes no count
-into the launch, so the same graph serves after branches were finished or
-pruned (eagerly) between replays.  Every replay is checked against the oracle."""
+round-trip per call): append one token to every active branch, attend, and
+complete the branches that reached their target length (with the early stop
+that follows).  The plan of the step lives on the device, the all-active append
+bakes no count into the launch and the completion takes its targets from device
+memory, so the same graph serves while branches finish inside it and are pruned
+(eagerly) between replays.  Every replay is checked against the oracle."""
 import numpy as np
 import pytest
 
@@ -17,7 +19,7 @@ pytestmark = pytest.mark.gpu
 
 def test_decode_step_graph_replays_across_finish_and_prune():
     import torch
-    cfg = wl.scaled(wl.CONFIGS[2], n_requests=4, nb=8, prompt_len=100, length_params=(150, 0.8), length_cap=900)
+    cfg = wl.scaled(wl.CONFIGS[2], n_requests=4, nb=8, quota=4, prompt_len=100, length_params=(150, 0.8), length_cap=900)
     L = wl.lengths(cfg)
     steps = 24
     pages = wl.pages_needed(cfg, L, growth_tokens=steps) + 8
@@ -27,6 +29,11 @@ def test_decode_step_graph_replays_across_finish_and_prune():
     g = GpuEngine(free_order=fo, **kw)
     populate(cfg, [o, g], L)
     H = cfg.n_handles
+    # target lengths: a few branches complete on most steps; request 2 reaches its quota of 4 (early stop)
+    rng = np.random.default_rng(3)
+    targets = (L.reshape(-1) + rng.integers(3, 40, size=H)).astype(np.int32)
+    targets[16:20] = L.reshape(-1)[16:20] + np.array([5, 5, 9, 12])
+    tdev = torch.from_numpy(targets).cuda()
     dev = lambda x: torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).view(torch.bfloat16).cuda()
     kbuf = torch.zeros((H, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
     vbuf = torch.zeros_like(kbuf)
@@ -43,11 +50,20 @@ def test_decode_step_graph_replays_across_finish_and_prune():
         kbuf[:n].copy_(dev(k[act])); vbuf[:n].copy_(dev(v[act])); qbuf[:n].copy_(dev(wl.query(cfg, s)[act]))
         return k[act], v[act], wl.query(cfg, s)[act]
 
+    n_finished = [0]
+
     def check(s, act, k, v, q):
         assert o.append(orc.SEQ_BRANCH, None, None, k, v) == orc.OK
+        ref = o.attention(q)
+        # the oracle completes the same branches from a host list: those whose length reached the target
+        st = o.state()
+        lens = st["seq_lens"][:len(act)]
+        fin = [int(b) for b, n in zip(act, lens) if n >= targets[b]]
+        if fin:
+            assert o.finish(fin) == orc.OK
+            n_finished[0] += len(fin)
         assert g.c.sync_status() == 0
         assert_state_equal(o.state(), g.state())
-        ref = o.attention(q)
         got = out[:len(act)].cpu().numpy().astype(np.float64)
         err = float(np.abs(got - ref).max())
         assert np.all(np.isfinite(got)) and err <= TOL["bf16"], f"step {s}: max abs err {err}"
@@ -61,6 +77,7 @@ def test_decode_step_graph_replays_across_finish_and_prune():
     with torch.cuda.stream(side):
         g.c.append_tokens(orc.SEQ_BRANCH, None, None, kbuf, vbuf, all_active=True)
         g.c.decode_attention(qbuf, out=out)
+        g.c.finish_reached(tdev)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     check(1, act, k, v, q)
@@ -71,13 +88,14 @@ def test_decode_step_graph_replays_across_finish_and_prune():
     with torch.cuda.graph(graph):
         g.c.append_tokens(orc.SEQ_BRANCH, None, None, kbuf, vbuf, all_active=True)
         g.c.decode_attention(qbuf, out=out)
+        g.c.finish_reached(tdev)
     graph.replay()                      # capture records, replay runs: this is step 2
     torch.cuda.synchronize()
     check(2, act, k, v, q)
 
     for s in range(3, steps + 1):
         if s == 8:                      # eager maintenance between replays: the batch shrinks
-            fin = [int(act[1]), int(act[10]), int(act[-1])]
+            fin = [int(act[1]), int(act[-1])]
             assert o.finish(fin) == orc.OK and g.finish(fin) == orc.OK
         if s == 14:
             sc = wl.scores(cfg, 0)[act]
@@ -88,7 +106,8 @@ def test_decode_step_graph_replays_across_finish_and_prune():
         graph.replay()
         torch.cuda.synchronize()
         check(s, act, k, v, q)
-    assert len(act) < H                 # the batch did change under the graph
+    assert len(act) < H and n_finished[0] >= 8      # the batch did change under the graph, and inside it
+    assert o.state()["req_counters"][:, 0].max() >= cfg.quota       # a request reached its quota: early stop ran
 
     # the row capacity of an all-active append is checked on the device
     small = kbuf[: len(act) - 1]
