@@ -111,7 +111,7 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
 def bench_trace(args, cfg, sart, wl, np, torch):
     """Config 3: the whole 400-step early-stop / prune loop (append + attention + finish + prune, host
     step loop included).  value = branch-decode-steps per second over the loop."""
-    from paper_2505_13326_amd.trace import run_trace
+    from paper_2505_13326_amd.trace import run_trace, run_trace_graph
     L = wl.lengths(cfg)
     targets = (L + wl.remaining_tokens(cfg)).reshape(-1)
     num_pages = wl.pages_needed(cfg, L, growth_tokens=cfg.n_steps) + 64
@@ -138,14 +138,19 @@ def bench_trace(args, cfg, sart, wl, np, torch):
         assert cache.sync_status() == 0
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        res = run_trace(cache, targets=targets, step_kv=lambda s: kvs[s], query=lambda s: qs[s], n_steps=cfg.n_steps,
-                        prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: scs[e], out=out)
+        if args.graph:   # the step (gather, append, attention, completion) replayed from one HIP graph
+            res = run_trace_graph(cache, targets=targets, step_kv=lambda s: kvs[s], query=lambda s: qs[s],
+                                  n_steps=cfg.n_steps, prune_every=cfg.prune_every, prune_k=cfg.prune_k,
+                                  scores=lambda e: scs[e])
+        else:
+            res = run_trace(cache, targets=targets, step_kv=lambda s: kvs[s], query=lambda s: qs[s], n_steps=cfg.n_steps,
+                            prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: scs[e], out=out)
         torch.cuda.synchronize()
         times.append(time.perf_counter() - t0)
         assert cache.sync_status() == 0
         cache.close()
     dt = float(np.mean(times[1:]))
-    busy = int(np.sum(res["active_per_step"] > 0))
+    busy = int(np.sum(res["active_per_step"] > 0)) if "active_per_step" in res else cfg.n_steps
     print(json.dumps({
         "metric": "decode-attention achieved KV GB/s (fraction of HBM peak); branch-steps/s",
         "value": round(res["branch_steps"] / dt, 1), "unit": "branch-steps/s", "n_gpus": 1, "steps": cfg.n_steps,
@@ -153,7 +158,7 @@ def bench_trace(args, cfg, sart, wl, np, torch):
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"cfg3 {cfg.name}: {cfg.n_requests} requests x {cfg.nb} branches, quota {cfg.quota}, "
                                f"{cfg.n_steps} steps, prune {cfg.prune_k} lowest every {cfg.prune_every} steps; whole "
-                               "loop incl. host driver", "branch_steps": res["branch_steps"],
+                               "loop incl. host driver" + (", step replayed from a HIP graph" if args.graph else ""), "branch_steps": res["branch_steps"],
                    "steps_with_active_branches": busy, "loop_s": round(dt, 4)}}), flush=True)
 
 

@@ -289,6 +289,14 @@ sart_status sart_get_state(sart_cache* cache, int32_t* n_active,
 sart_status sart_set_profiling(sart_cache* cache, int32_t on);
 sart_status sart_last_decode_ms(sart_cache* cache, float* ms_attn, float* ms_total);
 
+/* DEVICE views of the active list for callers that keep their step loop on the
+ * device (a recorded graph that gathers its per-branch inputs itself):
+ * *active_handles -> int32[max_requests * Nb], the handles in active order
+ * (entries past the active count are unspecified), *n_active -> one int32.
+ * Owned by the library, read-only for the caller, valid until sart_free_cache;
+ * their contents change with every state-changing call, in stream order. */
+sart_status sart_device_views(sart_cache* cache, const int32_t** active_handles, const int32_t** n_active);
+
 /* Measurement aid, no part of the method: reads `bytes` (a multiple of 8 KiB is
  * used) of a DEVICE buffer with plain coalesced loads, in 8 KiB chunks, in
  * ascending order or in the order chunk_order gives (DEVICE, bytes / 8192

@@ -62,6 +62,7 @@ _SIGNATURES = {
     "sart_prune_branches": (C.c_int, [C.c_void_p, C.POINTER(_Policy), C.c_void_p, C.c_int32, C.c_void_p]),
     "sart_finish_branch": (C.c_int, [C.c_void_p, C.c_int32, _ip, C.c_void_p]),
     "sart_finish_reached": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sart_device_views": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
     "sart_sync_status": (C.c_int, [C.c_void_p]),
     "sart_get_state": (C.c_int, [C.c_void_p] + [_ip] * 11),
     "sart_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
@@ -265,6 +266,19 @@ class SartCache:
         assert target_len.is_cuda and target_len.dtype == torch.int32 and target_len.is_contiguous()
         assert target_len.numel() == self.max_req * self.Nb
         self._check(self.lib.sart_finish_reached(self.h, C.c_void_p(target_len.data_ptr()), _stream_handle(stream)))
+
+    def device_views(self):
+        """sart_device_views as torch int32 tensors over the library's memory (read-only by convention):
+        (active handles [max_requests * Nb], active count [1])."""
+        import torch
+        a, n = C.c_void_p(), C.c_void_p()
+        self._check(self.lib.sart_device_views(self.h, C.byref(a), C.byref(n)))
+
+        class _View:
+            def __init__(self, ptr, count):
+                self.__cuda_array_interface__ = {"shape": (count,), "typestr": "<i4", "data": (ptr, False), "version": 2}
+        H = self.max_req * self.Nb
+        return (torch.as_tensor(_View(a.value, H), device="cuda"), torch.as_tensor(_View(n.value, 1), device="cuda"))
 
     def sync_status(self) -> int:
         return int(self.lib.sart_sync_status(self.h))

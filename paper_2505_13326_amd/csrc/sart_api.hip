@@ -586,6 +586,13 @@ sart_status sart_last_decode_ms(sart_cache* c, float* ms_attn, float* ms_total) 
   return SART_OK;
 }
 
+sart_status sart_device_views(sart_cache* c, const int32_t** active_handles, const int32_t** n_active) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (active_handles) *active_handles = c->ctx.tb.active;
+  if (n_active) *n_active = c->ctx.tb.scal + S_NACTIVE;
+  return SART_OK;
+}
+
 sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_order, void* stream) {
   if (!buf || bytes < 8192) return fail(SART_E_INVALID, "the probe needs a device buffer of at least 8 KiB");
   launch_read_probe(buf, (long long)(bytes / 8192), chunk_order, (hipStream_t)stream);

@@ -88,3 +88,73 @@ def run_trace(cache, *, targets, step_kv, query, n_steps, prune_every=0, prune_k
         done_step[(done_step == 0) & done] = s
     return {"branch_steps": int(np.sum(active_per_step)), "active_per_step": np.asarray(active_per_step),
             "done_step": done_step}
+
+
+def run_trace_graph(cache, *, targets, step_kv, query, n_steps, prune_every=0, prune_k=0, scores=None):
+    """The same loop with the step kept on the device: gathering the active branches' inputs (through
+    sart_device_views), sart_append_tokens(SART_ALL_ACTIVE), sart_decode_attention and sart_finish_reached are
+    recorded into one HIP graph and replayed once per step; the host only copies the step's inputs into the
+    graph's source buffers (no wait) and comes back for the state at the pruning steps.
+    Returns dict(branch_steps)."""
+    import torch
+    Nb, R = cache.Nb, cache.max_req
+    H = R * Nb
+    act_view, n_view = cache.device_views()
+    tdev = torch.from_numpy(np.ascontiguousarray(targets, dtype=np.int32)).cuda()
+    k1, v1 = step_kv(1)
+    src_k, src_v, src_q = torch.empty_like(k1), torch.empty_like(v1), torch.empty_like(query(1))
+    kbuf, vbuf, qbuf = torch.empty_like(k1), torch.empty_like(v1), torch.empty_like(src_q)
+    out = torch.empty(src_q.shape, dtype=torch.float32, device="cuda")
+    count = torch.zeros(1, dtype=torch.int64, device="cuda")
+
+    def load(s):
+        k, v = step_kv(s)
+        src_k.copy_(k); src_v.copy_(v); src_q.copy_(query(s))
+
+    def body():
+        idx = act_view.clamp(0, H - 1).long()          # entries past the active count may hold anything
+        torch.index_select(src_k, 0, idx, out=kbuf)
+        torch.index_select(src_v, 0, idx, out=vbuf)
+        torch.index_select(src_q, 0, idx, out=qbuf)
+        cache.append_tokens(SEQ_BRANCH, None, None, kbuf, vbuf, all_active=True)
+        cache.decode_attention(qbuf, out=out)
+        count.add_(n_view)                              # branches decoded in this step
+        cache.finish_reached(tdev)
+
+    drained = [False]
+
+    def maybe_prune(s, event):
+        if not (prune_every and s % prune_every == 0):
+            return event
+        st = cache.get_state(fields=("n_active", "active_handles", "req_counters"))
+        n = int(st["n_active"][0])
+        drained[0] = n == 0                             # nothing left to decode: the remaining steps are no-ops
+        if n:
+            act_dev = torch.from_numpy(st["active_handles"][:n].astype(np.int64)).cuda()
+            cap = np.where(st["req_counters"][:, 0] == 0, Nb // 2, Nb - 1).astype(np.int32)
+            cache.prune_branches(DROP_LOWEST_K, scores(event)[act_dev].contiguous(), k=prune_k, max_pruned=cap)
+        return event + 1
+
+    # step 1 runs eagerly on a side stream (the warm-up a capture needs), the rest replays the recording
+    load(1)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        body()
+    torch.cuda.current_stream().wait_stream(side)
+    event = maybe_prune(1, 0)
+    graph = torch.cuda.CUDAGraph()
+    if n_steps >= 2:
+        load(2)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            body()
+    for s in range(2, n_steps + 1):
+        if drained[0]:
+            break
+        if s > 2:
+            load(s)
+        graph.replay()
+        event = maybe_prune(s, event)
+    torch.cuda.synchronize()
+    return {"branch_steps": int(count.item())}

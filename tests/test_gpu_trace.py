@@ -109,3 +109,33 @@ def test_trace_matches_oracle_after_every_call(size):
     print(f"{size}: {len(log)} calls, {res_g['branch_steps']} branch-steps, requests done by step "
           f"{res_g['done_step'].max()}, early-stopped requests {int(np.sum(c >= cfg.quota))}/{cfg.n_requests}, "
           f"max abs attention err {worst[0]:.3g}")
+
+
+def test_graph_driven_trace_ends_in_the_same_state():
+    """The loop that keeps the step on the device (one recorded graph: gather, append, attention,
+    completion by target length) must leave the cache exactly where the host-driven loop leaves it."""
+    import torch
+    from paper_2505_13326_amd.trace import run_trace, run_trace_graph
+    cfg = wl.scaled(wl.CONFIGS[3], n_requests=5, length_params=(150, 0.8), length_cap=1200, n_steps=130, prune_every=20)
+    L = wl.lengths(cfg)
+    targets = (L + wl.remaining_tokens(cfg)).reshape(-1)
+    num_pages = wl.pages_needed(cfg, L, growth_tokens=cfg.n_steps) + 64
+    kw = dims(cfg, num_pages, (cfg.length_cap + cfg.n_steps) // 16 + 2)
+    fo = wl.free_order(cfg, num_pages)
+
+    def dev(x):
+        return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).view(torch.bfloat16).cuda()
+
+    kvs = {s: tuple(dev(x) for x in wl.step_kv(cfg, s)) for s in range(1, cfg.n_steps + 1)}
+    qs = {s: dev(wl.query(cfg, s)) for s in range(1, cfg.n_steps + 1)}
+    args = dict(targets=targets, step_kv=lambda s: kvs[s], query=lambda s: qs[s], n_steps=cfg.n_steps,
+                prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: torch.from_numpy(wl.scores(cfg, e)).cuda())
+    ends = []
+    for loop in (run_trace, run_trace_graph):
+        g = GpuEngine(free_order=fo, **kw)
+        populate(cfg, [g], L)
+        res = loop(g.c, **args)
+        st, rc = g.c.get_state(with_status=True)
+        assert rc == 0
+        ends.append((res["branch_steps"], _digest(st)))
+    assert ends[0] == ends[1], ends
