@@ -114,3 +114,51 @@ def test_decode_step_graph_replays_across_finish_and_prune():
     g.c.append_tokens(orc.SEQ_BRANCH, None, None, small, vbuf[: len(act) - 1], all_active=True)
     assert g.c.sync_status() == orc.E_INVALID
     assert_state_equal(o.state(), g.state())
+
+
+def test_finish_reached_edges():
+    """No branch at its target: nothing changes (and an append to another layer may still follow);
+    every branch at its target: the cache drains completely."""
+    import torch
+    cfg = wl.scaled(wl.CONFIGS[2], n_requests=2, nb=4, quota=0, prompt_len=40, length_params=(60, 0.5), length_cap=300)
+    L = wl.lengths(cfg)
+    pages = wl.pages_needed(cfg, L, growth_tokens=4) + 4
+    kw = dims(cfg, pages, int(-(-(L.max() + 4) // 16)) + 1)
+    o = orc.OracleCache(**kw)
+    g = GpuEngine(n_layers=2, **kw)
+    for r in range(cfg.n_requests):
+        k, v = wl.prefix_kv(cfg, r)
+        assert o.append(orc.SEQ_PREFIX, [r], [cfg.prompt_len], k, v) == orc.OK
+        ids = [r * cfg.nb + j for j in range(cfg.nb)]
+        ns = [int(L[r, j]) for j in range(cfg.nb)]
+        kb, vb = (np.concatenate(x) for x in zip(*[wl.branch_kv(cfg, b, n) for b, n in zip(ids, ns)]))
+        assert o.append(orc.SEQ_BRANCH, ids, ns, kb, vb) == orc.OK
+        for l in range(2):
+            g.c.append_tokens(orc.SEQ_PREFIX, [r], [cfg.prompt_len], k, v, layer=l)
+        for l in range(2):
+            g.c.append_tokens(orc.SEQ_BRANCH, ids, ns, kb, vb, layer=l)
+    assert g.c.sync_status() == 0
+    assert_state_equal(o.state(), g.state())
+    H = cfg.n_handles
+    act = o.state()["active_handles"][:H]
+    k, v = wl.step_kv(cfg, 1)
+    far = torch.full((H,), 1 << 30, dtype=torch.int32, device="cuda")
+    # layer 0 append, a completion call that finds nothing, then the other layer's append: still written
+    assert o.append(orc.SEQ_BRANCH, None, None, k[act], v[act]) == orc.OK
+    g.c.append_tokens(orc.SEQ_BRANCH, None, None, k[act], v[act], layer=0)
+    g.c.finish_reached(far)
+    g.c.append_tokens(orc.SEQ_BRANCH, None, None, k[act], v[act], layer=1)
+    assert g.c.sync_status() == 0
+    assert_state_equal(o.state(), g.state())
+    q = wl.query(cfg, 1)[act]
+    ref = o.attention(q)
+    for l in range(2):
+        got = g.c.decode_attention(q, layer=l).cpu().numpy().astype(np.float64)
+        assert float(np.abs(got - ref).max()) <= TOL["bf16"]
+    # every branch has reached a target of zero tokens: all complete, every page returns
+    g.c.finish_reached(torch.zeros(H, dtype=torch.int32, device="cuda"))
+    assert o.finish([int(b) for b in act]) == orc.OK
+    assert g.c.sync_status() == 0
+    st = g.state()
+    assert_state_equal(o.state(), st)
+    assert int(st["n_active"][0]) == 0 and int(st["free_top"][0]) == pages
