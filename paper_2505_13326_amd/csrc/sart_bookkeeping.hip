@@ -194,10 +194,11 @@ k_append_write(Ctx c, AppendArgs a) {
       i = (int)row;
     }
     const int t = (int)(row - (a.tok_off ? a.tok_off[i] : i));
-    const int id = tb.ap_id[i];
     const int pos = tb.ap_start[i] + t;
-    const int* table = a.kind == SART_SEQ_PREFIX ? tb.prefix_table + (long long)id * dm.max_pp
-                                                 : bt + (long long)tb.active_idx_of[id] * dm.max_bp;
+    // without an id list the sequences are the active rows themselves: no lookups of the handle and its row
+    const int* table = a.kind == SART_SEQ_PREFIX ? tb.prefix_table + (long long)tb.ap_id[i] * dm.max_pp
+                       : a.ids ? bt + (long long)tb.active_idx_of[tb.ap_id[i]] * dm.max_bp
+                               : bt + (long long)i * dm.max_bp;
     const int page = table[pos / dm.pt], slot = pos % dm.pt;
     const long long kb = tile_base(dm, page, head), vb = kb + dm.tile_elems;
     const T* ksrc = (const T*)a.k + (row * dm.Hkv + head) * dm.d;

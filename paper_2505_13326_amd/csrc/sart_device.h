@@ -206,9 +206,9 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
         blocks = dm.Hkv * nck * cnt;
         items = pc.inline_prefix == 2 ? dm.Hkv * nck * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : blocks;
       }
-      int tot, tot_i;
-      const int ex = block_excl_scan(blocks, s_scan, tot);
-      const int ex_i = block_excl_scan(items, s_scan, tot_i);
+      int ex3[3], tot3[3];
+      block_excl_scan3(blocks, items, 0, s_scan, ex3, tot3);
+      const int ex = ex3[0], ex_i = ex3[1], tot = tot3[0], tot_i = tot3[1];
       if (k < n_live) {
         tb.live_item_start[k] = i_carry + ex_i;
         tb.req_pstart[r] = b_carry + ex;
