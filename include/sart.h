@@ -5,7 +5,7 @@
  * request, decodes them in one batch, and removes branches from the batch when
  * they complete, are pruned by a reward threshold, or are early-stopped once
  * enough branches of the request completed (Algorithm 1, functions Prefill and
- * Decode).  Section 4 (last paragraph before "It is worthy to note") fixes the
+ * Decode).  Section 4 (its paragraph on KV-cache management) fixes the
  * KV-cache rule this library implements: the prompt's KV cache is shared by
  * all branches of a request, a branch's own KV cache is released immediately
  * when it is pruned, early-stopped or completed, and the shared prefix is
@@ -189,7 +189,7 @@ sart_status sart_append_tokens(sart_cache* cache, int32_t kind, int32_t n_seqs,
                                const void* k /*DEVICE*/, const void* v /*DEVICE*/,
                                int32_t layer, void* stream);
 
-/* A3-A6.  One decode step of attention ("Batch decoding", Algorithm 1,
+/* A3-A6.  One decode step of attention (the batched decoding step of Algorithm 1,
  * Decode): for every active branch b (row a) and query head h,
  *   out[a,h,:] = sum_t softmax_t(scale * q[a,h,:] . K[t, h/G, :]) * V[t, h/G, :]
  * over t = the request's prompt tokens followed by b's own tokens (the token
@@ -222,7 +222,7 @@ sart_status sart_decode_attention(sart_cache* cache, int32_t layer,
 sart_status sart_prefill_attention(sart_cache* cache, int32_t layer, int32_t n_seqs, const int32_t* request_ids,
                                    const int32_t* n_q, const void* q, float* out, float scale, void* stream);
 
-/* A7.  Prunes branches by score (Algorithm 1, Decode: "Prune the branch").
+/* A7.  Prunes branches by score (Algorithm 1, Decode: the pruning step).
  * scores: DEVICE float [n_scores], active order, n_scores >= active count.
  * Per request, over its active branches:
  *   DROP_LOWEST_K  the min(k, live) smallest keys (score, handle);
@@ -238,7 +238,7 @@ sart_status sart_prune_branches(sart_cache* cache, const sart_prune_policy* poli
                                 const float* scores, int32_t n_scores, void* stream);
 
 /* A8.  Marks the listed ACTIVE branches COMPLETED (Algorithm 1, Decode:
- * "Remove the completed branch"), frees their pages, counts them, and when a
+ * completed branches leave the batch), frees their pages, counts them, and when a
  * request has reached Q completions early-stops its remaining active branches
  * (Section 3, Solution 1).  Any listed branch not ACTIVE: SART_E_STATE,
  * nothing changes. */

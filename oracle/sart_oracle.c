@@ -19,8 +19,8 @@
  *     request; a branch's KV cache is released as soon as it is pruned,
  *     early-stopped or completed; the prefix is released only when all
  *     branches have terminated.
- *   - Section 4, "The prefilling process is the same as vanilla LLM inference"
- *     and Section 2 (one token generated per decode step): the attention is the
+ *   - Section 4 (prefilling is done as in plain LLM inference) and Section 2
+ *     (one token generated per decode step): the attention is the
  *     textbook one, softmax(q K^T / sqrt(d)) V of one query over all cached
  *     tokens, written out below as that definition.
  *

@@ -1,6 +1,6 @@
-// Decode-step attention over the active branches (the paper's "batch decoding"
-// step, Algorithm 1, Decode; arXiv 2505.13326).  The paper leaves the attention
-// itself to the serving engine (Section 4: same as vanilla inference), so what
+// Decode-step attention over the active branches (the batched decoding
+// step of Algorithm 1, Decode; arXiv 2505.13326).  The paper leaves the attention
+// itself to the serving engine (Section 4: as in plain LLM inference), so what
 // is computed is softmax(q K^T * scale) V of one query per (branch, head) over
 // the request's shared prompt tokens followed by the branch's own tokens
 // (Section 4: the prefix KV cache is shared across a request's branches).
