@@ -190,7 +190,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (requests are independent and would shard with no "
-              "collective; see DESIGN.md); --gpus > 1 is not supported", file=sys.stderr)
+              "collective); --gpus > 1 is not supported", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -27,7 +27,7 @@
  * The paper names N sampled branches and M required completions; here they are
  * Nb and Q.
  *
- * Readings the paper leaves open (fixed here, listed in the design notes):
+ * Readings the paper leaves open (fixed here):
  *   - pages hold page_tokens tokens; a prompt whose length is not a page
  *     multiple leaves its last page partly filled and private tokens start on
  *     a fresh page;

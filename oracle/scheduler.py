@@ -9,7 +9,7 @@ first completed branch, max_num_pruned N-1), counts completed branches, prunes
 incomplete ones whose reward is below the threshold while num_pruned is under
 the cap, and answers the request when num_completed >= M or num_completed +
 num_pruned == N; the answer is the completed branch with the highest reward
-(Section 5.1).  Readings shared with the product (see the design notes):
+(Section 5.1).  Readings shared with the product:
 completion and early stop act at the step they happen, a request's branches are
 admitted together when N more fit under B and a window's worth of pages is free,
 "first completed" = earliest step then lowest branch index.

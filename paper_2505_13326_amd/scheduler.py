@@ -18,7 +18,7 @@ What follows the paper:
   * KV of a branch is released as soon as it completes, is pruned or is
     early-stopped; the prompt's when the last branch is gone (Section 4).
 
-Readings where the paper leaves room (this build's, listed in the design notes):
+Readings where the paper leaves room:
   * N and M are called Nb and Q here.
   * A branch's completion is seen at the decode step it happens (its KV is
     released at once, and the Q-th completion early-stops the request's other
