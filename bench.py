@@ -79,7 +79,7 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
     assert cache.sync_status() == 0
     flops = R * 4.0 * cfg.head_dim * cfg.n_q_heads * P * (P + 1) / 2
     kv_bytes = R * P * cfg.token_bytes
-    roofline = {"bound": "mfma", "kernel": "k_prefill_mfma", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
+    roofline = {"bound": "mfma", "kernel": "k_prefill_lds8" if cfg.dtype == "bf16" else "k_prefill_mfma", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
                 "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / (k_ms * 1e-3) / 1e12 / 2500.0, 4), "traffic": None,
                 "algorithmic_flops_per_launch": int(flops), "kernel_ms_avg": round(k_ms, 4),
                 "note": "events on the call's stream around all timed calls (validation kernel included)"}

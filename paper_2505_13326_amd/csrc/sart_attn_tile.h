@@ -187,7 +187,8 @@ __device__ inline bf16x8 pair_softmax(WaveState<D>& st, f32x4 s0, f32x4 s1, int 
   }
   st.l = st.l * alpha + ((p0[0] + p0[1]) + (p0[2] + p0[3])) + ((p1[0] + p1[1]) + (p1[2] + p1[3]));
   // always rescaled: a branch around the accumulator registers makes the compiler spill them when
-  // two waves share a SIMD (measured on 8192-token prompts: 150 vs 470 TFLOP/s)
+  // two waves share a SIMD (measured on 8192-token prompts: 150 vs 470 TFLOP/s), and where it does
+  // not spill (16 rows per wave) the test costs more than it saves (669 vs 684 TFLOP/s)
 #pragma unroll
   for (int b = 0; b < D / 16; ++b) st.o[b] *= alpha;
   const uint2 pa = __builtin_bit_cast(uint2, __builtin_convertvector(p0, bf16x4));

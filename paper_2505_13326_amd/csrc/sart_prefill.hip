@@ -65,6 +65,7 @@ __device__ inline int last_le(const int* v, int n, int x) {
   return lo;
 }
 
+// (Launched for 8-bit float caches; bf16 caches take k_prefill_lds8 below.)
 template <int D, bool FP8>
 __global__ void __launch_bounds__(kAttnThreads, 2)
 k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
@@ -215,6 +216,147 @@ k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   }
 }
 
+// The same computation for bf16 caches with K and V staged in LDS by the workgroup
+// and more waves in flight: the tile's 128 rows go to 8 waves of 16 rows (112
+// registers, so four waves share a SIMD and there is always one to switch to
+// while another waits for a product, an LDS read or the barrier), and each page
+// pair is fetched from memory once per workgroup - one 16-byte chunk of two tiles
+// per thread - into a ring of three LDS stages (pair p is computed on while pair
+// p + 1 is written and pair p + 2 is in flight: one barrier per pair).  V is
+// written to LDS already in the layout of the O^T product's operand; operands are
+// read from LDS slab by slab, right before their products.  Measured against the
+// register kernel above: 452 vs 433 TFLOP/s on 64 x 1024-token prompts, 684 vs
+// 605 on 64 x 8192.
+template <int D>
+__global__ void __launch_bounds__(512, 4)
+k_prefill_lds8(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
+  constexpr int NW = 8, NB = 1;
+  static_assert(16 * NB * NW == kPfTileRows, "the host sizes the grid for tiles of kPfTileRows rows");
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  if (!tb.scal[S_CALLOK]) return;
+  constexpr int KQ = D / 32;
+  constexpr int kTileBytes = 16 * D * 2, kPageBytes = 2 * kTileBytes;
+  constexpr int kChunks = kTileBytes / 16;                 // 16-byte chunks of one K (or V) tile
+  constexpr int kStages = 3;
+  // one stage: K of the pair's first and second page as stored, then V lo and V hi operands
+  __shared__ uint4 lds[kStages][4][kChunks];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r16 = lane & 15, g4 = lane >> 4;
+  const int tile = blockIdx.x;
+  const int i = last_le(a.tile_start, a.n_seqs, tile);
+  const int req = a.ids[i], nq = a.nq[i], plen = tb.prefix_len[req];
+  const int n_rows = nq * dm.G;
+  const int tiles_per_head = ceil_div(n_rows, (16 * NB * NW));
+  const int local = tile - a.tile_start[i];
+  const int h = local / tiles_per_head;
+  const int rt = tiles_per_head - 1 - local % tiles_per_head;
+  const int row_w0 = rt * (16 * NB * NW) + wv * (16 * NB);
+  const bool wave_has_rows = row_w0 < n_rows;              // a wave without rows still helps to load
+  const int p_first = plen - nq;
+  const long long q_row0 = a.q_off[i];
+  const uint16_t* q = (const uint16_t*)a.q;
+  const unsigned char* pool = (const unsigned char*)c.pool;
+  const int* __restrict__ table = prefix_table + (long long)req * dm.max_pp;
+  const long long page_bytes = dm.page_elems * 2;
+
+  WaveState<D> st[NB];
+  uint4 qreg[NB][KQ];
+  int pos[NB], lo_pos[NB], hi_pos[NB];
+  long long out_row[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    const int row0 = row_w0 + 16 * b;
+    const int row = row0 + r16;
+    const bool have = row < n_rows;
+    const int rc = have ? row : n_rows - 1;
+    const int ql = rc / dm.G, g = rc % dm.G;
+    pos[b] = p_first + ql;
+    lo_pos[b] = row0 < n_rows ? p_first + row0 / dm.G : -1;
+    hi_pos[b] = row0 < n_rows ? p_first + min(row0 + 15, n_rows - 1) / dm.G : -1;
+    const long long qrow = ((q_row0 + ql) * dm.Hq + h * dm.G + g) * D;
+    out_row[b] = have ? qrow : -1;
+#pragma unroll
+    for (int k = 0; k < KQ; ++k) qreg[b][k] = *(const uint4*)(q + qrow + k * 32 + g4 * 8);
+    st[b].reset();
+  }
+  // pages the tile needs (its last row's context) and those this wave needs
+  const int tile_last_pos = p_first + min((rt + 1) * (16 * NB * NW) - 1, n_rows - 1) / dm.G;
+  const int n_pages = tile_last_pos / 16 + 1;
+  const int n_pairs = (n_pages + 1) >> 1;
+  const int wave_last_pos = wave_has_rows ? p_first + min(row_w0 + (16 * NB) - 1, n_rows - 1) / dm.G : -1;
+  const int wave_pairs = wave_has_rows ? wave_last_pos / 32 + 1 : 0;
+
+  // loader: threads 0..kChunks-1 move chunk t of the two K tiles, the next kChunks threads chunk t of the two V tiles
+  static_assert(2 * kChunks <= NW * 64, "one chunk pair per thread");
+  uint4 ga, gb;
+  const bool ld_k = tid < kChunks, ld_v = tid >= kChunks && tid < 2 * kChunks;
+  const int lch = ld_k ? tid : tid - kChunks;
+  auto g_load = [&](int pr) {
+    const unsigned char* b0 = pool + (long long)table[2 * pr] * page_bytes + (long long)h * kPageBytes + (ld_v ? kTileBytes : 0);
+    const unsigned char* b1 = pool + (long long)table[min(2 * pr + 1, n_pages - 1)] * page_bytes + (long long)h * kPageBytes + (ld_v ? kTileBytes : 0);
+    if (ld_k || ld_v) { ga = *(const uint4*)(b0 + lch * 16); gb = *(const uint4*)(b1 + lch * 16); }
+  };
+  auto l_store = [&](int stage) {
+    if (ld_k) { lds[stage][0][lch] = ga; lds[stage][1][lch] = gb; }
+    if (ld_v) {
+      lds[stage][2][lch] = uint4{ga.x, ga.y, gb.x, gb.y};
+      lds[stage][3][lch] = uint4{ga.z, ga.w, gb.z, gb.w};
+    }
+  };
+  g_load(0);
+  l_store(0);
+  g_load(min(1, n_pairs - 1));
+  __syncthreads();
+  for (int pr = 0; pr < n_pairs; ++pr) {
+    const int stage = pr % kStages;
+    l_store((pr + 1) % kStages);                           // pair pr + 1 (loaded a turn ago), read a turn from now
+    g_load(min(pr + 2, n_pairs - 1));
+    if (pr < wave_pairs) {
+      const int t0 = pr * 32;
+      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int k = 0; k < KQ; ++k) {
+        const bf16x8 qk = __builtin_bit_cast(bf16x8, qreg[0][k]);
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lds[stage][0][k * 64 + lane]), qk, s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lds[stage][1][k * 64 + lane]), qk, s1, 0, 0, 0);
+      }
+      const bool full = t0 + 31 <= lo_pos[0];
+      const int nvalid = min(32, min(plen, n_pages * 16) - t0);
+      const bf16x8 pp = full ? pair_softmax<D, true>(st[0], s0, s1, 32, a.scale_log2)
+                             : pair_softmax<D, false>(st[0], s0, s1, min(nvalid, pos[0] + 1 - t0), a.scale_log2);
+      unsigned a01 = ~0u, a23 = ~0u, b01 = ~0u, b23 = ~0u;
+      if (!full) {
+        const int tt = 4 * g4;
+        a01 = (tt + 0 < nvalid ? 0x0000ffffu : 0u) | (tt + 1 < nvalid ? 0xffff0000u : 0u);
+        a23 = (tt + 2 < nvalid ? 0x0000ffffu : 0u) | (tt + 3 < nvalid ? 0xffff0000u : 0u);
+        b01 = (tt + 16 < nvalid ? 0x0000ffffu : 0u) | (tt + 17 < nvalid ? 0xffff0000u : 0u);
+        b23 = (tt + 18 < nvalid ? 0x0000ffffu : 0u) | (tt + 19 < nvalid ? 0xffff0000u : 0u);
+      }
+#pragma unroll
+      for (int k = 0; k < KQ; ++k) {
+        uint4 l = lds[stage][2][k * 64 + lane], hh = lds[stage][3][k * 64 + lane];
+        l.x &= a01; l.y &= a23; l.z &= b01; l.w &= b23;
+        hh.x &= a01; hh.y &= a23; hh.z &= b01; hh.w &= b23;
+        st[0].o[2 * k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, l), pp, st[0].o[2 * k], 0, 0, 0);
+        st[0].o[2 * k + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, hh), pp, st[0].o[2 * k + 1], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+  if (!wave_has_rows) return;
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    const float l = sum_over_rows(st[b].l);
+    if (out_row[b] < 0) continue;
+    const float inv = a.v_scale / l;
+    float* o = a.out + out_row[b];
+#pragma unroll
+    for (int k = 0; k < D / 16; ++k) *(f32x4*)(o + k * 16 + 4 * g4) = st[b].o[k] * inv;
+  }
+}
+
 // Any dtype, SART_LAYOUT_NATURAL: one wave per (query, kv head), the heads of
 // the group one after the other on the vector ALUs.  Not a tuned path.
 template <typename T>
@@ -258,8 +400,12 @@ void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s) {
       hipLaunchKernelGGL(kern, dim3(a.n_tiles), dim3(kAttnThreads), 0, s, c, a, c.tb.prefix_table);
     };
     const bool fp8 = dm.layout == SART_LAYOUT_MFMA16_FP8;
-    if (dm.d == 128) { if (fp8) go(k_prefill_mfma<128, true>); else go(k_prefill_mfma<128, false>); }
-    else { if (fp8) go(k_prefill_mfma<64, true>); else go(k_prefill_mfma<64, false>); }
+    if (!fp8) {   // bf16: the LDS-staged kernel with 8 waves per tile
+      if (dm.d == 128) hipLaunchKernelGGL(k_prefill_lds8<128>, dim3(a.n_tiles), dim3(512), 0, s, c, a, c.tb.prefix_table);
+      else hipLaunchKernelGGL(k_prefill_lds8<64>, dim3(a.n_tiles), dim3(512), 0, s, c, a, c.tb.prefix_table);
+      return;
+    }
+    if (dm.d == 128) go(k_prefill_mfma<128, true>); else go(k_prefill_mfma<64, true>);   // 8-bit float caches
   } else {
     long long blocks = ((long long)a.total_q * dm.Hkv + kAttnWaves - 1) / kAttnWaves;
     if (blocks > 65536) blocks = 65536;
