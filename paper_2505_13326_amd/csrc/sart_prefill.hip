@@ -326,21 +326,17 @@ k_prefill_lds8(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
       const int nvalid = min(32, min(plen, n_pages * 16) - t0);
       const bf16x8 pp = full ? pair_softmax<D, true>(st[0], s0, s1, 32, a.scale_log2)
                              : pair_softmax<D, false>(st[0], s0, s1, min(nvalid, pos[0] + 1 - t0), a.scale_log2);
-      unsigned a01 = ~0u, a23 = ~0u, b01 = ~0u, b23 = ~0u;
-      if (!full) {
-        const int tt = 4 * g4;
-        a01 = (tt + 0 < nvalid ? 0x0000ffffu : 0u) | (tt + 1 < nvalid ? 0xffff0000u : 0u);
-        a23 = (tt + 2 < nvalid ? 0x0000ffffu : 0u) | (tt + 3 < nvalid ? 0xffff0000u : 0u);
-        b01 = (tt + 16 < nvalid ? 0x0000ffffu : 0u) | (tt + 17 < nvalid ? 0xffff0000u : 0u);
-        b23 = (tt + 18 < nvalid ? 0x0000ffffu : 0u) | (tt + 19 < nvalid ? 0xffff0000u : 0u);
-      }
+      if (full) {
 #pragma unroll
-      for (int k = 0; k < KQ; ++k) {
-        uint4 l = lds[stage][2][k * 64 + lane], hh = lds[stage][3][k * 64 + lane];
-        l.x &= a01; l.y &= a23; l.z &= b01; l.w &= b23;
-        hh.x &= a01; hh.y &= a23; hh.z &= b01; hh.w &= b23;
-        st[0].o[2 * k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, l), pp, st[0].o[2 * k], 0, 0, 0);
-        st[0].o[2 * k + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, hh), pp, st[0].o[2 * k + 1], 0, 0, 0);
+        for (int k = 0; k < KQ; ++k) {
+          st[0].o[2 * k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lds[stage][2][k * 64 + lane]), pp, st[0].o[2 * k], 0, 0, 0);
+          st[0].o[2 * k + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lds[stage][3][k * 64 + lane]), pp, st[0].o[2 * k + 1], 0, 0, 0);
+        }
+      } else {   // tokens the pair does not hold may be anything: zero their V
+        uint4 lo[KQ], hi[KQ];
+#pragma unroll
+        for (int k = 0; k < KQ; ++k) { lo[k] = lds[stage][2][k * 64 + lane]; hi[k] = lds[stage][3][k * 64 + lane]; }
+        pair_pv_lohi<D, false>(st[0], lo, hi, pp, nvalid);
       }
     }
     __syncthreads();
