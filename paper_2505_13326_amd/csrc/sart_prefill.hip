@@ -261,6 +261,7 @@ k_prefill_lds8(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   const int* __restrict__ table = prefix_table + (long long)req * dm.max_pp;
   const long long page_bytes = dm.page_elems * 2;
 
+  f32x4 lsum = {0.f, 0.f, 0.f, 0.f};                   // softmax denominators of the lane's query row (see pair_softmax_lagging)
   WaveState<D> st[NB];
   uint4 qreg[NB][KQ];
   int pos[NB], lo_pos[NB], hi_pos[NB];
@@ -324,8 +325,8 @@ k_prefill_lds8(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
       }
       const bool full = t0 + 31 <= lo_pos[0];
       const int nvalid = min(32, min(plen, n_pages * 16) - t0);
-      const bf16x8 pp = full ? pair_softmax<D, true>(st[0], s0, s1, 32, a.scale_log2)
-                             : pair_softmax<D, false>(st[0], s0, s1, min(nvalid, pos[0] + 1 - t0), a.scale_log2);
+      const bf16x8 pp = full ? pair_softmax_lagging<D, true>(st[0], lsum, s0, s1, 32, a.scale_log2)
+                             : pair_softmax_lagging<D, false>(st[0], lsum, s0, s1, min(nvalid, pos[0] + 1 - t0), a.scale_log2);
       if (full) {
 #pragma unroll
         for (int k = 0; k < KQ; ++k) {
@@ -344,7 +345,7 @@ k_prefill_lds8(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   if (!wave_has_rows) return;
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
-    const float l = sum_over_rows(st[b].l);
+    const float l = lsum[0];
     if (out_row[b] < 0) continue;
     const float inv = a.v_scale / l;
     float* o = a.out + out_row[b];

@@ -124,3 +124,21 @@ def test_full_size_prompts(cfg_id, n_req):
         qs.append(wl.prefix_query(cfg, r))
     err = _check(cfg, o, g, list(range(n_req)), [cfg.prompt_len] * n_req, qs)
     print(f"config {cfg_id} prompts: max abs err {err:.3g}")
+
+
+@pytest.mark.parametrize("slope", [0.25, 0.01])
+def test_scores_that_keep_rising(slope):
+    """Keys that grow with the position make every page pair raise the row maxima (steeply: by far more than
+    the kernel's lag on every pair; gently: by less, so that the reference stays behind for long stretches)."""
+    cfg = wl.scaled(wl.CONFIGS[2], n_requests=1, nb=2, prompt_len=300)
+    P = cfg.prompt_len
+    o, g = _pair(cfg, 24, 19)
+    rng = np.random.default_rng(11)
+    ramp = (np.arange(P, dtype=np.float32) * slope)[:, None, None]
+    k = wl.f32_to_bf16_bits(np.broadcast_to(ramp, (P, cfg.n_kv_heads, cfg.head_dim)).copy())
+    v = wl.f32_to_bf16_bits(rng.standard_normal((P, cfg.n_kv_heads, cfg.head_dim)).astype(np.float32))
+    for e in (o, g):
+        assert e.append(orc.SEQ_PREFIX, [0], [P], k, v) == orc.OK
+    q = wl.f32_to_bf16_bits(np.ones((P, cfg.n_q_heads, cfg.head_dim), np.float32))
+    err = _check(cfg, o, g, [0], [P], [q])
+    print(f"rising scores, slope {slope}: max abs err {err:.3g}")
