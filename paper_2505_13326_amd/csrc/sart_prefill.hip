@@ -9,21 +9,15 @@
 // Design for MI355X (gfx950).  Unlike decode this is a dense contraction with
 // reuse: a K/V page serves every later query.  The rows of one kv head -
 // (query, head of the GQA group), query-major - are cut into tiles of
-// kPfTileRows; a 4-wave workgroup takes a tile, each wave kPfBlocks 16-row
-// blocks of the matrix-core tile the decode kernel uses (S^T = K Q^T and
-// O^T += V^T P^T as 16x16x32 bf16 products; online softmax on the vector ALUs).
-// Pages are taken two at a time (32 tokens): one running-max update per 32
-// tokens.  A page pair loaded into registers is used by all blocks of the wave,
-// and the four waves of a workgroup walk the same pages together (the first
-// load of a page brings it to the CU's cache for the others).  Work goes phase
-// by phase over the wave's blocks - scores of all blocks, softmax updates,
-// O^T products - so K's registers are free for the next pair's loads after the
-// first phase and V's after the last; every load is unconditional.  Two blocks
-// per wave keep a wave under 256 registers, so two waves share a SIMD and one's
-// vector work overlaps the other's matrix-core work.  Blocks skip pairs that lie
-// wholly after their rows' positions and mask scores only on the pairs that
-// straddle them.  No split over the sequence: one wave sees a row's whole
-// context, so there is no merge.
+// kPfTileRows, one workgroup per tile, on the matrix-core tile the decode kernel
+// uses (S^T = K Q^T and O^T += V^T P^T as 16x16x32 bf16 products; online softmax
+// on the vector ALUs).  Pages are taken two at a time (32 tokens): one update of
+// the maximum per 32 tokens.  Blocks skip pairs that lie wholly after their
+// rows' positions and mask scores only on the pairs that straddle them.  No
+// split over the sequence: one wave sees a row's whole context, so there is no
+// merge.  Two kernels: k_prefill_mfma (8-bit float caches: every wave loads its
+// page pairs into registers and expands them there) and k_prefill_lds8 (bf16
+// caches: pairs staged once per workgroup in LDS, 8 waves per tile).
 #include <type_traits>
 
 #include "sart_attn_tile.h"
