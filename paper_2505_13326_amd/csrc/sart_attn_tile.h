@@ -214,9 +214,10 @@ __device__ inline bf16x8 pair_softmax_lagging(WaveState<D>& st, f32x4& lsum, f32
       if (16 + t0 + j >= nvalid_row) s1[j] = -__builtin_inff();
     }
   }
-  float mx = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])), fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
-  mx = max_over_rows(mx) * scale_log2;
-  if (__any(mx > st.m + kLag)) {                    // also the first pair: st.m = -inf
+  // the test needs no row maximum: a lane looks at its own eight scores, the vote does the rest
+  const float mine = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])), fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+  if (__any(mine * scale_log2 > st.m + kLag)) {     // also the first pair: st.m = -inf
+    const float mx = max_over_rows(mine) * scale_log2;
     const float m_new = fmaxf(st.m, mx);
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
     st.m = m_new;
