@@ -49,7 +49,8 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
     num_pages = R * pp + 8
     cache = sart.SartCache(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
                            page_tokens=cfg.page_tokens, num_pages=num_pages, max_requests=R, branches_per_request=cfg.nb,
-                           max_pages_per_branch=4, max_prefix_pages=pp, dtype=cfg.dtype,
+                           max_pages_per_branch=4, max_prefix_pages=pp,
+                           dtype="fp8" if args.kv_dtype == "fp8" else cfg.dtype,
                            free_order=wl.free_order(cfg, num_pages) if args.free_order == "scattered" else None)
 
     def dev(x):
