@@ -165,6 +165,11 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
     }
   }
   sart_cache* c = new sart_cache();
+  // any early return below (a failed HIP call, a failed allocation) releases what exists so far
+  struct Guard {
+    sart_cache* c;
+    ~Guard() { if (c) sart_free_cache(c); }
+  } guard{c};
   c->desc = *d;
   c->layer_bytes = pool_bytes / d->n_layers;
   c->desc.initial_free_order = nullptr;
@@ -186,7 +191,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
 #define ALLOC(ptr, n)                                           \
   do {                                                          \
     st = dev_alloc(c, &(ptr), (n));                             \
-    if (st != SART_OK) { sart_free_cache(c); return st; }       \
+    if (st != SART_OK) return st;                               \
   } while (0)
   ALLOC(tb.scal, S_COUNT);
   ALLOC(tb.free_stack, dm.num_pages);
@@ -210,7 +215,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   } else {
     void* p = nullptr;
     hipError_t e = hipMalloc(&p, pool_bytes);
-    if (e != hipSuccess) { sart_free_cache(c); return fail(SART_E_HIP, "hipMalloc(pool %zu B): %s", pool_bytes, hipGetErrorString(e)); }
+    if (e != hipSuccess) return fail(SART_E_HIP, "hipMalloc(pool %zu B): %s", pool_bytes, hipGetErrorString(e));
     c->allocs.push_back(p);
     c->ctx.pool = p;
     c->owns_pool = true;
@@ -262,6 +267,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   HIP_TRY(hipStreamSynchronize(nullptr));
   if (order_dev) HIP_TRY(hipFree(order_dev));
   HIP_TRY(hipGetLastError());
+  guard.c = nullptr;
   *out = c;
   return SART_OK;
 }
