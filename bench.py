@@ -295,17 +295,19 @@ def main():
         eager_step = step
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
+        def graph_body(j):
+            for l in range(NL):
+                cache.append_tokens(sart.SEQ_BRANCH, None, None, kvs[j][0], kvs[j][1], all_active=True, layer=l)
+                cache.decode_attention(qs[j], out=out, layer=l)
         with torch.cuda.stream(side):
-            cache.append_tokens(sart.SEQ_BRANCH, None, None, kvs[0][0], kvs[0][1], all_active=True)
-            cache.decode_attention(qs[0], out=out)
+            graph_body(0)
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
         graphs = []
         for j in range(n_in):
             gr = torch.cuda.CUDAGraph()
             with torch.cuda.graph(gr):
-                cache.append_tokens(sart.SEQ_BRANCH, None, None, kvs[j][0], kvs[j][1], all_active=True)
-                cache.decode_attention(qs[j], out=out)
+                graph_body(j)
             graphs.append(gr)
 
         def step(i):
