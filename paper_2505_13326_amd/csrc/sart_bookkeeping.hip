@@ -76,6 +76,42 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
     }
     a.n_seqs = nA;
   }
+  // The decode step's append - one token for every active row, at most one chunk of rows - in one pass:
+  // row i is sequence i, so nothing needs to be stashed and looked up again.
+  if (a.kind == SART_SEQ_BRANCH && !a.ids && !a.ntok && nA <= kPlanThreads) {
+    int len = 0, need = 0, bad = 0, b = 0;
+    if (tid < nA) {
+      len = tb.seq_len[tid];
+      b = tb.active[tid];
+      need = len % dm.pt == 0;                        // the token opens a new page
+      bad = need && len / dm.pt + 1 > dm.max_bp;
+      tb.ap_id[tid] = b;
+      tb.ap_start[tid] = len;
+    }
+    int total;
+    const int ex = block_excl_scan(need, lds, total);
+    if (__syncthreads_or(bad)) {
+      if (tid == 0) record_error(scal, SART_E_INVALID, a.call_seq);
+      return;
+    }
+    if (total > top) {
+      if (tid == 0) record_error(scal, SART_E_OOM_PAGES, a.call_seq);
+      return;
+    }
+    if (tid < nA) {
+      if (need) tb.bt[scal[S_BTSEL]][(long long)tid * dm.max_bp + len / dm.pt] = tb.free_stack[top - 1 - ex];
+      tb.seq_len[tid] = len + 1;
+      tb.branch_appended[b / dm.Nb] = 1;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      scal[S_FREETOP] = top - total;
+      scal[S_CALLOK] = 1;
+      scal[S_APPENDOK] = 1;
+    }
+    refresh_decode_plan(c, pc, lds);
+    return;
+  }
   // pass 1: validate, compute pages needed, stash id / start length
   int carry = 0, carry_new = 0;
   for (int base = 0; base < a.n_seqs; base += kPlanThreads) {
