@@ -60,11 +60,15 @@ typedef enum {
   SART_E_HIP = 4        /* a HIP runtime call failed; see sart_last_error      */
 } sart_status;
 
-/* Element type of the cache.  SART_FP8_E4M3: Q, K, V cross the boundary as bf16;
- * the pool keeps K and V as 8-bit floats (OCP E4M3: 4 exponent bits, bias 7, 3
- * mantissa bits, largest finite 448): code = nearest(x / scale), ties to even,
- * |x / scale| clamped to 448; read back as value(code) * scale, with one scale
- * for K and one for V per cache (k_scale, v_scale).  Inputs must be finite.
+/* Element type of the cache.  SART_FP8_E4M3 (an extension: the paper keeps KV in
+ * the model's dtype, Section 5.1): Q, K, V cross the boundary as bf16; the pool
+ * keeps K and V as 8-bit floats (OCP E4M3: 4 exponent bits, bias 7, 3 mantissa
+ * bits, subnormals, largest finite 448): code = the E4M3 value nearest to the
+ * exact quotient x / scale, ties to the even code, |x / scale| clamped to 448;
+ * read back as value(code) * scale, with one float32 scale for K and one for V
+ * per cache (k_scale, v_scale).  The library divides in float64, which decides
+ * every code as the exact quotient does (a float32 division or a multiplication
+ * by 1/scale would not).  Inputs must be finite.
  * Half the bytes of bf16 per cached token.  Needs page_tokens 16, head_dim 64 or
  * 128 and Hq/Hkv <= 16. */
 typedef enum { SART_F32 = 0, SART_BF16 = 1, SART_FP8_E4M3 = 2 } sart_dtype;
@@ -145,8 +149,11 @@ typedef struct {
  * num_pages * page_tokens * 2 * Hkv * d * sizeof(element). */
 size_t sart_pool_bytes(const sart_cache_desc* desc);
 
-/* A0.  Creates the cache: every page free, no request, no branch.  Zero-fills
- * the pool (so never-written slots hold finite values).  Synchronous. */
+/* A0.  Creates the cache: every page free, no request, no branch (Sections 1 and
+ * 2: the KV cache of the sampled branches is what limits how many can be batched,
+ * so the pool, its free list and the branch tables are sized once, here).
+ * Zero-fills the pool (so never-written slots hold finite values).  Synchronous.
+ * On any error nothing stays allocated. */
 sart_status sart_alloc_cache(const sart_cache_desc* desc, sart_cache** out);
 sart_status sart_free_cache(sart_cache* cache);
 int32_t sart_cache_layout(const sart_cache* cache); /* sart_kv_layout */
@@ -178,7 +185,9 @@ int32_t sart_cache_layout(const sart_cache* cache); /* sart_kv_layout */
  * An append to a layer > 0 writes that layer's K/V of the same tokens: it must
  * repeat the step's layer-0 append (same kind, list, counts; SART_E_INVALID at
  * once otherwise) and come before any other state-changing call; it changes no
- * state, and is skipped on the device if that layer-0 append failed there.
+ * state.  If that layer-0 append failed on the device, or a finish or prune
+ * moved rows since, nothing is written and the status SART_E_STATE is stored
+ * (sticky; after a failed layer-0 append its own status stays the first).
  * sart_decode_attention and sart_prefill_attention read the layer they name.
  * Pages are popped from the free stack sequence by sequence in list order,
  * each sequence taking its new pages in ascending logical page order.
@@ -278,17 +287,6 @@ sart_status sart_get_state(sart_cache* cache, int32_t* n_active,
                            int32_t* prefix_lens, int32_t* prefix_refcnt,
                            int32_t* branch_state, int32_t* req_counters);
 
-/* Launch statistics of the last sart_decode_attention on this cache, measured
- * with HIP events on the stream the kernels ran on (for bench harnesses).
- * sart_set_profiling(cache, n): n = 0 off; n = 1 each decode call records
- * events around its dominant (attention) kernel; n > 1 the call launches that
- * kernel n times back to back between the events (it is idempotent), which
- * amortises the events' own dispatch overhead; ms_attn is then the average per
- * launch.  ms_total: the whole call's device work.  sart_last_decode_ms waits
- * for the events. */
-sart_status sart_set_profiling(sart_cache* cache, int32_t on);
-sart_status sart_last_decode_ms(sart_cache* cache, float* ms_attn, float* ms_total);
-
 /* DEVICE views of the active list for callers that keep their step loop on the
  * device (a recorded graph that gathers its per-branch inputs itself):
  * *active_handles -> int32[max_requests * Nb], the handles in active order
@@ -296,46 +294,6 @@ sart_status sart_last_decode_ms(sart_cache* cache, float* ms_attn, float* ms_tot
  * Owned by the library, read-only for the caller, valid until sart_free_cache;
  * their contents change with every state-changing call, in stream order. */
 sart_status sart_device_views(sart_cache* cache, const int32_t** active_handles, const int32_t** n_active);
-
-/* Measurement aid, no part of the method: reads `bytes` (a multiple of 8 KiB is
- * used) of a DEVICE buffer with plain coalesced loads, in 8 KiB chunks, in
- * ascending order or in the order chunk_order gives (DEVICE, bytes / 8192
- * entries, each a chunk number below that; NULL: ascending).  Asynchronous on
- * `stream`; the caller times it.  bench.py reports the attention kernel's rate
- * against this one's on the same box. */
-sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_order, void* stream);
-
-/* Tuning knobs of the decode launch (defaults are chosen for MI355X):
- *   n_workgroups         persistent attention grid of 4-wave workgroups (<= 0:
- *                        one per CU);
- *   n_prompt_workgroups  how many of them, the last ones of the grid, serve only
- *                        the shared prompts while the others stream the branches'
- *                        own pages (<= 0, the default: every workgroup does both,
- *                        own pages first, then its share of the prompts);
- *   prefix_chunk_pages   prompt chunk of the LDS-staged mode (<= 0: sized on the
- *                        device from the active set);
- *   prompt_mode          how the shared prompt is read on the matrix-core
- *                        layouts.  2 (default) = in blocks of prompt pages, each
- *                        read once per tile of 16 query rows of the request
- *                        (rows = (branch, head of the GQA group), branch-major:
- *                        with G = 7 and 8 branches, 4 tiles instead of 8
- *                        per-branch reads, every row of the matrix-core tile
- *                        used); the items are ordered (request, kv head, chunk,
- *                        tile) and every wave serves its item(s) before its own
- *                        range, so the tiles' re-reads of a chunk are neighbours
- *                        in time and place and hit in L2.  1 = the same with one
- *                        block per (chunk, branch), G of 16 tile rows used.  0 =
- *                        each prompt chunk is staged once in LDS per workgroup
- *                        and reused by the request's branches, one wave each
- *                        (not for SART_FP8_E4M3 caches: 1 is taken).  -1 = keep
- *                        the current mode.  Natural-layout caches always use 1;
- *   skew_permille        work moved from odd to even streaming workgroups, in
- *                        1/1000 of the mean per-wave range (workgroups go round-
- *                        robin to the 8 XCDs, and the odd XCDs stream about 10 %
- *                        slower); default 80, 0 = equal. */
-sart_status sart_set_decode_launch(sart_cache* cache, int32_t n_workgroups,
-                                   int32_t n_prompt_workgroups, int32_t prefix_chunk_pages,
-                                   int32_t prompt_mode, int32_t skew_permille);
 
 /* Text of the last host-side error of this thread. */
 const char* sart_last_error(void);

@@ -1,0 +1,70 @@
+/*
+ * sart_bench.h - measurement and tuning aids of libsart.  NOT part of the
+ * method's interface (that is sart.h): nothing here is needed to serve requests.
+ * bench.py and the tests that sweep launch shapes call these; a serving loop
+ * never does.
+ */
+#ifndef SART_BENCH_H
+#define SART_BENCH_H
+
+#include "sart.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Launch statistics of the last sart_decode_attention on this cache, measured
+ * with HIP events on the stream the kernels ran on (for bench harnesses).
+ * sart_set_profiling(cache, n): n = 0 off; n = 1 each decode call records
+ * events around its dominant (attention) kernel; n > 1 the call launches that
+ * kernel n times back to back between the events (it is idempotent), which
+ * amortises the events' own dispatch overhead; ms_attn is then the average per
+ * launch.  ms_total: the whole call's device work.  sart_last_decode_ms waits
+ * for the events. */
+sart_status sart_set_profiling(sart_cache* cache, int32_t on);
+sart_status sart_last_decode_ms(sart_cache* cache, float* ms_attn, float* ms_total);
+
+/* Measurement aid, no part of the method: reads `bytes` (a multiple of 8 KiB is
+ * used) of a DEVICE buffer with plain coalesced loads, in 8 KiB chunks, in
+ * ascending order or in the order chunk_order gives (DEVICE, bytes / 8192
+ * entries, each a chunk number below that; NULL: ascending).  Asynchronous on
+ * `stream`; the caller times it.  bench.py reports the attention kernel's rate
+ * against this one's on the same box. */
+sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_order, void* stream);
+
+/* Tuning knobs of the decode launch (defaults are chosen for MI355X):
+ *   n_workgroups         persistent attention grid of 4-wave workgroups (<= 0:
+ *                        one per CU);
+ *   n_prompt_workgroups  how many of them, the last ones of the grid, serve only
+ *                        the shared prompts while the others stream the branches'
+ *                        own pages (<= 0, the default: every workgroup does both,
+ *                        own pages first, then its share of the prompts);
+ *   prefix_chunk_pages   prompt chunk of the LDS-staged mode (<= 0: sized on the
+ *                        device from the active set);
+ *   prompt_mode          how the shared prompt is read on the matrix-core
+ *                        layouts.  2 (default) = in blocks of prompt pages, each
+ *                        read once per tile of 16 query rows of the request
+ *                        (rows = (branch, head of the GQA group), branch-major:
+ *                        with G = 7 and 8 branches, 4 tiles instead of 8
+ *                        per-branch reads, every row of the matrix-core tile
+ *                        used); the items are ordered (request, kv head, chunk,
+ *                        tile) and every wave serves its item(s) before its own
+ *                        range, so the tiles' re-reads of a chunk are neighbours
+ *                        in time and place and hit in L2.  1 = the same with one
+ *                        block per (chunk, branch), G of 16 tile rows used.  0 =
+ *                        each prompt chunk is staged once in LDS per workgroup
+ *                        and reused by the request's branches, one wave each
+ *                        (not for SART_FP8_E4M3 caches: 1 is taken).  -1 = keep
+ *                        the current mode.  Natural-layout caches always use 1;
+ *   skew_permille        work moved from odd to even streaming workgroups, in
+ *                        1/1000 of the mean per-wave range (workgroups go round-
+ *                        robin to the 8 XCDs, and the odd XCDs stream about 10 %
+ *                        slower); default 80, 0 = equal. */
+sart_status sart_set_decode_launch(sart_cache* cache, int32_t n_workgroups,
+                                   int32_t n_prompt_workgroups, int32_t prefix_chunk_pages,
+                                   int32_t prompt_mode, int32_t skew_permille);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SART_BENCH_H */

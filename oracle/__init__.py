@@ -66,7 +66,9 @@ def _i32(a):
 
 
 def fp8_roundtrip(bits, scale=1.0):
-    """The oracle's E4M3 codec on bf16 bit patterns: (codes uint8, read-back values float64)."""
+    """The oracle's E4M3 codec on bf16 bit patterns: (codes uint8, read-back values float64).
+    scale is taken as the float32 value a cache description carries."""
+    scale = float(np.float32(scale))
     b = np.ascontiguousarray(bits, np.uint16)
     codes = np.zeros(b.size, np.uint8)
     vals = np.zeros(b.size, np.float64)
@@ -99,7 +101,8 @@ class OracleCache:
         if not self.h:
             raise ValueError("orc_create rejected the description")
         if dtype == "fp8":      # bf16 in and out, K and V kept as 8-bit floats (E4M3) of x / scale
-            if self.L.orc_set_fp8(self.h, float(k_scale), float(v_scale)) != OK:
+            # a cache description carries its scales as float32
+            if self.L.orc_set_fp8(self.h, float(np.float32(k_scale)), float(np.float32(v_scale))) != OK:
                 raise ValueError("orc_set_fp8 rejected the scales")
 
     def close(self):

@@ -139,15 +139,14 @@ static unsigned char* token_ptr(const orc* o, int page, int slot, int head, int 
  * model's dtype): OCP FP8 E4M3 - 1 sign, 4 exponent bits (bias 7), 3 mantissa
  * bits, subnormals, no infinities, S.1111.111 = NaN, largest finite 448.
  * value(code): e == 0: m/8 * 2^-6; else (1 + m/8) * 2^(e-7).
- * A value is stored as the nearest code of y = x * (1 / scale), both the
- * reciprocal and the product taken in float32 (the precision the cache's kernels
- * work in, so that both sides decide every code alike), ties to the even code,
- * |y| clamped to 448 first; it is read back as value(code) * scale.
+ * A value is stored as the nearest code of the quotient x / scale (ties to the
+ * even code, |x / scale| clamped to 448 first) and read back as value(code) *
+ * scale.  scale is the cache's float32 scale, widened exactly.  The quotient is
+ * taken in float64; that decides every code as the exact quotient would: x has
+ * 8 significant bits, scale 24 and a boundary between two codes at most 5, so a
+ * quotient that is not on a boundary is at least 2^-29 (relative) away from it,
+ * far more than the 2^-53 the float64 division can move it.
  */
-static double fp8_prescale(double x, double scale) {
-  const float inv = 1.0f / (float)scale;
-  return (double)((float)x * inv);
-}
 static double e4m3_value(unsigned code) {
   const unsigned e = (code >> 3) & 15, m = code & 7;
   const double mag = e == 0 ? ldexp(m / 8.0, -6) : ldexp(1.0 + m / 8.0, (int)e - 7);
@@ -187,7 +186,7 @@ static uint16_t value_bf16_bits(double v) {   /* exact for every E4M3 value */
 /* the codec by itself, for tests: bf16 bits in, codes and read-back values out */
 void orc_fp8_roundtrip(const uint16_t* in, int n, double scale, unsigned char* codes, double* values) {
   for (int i = 0; i < n; ++i) {
-    const unsigned c = e4m3_nearest(fp8_prescale(bf16_bits_value(in[i]), scale));
+    const unsigned c = e4m3_nearest(bf16_bits_value(in[i]) / scale);
     if (codes) codes[i] = (unsigned char)c;
     if (values) values[i] = e4m3_value(c) * scale;
   }
@@ -313,7 +312,7 @@ int orc_append(orc* o, int kind, int n_seqs, const int* ids, const int* n_tokens
             const uint16_t* in = (const uint16_t*)((const unsigned char*)(w ? v : k) + src);
             uint16_t* dst = (uint16_t*)token_ptr(o, page, slot, h, w);
             for (int c = 0; c < o->d; ++c)
-              dst[c] = value_bf16_bits(e4m3_value(e4m3_nearest(fp8_prescale(bf16_bits_value(in[c]), o->kv_scale[w]))));
+              dst[c] = value_bf16_bits(e4m3_value(e4m3_nearest(bf16_bits_value(in[c]) / o->kv_scale[w])));
           }
         }
       }

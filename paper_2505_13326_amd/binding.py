@@ -19,7 +19,7 @@ LAYOUT_NATURAL, LAYOUT_MFMA16, LAYOUT_MFMA16_FP8 = 0, 1, 2
 DEFAULT_SKEW_PERMILLE = 80   # the library's default of sart_set_decode_launch's skew_permille
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.environ.get("SART_LIB") or os.path.join(_DIR, "libsart.so")  # SART_LIB: a developer build
+_LIB_PATH = os.path.join(_DIR, "libsart.so")
 _lib = None
 
 _ip = C.POINTER(C.c_int32)

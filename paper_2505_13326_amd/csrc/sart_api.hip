@@ -57,8 +57,9 @@ struct sart_cache {
   size_t layer_bytes = 0;              // pool bytes of one layer
   float k_scale = 1.0f, v_scale = 1.0f; // 8-bit float caches: stored code * scale is the value
   // the last layer-0 append, which the same step's appends to the other layers must repeat
-  int last_kind = -1, last_n_seqs = 0, last_has_ids = 0;
+  int last_kind = -1, last_n_seqs = 0, last_has_ids = 0, last_has_ntok = 0;
   long long last_total = 0;
+  std::vector<int> last_ids, last_ntok;
   hipStream_t last_stream = nullptr;
   float* partials = nullptr;
   long long partial_cap = 0;
@@ -182,7 +183,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   dm.layout = pick_layout(d); dm.esize = d->kv_dtype == SART_F32 ? 4 : (d->kv_dtype == SART_FP8_E4M3 ? 1 : 2);
   c->k_scale = d->kv_dtype == SART_FP8_E4M3 && d->k_scale > 0.f ? d->k_scale : 1.0f;
   c->v_scale = d->kv_dtype == SART_FP8_E4M3 && d->v_scale > 0.f ? d->v_scale : 1.0f;
-  dm.k_inv_scale = 1.0f / c->k_scale; dm.v_inv_scale = 1.0f / c->v_scale;
+  dm.k_scale = c->k_scale; dm.v_scale = c->v_scale;
   dm.tile_elems = (long long)dm.pt * dm.d;
   dm.page_elems = (long long)dm.Hkv * 2 * dm.tile_elems;
 
@@ -258,14 +259,18 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   // tables + zero-filled pool
   int* order_dev = nullptr;
   if (d->initial_free_order) {
-    HIP_TRY(hipMalloc((void**)&order_dev, (size_t)dm.num_pages * sizeof(int)));
+    st = dev_alloc(c, &order_dev, (size_t)dm.num_pages);     // in the cache's list: released on every error path
+    if (st != SART_OK) return st;
     HIP_TRY(hipMemcpy(order_dev, d->initial_free_order, (size_t)dm.num_pages * sizeof(int), hipMemcpyHostToDevice));
   }
   launch_init_tables(c->ctx, order_dev, nullptr);
   launch_plan(c->ctx, c->plan, nullptr);
   HIP_TRY(hipMemsetAsync(c->ctx.pool, 0, pool_bytes, nullptr));
   HIP_TRY(hipStreamSynchronize(nullptr));
-  if (order_dev) HIP_TRY(hipFree(order_dev));
+  if (order_dev) {
+    c->allocs.pop_back();                                     // the last block allocated
+    HIP_TRY(hipFree(order_dev));
+  }
   HIP_TRY(hipGetLastError());
   guard.c = nullptr;
   *out = c;
@@ -304,7 +309,7 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
     a.kind = kind; a.n_seqs = n_seqs; a.total_rows = n_seqs < -dm.H ? dm.H : -n_seqs; a.k = k; a.v = v;
     a.call_seq = ++c->call_seq;
     a.write_only = layer > 0;
-    if (layer == 0) { c->last_kind = kind; c->last_n_seqs = n_seqs; c->last_has_ids = 0; c->last_total = -1; }
+    if (layer == 0) { c->last_kind = kind; c->last_n_seqs = n_seqs; c->last_has_ids = 0; c->last_has_ntok = 0; c->last_total = -1; }
     else if (c->last_kind != kind || c->last_n_seqs != n_seqs || c->last_total != -1)
       return fail(SART_E_INVALID, "an append to layer %d must repeat the step's layer-0 append", layer);
     launch_append(layer_ctx(c, layer), c->plan, a, st);
@@ -339,9 +344,17 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
   AppendArgs a{};
   a.kind = kind; a.n_seqs = n_seqs; a.total_rows = total; a.k = k; a.v = v; a.call_seq = ++c->call_seq;
   a.write_only = layer > 0;
-  if (layer == 0) { c->last_kind = kind; c->last_n_seqs = n_seqs; c->last_has_ids = ids != nullptr; c->last_total = total; }
-  else if (c->last_kind != kind || c->last_n_seqs != n_seqs || c->last_has_ids != (ids != nullptr) || c->last_total != total)
-    return fail(SART_E_INVALID, "an append to layer %d must repeat the step's layer-0 append", layer);
+  if (layer == 0) {
+    c->last_kind = kind; c->last_n_seqs = n_seqs; c->last_has_ids = ids != nullptr; c->last_has_ntok = n_tokens != nullptr;
+    c->last_total = total;
+    c->last_ids.assign(ids ? ids : nullptr, ids ? ids + n_seqs : nullptr);
+    c->last_ntok.assign(n_tokens ? n_tokens : nullptr, n_tokens ? n_tokens + n_seqs : nullptr);
+  } else if (c->last_kind != kind || c->last_n_seqs != n_seqs || c->last_has_ids != (ids != nullptr) ||
+             c->last_has_ntok != (n_tokens != nullptr) || c->last_total != total ||
+             (ids && memcmp(ids, c->last_ids.data(), (size_t)n_seqs * sizeof(int)) != 0) ||
+             (n_tokens && memcmp(n_tokens, c->last_ntok.data(), (size_t)n_seqs * sizeof(int)) != 0)) {
+    return fail(SART_E_INVALID, "an append to layer %d must repeat the step's layer-0 append (kind, ids, counts)", layer);
+  }
   const Ctx lctx = layer_ctx(c, layer);
   if (ids || n_tokens) {
     StageSlot* s;

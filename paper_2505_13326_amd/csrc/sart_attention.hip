@@ -19,26 +19,16 @@
 //     step are laid on one line and cut into equal ranges, one per wave
 //     (a range may cross branch boundaries); each piece yields a partial
 //     (m, l, o) that a merge kernel combines.
-//   * Shared prompt pages are read once per branch, but in blocks ordered
-//     (request, kv head, chunk, branch) that every wave serves before its own
-//     range, so the re-reads of a chunk are neighbours in time and on one XCD
-//     and hit in its L2 (default).  The other mode stages each prompt chunk in
-//     LDS once per workgroup for the request's branches, one wave each.
+//   * Shared prompt pages are read in blocks of pages, once per tile of 16
+//     query rows of the request (rows = (branch, head of the GQA group)), the
+//     work items ordered (request, kv head, chunk, tile) and served by every
+//     wave before its own range, so the tiles' re-reads of a chunk are
+//     neighbours in time and on one XCD and hit in its L2 (default).  Other
+//     modes: one block per (chunk, branch); or each prompt chunk staged in LDS
+//     once per workgroup for the request's branches, one wave each.
 #include "sart_attn_tile.h"
 
 namespace sart {
-
-#ifdef SART_TRACE
-// Developer build only: per-wave timestamps (100 MHz wall clock) at phase
-// boundaries of the attention kernel, read back with sart_debug_trace.
-__device__ unsigned long long g_trace[16384 * 8];
-#define SART_STAMP(k)                                                                              \
-  do {                                                                                             \
-    if ((threadIdx.x & 63) == 0) g_trace[((size_t)blockIdx.x * kAttnWaves + (threadIdx.x >> 6)) * 8 + (k)] = wall_clock64(); \
-  } while (0)
-#else
-#define SART_STAMP(k) do { } while (0)
-#endif
 
 // floats of one partial: o[G][d], then m[G], l[G], padded to a 16-byte multiple
 __host__ __device__ inline long long partial_floats(int G, int d) { return (long long)G * d + ((2 * G + 3) & ~3); }
@@ -123,14 +113,12 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
   const bool dedicated = n_own_wg < (int)gridDim.x;
   const bool prompt_wg = (int)blockIdx.x >= n_own_wg;
   const bool prompt_first = (blockIdx.x & 1) == 0;
-  SART_STAMP(0);
   WaveState<D> st;
   uint4 qreg[KQ];
 
   for (int phase = 0; phase < 2; ++phase) {
     if ((phase == 0) == prompt_first) {
       // ---- shared prompt items (LDS prompt mode) ----------------------------
-      SART_STAMP(1);
       if (FP8 || (dedicated && !prompt_wg)) continue;
       const int it0 = dedicated ? (int)blockIdx.x - n_own_wg : (int)blockIdx.x;
       const int it_step = dedicated ? (int)gridDim.x - n_own_wg : (int)gridDim.x;
@@ -201,7 +189,6 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         if (have_row)
           store_partial<D>(st, a.partials, prefix_base + ((long long)row * dm.Hkv + h) * npc + ck, dm);
       }
-      SART_STAMP(2);
       continue;
     }
 
@@ -213,7 +200,6 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
     const int4 wd0 = ((const int4*)(wave_desc + 16LL * wave_id))[0];
     const int4 wd2 = ((const int4*)(wave_desc + 16LL * wave_id))[2];
     const int4 wd3 = ((const int4*)(wave_desc + 16LL * wave_id))[3];
-    SART_STAMP(3);
     const long long page_bytes = dm.page_elems * (FP8 ? 1 : 2);
     // Streams pages [r0, r0 + rn) of `table` (kv head h) through kRing register
     // buffers in a software pipeline: kRing pages (8 KiB each) are in flight per
@@ -396,9 +382,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         u += line == 0 ? rn : cut.n_prompt;
       }
     }
-    SART_STAMP(6);
   }
-  SART_STAMP(7);
 }
 
 // ---------------------------------------------------------------------------
@@ -597,9 +581,3 @@ void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s) {
 }
 
 }  // namespace sart
-
-#ifdef SART_TRACE
-extern "C" int sart_debug_trace(unsigned long long* host_out, int n_waves) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(sart::g_trace), (size_t)n_waves * 8 * sizeof(unsigned long long));
-}
-#endif

@@ -200,13 +200,40 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
   refresh_decode_plan(c, pc, lds);
 }
 
+// OCP E4M3 code (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals, largest finite
+// 448) nearest to x / scale, ties to the even code, magnitude clamped to 448.  The quotient is taken
+// in float64 and rounded to the code's 4 significant bits in one step (v_rndne_f64), so the code is
+// the one the exact quotient has: x carries 8 significant bits (bf16), scale 24, and a boundary
+// between two codes at most 5, so a quotient that is not on a boundary is at least 2^-29 (relative)
+// away from it, which the float64 division (2^-53) cannot bridge.  A float32 division can: it turns
+// quotients within 2^-24 of a boundary into false ties.
+__device__ inline unsigned e4m3_code_of_quotient(float x, float scale) {
+  const double t = (double)x / (double)scale;
+  double a = __builtin_fabs(t);
+  if (!(a <= 448.0)) a = 448.0;
+  unsigned code;
+  if (a < 0x1p-6) {
+    code = (unsigned)__builtin_rint(a * 512.0);            // subnormal codes count 2^-9; 8 is the first normal code
+  } else {
+    const int e = (int)((__double_as_longlong(a) >> 52) & 0x7ff) - 1023;      // a is normal: 2^-6 <= a <= 448
+    const double s = __longlong_as_double(__double_as_longlong(a) - ((long long)(e - 3) << 52));   // a * 2^(3-e) in [8, 16)
+    code = (unsigned)((e + 7) << 3) + ((unsigned)__builtin_rint(s) - 8u);     // a carry runs into the exponent field
+  }
+  return (__double_as_longlong(t) < 0 ? 0x80u : 0u) | code;
+}
+
 // One wave copies one (token, kv head) row of K and V into its page slot.
 template <typename T>
 __global__ void __launch_bounds__(256)
 k_append_write(Ctx c, AppendArgs a) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
-  if (!tb.scal[a.write_only ? S_APPENDOK : S_CALLOK]) return;
+  if (!tb.scal[a.write_only ? S_APPENDOK : S_CALLOK]) {
+    // a write to a layer > 0 whose layer-0 append failed on the device, or after rows moved (a finish or
+    // prune since): nothing is written, and the caller is told (sticky)
+    if (a.write_only && blockIdx.x == 0 && threadIdx.x == 0) record_error(tb.scal, SART_E_STATE, a.call_seq);
+    return;
+  }
   const int lane = threadIdx.x & 63;
   const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
@@ -244,11 +271,10 @@ k_append_write(Ctx c, AppendArgs a) {
       if constexpr (sizeof(T) == 2) {
         unsigned char* pool8 = (unsigned char*)c.pool;
         for (int d = lane; d < dm.d; d += 64) {
-          const float kf = __uint_as_float((unsigned)ksrc[d] << 16) * dm.k_inv_scale;
-          const float vf = __uint_as_float((unsigned)vsrc[d] << 16) * dm.v_inv_scale;
-          const int codes = __builtin_amdgcn_cvt_pk_fp8_f32(fminf(fmaxf(kf, -448.f), 448.f), fminf(fmaxf(vf, -448.f), 448.f), 0, false);
-          pool8[kb + k_elem_off(dm.layout, dm.d, slot, d)] = (unsigned char)(codes & 0xff);
-          pool8[vb + v_elem_off(dm.layout, dm.d, slot, d)] = (unsigned char)((codes >> 8) & 0xff);
+          pool8[kb + k_elem_off(dm.layout, dm.d, slot, d)] =
+              (unsigned char)e4m3_code_of_quotient(__uint_as_float((unsigned)ksrc[d] << 16), dm.k_scale);
+          pool8[vb + v_elem_off(dm.layout, dm.d, slot, d)] =
+              (unsigned char)e4m3_code_of_quotient(__uint_as_float((unsigned)vsrc[d] << 16), dm.v_scale);
         }
       }
       continue;

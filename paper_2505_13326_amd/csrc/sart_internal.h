@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "sart.h"
+#include "sart_bench.h"
 
 namespace sart {
 
@@ -60,7 +61,7 @@ struct Dims {
   int Hq, Hkv, G, d, pt, num_pages, max_req, Nb, Q, max_bp, max_pp, H, dtype, layout, esize;
   long long tile_elems;   // pt * d: elements of one K (or V) tile
   long long page_elems;   // Hkv * 2 * tile_elems
-  float k_inv_scale, v_inv_scale;   // 8-bit float caches: what K and V are multiplied by before rounding
+  float k_scale, v_scale;           // 8-bit float caches: K and V are stored as codes of x / scale
 };
 
 struct Tables {

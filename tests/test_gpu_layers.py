@@ -73,12 +73,27 @@ def test_three_layers_share_tables_and_keep_their_own_kv():
     k, v = wl.step_kv(cfgs[1], 4)
     assert g.c.append_tokens(orc.SEQ_BRANCH, act[:3], None, k[act[:3]], v[act[:3]], layer=1, status=True) == orc.E_INVALID
     assert g.c.append_tokens(orc.SEQ_BRANCH, None, None, k[act], v[act], layer=NL, status=True) == orc.E_INVALID
-    # ... and after a call that moved rows it is skipped on the device: layer 1 keeps its data
+    # ... a different list of the same length is refused at once too ...
+    swapped = act.copy()
+    swapped[[0, 1]] = swapped[[1, 0]]
+    k0, v0 = wl.step_kv(cfgs[0], 4)
+    g.c.append_tokens(orc.SEQ_BRANCH, act, None, k0[act], v0[act], layer=0)
+    for l in range(NL):
+        kk, vv = wl.step_kv(cfgs[l], 4)
+        assert os_[l].append(orc.SEQ_BRANCH, None, None, kk[act], vv[act]) == orc.OK
+    assert g.c.append_tokens(orc.SEQ_BRANCH, swapped, None, k[swapped], v[swapped], layer=1, status=True) == orc.E_INVALID
+    for l in range(1, NL):
+        kk, vv = wl.step_kv(cfgs[l], 4)
+        g.c.append_tokens(orc.SEQ_BRANCH, act, None, kk[act], vv[act], layer=l)
+    assert g.c.sync_status() == 0
+    check_all_layers(4)
+    # ... and after a call that moved rows nothing is written (layer 1 keeps its data) and the caller is told
     fin = [int(act[0])]
     for l in range(NL):
         assert os_[l].finish(fin) == orc.OK
     assert g.finish(fin) == orc.OK
-    g.c.append_tokens(orc.SEQ_BRANCH, None, None, k[act], v[act], layer=1, all_active=True)
+    g.c.append_tokens(orc.SEQ_BRANCH, act, None, k[act], v[act], layer=1)
+    assert g.c.sync_status() == orc.E_STATE
     assert g.c.sync_status() == 0
     assert_state_equal(os_[0].state(), g.state())
     check_all_layers(5)

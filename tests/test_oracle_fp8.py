@@ -1,7 +1,10 @@
 """Pins of the oracle's 8-bit float (OCP FP8 E4M3) cache against things other
 than itself: the format's definition written out as a table, torch's
-float8_e4m3fn conversion (a library's), and the attention of a bf16 cache that
-was handed the already rounded values."""
+float8_e4m3fn conversion (a library's), exact rational arithmetic for scaled
+values (with hand-worked ties), and the attention of a bf16 cache that was
+handed the already rounded values."""
+from fractions import Fraction
+
 import numpy as np
 import pytest
 import torch
@@ -43,12 +46,53 @@ def test_rounding_matches_torch_float8_e4m3fn_on_every_bf16_value():
                      [((c & 7) / 8) * 2.0 ** -6 if (c >> 3) == 0 else (1 + (c & 7) / 8) * 2.0 ** ((c >> 3) - 7) for c in range(1, 127)])
     best = np.abs(np.abs(clamped)[:, None] - table[None, :]).min(1)
     np.testing.assert_array_equal(np.abs(back - clamped), best)
-    # a scale divides before rounding and multiplies after
-    _, scaled = orc.fp8_roundtrip(bits[::97], scale=0.37)
-    with np.errstate(over="ignore"):                     # the largest bf16 values overflow to inf, then clamp to 448
-        pre = vals[::97].astype(np.float32) * (np.float32(1.0) / np.float32(0.37))     # float32, like the cache's kernels
-    ref2 = torch.from_numpy(np.clip(pre, -448, 448)).to(torch.float8_e4m3fn).to(torch.float32).numpy()
-    np.testing.assert_array_equal(scaled, ref2.astype(np.float64) * 0.37)
+
+
+def _e4m3_table():
+    """The 127 finite magnitudes by code, as exact fractions (the format's definition)."""
+    return [Fraction(c & 7, 8) * Fraction(1, 64) if (c >> 3) == 0 else (1 + Fraction(c & 7, 8)) * Fraction(2) ** ((c >> 3) - 7)
+            for c in range(127)]
+
+
+def _exact_code(x, scale, table):
+    """Nearest code of |x / scale| in exact rational arithmetic, ties to the even code, clamped to 448."""
+    t = min(abs(Fraction(float(x)) / Fraction(float(scale))), Fraction(448))
+    return min(range(127), key=lambda c: (abs(table[c] - t), c & 1))
+
+
+def test_scaled_codes_are_those_of_the_exact_quotient():
+    """code = nearest(x / scale): checked against exact rational arithmetic (no floating point decides
+    anything), on every bf16 value of eight binades for scales where float32 short-cuts go wrong."""
+    table = _e4m3_table()
+    # hand-worked ties.  91/1024 / 7 = 13/1024 = 6.5 * 2^-9: halfway between subnormal codes 6 and 7, so the even
+    # code 6; 175/1024 / 7 = 25/1024 = 12.5 * 2^-9: halfway between codes 12 and 13 ((8 + m) * 2^-9 in that
+    # binade), so 12.  Multiplying by the float32 reciprocal of 7 (which is above 1/7) lands above both ties.
+    for num, want in ((91, 6), (175, 12)):
+        x = np.float32(num / 1024.0)
+        bits = wl.f32_to_bf16_bits(np.array([x, -x], np.float32))
+        assert wl.bf16_bits_to_f32(bits)[0] == x                       # exact in bf16
+        codes, back = orc.fp8_roundtrip(bits, scale=7.0)
+        assert list(codes) == [want, 0x80 | want]
+        assert back[0] == float(table[want]) * 7.0
+        recip = np.float32(x) * (np.float32(1.0) / np.float32(7.0))    # the short-cut, for contrast
+        assert _exact_code(recip, 1.0, table) == want + 1
+    # every bf16 value from 2^-7 up to 2^1, four scales (float32 values, as a cache description carries them)
+    bits = np.arange(0x3C00, 0x4000, dtype=np.uint32).astype(np.uint16)
+    bits = np.concatenate([bits, bits | 0x8000])
+    vals = wl.bf16_bits_to_f32(bits)
+    n_recip = n_div32 = 0
+    for scale in (7.0, 0.37, 1.7, 0.011):
+        s32 = np.float32(scale)
+        codes, back = orc.fp8_roundtrip(bits, scale=scale)
+        want = np.array([_exact_code(x, s32, table) for x in vals])
+        np.testing.assert_array_equal(codes & 0x7F, want)
+        np.testing.assert_array_equal((codes & 0x80) != 0, np.signbit(vals))
+        np.testing.assert_array_equal(back, np.where(np.signbit(vals), -1.0, 1.0) *
+                                      np.array([float(table[c]) for c in want]) * float(s32))
+        # the pin tells the definitions apart: both float32 short-cuts decide some of these codes differently
+        n_recip += sum(_exact_code(x * (np.float32(1.0) / s32), 1.0, table) != w for x, w in zip(vals, want))
+        n_div32 += sum(_exact_code(x / s32, 1.0, table) != w for x, w in zip(vals, want))
+    assert n_recip > 0 and n_div32 > 0, (n_recip, n_div32)
 
 
 @pytest.mark.parametrize("scales", [(1.0, 1.0), (0.5, 0.25)])
