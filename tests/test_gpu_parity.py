@@ -220,31 +220,61 @@ def _request_arrays(cfg, r, L):
     return r, pk, pv, ids, ns, np.concatenate([x[0] for x in kv]), np.concatenate([x[1] for x in kv])
 
 
-def _populate_full(cfg, g, o, L, sample_reqs):
-    """All requests go to the GPU cache; only the sampled ones to the oracle
-    (attention does not depend on which physical pages hold the tokens)."""
+class _IntegerShadow:
+    """The oracle's bookkeeping at full size without the KV bytes: integer state (free stack, tables, lengths,
+    states, counters) does not depend on the head geometry, so a second oracle cache with ONE kv head of
+    8 elements, the same pool size, free order, limits and call sequence, fed zeros, holds exactly the state
+    the real-size cache must hold."""
+
+    def __init__(self, cfg, num_pages, max_bp, free_order):
+        tiny = wl.scaled(cfg, n_q_heads=1, n_kv_heads=1, head_dim=8)
+        self.o = orc.OracleCache(free_order=free_order, **dims(tiny, num_pages, max_bp))
+
+    def append(self, kind, ids, ns, k, v):
+        n = int(np.sum(ns)) if ns is not None else (len(ids) if ids is not None else self.o.n_active)
+        z = np.zeros((n, 1, 8), np.uint16)
+        return self.o.append(kind, ids, ns, z, z)
+
+    def prune(self, *a, **kw):
+        return self.o.prune(*a, **kw)
+
+    def state(self):
+        return self.o.state()
+
+
+def _populate_full(cfg, g, o, shadow, L, sample_reqs):
+    """All requests go to the GPU cache and to the integer shadow; only the sampled ones to the attention
+    oracle (attention does not depend on which physical pages hold the tokens)."""
     with ThreadPoolExecutor(max_workers=8) as ex:
         for r, pk, pv, ids, ns, bk, bv in ex.map(lambda r: _request_arrays(cfg, r, L), range(cfg.n_requests)):
-            for e in ([g, o] if r in sample_reqs else [g]):
+            for e in ([g, o, shadow] if r in sample_reqs else [g, shadow]):
                 assert e.append(orc.SEQ_PREFIX, [r], [cfg.prompt_len], pk, pv) == orc.OK
                 assert e.append(orc.SEQ_BRANCH, ids, ns, bk, bv) == orc.OK
 
 
 @pytest.mark.parametrize("cfg_id,sample", [(2, (0, 7, 15)), (4, (3, 40)), (5, (0,))])
 def test_full_size_configs_sampled_rows(cfg_id, sample):
+    """Configurations 2, 4 and 5 at full size in the launch shape bench.py times: the whole integer state
+    bit-exact against the oracle's bookkeeping (after the build, after a decode step's append, and for
+    configuration 5 after keeping the top 16 of 64 branches), attention on sampled requests."""
     cfg = wl.CONFIGS[cfg_id]
     L = wl.lengths(cfg)
-    num_pages = wl.pages_needed(cfg, L) + 64
+    num_pages = wl.pages_needed(cfg, L, growth_tokens=1) + 64
     max_bp = cfg.length_cap // 16 + 1
-    g = GpuEngine(free_order=wl.free_order(cfg, num_pages), **dims(cfg, num_pages, max_bp))
+    fo = wl.free_order(cfg, num_pages)
+    g = GpuEngine(free_order=fo, **dims(cfg, num_pages, max_bp))
+    shadow = _IntegerShadow(cfg, num_pages, max_bp, fo)
     Ls = L[list(sample)]
-    o = orc.OracleCache(**dims(cfg, int(np.sum((Ls + 15) // 16)) + len(sample) * (cfg.prompt_len // 16) + 8, max_bp))
-    _populate_full(cfg, g, o, L, set(sample))
-    check_invariants(g.state(), pt=16, num_pages=num_pages, Nb=cfg.nb, max_req=cfg.n_requests)
+    o = orc.OracleCache(**dims(cfg, int(np.sum((Ls + 16) // 16)) + len(sample) * (cfg.prompt_len // 16) + 8, max_bp))
+    _populate_full(cfg, g, o, shadow, L, set(sample))
+    stg = g.state()
+    check_invariants(stg, pt=16, num_pages=num_pages, Nb=cfg.nb, max_req=cfg.n_requests)
+    assert_state_equal(shadow.state(), stg)
     q = wl.query(cfg, 0)
 
     def compare(tag):
         stg, sto = g.state(), o.state()
+        assert_state_equal(shadow.state(), stg)                  # all 11 arrays, bit for bit
         nA, nO = int(stg["n_active"][0]), int(sto["n_active"][0])
         act_g = list(stg["active_handles"][:nA])
         act_o = sto["active_handles"][:nO]
@@ -256,13 +286,22 @@ def test_full_size_configs_sampled_rows(cfg_id, sample):
         print(f"cfg{cfg_id} {tag}: {nA} rows, {nO} sampled, max abs err {err:.3g}")
         assert err <= TOL[cfg.dtype]
 
-    compare("step")
+    compare("built")
+    # a decode step: one token for every active branch (some cross into a new page), then attention
+    k, v = wl.step_kv(cfg, 1)
+    act = stg["active_handles"][:int(stg["n_active"][0])]
+    act_o = o.state()["active_handles"][:int(o.state()["n_active"][0])]
+    assert g.append(orc.SEQ_BRANCH, None, None, k[act], v[act]) == orc.OK
+    assert shadow.append(orc.SEQ_BRANCH, None, None, None, None) == orc.OK
+    assert o.append(orc.SEQ_BRANCH, None, None, k[act_o], v[act_o]) == orc.OK
+    compare("after a step's append")
     if cfg_id == 5:  # prune to 16 branches by score, then decode again
         sc = wl.scores(cfg, 0)
-        assert g.prune(orc.KEEP_TOP_K, sc, k=16) == orc.OK and o.prune(orc.KEEP_TOP_K, sc, k=16) == orc.OK
-        assert_state_equal({k: v for k, v in o.state().items() if k in ("active_handles", "seq_lens", "branch_state", "req_counters")},
-                           {k: v for k, v in g.state().items() if k in ("active_handles", "seq_lens", "branch_state", "req_counters")})
-        compare("after prune")
+        for e in (g, o, shadow):
+            assert e.prune(orc.KEEP_TOP_K, sc, k=16) == orc.OK
+        assert int(g.state()["n_active"][0]) == 16
+        check_invariants(g.state(), pt=16, num_pages=num_pages, Nb=cfg.nb, max_req=cfg.n_requests)
+        compare("after keeping the top 16")
 
 
 # ---------------------------------------------------------------------------

@@ -180,3 +180,43 @@ def test_argument_errors_change_nothing():
     # a prefix append after a branch append of the same request is refused
     assert o.append(orc.SEQ_PREFIX, [0], [1], one[:1], one[:1]) == orc.E_STATE
     assert_state_equal(s0, o.state())
+
+
+def test_integer_state_does_not_depend_on_the_head_geometry():
+    """The same call sequence on caches that differ only in heads, head size and element type leaves the same
+    integer state (the full-size GPU parity tests compare against a one-head, 8-element oracle cache)."""
+    rng = np.random.default_rng(91)
+    R, Nb, pt, num_pages = 4, 4, 4, 160
+    fo = rng.permutation(num_pages).astype(np.int32)
+    geoms = [dict(Hq=2, Hkv=1, d=8, dtype="f32"), dict(Hq=12, Hkv=3, d=32, dtype="bf16")]
+    caches = [make_oracle(pt=pt, num_pages=num_pages, max_req=R, Nb=Nb, Q=2, max_bp=16, max_pp=4, free_order=fo, **gm)
+              for gm in geoms]
+
+    def kv(n, gm):
+        return np.zeros((n, gm["Hkv"], gm["d"]), np.float32 if gm["dtype"] == "f32" else np.uint16)
+
+    def all_do(fn):
+        rcs = [fn(c, gm) for c, gm in zip(caches, geoms)]
+        assert rcs[0] == rcs[1]
+        assert_state_equal(caches[0].state(), caches[1].state())
+        return rcs[0]
+
+    for r in range(R):
+        all_do(lambda c, gm: c.append(orc.SEQ_PREFIX, [r], [5 + r], kv(5 + r, gm), kv(5 + r, gm)))
+    for _ in range(40):
+        st = caches[0].state()
+        nA = int(st["n_active"][0])
+        if nA == 0:
+            break
+        op = int(rng.integers(0, 4))
+        if op <= 1:
+            n = rng.integers(0, 7, size=nA)
+            all_do(lambda c, gm: c.append(orc.SEQ_BRANCH, None, n, kv(int(n.sum()), gm), kv(int(n.sum()), gm)))
+        elif op == 2:
+            sc = rng.random(nA).astype(np.float32)
+            mode, k = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+            th, mp = rng.random(R).astype(np.float32), rng.integers(0, Nb, size=R)
+            all_do(lambda c, gm: c.prune(mode, sc, k=k, threshold=th, max_pruned=mp))
+        else:
+            hs = rng.choice(st["active_handles"][:nA], size=1)
+            all_do(lambda c, gm: c.finish(hs))
