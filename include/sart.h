@@ -210,6 +210,27 @@ sart_status sart_decode_attention(sart_cache* cache, int32_t layer,
                                   const void* q, float* out, int32_t n_rows,
                                   float scale, void* stream);
 
+/* sart_decode_attention for callers that must not allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid device allocation.  Same
+ * arguments, same result (bit for bit) and same errors as sart_decode_attention,
+ * but the kernels' scratch (the partial results that the merge combines) is a
+ * fixed array of SART_STATIC_SCRATCH_BYTES inside the library's device image
+ * instead of memory the cache allocated: the call allocates and frees nothing.
+ * Each GPU the library runs on holds that array until the process ends.
+ * Limits: the cache's device must be current; the LDS-staged prompt mode is not
+ * run (SART_E_INVALID); and n_rows (counted up to max_requests * Nb) must be
+ * small enough that the largest step it admits fits the array,
+ *   W + S + max(S, 4 W) <= SART_STATIC_SCRATCH_BYTES / (4 * (G*d + pad4(2G)))
+ * with W = 4 * workgroups of the decode launch (1024 by default) and
+ * S = n_rows * Hkv; otherwise SART_E_INVALID and nothing is enqueued (configs 2
+ * and 4 of the paper-like workloads need 5632 and 7168 of 9198 and 12865).
+ * All calls on one GPU share the array, whatever their cache or stream: calls
+ * that overlap in time on one GPU race; the caller orders them. */
+#define SART_STATIC_SCRATCH_BYTES (32u << 20)
+sart_status sart_decode_attention_static(sart_cache* cache, int32_t layer,
+                                         const void* q, float* out, int32_t n_rows,
+                                         float scale, void* stream);
+
 /* Prefill attention (Algorithm 1, Prefill; Section 4 takes the prefill phase
  * from plain LLM inference): causal self-attention over prompts already in the
  * cache.  For each listed request the queries are its LAST n_q[i] prompt tokens:

@@ -57,6 +57,8 @@ _SIGNATURES = {
                                      C.c_int32, C.c_void_p]),
     "sart_decode_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float,
                                         C.c_void_p]),
+    "sart_decode_attention_static": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_float,
+                                               C.c_void_p]),
     "sart_prefill_attention": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, _ip, _ip, C.c_void_p, C.c_void_p, C.c_float,
                                          C.c_void_p]),
     "sart_prune_branches": (C.c_int, [C.c_void_p, C.POINTER(_Policy), C.c_void_p, C.c_int32, C.c_void_p]),
@@ -204,15 +206,18 @@ class SartCache:
         self._check(rc)
         return OK
 
-    def decode_attention(self, q, out=None, scale=0.0, stream=None, layer=0):
-        """sart_decode_attention.  q: [n_rows, Hq, d]; returns out [n_rows, Hq, d] float32 (device)."""
+    def decode_attention(self, q, out=None, scale=0.0, stream=None, layer=0, static_scratch=False):
+        """sart_decode_attention (static_scratch: sart_decode_attention_static, which needs `out` from the
+        caller since it allocates nothing).  q: [n_rows, Hq, d]; returns out [n_rows, Hq, d] float32 (device)."""
         import torch
         q = self._dev(q, (self.Hq, self.d))
         if out is None:
+            assert not static_scratch
             out = torch.zeros((q.shape[0], self.Hq, self.d), dtype=torch.float32, device=q.device)
         assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
-        self._check(self.lib.sart_decode_attention(self.h, int(layer), C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()),
-                                                   q.shape[0], float(scale), _stream_handle(stream)))
+        fn = self.lib.sart_decode_attention_static if static_scratch else self.lib.sart_decode_attention
+        self._check(fn(self.h, int(layer), C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()), q.shape[0], float(scale),
+                       _stream_handle(stream)))
         return out
 
     def prefill_attention(self, request_ids, n_q, q, out=None, scale=0.0, stream=None, status=False, layer=0):

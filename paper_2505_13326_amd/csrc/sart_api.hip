@@ -380,12 +380,9 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
   return SART_OK;
 }
 
-sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows,
-                                  float scale, void* stream) {
-  if (!c) return fail(SART_E_INVALID, "null cache");
-  if (layer < 0 || layer >= c->desc.n_layers) return fail(SART_E_INVALID, "layer out of range");
-  if (n_rows < 0) return fail(SART_E_INVALID, "negative n_rows");
-  if (n_rows > 0 && (!q || !out)) return fail(SART_E_INVALID, "null q or out");
+// Shared by the two decode entry points: `partials` / `partial_cap` name the scratch the kernels use.
+static sart_status decode_common(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows, float scale,
+                                 void* stream, float* partials, long long partial_cap, bool profile) {
   const Dims& dm = c->ctx.dm;
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)dm.d);
   hipStream_t st = (hipStream_t)stream;
@@ -396,14 +393,53 @@ sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, f
   a.v_scale = c->v_scale;
   a.n_wg = c->plan.n_wg;
   a.inline_prefix = c->plan.inline_prefix;
-  a.partials = c->partials; a.partial_cap = c->partial_cap;
+  a.partials = partials; a.partial_cap = partial_cap;
   a.call_seq = ++c->call_seq;
-  for (int i = 0; i < 4; ++i) a.ev[i] = c->profiling ? c->ev[i] : nullptr;
-  a.repeats = c->profiling;
+  for (int i = 0; i < 4; ++i) a.ev[i] = profile && c->profiling ? c->ev[i] : nullptr;
+  a.repeats = profile ? c->profiling : 0;
   launch_decode(layer_ctx(c, layer), a, st);
-  c->ev_valid = c->profiling > 0;
+  if (profile) c->ev_valid = c->profiling > 0;
   HIP_TRY(hipGetLastError());
   return SART_OK;
+}
+
+static sart_status check_decode_args(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (layer < 0 || layer >= c->desc.n_layers) return fail(SART_E_INVALID, "layer out of range");
+  if (n_rows < 0) return fail(SART_E_INVALID, "negative n_rows");
+  if (n_rows > 0 && (!q || !out)) return fail(SART_E_INVALID, "null q or out");
+  return SART_OK;
+}
+
+sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows,
+                                  float scale, void* stream) {
+  sart_status rc = check_decode_args(c, layer, q, out, n_rows);
+  if (rc != SART_OK) return rc;
+  return decode_common(c, layer, q, out, n_rows, scale, stream, c->partials, c->partial_cap, true);
+}
+
+sart_status sart_decode_attention_static(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows,
+                                         float scale, void* stream) {
+  sart_status rc = check_decode_args(c, layer, q, out, n_rows);
+  if (rc != SART_OK) return rc;
+  const Dims& dm = c->ctx.dm;
+  if (c->plan.inline_prefix == 0)
+    return fail(SART_E_INVALID, "sart_decode_attention_static does not run the LDS-staged prompt mode");
+  // the current device's copy of the scratch array (looked up once per device)
+  int dev = -1;
+  void* scratch_ptr = nullptr;
+  HIP_TRY(static_scratch(&dev, &scratch_ptr));
+  if (dev != c->device) return fail(SART_E_INVALID, "the cache lives on device %d but device %d is current", c->device, dev);
+  // what a step over n_rows rows can need at most (see refresh_decode_plan): own pieces, then prompt blocks
+  const long long pf_bytes = partial_floats(dm.G, dm.d) * (long long)sizeof(float);
+  const long long cap = (long long)kStaticScratchBytes / pf_bytes;
+  const long long rows = n_rows < dm.H ? n_rows : dm.H, S = rows * dm.Hkv, waves = (long long)c->plan.n_wg * kAttnWaves;
+  const long long need = waves + S + (S > 4 * waves ? S : 4 * waves);
+  if (need > cap)
+    return fail(SART_E_INVALID, "n_rows %d with %d kv heads and %d workgroups may need %lld partial results of %lld bytes: "
+                "more than the static scratch of %zu bytes holds (%lld)", n_rows, dm.Hkv, c->plan.n_wg, need, pf_bytes,
+                (size_t)kStaticScratchBytes, cap);
+  return decode_common(c, layer, q, out, n_rows, scale, stream, (float*)scratch_ptr, cap, false);
 }
 
 sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs, const int32_t* request_ids,

@@ -26,12 +26,18 @@
 //     neighbours in time and on one XCD and hit in its L2 (default).  Other
 //     modes: one block per (chunk, branch); or each prompt chunk staged in LDS
 //     once per workgroup for the request's branches, one wave each.
+#include <mutex>
+
 #include "sart_attn_tile.h"
 
 namespace sart {
 
-// floats of one partial: o[G][d], then m[G], l[G], padded to a 16-byte multiple
-__host__ __device__ inline long long partial_floats(int G, int d) { return (long long)G * d + ((2 * G + 3) & ~3); }
+// partial slots the current plan writes: own pieces (one per range and per (row, kv head) it crosses),
+// then the prompts' blocks (inline modes) or LDS-staged chunks
+__device__ inline long long slots_needed(const int* scal, int Hkv, int inline_prefix) {
+  const long long S = (long long)scal[S_D_NA] * Hkv;
+  return (long long)scal[S_D_NOWN] + S + (inline_prefix ? (long long)scal[S_D_NBLOCKS] : S * scal[S_D_NPC]);
+}
 
 template <int D>
 __device__ inline void load_q(uint4* qreg, const uint16_t* q, const Dims& dm, int row, int head) {
@@ -94,8 +100,9 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
 
   const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nA = scal[S_D_NA];
-  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != (int)gridDim.x) {
-    // a row buffer smaller than the active list, or a launch that does not match the plan
+  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != (int)gridDim.x || slots_needed(scal, dm.Hkv, a.inline_prefix) > a.partial_cap) {
+    // a row buffer smaller than the active list, a launch that does not match the plan, or a scratch
+    // buffer too small for the plan's partial results
     if (blockIdx.x == 0 && threadIdx.x == 0) record_error(scal, SART_E_INVALID, a.call_seq);
     return;
   }
@@ -397,7 +404,7 @@ k_attn_generic(Ctx c, DecodeArgs a) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
-  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != (int)gridDim.x) {
+  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != (int)gridDim.x || slots_needed(scal, dm.Hkv, 1) > a.partial_cap) {
     if (blockIdx.x == 0 && threadIdx.x == 0) record_error(scal, SART_E_INVALID, a.call_seq);
     return;
   }
@@ -493,7 +500,7 @@ k_merge(Ctx c, DecodeArgs a, int inline_prefix) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   const int* scal = tb.scal;
-  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != a.n_wg) return;
+  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != a.n_wg || slots_needed(scal, dm.Hkv, inline_prefix) > a.partial_cap) return;
   const int nA = scal[S_D_NA];
   const int chunk = scal[S_D_CHUNK], npc = scal[S_D_NPC];
   const Cut cut = load_cut(scal);
@@ -578,6 +585,41 @@ void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s) {
   if (blocks > 8192) blocks = 8192;
   hipLaunchKernelGGL(k_merge, dim3((unsigned)blocks), dim3(256), 0, s, c, a, a.inline_prefix);
   if (a.ev[3]) (void)hipEventRecord(a.ev[3], s);
+}
+
+
+// ---------------------------------------------------------------------------
+// Scratch of sart_decode_attention_static: the partial results live in this
+// array instead of the cache's own allocation.  Every GPU the library runs on
+// holds its own copy at its own address (until the process ends); the array's
+// name is only a host-side stand-in, so host code asks the runtime once per
+// device, with that device current, where the copy is and uses that address
+// from then on.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+hipError_t static_scratch(int* device, void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));     // the current device's copy
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *device = dev;
+  *ptr = g_scratch_ptr[dev];
+  return hipSuccess;
 }
 
 }  // namespace sart

@@ -192,30 +192,39 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   __syncthreads();                       // live_req, req_first, page_cum, req_pstart written
   int n_items = 0;
   if (pc.inline_prefix) {
-    // first prompt block of every live request
-    // (partial slots) and first work item of every live request
+    // first prompt block (partial slot) and first work item of every live request.  The blocks are the
+    // prompts' partial results, one slot each: should there be more than max(4 per wave, one per (row, kv
+    // head)), the block size is doubled until they fit (one block per prompt at the latest), so that
+    //   n_own + nA * Hkv + max(nA * Hkv, 4 * n_waves)
+    // partial slots always hold a decode step (what callers with a fixed scratch size rely on).
+    const long long max_blocks = (long long)nA * dm.Hkv > 4LL * n_waves ? (long long)nA * dm.Hkv : 4LL * n_waves;
     int b_carry = 0, i_carry = 0;
-    for (int base = 0; base < n_live; base += kPlanThreads) {
-      const int k = base + tid;
-      int blocks = 0, items = 0, r = 0;
-      if (k < n_live) {
-        const bool in_lds = k < kPlanLdsLive;
-        r = in_lds ? s_lreq[k] : tb.live_req[k];
-        const int plen = in_lds ? s_lplen[k] : tb.prefix_len[r], cnt = in_lds ? s_lcnt[k] : tb.refcnt[r];
-        const int nck = ceil_div(ceil_div(plen, dm.pt), cut.pb);
-        blocks = dm.Hkv * nck * cnt;
-        items = pc.inline_prefix == 2 ? dm.Hkv * nck * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : blocks;
+    for (;;) {
+      b_carry = 0; i_carry = 0;
+      for (int base = 0; base < n_live; base += kPlanThreads) {
+        const int k = base + tid;
+        int blocks = 0, items = 0, r = 0;
+        if (k < n_live) {
+          const bool in_lds = k < kPlanLdsLive;
+          r = in_lds ? s_lreq[k] : tb.live_req[k];
+          const int plen = in_lds ? s_lplen[k] : tb.prefix_len[r], cnt = in_lds ? s_lcnt[k] : tb.refcnt[r];
+          const int nck = ceil_div(ceil_div(plen, dm.pt), cut.pb);
+          blocks = dm.Hkv * nck * cnt;
+          items = pc.inline_prefix == 2 ? dm.Hkv * nck * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : blocks;
+        }
+        int ex3[3], tot3[3];
+        block_excl_scan3(blocks, items, 0, s_scan, ex3, tot3);
+        const int ex = ex3[0], ex_i = ex3[1], tot = tot3[0], tot_i = tot3[1];
+        if (k < n_live) {
+          tb.live_item_start[k] = i_carry + ex_i;
+          tb.req_pstart[r] = b_carry + ex;
+          if (k < kPlanLdsLive) { s_item[k] = i_carry + ex_i; s_lpstart[k] = b_carry + ex; }
+        }
+        b_carry += tot;
+        i_carry += tot_i;
       }
-      int ex3[3], tot3[3];
-      block_excl_scan3(blocks, items, 0, s_scan, ex3, tot3);
-      const int ex = ex3[0], ex_i = ex3[1], tot = tot3[0], tot_i = tot3[1];
-      if (k < n_live) {
-        tb.live_item_start[k] = i_carry + ex_i;
-        tb.req_pstart[r] = b_carry + ex;
-        if (k < kPlanLdsLive) { s_item[k] = i_carry + ex_i; s_lpstart[k] = b_carry + ex; }
-      }
-      b_carry += tot;
-      i_carry += tot_i;
+      if (b_carry <= max_blocks || cut.pb >= dm.max_pp) break;     // uniform: the scans' totals
+      cut.pb *= 2;
     }
     cut.n_blocks = b_carry;
     cut.n_pitems = i_carry;

@@ -238,6 +238,11 @@ struct DecodeArgs {
   int repeats;          // profiling: attention launches between ev[1] and ev[2]
 };
 void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s);
+// floats of one partial result: o[G][d], then m[G], l[G], padded to a 16-byte multiple
+__host__ __device__ inline long long partial_floats(int G, int d) { return (long long)G * d + ((2 * G + 3) & ~3); }
+// the fixed scratch of sart_decode_attention_static (bytes), and where the current device keeps it
+constexpr size_t kStaticScratchBytes = SART_STATIC_SCRATCH_BYTES;
+hipError_t static_scratch(int* device, void** ptr);
 
 struct PrefillArgs {
   int n_seqs;
