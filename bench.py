@@ -163,12 +163,44 @@ def bench_trace(args, cfg, sart, wl, np, torch):
                    "steps_with_active_branches": busy, "loop_s": round(dt, 4)}}), flush=True)
 
 
+def bench_probe_sweep(args, sart, np, torch):
+    """What plain reads reach on this machine: the read probe (8 KiB chunks of a 2 GiB buffer) over workgroups,
+    chunks in flight per wave, load flavour, chunk order and chunk-to-wave assignment.  One JSON line with
+    the whole table (GB/s), best first."""
+    nbytes = 1 << 31
+    probe = torch.ones(nbytes, dtype=torch.uint8, device="cuda")
+    shuffled = torch.randperm(nbytes // 8192, device="cuda", dtype=torch.int32,
+                              generator=torch.Generator(device="cuda").manual_seed(1))
+    rows = []
+    for order_name, od in (("sequential", None), ("shuffled", shuffled)):
+        for inter in (0, 1):
+            for flavour in (0, 1):
+                for depth in (1, 2, 4, 8):
+                    for wgs in (256, 512, 1024, 2048, 4096):
+                        shape = (wgs, depth, flavour, inter)
+                        for _ in range(2):
+                            sart.read_probe(probe, od, shape=shape)
+                        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                        ev[0].record()
+                        for _ in range(args.steps if args.steps < 50 else 8):
+                            sart.read_probe(probe, od, shape=shape)
+                        ev[1].record()
+                        torch.cuda.synchronize()
+                        n = args.steps if args.steps < 50 else 8
+                        rows.append({"order": order_name, "assignment": "interleaved" if inter else "contiguous",
+                                     "loads": "non-temporal" if flavour else "plain", "chunks_in_flight": depth,
+                                     "workgroups": wgs, "gbs": round(nbytes * n / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9, 1)})
+    rows.sort(key=lambda r: -r["gbs"])
+    print(json.dumps({"metric": "plain read rate, 2 GiB buffer in 8 KiB chunks", "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                      "best": rows[0], "table": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "copy", "prefill4", "prefill5"],
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "copy", "probe", "prefill4", "prefill5"],
                     help="copy = a plain 1 GiB device copy, the known-size kernel that calibrates the "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters; prefillN = prefill attention over the prompts "
                          "of config N")
@@ -216,6 +248,8 @@ def main():
         print(json.dumps({"metric": "device copy", "bytes_read": n, "bytes_written": n, "steps": args.steps,
                           "ms_per_step": round(dt * 1e3, 4), "value": round(2 * n / dt / 1e9, 1), "unit": "GB/s"}))
         return
+    if args.workload == "probe":
+        return bench_probe_sweep(args, sart, np, torch)
     cfg = wl.CONFIGS[int(args.workload[-1])]
     if args.prompt_len >= 0:
         cfg = wl.scaled(cfg, prompt_len=args.prompt_len)

@@ -32,6 +32,17 @@ sart_status sart_last_decode_ms(sart_cache* cache, float* ms_attn, float* ms_tot
  * against this one's on the same box. */
 sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_order, void* stream);
 
+/* The same probe with its launch shape given, for the sweep that looks for the
+ * best rate plain reads reach (bench.py --workload probe): n_workgroups of 256
+ * threads (4 waves; 256 workgroups = one wave per SIMD), depth = 8 KiB chunks in
+ * flight per wave (1, 2, 4 or 8), flavour 0 = plain loads, 1 = loads with the
+ * non-temporal hint, interleave 0 = a wave reads a contiguous run of chunks,
+ * 1 = wave w reads chunks w, w + waves, ... (neighbouring waves read
+ * neighbouring chunks at the same time).  sart_read_probe is the shape
+ * (2048, 4, plain, contiguous). */
+sart_status sart_read_probe_shaped(const void* buf, size_t bytes, const int32_t* chunk_order, int32_t n_workgroups,
+                                   int32_t depth, int32_t flavour, int32_t interleave, void* stream);
+
 /* Tuning knobs of the decode launch (defaults are chosen for MI355X):
  *   n_workgroups         persistent attention grid of 4-wave workgroups (<= 0:
  *                        one per CU);

@@ -71,6 +71,8 @@ _SIGNATURES = {
     "sart_last_decode_ms": (C.c_int, [C.c_void_p, _fp, _fp]),
     "sart_set_decode_launch": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "sart_read_probe": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+    "sart_read_probe_shaped": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                         C.c_void_p]),
     "sart_last_error": (C.c_char_p, []),
 }
 
@@ -98,11 +100,16 @@ def load_library():
     return _lib
 
 
-def read_probe(buf, chunk_order=None, stream=None):
-    """sart_read_probe over a torch device tensor (measurement aid)."""
+def read_probe(buf, chunk_order=None, stream=None, shape=None):
+    """sart_read_probe over a torch device tensor (measurement aid).  shape: (workgroups, depth, flavour,
+    interleave) of sart_read_probe_shaped, or None for the default probe."""
     lib = load_library()
-    rc = lib.sart_read_probe(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
-                             None if chunk_order is None else C.c_void_p(chunk_order.data_ptr()), _stream_handle(stream))
+    order = None if chunk_order is None else C.c_void_p(chunk_order.data_ptr())
+    if shape is None:
+        rc = lib.sart_read_probe(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), order, _stream_handle(stream))
+    else:
+        rc = lib.sart_read_probe_shaped(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), order,
+                                        *[int(x) for x in shape], _stream_handle(stream))
     if rc != OK:
         raise SartError(rc, lib.sart_last_error().decode())
 

@@ -649,8 +649,17 @@ sart_status sart_device_views(sart_cache* c, const int32_t** active_handles, con
 }
 
 sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_order, void* stream) {
+  return sart_read_probe_shaped(buf, bytes, chunk_order, 2048, 4, 0, 0, stream);
+}
+
+sart_status sart_read_probe_shaped(const void* buf, size_t bytes, const int32_t* chunk_order, int32_t n_workgroups,
+                                   int32_t depth, int32_t flavour, int32_t interleave, void* stream) {
   if (!buf || bytes < 8192) return fail(SART_E_INVALID, "the probe needs a device buffer of at least 8 KiB");
-  launch_read_probe(buf, (long long)(bytes / 8192), chunk_order, (hipStream_t)stream);
+  if (n_workgroups < 1 || n_workgroups > 65536) return fail(SART_E_INVALID, "probe workgroups out of range");
+  if (depth != 1 && depth != 2 && depth != 4 && depth != 8) return fail(SART_E_INVALID, "probe depth must be 1, 2, 4 or 8");
+  if (flavour < 0 || flavour > 1) return fail(SART_E_INVALID, "probe flavour must be 0 (plain) or 1 (non-temporal)");
+  launch_read_probe(buf, (long long)(bytes / 8192), chunk_order, n_workgroups, depth, flavour, interleave != 0,
+                    (hipStream_t)stream);
   HIP_TRY(hipGetLastError());
   return SART_OK;
 }

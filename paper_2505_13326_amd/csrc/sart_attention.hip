@@ -27,6 +27,7 @@
 //     modes: one block per (chunk, branch); or each prompt chunk staged in LDS
 //     once per workgroup for the request's branches, one wave each.
 #include <mutex>
+#include <type_traits>
 
 #include "sart_attn_tile.h"
 
@@ -215,14 +216,22 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
     // vmcnt(8*kRing-1 ...)) while the newer pages are still in flight; page ids
     // are wave-uniform scalar reads of the table.  full(k, v): a page of 16
     // valid tokens; part(k, v, nv): a page that may hold fewer (the last one).
-    auto stream_pages = [&](const int* __restrict__ table, int r0, int rn, int n_last, int h, auto&& full, auto&& part) {
+    // once: a branch's own pages are read once per step, so their loads carry the non-temporal hint (measured
+    // on plain reads of 8 KiB chunks: 6.7 against 6.0 TB/s); prompt pages are read again by the request's
+    // other row tiles and stay ordinary loads that the L2 keeps.
+    auto stream_pages = [&](auto once, const int* __restrict__ table, int r0, int rn, int n_last, int h, auto&& full, auto&& part) {
       const long long head_off = (long long)h * kPageBytes + lane * 16;
       auto load_page = [&](uint4* kq, uint4* vq, int pid) {
         const unsigned char* base = pool + (long long)pid * page_bytes + head_off;
 #pragma unroll
         for (int i = 0; i < KR; ++i) {
-          kq[i] = *(const uint4*)(base + i * 1024);
-          vq[i] = *(const uint4*)(base + kTileBytes + i * 1024);
+          if constexpr (decltype(once)::value) {
+            kq[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4*)(base + i * 1024)));
+            vq[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4*)(base + kTileBytes + i * 1024)));
+          } else {
+            kq[i] = *(const uint4*)(base + i * 1024);
+            vq[i] = *(const uint4*)(base + kTileBytes + i * 1024);
+          }
         }
       };
       uint4 kb[kRing][KR], vb[kRing][KR];
@@ -300,7 +309,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
           for (int i = 0; i < KQ; ++i) qb[b][i] = *(const uint4*)(qrow + i * 32 + g4 * 8);
           sb[b].reset();
         }
-        stream_pages(prefix_table + (long long)r * dm.max_pp, r0, rn, n_last, h,
+        stream_pages(std::false_type{}, prefix_table + (long long)r * dm.max_pp, r0, rn, n_last, h,
                      [&](const uint4* kq, const uint4* vq) {
 #pragma unroll
                        for (int b = 0; b < kSharedBlocks; ++b)
@@ -382,9 +391,10 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         }
         load_q<D>(qreg, q, dm, row, h);
         st.reset();
-        stream_pages(table, r0, rn, n_last, h,
-                     [&](const uint4* kq, const uint4* vq) { process_raw<D, FP8, true>(st, kq, vq, qreg, 16, 16, a.scale_log2); },
-                     [&](const uint4* kq, const uint4* vq, int nv) { process_raw<D, FP8, false>(st, kq, vq, qreg, nv, nv, a.scale_log2); });
+        auto full = [&](const uint4* kq, const uint4* vq) { process_raw<D, FP8, true>(st, kq, vq, qreg, 16, 16, a.scale_log2); };
+        auto part = [&](const uint4* kq, const uint4* vq, int nv) { process_raw<D, FP8, false>(st, kq, vq, qreg, nv, nv, a.scale_log2); };
+        if (line == 0) stream_pages(std::true_type{}, table, r0, rn, n_last, h, full, part);
+        else stream_pages(std::false_type{}, table, r0, rn, n_last, h, full, part);
         store_partial<D>(st, a.partials, slot, dm);
         u += line == 0 ? rn : cut.n_prompt;
       }

@@ -261,6 +261,7 @@ struct PrefillArgs {
 void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s);
 
 void launch_init_tables(const Ctx& c, const int* free_order_dev, hipStream_t s);
-void launch_read_probe(const void* buf, long long n_chunks, const int* order, hipStream_t s);
+void launch_read_probe(const void* buf, long long n_chunks, const int* order, int n_workgroups, int depth, int flavour,
+                       int interleave, hipStream_t s);
 
 }  // namespace sart
