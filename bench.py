@@ -217,6 +217,9 @@ def main():
                     "(E4M3; bf16 crosses the boundary): half the bytes per cached token")
     ap.add_argument("--layers", type=int, default=1, help="layers sharing the tables; a step appends to and attends over "
                     "every layer (same values in every layer)")
+    ap.add_argument("--merge", default="kernel", choices=["in-kernel", "kernel"], help="where a step's partial results "
+                    "are merged: by the separate merge kernel (default) or by the attention kernel's last writers")
+    ap.add_argument("--no-stagger", action="store_true", help="every wave serves its prompt work before its own range")
     ap.add_argument("--graph", action="store_true", help="replay the step (append + attention) from a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
@@ -269,6 +272,10 @@ def main():
                            branches_per_request=cfg.nb, finish_quota=cfg.quota, max_pages_per_branch=max_bp,
                            max_prefix_pages=max(1, cfg.prompt_len // cfg.page_tokens),
                            dtype="fp8" if args.kv_dtype == "fp8" else cfg.dtype, free_order=fo, n_layers=NL)
+    if args.merge == "in-kernel":
+        cache.set_merge_mode(True)
+    if args.no_stagger:
+        cache.set_prompt_stagger(False)
     if args.workgroups or args.chunk_pages or args.prompt_mode >= 0 or args.skew is not None or args.prompt_workgroups >= 0:
         cache.set_decode_launch(args.workgroups, args.prompt_workgroups, args.chunk_pages, args.prompt_mode,
                                 sart.DEFAULT_SKEW_PERMILLE if args.skew is None else args.skew)

@@ -220,10 +220,10 @@ sart_status sart_decode_attention(sart_cache* cache, int32_t layer,
  * Limits: the cache's device must be current; the LDS-staged prompt mode is not
  * run (SART_E_INVALID); and n_rows (counted up to max_requests * Nb) must be
  * small enough that the largest step it admits fits the array,
- *   W + S + max(S, 4 W) <= SART_STATIC_SCRATCH_BYTES / (4 * (G*d + pad4(2G)))
- * with W = 4 * workgroups of the decode launch (1024 by default) and
- * S = n_rows * Hkv; otherwise SART_E_INVALID and nothing is enqueued (configs 2
- * and 4 of the paper-like workloads need 5632 and 7168 of 9198 and 12865).
+ *   W + S + max(S, 4 W) <= (SART_STATIC_SCRATCH_BYTES - 256 KiB) / (4 * (G*d + pad4(2G)))
+ * and S <= 65536, with W = 4 * workgroups of the decode launch (1024 by default)
+ * and S = n_rows * Hkv; otherwise SART_E_INVALID and nothing is enqueued (configs
+ * 2 and 4 of the paper-like workloads need 5632 and 7168 of 9126 and 12765).
  * All calls on one GPU share the array, whatever their cache or stream: calls
  * that overlap in time on one GPU race; the caller orders them. */
 #define SART_STATIC_SCRATCH_BYTES (32u << 20)

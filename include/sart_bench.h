@@ -75,6 +75,23 @@ sart_status sart_set_decode_launch(sart_cache* cache, int32_t n_workgroups,
                                    int32_t n_prompt_workgroups, int32_t prefix_chunk_pages,
                                    int32_t prompt_mode, int32_t skew_permille);
 
+/* Order of a wave's two parts in the matrix-core attention kernel, its share of
+ * the prompts and its range of the branches' own pages.  on != 0 (default):
+ * groups of 8 workgroups alternate, prompts first / own range first, so that at
+ * any time half of the waves at most are in the latency-bound prompt part;
+ * 0: every wave serves its prompt work first. */
+sart_status sart_set_prompt_stagger(sart_cache* cache, int32_t on);
+
+/* Where the partial results of a decode step are merged: in_kernel = 0 (the
+ * default): by the separate merge kernel; != 0: by the attention kernel's own
+ * last writers where the kernel can (the matrix-core kernel with the prompts
+ * read inline): every piece counts itself in for its (row, kv head) and the
+ * last one folds.  Same results bit for bit.  Measured on MI355X the in-kernel
+ * form is the slower one (7B-like config: call 0.2595 against 0.2547 ms;
+ * 32B-like: 1.656 against 1.611 ms): each piece waits for its stores and for the
+ * counter's round trip while no other wave can use its SIMD. */
+sart_status sart_set_merge_mode(sart_cache* cache, int32_t in_kernel);
+
 #ifdef __cplusplus
 }
 #endif

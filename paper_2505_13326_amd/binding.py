@@ -70,6 +70,8 @@ _SIGNATURES = {
     "sart_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_last_decode_ms": (C.c_int, [C.c_void_p, _fp, _fp]),
     "sart_set_decode_launch": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "sart_set_merge_mode": (C.c_int, [C.c_void_p, C.c_int32]),
+    "sart_set_prompt_stagger": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_read_probe": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "sart_read_probe_shaped": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_void_p]),
@@ -325,6 +327,12 @@ class SartCache:
     # -- measurement / tuning -------------------------------------------------
     def set_profiling(self, repeats: int):
         self._check(self.lib.sart_set_profiling(self.h, int(repeats)))
+
+    def set_prompt_stagger(self, on: bool):
+        self._check(self.lib.sart_set_prompt_stagger(self.h, 1 if on else 0))
+
+    def set_merge_mode(self, in_kernel: bool):
+        self._check(self.lib.sart_set_merge_mode(self.h, 1 if in_kernel else 0))
 
     def last_decode_ms(self):
         a, t = C.c_float(0), C.c_float(0)

@@ -64,6 +64,8 @@ struct sart_cache {
   float* partials = nullptr;
   long long partial_cap = 0;
   PlanCfg plan{0, 0, 0, 0, 0};         // launch shape of the decode plan
+  int stagger_prompt = 1;              // see sart_set_prompt_stagger
+  int merge_mode = 0;                  // 1: merged inside the attention kernel where it can be, 0: by the merge kernel (faster, measured)
   int max_wg = 0;
   int profiling = 0;                   // 0 off, n >= 1: events around n attention launches
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -237,6 +239,9 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   ALLOC(tb.wave_row, (size_t)2 * c->max_wg * kAttnWaves);
   ALLOC(tb.req_pstart, R);
   ALLOC(tb.wave_desc, (size_t)16 * c->max_wg * kAttnWaves);
+  ALLOC(tb.row_desc, 8 * H);
+  ALLOC(tb.seg_count, H * dm.Hkv);
+  HIP_TRY(hipMemset(tb.seg_count, 0, H * dm.Hkv * sizeof(int)));
   // partial slots: one per private wave, one per (row, kv head) crossing, and
   // the prompt chunks of every (row, kv head) at the smallest chunk size
   const long long S = (long long)H * dm.Hkv;
@@ -382,7 +387,7 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
 
 // Shared by the two decode entry points: `partials` / `partial_cap` name the scratch the kernels use.
 static sart_status decode_common(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows, float scale,
-                                 void* stream, float* partials, long long partial_cap, bool profile) {
+                                 void* stream, float* partials, long long partial_cap, int* seg_count, bool profile) {
   const Dims& dm = c->ctx.dm;
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)dm.d);
   hipStream_t st = (hipStream_t)stream;
@@ -393,7 +398,9 @@ static sart_status decode_common(sart_cache* c, int32_t layer, const void* q, fl
   a.v_scale = c->v_scale;
   a.n_wg = c->plan.n_wg;
   a.inline_prefix = c->plan.inline_prefix;
-  a.partials = partials; a.partial_cap = partial_cap;
+  a.partials = partials; a.partial_cap = partial_cap; a.seg_count = seg_count;
+  a.fused_merge = c->merge_mode;
+  a.stagger_prompt = c->stagger_prompt;
   a.call_seq = ++c->call_seq;
   for (int i = 0; i < 4; ++i) a.ev[i] = profile && c->profiling ? c->ev[i] : nullptr;
   a.repeats = profile ? c->profiling : 0;
@@ -415,7 +422,7 @@ sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, f
                                   float scale, void* stream) {
   sart_status rc = check_decode_args(c, layer, q, out, n_rows);
   if (rc != SART_OK) return rc;
-  return decode_common(c, layer, q, out, n_rows, scale, stream, c->partials, c->partial_cap, true);
+  return decode_common(c, layer, q, out, n_rows, scale, stream, c->partials, c->partial_cap, c->ctx.tb.seg_count, true);
 }
 
 sart_status sart_decode_attention_static(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows,
@@ -430,16 +437,19 @@ sart_status sart_decode_attention_static(sart_cache* c, int32_t layer, const voi
   void* scratch_ptr = nullptr;
   HIP_TRY(static_scratch(&dev, &scratch_ptr));
   if (dev != c->device) return fail(SART_E_INVALID, "the cache lives on device %d but device %d is current", c->device, dev);
-  // what a step over n_rows rows can need at most (see refresh_decode_plan): own pieces, then prompt blocks
+  // The array holds the merge's arrival counters (one int per (row, kv head), zero between kernels: the
+  // image starts zeroed and every kernel leaves them so), then the partial results.  What a step over
+  // n_rows rows can need at most (see refresh_decode_plan): own pieces, then prompt blocks.
   const long long pf_bytes = partial_floats(dm.G, dm.d) * (long long)sizeof(float);
-  const long long cap = (long long)kStaticScratchBytes / pf_bytes;
+  const long long cap = (long long)(kStaticScratchBytes - kStaticCounterBytes) / pf_bytes;
   const long long rows = n_rows < dm.H ? n_rows : dm.H, S = rows * dm.Hkv, waves = (long long)c->plan.n_wg * kAttnWaves;
   const long long need = waves + S + (S > 4 * waves ? S : 4 * waves);
-  if (need > cap)
+  if (need > cap || S * (long long)sizeof(int) > (long long)kStaticCounterBytes)
     return fail(SART_E_INVALID, "n_rows %d with %d kv heads and %d workgroups may need %lld partial results of %lld bytes: "
-                "more than the static scratch of %zu bytes holds (%lld)", n_rows, dm.Hkv, c->plan.n_wg, need, pf_bytes,
-                (size_t)kStaticScratchBytes, cap);
-  return decode_common(c, layer, q, out, n_rows, scale, stream, (float*)scratch_ptr, cap, false);
+                "more than the static scratch of %zu bytes holds (%lld, and %zu (row, kv head) pairs)", n_rows, dm.Hkv,
+                c->plan.n_wg, need, pf_bytes, (size_t)kStaticScratchBytes, cap, (size_t)kStaticCounterBytes / sizeof(int));
+  return decode_common(c, layer, q, out, n_rows, scale, stream, (float*)((char*)scratch_ptr + kStaticCounterBytes), cap,
+                       (int*)scratch_ptr, false);
 }
 
 sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs, const int32_t* request_ids,
@@ -661,6 +671,18 @@ sart_status sart_read_probe_shaped(const void* buf, size_t bytes, const int32_t*
   launch_read_probe(buf, (long long)(bytes / 8192), chunk_order, n_workgroups, depth, flavour, interleave != 0,
                     (hipStream_t)stream);
   HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
+
+sart_status sart_set_prompt_stagger(sart_cache* c, int32_t on) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  c->stagger_prompt = on != 0;
+  return SART_OK;
+}
+
+sart_status sart_set_merge_mode(sart_cache* c, int32_t in_kernel) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  c->merge_mode = in_kernel != 0;
   return SART_OK;
 }
 

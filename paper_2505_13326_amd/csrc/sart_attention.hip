@@ -51,18 +51,155 @@ __device__ inline void load_q(uint4* qreg, const uint16_t* q, const Dims& dm, in
   }
 }
 
-template <int D>
+// Partial results that another wave of the same kernel reads back (the in-kernel merge) are written and
+// read with device-scope relaxed atomic accesses, one float each: such stores go through to memory and such
+// loads do not take a stale line of the reader's L2 (the 8 XCDs have one L2 each, not coherent with each
+// other for ordinary accesses), so no cache has to be written back or invalidated as a whole - a device-scope
+// fence does exactly that and, measured, costs about 25 us per piece (config 2 kernel 0.336 against 0.244 ms).
+// A partial result is a few KB per piece; the float-wise accesses do not show in the kernel's time.
+template <bool COHERENT>
+__device__ inline void put_f32x4(float* p, f32x4 v) {
+  if constexpr (COHERENT) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) __hip_atomic_store(p + k, v[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else {
+    *(f32x4*)p = v;
+  }
+}
+template <bool COHERENT>
+__device__ inline void put_f32(float* p, float v) {
+  if constexpr (COHERENT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+template <bool COHERENT>
+__device__ inline f32x4 get_f32x4(const float* p) {
+  if constexpr (COHERENT) {
+    f32x4 v;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = __hip_atomic_load(p + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return v;
+  } else {
+    return *(const f32x4*)p;
+  }
+}
+template <bool COHERENT>
+__device__ inline float get_f32(const float* p) {
+  if constexpr (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else return *p;
+}
+
+template <int D, bool COHERENT>
 __device__ inline void store_partial(const WaveState<D>& st, float* partials, long long slot, const Dims& dm) {
   const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
   const float l = sum_over_rows(st.l);
   if (r >= dm.G) return;
   float* base = partials + slot * partial_floats(dm.G, D);
 #pragma unroll
-  for (int b = 0; b < D / 16; ++b) *(f32x4*)(base + (long long)r * D + b * 16 + 4 * g) = st.o[b];
+  for (int b = 0; b < D / 16; ++b) put_f32x4<COHERENT>(base + (long long)r * D + b * 16 + 4 * g, st.o[b]);
   if (g == 0) {
-    base[(long long)dm.G * D + r] = st.m;
-    base[(long long)dm.G * D + dm.G + r] = l;
+    put_f32<COHERENT>(base + (long long)dm.G * D + r, st.m);
+    put_f32<COHERENT>(base + (long long)dm.G * D + dm.G + r, l);
   }
+}
+
+// ---------------------------------------------------------------------------
+// A6 inside the attention kernel.  Every piece (a wave's part of one (row, kv
+// head), or a prompt block) stores its partial result, then counts itself in
+// for that (row, kv head); the plan says how many writers there are, so the
+// writer that arrives last knows it is last and folds all the partial results
+// in slot order (prompt chunks, then own pieces: the order does not depend on
+// who arrived when, so the output is reproducible bit for bit) and writes the
+// output rows.  No wave ever waits for another.  The counter is back to zero
+// when the kernel ends.
+// ---------------------------------------------------------------------------
+struct RowInfo { int cum, pages, seq, prompt_writers, pslot, cnt, nck; };   // see refresh_decode_plan (row_desc)
+__device__ inline RowInfo load_row_info(const int* __restrict__ row_desc, int row) {
+  const int4 x = ((const int4*)(row_desc + 8LL * row))[0], y = ((const int4*)(row_desc + 8LL * row))[1];
+  return RowInfo{x.x, x.y, x.z, x.w, y.x, y.y, y.z};
+}
+// the own-line pieces of (row, kv head h): first range w0 and their number sn
+__device__ inline void own_pieces(const Cut& cut, int Hkv, const RowInfo& ri, int h, long long& w0, int& sn) {
+  w0 = 0; sn = 0;
+  if (ri.pages == 0) return;
+  const long long us = (long long)ri.cum * Hkv + (long long)h * ri.pages;
+  w0 = own_of_unit(cut, us);
+  sn = (int)(own_of_unit(cut, us + ri.pages - 1) - w0) + 1;
+}
+// Folds, for query head r of the group and output columns 4 d4 .. 4 d4 + 3, the partial results at slots
+// pa + i * pstride (i < pn: prompt pieces) and then sa + i (i < sn: own pieces) with the running form of
+//   m = max m_i,  l = sum l_i 2^(m_i - m),  out = sum o_i 2^(m_i - m) / l
+// and writes the four outputs.  The loads of successive partial results are independent, so they overlap.
+template <bool COHERENT>
+__device__ inline void fold_columns(const float* partials, float* __restrict__ out_row, long long pf, int G, int D,
+                                    int r, int d4, long long pa, long long pstride, int pn, long long sa, int sn, float v_scale) {
+  float m = -__builtin_inff(), l = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int i = 0; i < pn + sn; ++i) {
+    const long long slot = i < pn ? pa + i * pstride : sa + (i - pn);
+    const float* pb = partials + slot * pf;
+    const float mi = get_f32<COHERENT>(pb + (long long)G * D + r);
+    const float li = get_f32<COHERENT>(pb + (long long)G * D + G + r);
+    const f32x4 oi = get_f32x4<COHERENT>(pb + (long long)r * D + 4 * d4);
+    const float mn = fmaxf(m, mi);
+    const float ws = __builtin_amdgcn_exp2f(m - mn), wi = __builtin_amdgcn_exp2f(mi - mn);
+    l = l * ws + li * wi;
+    acc = acc * ws + oi * wi;
+    m = mn;
+  }
+  const float inv = l > 0.f ? 1.0f / l : 0.f;
+  *(f32x4*)(out_row + 4 * d4) = acc * (inv * v_scale);
+}
+// Counts this wave's piece in for its (row, kv head); true for the writer that completes it (all lanes alike).
+__device__ inline bool arrive_last(int* counter, int expected) {
+  // the wave's partial-result stores (device-scope, see above) have completed before it counts itself in
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);
+  int old = 0;
+  if ((threadIdx.x & 63) == 0) old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  old = __builtin_amdgcn_readfirstlane(old);
+  if (old != expected - 1) return false;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  if ((threadIdx.x & 63) == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return true;
+}
+// One wave folds (row, kv head h) and writes its G output rows.
+template <int D>
+__device__ inline void fold_segment(const DecodeArgs& a, const Dims& dm, long long prompt_slot_base, int row, int h,
+                                    const RowInfo& ri, long long w0, int sn) {
+  const int lane = threadIdx.x & 63;
+  constexpr int D4 = D / 4;
+  const long long pf = partial_floats(dm.G, D);
+  const long long sa = w0 + (long long)row * dm.Hkv + h;
+  const long long pa = prompt_slot_base + ri.pslot + (long long)h * ri.nck * ri.cnt;
+  for (int e = lane; e < dm.G * D4; e += 64) {
+    const int r = e / D4, d4 = e % D4;
+    fold_columns<true>(a.partials, a.out + ((long long)row * dm.Hq + h * dm.G + r) * D, pf, dm.G, D, r, d4, pa, ri.cnt, ri.nck, sa,
+                       sn, a.v_scale);
+  }
+}
+// End of a piece of (row, kv head h) whose state is st: the only piece writes the output rows itself; otherwise
+// the partial result goes to `slot` and the last writer merges.
+template <int D>
+__device__ inline void finish_piece(const DecodeArgs& a, const Dims& dm, const Cut& cut, long long prompt_slot_base,
+                                    const WaveState<D>& st, long long slot, int row, int h, const RowInfo& ri) {
+  long long w0;
+  int sn;
+  own_pieces(cut, dm.Hkv, ri, h, w0, sn);
+  const int expected = ri.prompt_writers + sn;
+  if (expected == 1) {
+    const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    const float l = sum_over_rows(st.l);
+    if (r >= dm.G) return;
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    float* orow = a.out + ((long long)row * dm.Hq + h * dm.G + r) * D;
+#pragma unroll
+    for (int b = 0; b < D / 16; ++b) *(f32x4*)(orow + b * 16 + 4 * g) = st.o[b] * (inv * a.v_scale);
+    return;
+  }
+  store_partial<D, true>(st, a.partials, slot, dm);
+  if (arrive_last(a.seg_count + ((long long)row * dm.Hkv + h), expected))
+    fold_segment<D>(a, dm, prompt_slot_base, row, h, ri, w0, sn);
 }
 
 // ---------------------------------------------------------------------------
@@ -85,7 +222,8 @@ __device__ inline void store_partial(const WaveState<D>& st, float* partials, lo
 template <int D, bool FP8>
 __global__ void __launch_bounds__(kAttnThreads)
 k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restrict__ bt1,
-            const int* __restrict__ item_desc, const int* __restrict__ prefix_table, const int* __restrict__ wave_desc) {
+            const int* __restrict__ item_desc, const int* __restrict__ prefix_table, const int* __restrict__ wave_desc,
+            const int* __restrict__ row_desc) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
@@ -195,7 +333,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
           __syncthreads();
         }
         if (have_row)
-          store_partial<D>(st, a.partials, prefix_base + ((long long)row * dm.Hkv + h) * npc + ck, dm);
+          store_partial<D, false>(st, a.partials, prefix_base + ((long long)row * dm.Hkv + h) * npc + ck, dm);
       }
       continue;
     }
@@ -266,137 +404,198 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
       }
     };
 
-    // ---- shared-rows prompt mode: a work item is (request, kv head, chunk of pb prompt pages, tile of up
-    //      to 16 * kSharedBlocks query rows); its pages are read once and every page feeds the tile's
-    //      blocks (rows = (branch, head of the group), branch-major).  One partial per (branch, kv head,
-    //      chunk), in the slots the per-branch blocks would have used. -------------------------------
-    if (a.inline_prefix == 2 && wave_id >= n_waves - cut.n_prompt) {
-      const int r16 = lane & 15, g4 = lane >> 4;
-      const long long pf = partial_floats(dm.G, D);
-      int cursor = wd3.z;
-      bool resolved = wd3.w != 0;                                  // the first item's request came with the descriptor
-      for (long long item = prompt_range_of_wave(wave_id - (n_waves - cut.n_prompt), cut.n_prompt); item < cut.n_pitems;
-           item += cut.n_prompt) {
-        int r = wd2.x, cnt = wd2.y, plen = wd2.z, first_row = wd2.w, pstart = wd3.x, istart = wd3.y;
-        if (!resolved) {                                           // rare: more items than waves
-          while (item >= tb.live_item_start[cursor + 1]) ++cursor; // the live request owning the item
-          r = tb.live_req[cursor];
-          cnt = tb.refcnt[r]; plen = tb.prefix_len[r]; first_row = tb.req_first[r]; pstart = tb.req_pstart[r];
-          istart = tb.live_item_start[cursor];
+    // One piece: pages [r0, r0 + rn) of `table` for the G query heads of (row, kv head h); its partial
+    // result goes to `slot` (or, merged, to the output).  `table` is passed down from a kernel argument in
+    // every call, so that the page ids stay scalar loads in each instance of the streaming loop.
+    auto run_piece = [&](auto once, const int* __restrict__ table, int row, int h, int r0, int rn, int n_last, long long slot,
+                         const RowInfo& ri) {
+      load_q<D>(qreg, q, dm, row, h);
+      st.reset();
+      stream_pages(once, table, r0, rn, n_last, h,
+                   [&](const uint4* kq, const uint4* vq) { process_raw<D, FP8, true>(st, kq, vq, qreg, 16, 16, a.scale_log2); },
+                   [&](const uint4* kq, const uint4* vq, int nv) { process_raw<D, FP8, false>(st, kq, vq, qreg, nv, nv, a.scale_log2); });
+      if (a.fused_merge) finish_piece<D>(a, dm, cut, prompt_slot_base, st, slot, row, h, ri);
+      else store_partial<D, false>(st, a.partials, slot, dm);
+    };
+
+    // The wave's prompt work and its own range are two parts; which comes first alternates between groups of 8
+    // workgroups (one per XCD): while one half of the waves is in its prompt part, which is bound by latency
+    // (a few pages, mostly L2 hits), the other half keeps HBM busy, and at the end of the kernel the same
+    // the other way round.  The waves of a workgroup take the same order, so the row tiles of a chunk, which
+    // they serve, still read it at the same time.
+    const bool prompt_part_first = !a.stagger_prompt || ((blockIdx.x >> 3) & 1) == 0;
+    for (int turn = 0; turn < 2; ++turn) {
+      if ((turn == 0) == prompt_part_first) {
+        // ---- shared-rows prompt mode: a work item is (request, kv head, chunk of pb prompt pages, tile of up
+        //      to 16 * kSharedBlocks query rows); its pages are read once and every page feeds the tile's
+        //      blocks (rows = (branch, head of the group), branch-major).  One partial per (branch, kv head,
+        //      chunk), in the slots the per-branch blocks would have used. -------------------------------
+        if (a.inline_prefix == 2 && wave_id >= n_waves - cut.n_prompt) {
+          const int r16 = lane & 15, g4 = lane >> 4;
+          const long long pf = partial_floats(dm.G, D);
+          int cursor = wd3.z;
+          bool resolved = wd3.w != 0;                                  // the first item's request came with the descriptor
+          for (long long item = prompt_range_of_wave(wave_id - (n_waves - cut.n_prompt), cut.n_prompt); item < cut.n_pitems;
+               item += cut.n_prompt) {
+            int r = wd2.x, cnt = wd2.y, plen = wd2.z, first_row = wd2.w, pstart = wd3.x, istart = wd3.y;
+            if (!resolved) {                                           // rare: more items than waves
+              while (item >= tb.live_item_start[cursor + 1]) ++cursor; // the live request owning the item
+              r = tb.live_req[cursor];
+              cnt = tb.refcnt[r]; plen = tb.prefix_len[r]; first_row = tb.req_first[r]; pstart = tb.req_pstart[r];
+              istart = tb.live_item_start[cursor];
+            }
+            resolved = false;
+            const int pp = ceil_div(plen, 16), nck = ceil_div(pp, cut.pb);
+            const int rows = cnt * dm.G, ntile = ceil_div(rows, 16 * kSharedBlocks);
+            const int local = (int)(item - istart);
+            const int rt = local % ntile, ck = (local / ntile) % nck, h = local / (ntile * nck);
+            const int r0 = ck * cut.pb, rn = min(cut.pb, pp - r0);
+            const int n_last = min(16, plen - (r0 + rn - 1) * 16);
+            const int row0 = rt * 16 * kSharedBlocks;
+            const int nb = min(kSharedBlocks, ceil_div(rows - row0, 16));          // blocks with rows (wave-uniform)
+            WaveState<D> sb[kSharedBlocks];
+            uint4 qb[kSharedBlocks][KQ];
+            int br[kSharedBlocks], hd[kSharedBlocks];                              // this lane's branch and head per block, -1: no row
+    #pragma unroll
+            for (int b = 0; b < kSharedBlocks; ++b) {
+              const int flat = row0 + 16 * b + r16;
+              const bool have = flat < rows;
+              const int fc = have ? flat : rows - 1;                               // lanes past the end shadow the last row
+              const int j = fc / dm.G, g = fc % dm.G;
+              br[b] = have ? j : -1;
+              hd[b] = g;
+              const uint16_t* qrow = q + ((long long)(first_row + j) * dm.Hq + h * dm.G + g) * D;
+    #pragma unroll
+              for (int i = 0; i < KQ; ++i) qb[b][i] = *(const uint4*)(qrow + i * 32 + g4 * 8);
+              sb[b].reset();
+            }
+            stream_pages(std::false_type{}, prefix_table + (long long)r * dm.max_pp, r0, rn, n_last, h,
+                         [&](const uint4* kq, const uint4* vq) {
+    #pragma unroll
+                           for (int b = 0; b < kSharedBlocks; ++b)
+                             if (b < nb) process_raw<D, FP8, true>(sb[b], kq, vq, qb[b], 16, 16, a.scale_log2);
+                         },
+                         [&](const uint4* kq, const uint4* vq, int nv) {
+    #pragma unroll
+                           for (int b = 0; b < kSharedBlocks; ++b)
+                             if (b < nb) process_raw<D, FP8, false>(sb[b], kq, vq, qb[b], nv, nv, a.scale_log2);
+                         });
+            const long long slot0 = prompt_slot_base + pstart + ((long long)h * nck + ck) * cnt;
+    #pragma unroll
+            for (int b = 0; b < kSharedBlocks; ++b) {
+              if (b >= nb) continue;
+              const float l = sum_over_rows(sb[b].l);
+              if (br[b] < 0) continue;
+              float* base = a.partials + (slot0 + br[b]) * pf;
+              if (a.fused_merge) {
+    #pragma unroll
+                for (int k = 0; k < D / 16; ++k) put_f32x4<true>(base + (long long)hd[b] * D + k * 16 + 4 * g4, sb[b].o[k]);
+                if (g4 == 0) {
+                  put_f32<true>(base + (long long)dm.G * D + hd[b], sb[b].m);
+                  put_f32<true>(base + (long long)dm.G * D + dm.G + hd[b], l);
+                }
+              } else {
+    #pragma unroll
+                for (int k = 0; k < D / 16; ++k) put_f32x4<false>(base + (long long)hd[b] * D + k * 16 + 4 * g4, sb[b].o[k]);
+                if (g4 == 0) {
+                  put_f32<false>(base + (long long)dm.G * D + hd[b], sb[b].m);
+                  put_f32<false>(base + (long long)dm.G * D + dm.G + hd[b], l);
+                }
+              }
+            }
+            if (a.fused_merge) {
+              // one lane per branch of the tile (the one holding the branch's first row in the tile) counts the
+              // tile in for (branch, kv head); the branches completed by that are merged by the whole wave in turn
+              static_assert(kSharedBlocks == 1, "the in-kernel merge expects one 16-row block per prompt item");
+              __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // the tile's partial results have been stored
+              __builtin_amdgcn_s_waitcnt(0);
+              bool last = false;
+              const int j = br[0], flat = row0 + r16;
+              if (j >= 0 && g4 == 0 && flat == max(row0, j * dm.G)) {
+                const RowInfo ri = load_row_info(row_desc, first_row + j);
+                long long w0;
+                int sn;
+                own_pieces(cut, dm.Hkv, ri, h, w0, sn);
+                const int old = __hip_atomic_fetch_add(a.seg_count + ((long long)(first_row + j) * dm.Hkv + h), 1, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+                last = old == ri.prompt_writers + sn - 1;
+              }
+              unsigned long long done = __ballot(last);
+              if (done) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                while (done) {
+                  const int ln = __builtin_ctzll(done);
+                  done &= done - 1;
+                  const int row = first_row + __builtin_amdgcn_readlane(j, ln);
+                  const RowInfo ri = load_row_info(row_desc, row);
+                  long long w0;
+                  int sn;
+                  own_pieces(cut, dm.Hkv, ri, h, w0, sn);
+                  if (lane == 0) __hip_atomic_store(a.seg_count + ((long long)row * dm.Hkv + h), 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                  fold_segment<D>(a, dm, prompt_slot_base, row, h, ri, w0, sn);
+                }
+              }
+            }
+          }
         }
-        resolved = false;
-        const int pp = ceil_div(plen, 16), nck = ceil_div(pp, cut.pb);
-        const int rows = cnt * dm.G, ntile = ceil_div(rows, 16 * kSharedBlocks);
-        const int local = (int)(item - istart);
-        const int rt = local % ntile, ck = (local / ntile) % nck, h = local / (ntile * nck);
-        const int r0 = ck * cut.pb, rn = min(cut.pb, pp - r0);
-        const int n_last = min(16, plen - (r0 + rn - 1) * 16);
-        const int row0 = rt * 16 * kSharedBlocks;
-        const int nb = min(kSharedBlocks, ceil_div(rows - row0, 16));          // blocks with rows (wave-uniform)
-        WaveState<D> sb[kSharedBlocks];
-        uint4 qb[kSharedBlocks][KQ];
-        int br[kSharedBlocks], hd[kSharedBlocks];                              // this lane's branch and head per block, -1: no row
-#pragma unroll
-        for (int b = 0; b < kSharedBlocks; ++b) {
-          const int flat = row0 + 16 * b + r16;
-          const bool have = flat < rows;
-          const int fc = have ? flat : rows - 1;                               // lanes past the end shadow the last row
-          const int j = fc / dm.G, g = fc % dm.G;
-          br[b] = have ? j : -1;
-          hd[b] = g;
-          const uint16_t* qrow = q + ((long long)(first_row + j) * dm.Hq + h * dm.G + g) * D;
-#pragma unroll
-          for (int i = 0; i < KQ; ++i) qb[b][i] = *(const uint4*)(qrow + i * 32 + g4 * 8);
-          sb[b].reset();
+
+        // ---- per-branch prompt blocks (prompt mode 1): block u is (request, kv head, chunk, branch); served before
+        //      the own range, all waves at the same time, so that the branches' re-reads of a chunk hit in L2 -----
+        if (a.inline_prefix == 1 && wave_id >= n_waves - cut.n_prompt) {
+          const long long i = wave_id - (n_waves - cut.n_prompt);
+          int cursor = tb.wave_row[n_waves + i];                       // live request index
+          for (long long u = prompt_range_of_wave(i, cut.n_prompt); u < cut.n_blocks; u += cut.n_prompt) {
+            while (u >= tb.live_item_start[cursor + 1]) ++cursor;      // the live request owning block u
+            const int r = tb.live_req[cursor];
+            const int cnt = tb.refcnt[r], plen = tb.prefix_len[r];
+            const int pp = ceil_div(plen, 16), nck = ceil_div(pp, cut.pb);
+            const int local = (int)(u - tb.live_item_start[cursor]);
+            const int j = local % cnt, ck = (local / cnt) % nck, h = local / (cnt * nck);
+            const int r0 = ck * cut.pb, rn = min(cut.pb, pp - r0);
+            const int row = tb.req_first[r] + j;
+            RowInfo ri{};
+            if (a.fused_merge) ri = load_row_info(row_desc, row);
+            run_piece(std::false_type{}, prefix_table + (long long)r * dm.max_pp, row, h, r0, rn, min(16, plen - (r0 + rn - 1) * 16),
+                      prompt_slot_base + u, ri);
+          }
         }
-        stream_pages(std::false_type{}, prefix_table + (long long)r * dm.max_pp, r0, rn, n_last, h,
-                     [&](const uint4* kq, const uint4* vq) {
-#pragma unroll
-                       for (int b = 0; b < kSharedBlocks; ++b)
-                         if (b < nb) process_raw<D, FP8, true>(sb[b], kq, vq, qb[b], 16, 16, a.scale_log2);
-                     },
-                     [&](const uint4* kq, const uint4* vq, int nv) {
-#pragma unroll
-                       for (int b = 0; b < kSharedBlocks; ++b)
-                         if (b < nb) process_raw<D, FP8, false>(sb[b], kq, vq, qb[b], nv, nv, a.scale_log2);
-                     });
-        const long long slot0 = prompt_slot_base + pstart + ((long long)h * nck + ck) * cnt;
-#pragma unroll
-        for (int b = 0; b < kSharedBlocks; ++b) {
-          if (b >= nb) continue;
-          const float l = sum_over_rows(sb[b].l);
-          if (br[b] < 0) continue;
-          float* base = a.partials + (slot0 + br[b]) * pf;
-#pragma unroll
-          for (int k = 0; k < D / 16; ++k) *(f32x4*)(base + (long long)hd[b] * D + k * 16 + 4 * g4) = sb[b].o[k];
-          if (g4 == 0) {
-            base[(long long)dm.G * D + hd[b]] = sb[b].m;
-            base[(long long)dm.G * D + dm.G + hd[b]] = l;
+
+      } else {
+        // ---- own line: this wave's range [u, u1) of the (row, kv head, page) units, one piece per (row, kv head) it
+        //      crosses; piece of range x for (row, h) goes to slot x + row * Hkv + h ---------------------------------
+        if (wave_id < cut.n_own) {
+          const long long x = wave_id, u1 = own_end(cut, x);
+          long long u = own_start(cut, x);
+          int cursor = wd0.x, c_cum = wd0.y, c_pages = wd0.z, c_seq = wd0.w;   // active row, its page_cum, private pages, tokens
+          RowInfo ri{};
+          if (u < u1) ri = load_row_info(row_desc, cursor);          // the merge's facts about the row: needed when a piece ends
+          while (u < u1) {
+            long long rem = u - (long long)c_cum * dm.Hkv;
+            while (c_pages == 0 || rem >= (long long)c_pages * dm.Hkv) {   // next row (skipping rows without private pages)
+              ++cursor;
+              ri = load_row_info(row_desc, cursor);
+              c_cum = ri.cum;
+              c_pages = ri.pages;
+              c_seq = ri.seq;
+              rem = u - (long long)c_cum * dm.Hkv;
+            }
+            const int row = cursor, h = (int)(rem / c_pages), r0 = (int)(rem % c_pages);
+            const int rn = (int)min((long long)(c_pages - r0), u1 - u);
+            run_piece(std::true_type{}, bt + (long long)row * dm.max_bp, row, h, r0, rn, min(16, c_seq - (r0 + rn - 1) * 16),
+                      x + (long long)row * dm.Hkv + h, ri);
+            u += rn;
           }
         }
       }
     }
-
-    for (int line = a.inline_prefix == 2 ? 0 : 1; line >= 0; --line) {   // prompt blocks first: all waves start them together, so neighbours share pages in time
-      long long x, u, u1;          // range number and its units on this line
-      int cursor;                  // own line: active row; prompt line: live request index
-      int c_cum = 0, c_pages = 0, c_seq = 0;   // own line: page_cum, private pages and tokens of row `cursor`
-      if (line == 0) {
-        if (wave_id >= cut.n_own) continue;
-        x = wave_id; u = own_start(cut, x); u1 = own_end(cut, x);
-        if (u >= u1) continue;
-        cursor = wd0.x; c_cum = wd0.y; c_pages = wd0.z; c_seq = wd0.w;
-      } else {
-        if (wave_id < n_waves - cut.n_prompt) continue;
-        const long long i = wave_id - (n_waves - cut.n_prompt);
-        x = 0; u = prompt_range_of_wave(i, cut.n_prompt); u1 = cut.n_blocks;   // u counts prompt blocks here
-        if (u >= u1) continue;
-        cursor = tb.wave_row[n_waves + i];
-      }
-      while (u < u1) {
-        // ---- next piece: pages [r0, r0 + rn) of `table`, for query rows (row, h)
-        int row, h, r0, rn, n_last;
-        long long slot;
-        const int* __restrict__ table;
-        if (line == 0) {
-          long long rem = u - (long long)c_cum * dm.Hkv;
-          while (c_pages == 0 || rem >= (long long)c_pages * dm.Hkv) {   // next row (skipping rows without private pages)
-            ++cursor;
-            c_cum = tb.page_cum[cursor];
-            c_pages = tb.page_cum[cursor + 1] - c_cum;
-            c_seq = tb.seq_len[cursor];
-            rem = u - (long long)c_cum * dm.Hkv;
-          }
-          row = cursor;
-          h = (int)(rem / c_pages);
-          r0 = (int)(rem % c_pages);
-          rn = (int)min((long long)(c_pages - r0), u1 - u);
-          n_last = min(16, c_seq - (r0 + rn - 1) * 16);
-          table = bt + (long long)row * dm.max_bp;
-          slot = x + (long long)row * dm.Hkv + h;
-        } else {
-          while (u >= tb.live_item_start[cursor + 1]) ++cursor;   // the live request owning block u
-          const int r = tb.live_req[cursor];
-          const int cnt = tb.refcnt[r], plen = tb.prefix_len[r];
-          const int pp = ceil_div(plen, 16), nck = ceil_div(pp, cut.pb);
-          const int local = (int)(u - tb.live_item_start[cursor]);
-          const int j = local % cnt, ck = (local / cnt) % nck;
-          h = local / (cnt * nck);
-          r0 = ck * cut.pb;
-          rn = min(cut.pb, pp - r0);
-          n_last = min(16, plen - (r0 + rn - 1) * 16);
-          row = tb.req_first[r] + j;
-          table = prefix_table + (long long)r * dm.max_pp;
-          slot = prompt_slot_base + u;
-        }
-        load_q<D>(qreg, q, dm, row, h);
-        st.reset();
-        auto full = [&](const uint4* kq, const uint4* vq) { process_raw<D, FP8, true>(st, kq, vq, qreg, 16, 16, a.scale_log2); };
-        auto part = [&](const uint4* kq, const uint4* vq, int nv) { process_raw<D, FP8, false>(st, kq, vq, qreg, nv, nv, a.scale_log2); };
-        if (line == 0) stream_pages(std::true_type{}, table, r0, rn, n_last, h, full, part);
-        else stream_pages(std::false_type{}, table, r0, rn, n_last, h, full, part);
-        store_partial<D>(st, a.partials, slot, dm);
-        u += line == 0 ? rn : cut.n_prompt;
+    // (row, kv head) pairs without any context have no writer: their output rows are zero
+    if (a.fused_merge && wv == 0) {
+      for (long long seg = blockIdx.x; seg < S; seg += gridDim.x) {
+        const int row = (int)(seg / dm.Hkv), h = (int)(seg % dm.Hkv);
+        const RowInfo ri = load_row_info(row_desc, row);
+        if (ri.pages != 0 || ri.prompt_writers != 0) continue;
+        for (int e = lane; e < dm.G * (D / 4); e += 64)
+          *(f32x4*)(a.out + ((long long)row * dm.Hq + h * dm.G) * D + 4LL * e) = f32x4{0.f, 0.f, 0.f, 0.f};
       }
     }
   }
@@ -521,56 +720,40 @@ k_merge(Ctx c, DecodeArgs a, int inline_prefix) {
   const long long prefix_base = (long long)cut.n_own + S;
   for (long long seg = blockIdx.x; seg < S; seg += gridDim.x) {
     const int row = (int)(seg / dm.Hkv), h = (int)(seg % dm.Hkv);
-    // slot ranges: [pa, pa+pn) prompt pieces or chunks, [sa, sa+sn) own pieces
-    long long pa = 0, sa = 0, pstride = 1;
-    int pn = 0, sn = 0;
-    {
-      const int r = tb.active[row] / dm.Nb;
-      const int pp = ceil_div(tb.prefix_len[r], dm.pt);
-      if (pp > 0 && inline_prefix) {
-        // one block per prompt chunk: req_pstart + ((head * chunks + chunk) * branches + branch)
-        const int cnt = tb.refcnt[r], j = row - tb.req_first[r];
-        pn = ceil_div(pp, cut.pb);
-        pstride = cnt;
-        pa = prompt_slot_base + tb.req_pstart[r] + (long long)h * pn * cnt + j;
-      } else if (pp > 0) {
+    // slot ranges: [pa, pa+pn) prompt pieces or chunks, [sa, sa+sn) own pieces; the row's facts come from the
+    // plan's descriptor (one load), so that the partial results can be requested right after it
+    const RowInfo ri = load_row_info(tb.row_desc, row);
+    long long pa = 0, sa = 0, pstride = 1, w0;
+    int pn = 0, sn;
+    if (inline_prefix) {
+      // one block per prompt chunk: first slot of the row + (head * chunks + chunk) * branches
+      pn = ri.nck;
+      pstride = ri.cnt;
+      pa = prompt_slot_base + ri.pslot + (long long)h * ri.nck * ri.cnt;
+    } else {
+      const int pp = ceil_div(tb.prefix_len[tb.active[row] / dm.Nb], dm.pt);
+      if (pp > 0) {
         pn = ceil_div(pp, chunk);
         pa = prefix_base + seg * npc;
       }
     }
-    const int pages = tb.page_cum[row + 1] - tb.page_cum[row];
-    if (pages > 0) {
-      const long long us = (long long)tb.page_cum[row] * dm.Hkv + (long long)h * pages;
-      const long long w0 = own_of_unit(cut, us), w1 = own_of_unit(cut, us + pages - 1);
-      sa = w0 + seg;
-      sn = (int)(w1 - w0 + 1);
-    }
+    own_pieces(cut, dm.Hkv, ri, h, w0, sn);
+    sa = w0 + seg;
     for (int e = threadIdx.x; e < G * D4; e += blockDim.x) {
       const int r = e / D4, d4 = e % D4;
-      float m = -__builtin_inff(), l = 0.f;
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-      for (int i = 0; i < pn + sn; ++i) {
-        const long long slot = i < pn ? pa + i * pstride : sa + (i - pn);
-        const float* pb = a.partials + slot * pf;
-        const float mi = pb[(long long)G * D + r];
-        const float li = pb[(long long)G * D + G + r];
-        const f32x4 oi = *(const f32x4*)(pb + (long long)r * D + 4 * d4);
-        const float mn = fmaxf(m, mi);
-        const float ws = __builtin_amdgcn_exp2f(m - mn), wi = __builtin_amdgcn_exp2f(mi - mn);
-        l = l * ws + li * wi;
-        acc = acc * ws + oi * wi;
-        m = mn;
-      }
-      const float inv = l > 0.f ? 1.0f / l : 0.f;
-      *(f32x4*)(a.out + ((long long)row * dm.Hq + h * G + r) * D + 4 * d4) = acc * (inv * a.v_scale);
+      fold_columns<false>(a.partials, a.out + ((long long)row * dm.Hq + h * G + r) * D, pf, G, D, r, d4, pa, pstride, pn, sa, sn,
+                          a.v_scale);
     }
   }
 }
 
-void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s) {
+void launch_decode(const Ctx& c, const DecodeArgs& a_in, hipStream_t s) {
   const Dims& dm = c.dm;
   const bool mfma = dm.layout != SART_LAYOUT_NATURAL;
+  DecodeArgs a = a_in;
+  // the matrix-core kernel merges in its own last writers when the prompts are read inline; the LDS prompt
+  // mode and the generic kernel leave their partial results to the merge kernel
+  a.fused_merge = a_in.fused_merge && mfma && a.inline_prefix != 0;
   if (a.ev[0]) (void)hipEventRecord(a.ev[0], s);
   if (a.ev[1]) (void)hipEventRecord(a.ev[1], s);
   // profiling with repeats > 1 launches the (idempotent) attention kernel that many times
@@ -579,7 +762,7 @@ void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s) {
   if (mfma) {
     auto go = [&](auto kern) {
       hipLaunchKernelGGL(kern, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], c.tb.bt[1], c.tb.item_desc,
-                         c.tb.prefix_table, c.tb.wave_desc);
+                         c.tb.prefix_table, c.tb.wave_desc, c.tb.row_desc);
     };
     const bool fp8 = dm.layout == SART_LAYOUT_MFMA16_FP8;
     if (dm.d == 128) { if (fp8) go(k_attn_mfma<128, true>); else go(k_attn_mfma<128, false>); }
@@ -591,9 +774,11 @@ void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s) {
   }
   }
   if (a.ev[2]) (void)hipEventRecord(a.ev[2], s);
-  long long blocks = (long long)dm.H * dm.Hkv;
-  if (blocks > 8192) blocks = 8192;
-  hipLaunchKernelGGL(k_merge, dim3((unsigned)blocks), dim3(256), 0, s, c, a, a.inline_prefix);
+  if (!a.fused_merge) {
+    long long blocks = (long long)dm.H * dm.Hkv;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_merge, dim3((unsigned)blocks), dim3(256), 0, s, c, a, a.inline_prefix);
+  }
   if (a.ev[3]) (void)hipEventRecord(a.ev[3], s);
 }
 

@@ -269,6 +269,23 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       d[1] = make_int4(local % nck, bg, r, 0);
     }
   }
+  // What the pieces of a row need to merge in the attention kernel itself, 8 ints per active row:
+  //   [0] page_cum of the row  [1] its private pages  [2] its private tokens
+  //   [3] writers of prompt partial results per kv head: chunks x row tiles holding the branch's rows
+  //       (shared rows), chunks (per-branch blocks), 0 without a prompt or in the LDS prompt mode
+  //   [4] first prompt partial slot of the row, relative to the prompts' slots: chunk ck of kv head h is
+  //       slot [4] + (h * [6] + ck) * [5]   [5] live branches of the request   [6] prompt chunks   [7] 0
+  for (int i = tid; i < nA; i += kPlanThreads) {
+    const int r = tb.active[i] / dm.Nb;
+    const int j = i - tb.req_first[r], cnt = tb.refcnt[r];
+    const int pp = ceil_div(tb.prefix_len[r], dm.pt);
+    const int nck = pc.inline_prefix && pp > 0 ? ceil_div(pp, cut.pb) : 0;
+    const int tiles = pc.inline_prefix == 2 ? ((j + 1) * dm.G - 1) / (16 * kSharedBlocks) - (j * dm.G) / (16 * kSharedBlocks) + 1 : 1;
+    const int c0 = nA <= kPlanLdsRows ? s_cum[i] : tb.page_cum[i], c1 = nA <= kPlanLdsRows ? s_cum[i + 1] : tb.page_cum[i + 1];
+    int4* rd = (int4*)(tb.row_desc + 8LL * i);
+    rd[0] = make_int4(c0, c1 - c0, i < kPlanLdsRows ? s_seq[i] : tb.seq_len[i], nck * tiles);
+    rd[1] = make_int4(nck ? tb.req_pstart[r] + j : 0, cnt, nck, 0);
+  }
   // Where every wave starts.  wave_row (generic kernel): active row of an own
   // range's first unit and, after those entries, the live request of a prompt
   // wave's first work item.  wave_desc (matrix-core kernel), 16 ints per wave,

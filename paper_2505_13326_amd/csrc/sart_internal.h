@@ -102,6 +102,8 @@ struct Tables {
   int* wave_row;         // [max attention waves] own ranges: active row of the first unit; prompt ranges: live request index
   int* req_pstart;       // [max_req] first prompt block of the request
   int* wave_desc;        // [max attention waves][16] where each wave starts (see refresh_decode_plan)
+  int* row_desc;         // [H][8] per active row: what a piece of the row needs to know to merge (see refresh_decode_plan)
+  int* seg_count;        // [H * Hkv] arrivals per (row, kv head) in the running attention kernel; 0 between kernels
 };
 
 // Launch shape the decode plan is made for (host-chosen, passed to every
@@ -232,6 +234,9 @@ struct DecodeArgs {
   int inline_prefix;    // the plan's prompt mode
   float* partials;      // scratch
   long long partial_cap; // partial slots available
+  int* seg_count;       // scratch: arrival counters of the in-kernel merge, one per (row, kv head), zero between kernels
+  int fused_merge;      // the attention kernel's last writer of a (row, kv head) merges its partial results
+  int stagger_prompt;   // half of the workgroups serve their prompt work after their own range instead of before
   int call_seq;
   float v_scale;        // 8-bit float caches: what the output is multiplied by (1 otherwise)
   hipEvent_t ev[4];     // optional profiling events (null: none)
@@ -242,6 +247,7 @@ void launch_decode(const Ctx& c, const DecodeArgs& a, hipStream_t s);
 __host__ __device__ inline long long partial_floats(int G, int d) { return (long long)G * d + ((2 * G + 3) & ~3); }
 // the fixed scratch of sart_decode_attention_static (bytes), and where the current device keeps it
 constexpr size_t kStaticScratchBytes = SART_STATIC_SCRATCH_BYTES;
+constexpr size_t kStaticCounterBytes = 256u << 10;    // its first part: the in-kernel merge's arrival counters
 hipError_t static_scratch(int* device, void** ptr);
 
 struct PrefillArgs {

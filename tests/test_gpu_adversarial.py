@@ -45,9 +45,15 @@ def _check(o, g, q, mode, launches=((0, 80), (64, 0), (7, 300))):
     worst = 0.0
     for n_wg, skew in launches:
         g.c.set_decode_launch(n_wg, 0, 0, PROMPT_MODES[mode], skew)
-        got = g.c.decode_attention(q).cpu().numpy().astype(np.float64)
-        assert g.c.sync_status() == 0 and np.all(np.isfinite(got))
-        worst = max(worst, float(np.abs(got - ref).max()))
+        outs = []
+        for in_kernel in (False, True):           # merged by the merge kernel / by the attention kernel's last writers
+            g.c.set_merge_mode(in_kernel)
+            got = g.c.decode_attention(q).cpu().numpy()
+            assert g.c.sync_status() == 0 and np.all(np.isfinite(got))
+            worst = max(worst, float(np.abs(got.astype(np.float64) - ref).max()))
+            outs.append(got)
+        assert np.array_equal(outs[0], outs[1])   # same fold order: the same bits
+    g.c.set_merge_mode(False)
     assert worst <= TOL["bf16"], f"max abs err {worst}"
     return ref, worst
 

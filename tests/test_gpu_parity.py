@@ -143,7 +143,9 @@ def test_bf16_small_all_rows(shape, mode):
     # other launch shapes cut the unit line elsewhere; the result must not depend on it
     for n_wg, n_pw, chunk, skew in ((3, 1, 4, 45), (64, 0, 8, 300), (1000, 900, 0, -200), (256, -1, 0, 0), (1, 0, 0, 50)):
         g.c.set_decode_launch(n_wg, n_pw, chunk, pmode, skew)
-        compare_attention(cfg, o, g, wl.query(cfg, 1))
+        for in_kernel in (False, True):        # the merge kernel / the attention kernel's last writers
+            g.c.set_merge_mode(in_kernel)
+            compare_attention(cfg, o, g, wl.query(cfg, 1))
 
 
 def test_edge_cases_empty_and_short_contexts():
