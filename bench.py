@@ -5,12 +5,17 @@ A step = one pass of the hot path over the batch: append one token of K/V to
 every active branch (sart_append_tokens), then the decode attention of all
 active branches (sart_decode_attention: partition, shared-prompt + private
 split-K attention, merge).  Inputs are resident in HBM before timing starts.
-The default workload is the benchmark's config 2 (7B-like GQA, 16 requests x 8
-branches, prompt 512, lognormal private lengths); prune / finish are timed
-once after the step loop and reported in microseconds.
 
-Prints ONE JSON line (see the keys below).  --gpus > 1 is refused: this build
-is single-GPU by design.
+The default run (--workload all) prints ONE JSON line whose top level is the
+32B-like configuration (the benchmark's config 4, the largest single-GPU one),
+with the 7B-like configuration (config 2) under "cfg2" and the early-stop /
+prune trace (config 3, branch-steps/s over the whole 400-step loop) under
+"cfg3"; each carries its own `roofline` (the attention kernel against the HBM
+peak, and the whole sart_decode_attention call as decode_call_*) and
+`cpu_baseline` (the float64 oracle on a stated sample).  --workload cfgN runs
+one configuration alone.  prune / finish are timed once after the step loop
+and reported in microseconds.  --gpus > 1 is refused: this build is
+single-GPU by design.
 """
 from __future__ import annotations
 
@@ -26,9 +31,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM traffic of the dominant kernel per launch measured offline with
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None = not measured
-MEASURED_TRAFFIC_BYTES = {"cfg2": 1450509075, "cfg4": 10928159910}  # profiles/k_attn_mfma_hbm_traffic_and_sq_counters.md
+# HBM traffic of the dominant kernel per launch: NOT measured in this run but copied from the rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE summary under profiles/ (k_attn_mfma_hbm_traffic_and_sq_counters.md), which states the
+# commands; None = not measured for that workload
+MEASURED_TRAFFIC_BYTES = {"cfg2": None, "cfg4": None}
 
 
 def _request_arrays(wl, cfg, r, L):
@@ -111,7 +117,7 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
 
 def bench_trace(args, cfg, sart, wl, np, torch):
     """Config 3: the whole 400-step early-stop / prune loop (append + attention + finish + prune, host
-    step loop included).  value = branch-decode-steps per second over the loop."""
+    step loop included).  value = branch-decode-steps per second over the loop.  Returns the JSON record."""
     from paper_2505_13326_amd.trace import run_trace, run_trace_graph
     L = wl.lengths(cfg)
     targets = (L + wl.remaining_tokens(cfg)).reshape(-1)
@@ -125,18 +131,24 @@ def bench_trace(args, cfg, sart, wl, np, torch):
     qs = [dev(wl.query(cfg, s)) for s in range(cfg.n_steps + 1)]
     scs = [torch.from_numpy(wl.scores(cfg, e)).cuda() for e in range(cfg.n_steps // cfg.prune_every + 1)]
     out = torch.empty((cfg.n_handles, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
-    times, res = [], None
-    for rep in range(1 + max(1, min(args.steps, 3))):     # first repetition is the warm-up
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        arrays = list(ex.map(lambda r: _request_arrays(wl, cfg, r, L), range(cfg.n_requests)))
+
+    def new_cache():
         cache = sart.SartCache(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
                                page_tokens=cfg.page_tokens, num_pages=num_pages, max_requests=cfg.n_requests,
                                branches_per_request=cfg.nb, finish_quota=cfg.quota, max_pages_per_branch=max_bp,
                                max_prefix_pages=cfg.prompt_len // cfg.page_tokens, dtype=cfg.dtype,
                                free_order=wl.free_order(cfg, num_pages))
-        with ThreadPoolExecutor(max_workers=8) as ex:
-            for r, pk, pv, ids, ns, bk, bv in ex.map(lambda r: _request_arrays(wl, cfg, r, L), range(cfg.n_requests)):
-                cache.append_tokens(sart.SEQ_PREFIX, [r], [cfg.prompt_len], pk, pv)
-                cache.append_tokens(sart.SEQ_BRANCH, ids, ns, bk, bv)
+        for r, pk, pv, ids, ns, bk, bv in arrays:
+            cache.append_tokens(sart.SEQ_PREFIX, [r], [cfg.prompt_len], pk, pv)
+            cache.append_tokens(sart.SEQ_BRANCH, ids, ns, bk, bv)
         assert cache.sync_status() == 0
+        return cache
+
+    times, res = [], None
+    for rep in range(1 + max(1, min(args.steps, 3))):     # first repetition is the warm-up
+        cache = new_cache()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         if args.graph:   # the step (gather, append, attention, completion) replayed from one HIP graph
@@ -152,7 +164,57 @@ def bench_trace(args, cfg, sart, wl, np, torch):
         cache.close()
     dt = float(np.mean(times[1:]))
     busy = int(np.sum(res["active_per_step"] > 0)) if "active_per_step" in res else cfg.n_steps
-    print(json.dumps({
+
+    # ---- the attention kernel's share of the loop: one more pass with HIP events around every step's kernel
+    #      (each read waits for the device, so this pass is not the timed one) -------------------------------
+    cache = new_cache()
+    cache.set_profiling(1)
+    k_ms, k_bytes = [], []
+
+    def on_call(name, step, c, extra):
+        if name != "attention":
+            return
+        a_ms, _ = c.last_decode_ms()
+        st = c.get_state(fields=("n_active", "seq_lens", "prefix_refcnt"))
+        n = int(st["n_active"][0])
+        live = int(np.sum(st["prefix_refcnt"] > 0))
+        k_ms.append(a_ms)
+        k_bytes.append((int(st["seq_lens"][:n].sum()) + live * cfg.prompt_len) * cfg.token_bytes
+                       + n * cfg.n_q_heads * cfg.head_dim * (cfg.elem_bytes + 4))
+    run_trace(cache, targets=targets, step_kv=lambda s: kvs[s], query=lambda s: qs[s], n_steps=cfg.n_steps,
+              prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: scs[e], out=out, on_call=on_call)
+    cache.close()
+    attn_s, attn_bytes = float(np.sum(k_ms)) * 1e-3, float(np.sum(k_bytes))
+    roofline = {"bound": "hbm", "kernel": "k_attn_mfma", "achieved": round(attn_bytes / attn_s / 1e9, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(attn_bytes / attn_s / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_all_launches": int(attn_bytes), "launches": len(k_ms), "kernel_ms_sum": round(attn_s * 1e3, 3),
+                "kernel_ms_avg": round(attn_s * 1e3 / max(1, len(k_ms)), 4), "kernel_share_of_loop": round(attn_s / dt, 3),
+                "note": "sum over the loop's attention launches (the batch shrinks from 256 to 0 branches): bytes / kernel time"}
+
+    # ---- CPU baseline: the oracle's own loop on the same state, first steps only ---------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        from oracle.trace import run_trace as oracle_trace
+        n_cpu_steps = 3
+        oc = orc.OracleCache(n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+                             page_tokens=cfg.page_tokens, num_pages=num_pages, max_requests=cfg.n_requests,
+                             branches_per_request=cfg.nb, finish_quota=cfg.quota, max_pages_per_branch=max_bp,
+                             max_prefix_pages=cfg.prompt_len // cfg.page_tokens, dtype=cfg.dtype,
+                             free_order=wl.free_order(cfg, num_pages))
+        for r, pk, pv, ids, ns, bk, bv in arrays:
+            assert oc.append(0, [r], [cfg.prompt_len], pk, pv) == 0
+            assert oc.append(1, ids, ns, bk, bv) == 0
+        t1 = time.perf_counter()
+        ores = oracle_trace(oc, targets=targets, step_kv=lambda s: wl.step_kv(cfg, s), n_steps=n_cpu_steps,
+                            prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: wl.scores(cfg, e),
+                            query=lambda s: wl.query(cfg, s))
+        t_cpu = time.perf_counter() - t1
+        cpu = {"value": round(ores["branch_steps"] / t_cpu, 2), "unit": "branch-steps/s", "cores": orc.num_threads(),
+               "kind": "oracle", "sample": f"the oracle's own step loop (append, float64 attention of every active branch, "
+               f"finish), steps 1..{n_cpu_steps} of {cfg.n_steps} ({ores['branch_steps']} branch-steps, {t_cpu:.2f} s wall, "
+               "input generation included)"}
+    return {
         "metric": "decode-attention achieved KV GB/s (fraction of HBM peak); branch-steps/s",
         "value": round(res["branch_steps"] / dt, 1), "unit": "branch-steps/s", "n_gpus": 1, "steps": cfg.n_steps,
         "warmup": 1, "ms_per_step": round(dt / max(1, busy) * 1e3, 4), "higher_is_better": True, "scaling": "weak",
@@ -160,7 +222,8 @@ def bench_trace(args, cfg, sart, wl, np, torch):
         "config": {"workload": f"cfg3 {cfg.name}: {cfg.n_requests} requests x {cfg.nb} branches, quota {cfg.quota}, "
                                f"{cfg.n_steps} steps, prune {cfg.prune_k} lowest every {cfg.prune_every} steps; whole "
                                "loop incl. host driver" + (", step replayed from a HIP graph" if args.graph else ""), "branch_steps": res["branch_steps"],
-                   "steps_with_active_branches": busy, "loop_s": round(dt, 4)}}), flush=True)
+                   "steps_with_active_branches": busy, "loop_s": round(dt, 4)},
+        "roofline": roofline, "cpu_baseline": cpu}
 
 
 def bench_probe_sweep(args, sart, np, torch):
@@ -195,72 +258,9 @@ def bench_probe_sweep(args, sart, np, torch):
                       "best": rows[0], "table": rows}))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "copy", "probe", "prefill4", "prefill5"],
-                    help="copy = a plain 1 GiB device copy, the known-size kernel that calibrates the "
-                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters; prefillN = prefill attention over the prompts "
-                         "of config N")
-    ap.add_argument("--free-order", default="scattered", choices=["scattered", "identity"])
-    ap.add_argument("--workgroups", type=int, default=0, help="attention workgroups (0 = library default)")
-    ap.add_argument("--chunk-pages", type=int, default=0, help="prompt chunk in pages (0 = chosen on device)")
-    ap.add_argument("--prompt-mode", type=int, default=-1, help="0 = prompt staged in LDS and shared, 1 = prompt blocks read by every branch, 2 = prompt blocks read once for all of a request's query rows, -1 = library default")
-    ap.add_argument("--skew", type=int, default=None, help="per-mille of work moved from odd to even workgroups (default: library's)")
-    ap.add_argument("--prompt-workgroups", type=int, default=-1, help="workgroups serving only the prompts (-1 = half the grid)")
-    ap.add_argument("--prompt-len", type=int, default=-1, help="override the workload's prompt length (experiments)")
-    ap.add_argument("--kernel-repeats", type=int, default=8,
-                    help="launches of the attention kernel between the two HIP events of the profiled pass")
-    ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"], help="fp8: the cache keeps K and V as 8-bit floats "
-                    "(E4M3; bf16 crosses the boundary): half the bytes per cached token")
-    ap.add_argument("--layers", type=int, default=1, help="layers sharing the tables; a step appends to and attends over "
-                    "every layer (same values in every layer)")
-    ap.add_argument("--merge", default="kernel", choices=["in-kernel", "kernel"], help="where a step's partial results "
-                    "are merged: by the separate merge kernel (default) or by the attention kernel's last writers")
-    ap.add_argument("--no-stagger", action="store_true", help="every wave serves its prompt work before its own range")
-    ap.add_argument("--graph", action="store_true", help="replay the step (append + attention) from a HIP graph")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (requests are independent and would shard with no "
-              "collective); --gpus > 1 is not supported", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
-    import torch
-    import paper_2505_13326_amd as sart
-    import workloads as wl
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    if args.workload == "copy":
-        n = 1 << 30
-        src = torch.ones(n, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(args.warmup):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / args.steps
-        print(json.dumps({"metric": "device copy", "bytes_read": n, "bytes_written": n, "steps": args.steps,
-                          "ms_per_step": round(dt * 1e3, 4), "value": round(2 * n / dt / 1e9, 1), "unit": "GB/s"}))
-        return
-    if args.workload == "probe":
-        return bench_probe_sweep(args, sart, np, torch)
-    cfg = wl.CONFIGS[int(args.workload[-1])]
-    if args.prompt_len >= 0:
-        cfg = wl.scaled(cfg, prompt_len=args.prompt_len)
-    if args.workload.startswith("prefill"):
-        return bench_prefill(args, cfg, sart, wl, np, torch)
-    if cfg.cfg_id == 3:
-        return bench_trace(args, cfg, sart, wl, np, torch)
-    K, W = args.steps, args.warmup
+def bench_decode(args, cfg, workload, sart, wl, np, torch, K, W):
+    """One configuration's step loop (append + decode attention), K timed steps after W warm-up steps.
+    Returns the JSON record."""
     NL = max(1, args.layers)
     L = wl.lengths(cfg)
     growth = K + W + 2 * K + 64           # timed + profiled passes append one token per step
@@ -396,7 +396,7 @@ def main():
     achieved = alg_bytes_prof / (attn_avg * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "k_attn_mfma", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if args.kv_dtype == "bf16" else None,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(workload) if args.kv_dtype == "bf16" else None,
                 "algorithmic_bytes_per_launch": int(alg_bytes_prof), "kernel_ms_avg": round(attn_avg, 4),
                 "kernel_ms_p10_p50_p90": [round(float(np.percentile(attn_ms, p)), 4) for p in (10, 50, 90)],
                 "launches_per_event_pair": args.kernel_repeats}
@@ -413,23 +413,26 @@ def main():
     roofline["decode_call_ms_avg"] = round(call_ms, 4)
     roofline["decode_call_frac"] = round(call_bytes / (call_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
 
-    # ---- what plain reads reach on this machine: 8 KiB chunks of a 2 GiB buffer, in order and shuffled ----
+    # ---- what plain reads reach on this machine: 8 KiB chunks of a 2 GiB buffer, in order and shuffled, with ordinary
+    #      loads and with the non-temporal hint the attention kernel's own-page loads carry (the best launch
+    #      shapes of `--workload probe`, profiles/read_probe_sweep.md) ------------------------------------------
     probe = torch.ones(1 << 31, dtype=torch.uint8, device="cuda")
     order = torch.randperm((1 << 31) // 8192, device="cuda", dtype=torch.int32, generator=torch.Generator(device="cuda").manual_seed(1))
-    rates = []
-    for od in (None, order):
+    rates = {}
+    for name, od, shape in (("sequential", None, None), ("shuffled_8KiB", order, None),
+                            ("sequential_nontemporal", None, (256, 1, 1, 1)), ("shuffled_8KiB_nontemporal", order, (2048, 4, 1, 0))):
         for _ in range(3):
-            sart.read_probe(probe, od)
+            sart.read_probe(probe, od, shape=shape)
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         evs[0].record()
         for _ in range(10):
-            sart.read_probe(probe, od)
+            sart.read_probe(probe, od, shape=shape)
         evs[1].record()
         torch.cuda.synchronize()
-        rates.append((1 << 31) * 10 / (evs[0].elapsed_time(evs[1]) * 1e-3) / 1e9)
+        rates[name] = round((1 << 31) * 10 / (evs[0].elapsed_time(evs[1]) * 1e-3) / 1e9, 1)
     del probe, order
-    roofline["read_probe_gbs"] = {"sequential": round(rates[0], 1), "shuffled_8KiB": round(rates[1], 1)}
-    roofline["frac_of_read_probe"] = round(achieved / rates[1], 4)
+    roofline["read_probe_gbs"] = rates
+    roofline["frac_of_read_probe"] = round(achieved / rates["shuffled_8KiB_nontemporal"], 4)
 
     # ---- maintenance calls, once each (they change the batch, so after the step loop) --
     sc = torch.from_numpy(wl.scores(cfg, 0)).cuda()
@@ -470,7 +473,7 @@ def main():
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype if args.kv_dtype == "bf16" else "bf16 arithmetic on an fp8 (E4M3) cache", "data": "synthetic",
-        "config": {"workload": f"{args.workload} {cfg.name}: {cfg.n_requests} requests x {cfg.nb} branches, "
+        "config": {"workload": f"{workload} {cfg.name}: {cfg.n_requests} requests x {cfg.nb} branches, "
                                f"Hq{cfg.n_q_heads}/Hkv{cfg.n_kv_heads} d{cfg.head_dim} {cfg.dtype if args.kv_dtype == 'bf16' else 'fp8 cache'}, prompt "
                                f"{cfg.prompt_len}, private lengths {cfg.length_dist}{cfg.length_params} cap "
                                f"{cfg.length_cap}, page 16, free order {args.free_order}",
@@ -484,7 +487,92 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
-    print(json.dumps(line), flush=True)
+    cache.close()
+    if ocache is not None:
+        ocache.close()
+    return line
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="all", choices=["all", "cfg2", "cfg3", "cfg4", "cfg5", "copy", "probe", "prefill4", "prefill5"],
+                    help="all = config 4 (the headline) with configs 2 and 3 nested in the same line; copy = a plain 1 GiB device copy, the known-size kernel that calibrates the "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters; prefillN = prefill attention over the prompts "
+                         "of config N")
+    ap.add_argument("--free-order", default="scattered", choices=["scattered", "identity"])
+    ap.add_argument("--workgroups", type=int, default=0, help="attention workgroups (0 = library default)")
+    ap.add_argument("--chunk-pages", type=int, default=0, help="prompt chunk in pages (0 = chosen on device)")
+    ap.add_argument("--prompt-mode", type=int, default=-1, help="0 = prompt staged in LDS and shared, 1 = prompt blocks read by every branch, 2 = prompt blocks read once for all of a request's query rows, -1 = library default")
+    ap.add_argument("--skew", type=int, default=None, help="per-mille of work moved from odd to even workgroups (default: library's)")
+    ap.add_argument("--prompt-workgroups", type=int, default=-1, help="workgroups serving only the prompts (-1 = half the grid)")
+    ap.add_argument("--prompt-len", type=int, default=-1, help="override the workload's prompt length (experiments)")
+    ap.add_argument("--kernel-repeats", type=int, default=8,
+                    help="launches of the attention kernel between the two HIP events of the profiled pass")
+    ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"], help="fp8: the cache keeps K and V as 8-bit floats "
+                    "(E4M3; bf16 crosses the boundary): half the bytes per cached token")
+    ap.add_argument("--layers", type=int, default=1, help="layers sharing the tables; a step appends to and attends over "
+                    "every layer (same values in every layer)")
+    ap.add_argument("--merge", default="kernel", choices=["in-kernel", "kernel"], help="where a step's partial results "
+                    "are merged: by the separate merge kernel (default) or by the attention kernel's last writers")
+    ap.add_argument("--no-stagger", action="store_true", help="every wave serves its prompt work before its own range")
+    ap.add_argument("--graph", action="store_true", help="replay the step (append + attention) from a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (requests are independent and would shard with no "
+              "collective); --gpus > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2505_13326_amd as sart
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.workload == "copy":
+        n = 1 << 30
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.warmup):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / args.steps
+        print(json.dumps({"metric": "device copy", "bytes_read": n, "bytes_written": n, "steps": args.steps,
+                          "ms_per_step": round(dt * 1e3, 4), "value": round(2 * n / dt / 1e9, 1), "unit": "GB/s"}))
+        return
+    if args.workload == "probe":
+        return bench_probe_sweep(args, sart, np, torch)
+    if args.workload == "all":
+        # the headline: config 4 (largest single-GPU configuration), with config 2 and the config 3 trace nested
+        line = bench_decode(args, wl.CONFIGS[4], "cfg4", sart, wl, np, torch, args.steps, args.warmup)
+        torch.cuda.empty_cache()
+        keep = ("value", "unit", "steps", "warmup", "ms_per_step", "dtype", "config", "frac_of_hbm_peak", "branch_steps_per_s",
+                "logical_kv_gbs", "prune_us", "finish_us", "roofline", "cpu_baseline")
+        sub = bench_decode(args, wl.CONFIGS[2], "cfg2", sart, wl, np, torch, max(args.steps, 50), max(args.warmup, 10))
+        line["cfg2"] = {k: sub[k] for k in keep}
+        torch.cuda.empty_cache()
+        sub = bench_trace(args, wl.CONFIGS[3], sart, wl, np, torch)
+        line["cfg3"] = {k: sub[k] for k in keep if k in sub}
+        print(json.dumps(line), flush=True)
+        return
+    cfg = wl.CONFIGS[int(args.workload[-1])]
+    if args.prompt_len >= 0:
+        cfg = wl.scaled(cfg, prompt_len=args.prompt_len)
+    if args.workload.startswith("prefill"):
+        return bench_prefill(args, cfg, sart, wl, np, torch)
+    if cfg.cfg_id == 3:
+        print(json.dumps(bench_trace(args, cfg, sart, wl, np, torch)), flush=True)
+        return
+    print(json.dumps(bench_decode(args, cfg, args.workload, sart, wl, np, torch, args.steps, args.warmup)), flush=True)
 
 
 if __name__ == "__main__":

@@ -229,8 +229,8 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
   int* scal = tb.scal;
   constexpr int KQ = D / 32;                       // 16-byte bf16 chunks per lane per tile
   constexpr int KR = raw_chunks<D, FP8>();         // 16-byte chunks per lane per tile as stored
-  constexpr int kRing = 4;                         // pages in flight per wave while streaming (3: the same; 5, 6 and,
-                                                   // for 8-bit float caches, 8: slower, measured)
+  constexpr int kRing = 4;                         // pages in flight per wave while streaming (3, 5 and 6 take the same time,
+                                                   // measured; 8 on 8-bit float caches is slower)
   constexpr int kTileBytes = 16 * D * (FP8 ? 1 : 2);   // one K (or V) tile
   constexpr int kPageBytes = 2 * kTileBytes;       // K tile + V tile of one kv head
   constexpr int kRound = kAttnThreads * 16;                // bytes one load round of the workgroup covers
