@@ -282,7 +282,7 @@ def bench_decode(args, cfg, workload, sart, wl, np, torch, K, W):
 
     # ---- CPU baseline cache (oracle) on a bounded sample of the same workload ------------
     do_cpu = not args.no_cpu_baseline and args.kv_dtype == "bf16"     # the CPU baseline is timed on the bf16 cache
-    n_cpu = args.cpu_sample_requests or {2: cfg.n_requests, 4: 4, 5: 1}[cfg.cfg_id]
+    n_cpu = args.cpu_sample_requests or {2: 16, 4: 4, 5: 1}[cfg.cfg_id]
     n_cpu = min(n_cpu, cfg.n_requests)
     ocache = None
     if do_cpu:
@@ -509,6 +509,7 @@ def main():
     ap.add_argument("--skew", type=int, default=None, help="per-mille of work moved from odd to even workgroups (default: library's)")
     ap.add_argument("--prompt-workgroups", type=int, default=-1, help="workgroups serving only the prompts (-1 = half the grid)")
     ap.add_argument("--prompt-len", type=int, default=-1, help="override the workload's prompt length (experiments)")
+    ap.add_argument("--requests", type=int, default=-1, help="override the workload's number of requests (experiments)")
     ap.add_argument("--kernel-repeats", type=int, default=8,
                     help="launches of the attention kernel between the two HIP events of the profiled pass")
     ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"], help="fp8: the cache keeps K and V as 8-bit floats "
@@ -567,6 +568,8 @@ def main():
     cfg = wl.CONFIGS[int(args.workload[-1])]
     if args.prompt_len >= 0:
         cfg = wl.scaled(cfg, prompt_len=args.prompt_len)
+    if args.requests > 0:
+        cfg = wl.scaled(cfg, n_requests=args.requests)
     if args.workload.startswith("prefill"):
         return bench_prefill(args, cfg, sart, wl, np, torch)
     if cfg.cfg_id == 3:
