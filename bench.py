@@ -276,9 +276,8 @@ def bench_decode(args, cfg, workload, sart, wl, np, torch, K, W):
         cache.set_merge_mode(True)
     if args.no_stagger:
         cache.set_prompt_stagger(False)
-    if args.workgroups or args.chunk_pages or args.prompt_mode >= 0 or args.skew is not None or args.prompt_workgroups >= 0:
-        cache.set_decode_launch(args.workgroups, args.prompt_workgroups, args.chunk_pages, args.prompt_mode,
-                                sart.DEFAULT_SKEW_PERMILLE if args.skew is None else args.skew)
+    if args.workgroups or args.prompt_mode >= 0 or args.skew is not None:
+        cache.set_decode_launch(args.workgroups, args.prompt_mode, sart.DEFAULT_SKEW_PERMILLE if args.skew is None else args.skew)
 
     # ---- CPU baseline cache (oracle) on a bounded sample of the same workload ------------
     do_cpu = not args.no_cpu_baseline and args.kv_dtype == "bf16"     # the CPU baseline is timed on the bf16 cache
@@ -504,10 +503,8 @@ def main():
                          "of config N")
     ap.add_argument("--free-order", default="scattered", choices=["scattered", "identity"])
     ap.add_argument("--workgroups", type=int, default=0, help="attention workgroups (0 = library default)")
-    ap.add_argument("--chunk-pages", type=int, default=0, help="prompt chunk in pages (0 = chosen on device)")
-    ap.add_argument("--prompt-mode", type=int, default=-1, help="0 = prompt staged in LDS and shared, 1 = prompt blocks read by every branch, 2 = prompt blocks read once for all of a request's query rows, -1 = library default")
+    ap.add_argument("--prompt-mode", type=int, default=-1, help="1 = prompt blocks read by every branch, 2 = prompt blocks read once for a tile of 16 of a request's query rows, -1 = library default")
     ap.add_argument("--skew", type=int, default=None, help="per-mille of work moved from odd to even workgroups (default: library's)")
-    ap.add_argument("--prompt-workgroups", type=int, default=-1, help="workgroups serving only the prompts (-1 = half the grid)")
     ap.add_argument("--prompt-len", type=int, default=-1, help="override the workload's prompt length (experiments)")
     ap.add_argument("--requests", type=int, default=-1, help="override the workload's number of requests (experiments)")
     ap.add_argument("--kernel-repeats", type=int, default=8,

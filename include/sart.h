@@ -217,9 +217,9 @@ sart_status sart_decode_attention(sart_cache* cache, int32_t layer,
  * fixed array of SART_STATIC_SCRATCH_BYTES inside the library's device image
  * instead of memory the cache allocated: the call allocates and frees nothing.
  * Each GPU the library runs on holds that array until the process ends.
- * Limits: the cache's device must be current; the LDS-staged prompt mode is not
- * run (SART_E_INVALID); and n_rows (counted up to max_requests * Nb) must be
- * small enough that the largest step it admits fits the array,
+ * Limits: the cache's device must be current, and n_rows (counted up to
+ * max_requests * Nb) must be small enough that the largest step it admits fits
+ * the array,
  *   W + S + max(S, 4 W) <= (SART_STATIC_SCRATCH_BYTES - 256 KiB) / (4 * (G*d + pad4(2G)))
  * and S <= 65536, with W = 4 * workgroups of the decode launch (1024 by default)
  * and S = n_rows * Hkv; otherwise SART_E_INVALID and nothing is enqueued (configs

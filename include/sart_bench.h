@@ -44,36 +44,26 @@ sart_status sart_read_probe_shaped(const void* buf, size_t bytes, const int32_t*
                                    int32_t depth, int32_t flavour, int32_t interleave, void* stream);
 
 /* Tuning knobs of the decode launch (defaults are chosen for MI355X):
- *   n_workgroups         persistent attention grid of 4-wave workgroups (<= 0:
- *                        one per CU);
- *   n_prompt_workgroups  how many of them, the last ones of the grid, serve only
- *                        the shared prompts while the others stream the branches'
- *                        own pages (<= 0, the default: every workgroup does both,
- *                        own pages first, then its share of the prompts);
- *   prefix_chunk_pages   prompt chunk of the LDS-staged mode (<= 0: sized on the
- *                        device from the active set);
- *   prompt_mode          how the shared prompt is read on the matrix-core
- *                        layouts.  2 (default) = in blocks of prompt pages, each
- *                        read once per tile of 16 query rows of the request
- *                        (rows = (branch, head of the GQA group), branch-major:
- *                        with G = 7 and 8 branches, 4 tiles instead of 8
- *                        per-branch reads, every row of the matrix-core tile
- *                        used); the items are ordered (request, kv head, chunk,
- *                        tile) and every wave serves its item(s) before its own
- *                        range, so the tiles' re-reads of a chunk are neighbours
- *                        in time and place and hit in L2.  1 = the same with one
- *                        block per (chunk, branch), G of 16 tile rows used.  0 =
- *                        each prompt chunk is staged once in LDS per workgroup
- *                        and reused by the request's branches, one wave each
- *                        (not for SART_FP8_E4M3 caches: 1 is taken).  -1 = keep
- *                        the current mode.  Natural-layout caches always use 1;
- *   skew_permille        work moved from odd to even streaming workgroups, in
- *                        1/1000 of the mean per-wave range (workgroups go round-
- *                        robin to the 8 XCDs, and the odd XCDs stream about 10 %
- *                        slower); default 80, 0 = equal. */
-sart_status sart_set_decode_launch(sart_cache* cache, int32_t n_workgroups,
-                                   int32_t n_prompt_workgroups, int32_t prefix_chunk_pages,
-                                   int32_t prompt_mode, int32_t skew_permille);
+ *   n_workgroups   persistent attention grid of 4-wave workgroups (<= 0: one per
+ *                  CU);
+ *   prompt_mode    how the shared prompt is read.  2 (default on the matrix-core
+ *                  layouts) = in blocks of prompt pages, each read once per tile
+ *                  of 16 query rows of the request (rows = (branch, head of the
+ *                  GQA group), branch-major: with G = 7 and 8 branches, 4 tiles
+ *                  instead of 8 per-branch reads, every row of the matrix-core
+ *                  tile used); the items are ordered (request, kv head, chunk,
+ *                  tile) and neighbours are served at the same time by waves of
+ *                  one workgroup / XCD, so the tiles' re-reads of a chunk hit in
+ *                  L2.  1 = the same with one block per (chunk, branch), G of 16
+ *                  tile rows used; natural-layout caches always use 1.  -1 =
+ *                  keep the current mode.  (A mode that staged each prompt chunk
+ *                  in LDS once per workgroup was measured 2.5 to 3 times slower
+ *                  on prompt-heavy workloads and is not in the library.)
+ *   skew_permille  work moved from odd to even workgroups, in 1/1000 of the
+ *                  mean per-wave range (workgroups go round-robin to the 8 XCDs,
+ *                  and the odd XCDs stream about 10 % slower); default 80,
+ *                  0 = equal. */
+sart_status sart_set_decode_launch(sart_cache* cache, int32_t n_workgroups, int32_t prompt_mode, int32_t skew_permille);
 
 /* Order of a wave's two parts in the matrix-core attention kernel, its share of
  * the prompts and its range of the branches' own pages.  on != 0 (default):

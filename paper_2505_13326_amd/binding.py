@@ -69,7 +69,7 @@ _SIGNATURES = {
     "sart_get_state": (C.c_int, [C.c_void_p] + [_ip] * 11),
     "sart_set_profiling": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_last_decode_ms": (C.c_int, [C.c_void_p, _fp, _fp]),
-    "sart_set_decode_launch": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "sart_set_decode_launch": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
     "sart_set_merge_mode": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_set_prompt_stagger": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_read_probe": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
@@ -339,7 +339,5 @@ class SartCache:
         self._check(self.lib.sart_last_decode_ms(self.h, C.byref(a), C.byref(t)))
         return a.value, t.value
 
-    def set_decode_launch(self, n_workgroups=0, n_prompt_workgroups=-1, prefix_chunk_pages=0, prompt_mode=-1,
-                          skew_permille=DEFAULT_SKEW_PERMILLE):
-        self._check(self.lib.sart_set_decode_launch(self.h, int(n_workgroups), int(n_prompt_workgroups),
-                                                    int(prefix_chunk_pages), int(prompt_mode), int(skew_permille)))
+    def set_decode_launch(self, n_workgroups=0, prompt_mode=-1, skew_permille=DEFAULT_SKEW_PERMILLE):
+        self._check(self.lib.sart_set_decode_launch(self.h, int(n_workgroups), int(prompt_mode), int(skew_permille)))

@@ -63,7 +63,7 @@ struct sart_cache {
   hipStream_t last_stream = nullptr;
   float* partials = nullptr;
   long long partial_cap = 0;
-  PlanCfg plan{0, 0, 0, 0, 0};         // launch shape of the decode plan
+  PlanCfg plan{0, 0, 0};               // launch shape of the decode plan
   int stagger_prompt = 1;              // see sart_set_prompt_stagger
   int merge_mode = 0;                  // 1: merged inside the attention kernel where it can be, 0: by the merge kernel (faster, measured)
   int max_wg = 0;
@@ -207,11 +207,6 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   ALLOC(tb.req_first, R); ALLOC(tb.req_push_off, R); ALLOC(tb.req_touched, R);
   ALLOC(tb.ap_id, H); ALLOC(tb.ap_start, H);
   ALLOC(tb.page_cum, H + 1); ALLOC(tb.live_req, R); ALLOC(tb.live_item_start, R + 1);
-  {
-    const size_t max_items = R * dm.Hkv * ((dm.max_pp + kStagePages - 1) / kStagePages) *
-                             ((dm.Nb + kAttnWaves - 1) / kAttnWaves);
-    ALLOC(tb.item_desc, 8 * max_items);
-  }
 
   if (d->kv_pool) {
     c->ctx.pool = d->kv_pool;
@@ -230,11 +225,8 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   c->max_wg = cus * 16;
   c->plan.n_wg = cus;                // one 4-wave workgroup per CU, one wave per SIMD
-  c->plan.n_wg_prompt = 0;           // every wave serves the own line, then the prompt line
-  c->plan.chunk_pages = 0;
-  // prompt blocks read once per tile of 16 query rows of the request (matrix-core layouts), per branch otherwise:
-  // measured faster than the LDS-staged prompt phase on every config
-  c->plan.inline_prefix = dm.layout == SART_LAYOUT_NATURAL ? 1 : 2;
+  // prompt blocks read once per tile of 16 query rows of the request (matrix-core layouts), per branch otherwise
+  c->plan.prompt_mode = dm.layout == SART_LAYOUT_NATURAL ? 1 : 2;
   c->plan.skew_permille = kDefaultSkewPermille;
   ALLOC(tb.wave_row, (size_t)2 * c->max_wg * kAttnWaves);
   ALLOC(tb.req_pstart, R);
@@ -242,12 +234,10 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   ALLOC(tb.row_desc, 8 * H);
   ALLOC(tb.seg_count, H * dm.Hkv);
   HIP_TRY(hipMemset(tb.seg_count, 0, H * dm.Hkv * sizeof(int)));
-  // partial slots: one per private wave, one per (row, kv head) crossing, and
-  // the prompt chunks of every (row, kv head) at the smallest chunk size
-  const long long S = (long long)H * dm.Hkv;
-  const long long npc_max = (dm.max_pp + kStagePages - 1) / kStagePages;
-  // own pieces (ranges + segments), then prompt blocks (at least 4 pages each) or LDS prompt chunks
-  c->partial_cap = (long long)c->max_wg * kAttnWaves + S * (1 + npc_max + 1);
+  // partial slots: one per own range (wave), one per (row, kv head) a range boundary falls in, and the prompts'
+  // blocks, which the planning kernel keeps to max(S, 4 per wave)
+  const long long S = (long long)H * dm.Hkv, max_waves = (long long)c->max_wg * kAttnWaves;
+  c->partial_cap = max_waves + S + (S > 4 * max_waves ? S : 4 * max_waves);
   const long long pf = (long long)dm.G * dm.d + ((2 * dm.G + 3) & ~3);
   ALLOC(c->partials, (size_t)(c->partial_cap * pf));
 #undef ALLOC
@@ -397,7 +387,7 @@ static sart_status decode_common(sart_cache* c, int32_t layer, const void* q, fl
   a.scale_log2 = scale * 1.44269504088896340736f * c->k_scale;
   a.v_scale = c->v_scale;
   a.n_wg = c->plan.n_wg;
-  a.inline_prefix = c->plan.inline_prefix;
+  a.prompt_mode = c->plan.prompt_mode;
   a.partials = partials; a.partial_cap = partial_cap; a.seg_count = seg_count;
   a.fused_merge = c->merge_mode;
   a.stagger_prompt = c->stagger_prompt;
@@ -430,8 +420,6 @@ sart_status sart_decode_attention_static(sart_cache* c, int32_t layer, const voi
   sart_status rc = check_decode_args(c, layer, q, out, n_rows);
   if (rc != SART_OK) return rc;
   const Dims& dm = c->ctx.dm;
-  if (c->plan.inline_prefix == 0)
-    return fail(SART_E_INVALID, "sart_decode_attention_static does not run the LDS-staged prompt mode");
   // the current device's copy of the scratch array (looked up once per device)
   int dev = -1;
   void* scratch_ptr = nullptr;
@@ -686,26 +674,17 @@ sart_status sart_set_merge_mode(sart_cache* c, int32_t in_kernel) {
   return SART_OK;
 }
 
-sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t n_prompt_workgroups,
-                                   int32_t prefix_chunk_pages, int32_t prompt_mode, int32_t skew_permille) {
+sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t prompt_mode, int32_t skew_permille) {
   if (!c) return fail(SART_E_INVALID, "null cache");
-  if (prompt_mode < -1 || prompt_mode > 2) return fail(SART_E_INVALID, "prompt_mode must be -1, 0, 1 or 2");
+  if (prompt_mode != -1 && prompt_mode != 1 && prompt_mode != 2) return fail(SART_E_INVALID, "prompt_mode must be -1, 1 or 2");
   if (skew_permille < -500 || skew_permille > 500) return fail(SART_E_INVALID, "skew_permille out of range");
   if (n_workgroups > c->max_wg) return fail(SART_E_INVALID, "at most %d workgroups", c->max_wg);
   hipDeviceProp_t prop;
   HIP_TRY(hipGetDeviceProperties(&prop, c->device));
   const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  const int n_wg = n_workgroups > 0 ? n_workgroups : cus;
-  const int n_pw = n_prompt_workgroups >= 0 ? n_prompt_workgroups : 0;
-  if (n_pw >= n_wg && n_pw > 0) return fail(SART_E_INVALID, "n_prompt_workgroups must leave a streaming workgroup");
-  if (prompt_mode >= 0) {
-    const int layout = c->ctx.dm.layout;   // natural layout: per-branch blocks only; 8-bit float: no LDS staging
-    c->plan.inline_prefix = layout == SART_LAYOUT_NATURAL ? 1 : (layout == SART_LAYOUT_MFMA16_FP8 && prompt_mode == 0 ? 1 : prompt_mode);
-  }
+  if (prompt_mode >= 0) c->plan.prompt_mode = c->ctx.dm.layout == SART_LAYOUT_NATURAL ? 1 : prompt_mode;   // natural layout: per-branch blocks only
   c->plan.skew_permille = skew_permille;
-  c->plan.n_wg = n_wg;
-  c->plan.n_wg_prompt = n_pw;
-  c->plan.chunk_pages = prefix_chunk_pages > 0 ? prefix_chunk_pages : 0;
+  c->plan.n_wg = n_workgroups > 0 ? n_workgroups : cus;
   launch_plan(c->ctx, c->plan, c->last_stream);   // the plan follows the launch shape
   HIP_TRY(hipGetLastError());
   return SART_OK;

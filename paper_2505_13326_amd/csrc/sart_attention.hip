@@ -23,9 +23,10 @@
 //     query rows of the request (rows = (branch, head of the GQA group)), the
 //     work items ordered (request, kv head, chunk, tile) and served by every
 //     wave before its own range, so the tiles' re-reads of a chunk are
-//     neighbours in time and on one XCD and hit in its L2 (default).  Other
-//     modes: one block per (chunk, branch); or each prompt chunk staged in LDS
-//     once per workgroup for the request's branches, one wave each.
+//     neighbours in time and on one XCD and hit in its L2 (default).  The
+//     other mode: one block per (chunk, branch).  (Staging prompt chunks in LDS
+//     was built and measured: 2.5 to 3 times slower on the prompt-heavy
+//     workloads and about twice the fetches; it is not in the library.)
 #include <mutex>
 #include <type_traits>
 
@@ -33,11 +34,15 @@
 
 namespace sart {
 
+// A prompt of pp pages is read in nck = ceil(pp / pb) chunks (pb: the plan's block size); the chunks are made
+// equal, ceil(pp / nck) pages rounded up to whole rings of 4 (never more than pb, so still nck chunks), rather
+// than nck - 1 of pb pages and a short one: the work items over the chunks then take the same time.
+__device__ inline int prompt_chunk_pages(int pp, int nck) { return ceil_div(ceil_div(pp, nck), 4) * 4; }
+
 // partial slots the current plan writes: own pieces (one per range and per (row, kv head) it crosses),
-// then the prompts' blocks (inline modes) or LDS-staged chunks
-__device__ inline long long slots_needed(const int* scal, int Hkv, int inline_prefix) {
-  const long long S = (long long)scal[S_D_NA] * Hkv;
-  return (long long)scal[S_D_NOWN] + S + (inline_prefix ? (long long)scal[S_D_NBLOCKS] : S * scal[S_D_NPC]);
+// then the prompts' blocks
+__device__ inline long long slots_needed(const int* scal, int Hkv) {
+  return (long long)scal[S_D_NOWN] + (long long)scal[S_D_NA] * Hkv + (long long)scal[S_D_NBLOCKS];
 }
 
 template <int D>
@@ -207,23 +212,18 @@ __device__ inline void finish_piece(const DecodeArgs& a, const Dims& dm, const C
 // One 4-wave workgroup per CU, one wave per SIMD: two waves on a SIMD do not
 // share it fairly (the older one streams about 1.5x faster, measured), which a
 // static partition cannot absorb; memory-level parallelism comes from the
-// per-wave ring of page buffers instead.  Each workgroup has an LDS prompt phase
-// (its items of the plan, K/V staged through LDS, one wave per branch; empty when
-// the prompt is read inline, the default) and a streaming phase (each wave
-// streams its prompt blocks, then its range of the own line).  With LDS prompt
-// items, even workgroups run that phase first, odd ones last, so that the
-// latency-bound phases do not all idle HBM at once.
+// per-wave ring of page buffers instead.  Every wave serves its share of the
+// prompt work items and its range of the own line.
 // bt0 / bt1 are the two block-table buffers again, as noalias kernel arguments:
 // the compiler may then read page ids with scalar loads, which do not queue
 // behind the in-flight vector loads of K/V tiles.
 // ---------------------------------------------------------------------------
 // FP8: an 8-bit float cache (SART_LAYOUT_MFMA16_FP8): half the bytes per tile, expanded
-// to bf16 operands in registers; its prompts are always read inline.
+// to bf16 operands in registers.
 template <int D, bool FP8>
 __global__ void __launch_bounds__(kAttnThreads)
 k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restrict__ bt1,
-            const int* __restrict__ item_desc, const int* __restrict__ prefix_table, const int* __restrict__ wave_desc,
-            const int* __restrict__ row_desc) {
+            const int* __restrict__ prefix_table, const int* __restrict__ wave_desc, const int* __restrict__ row_desc) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
@@ -233,113 +233,26 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
                                                    // measured; 8 on 8-bit float caches is slower)
   constexpr int kTileBytes = 16 * D * (FP8 ? 1 : 2);   // one K (or V) tile
   constexpr int kPageBytes = 2 * kTileBytes;       // K tile + V tile of one kv head
-  constexpr int kRound = kAttnThreads * 16;                // bytes one load round of the workgroup covers
-  constexpr int kCPT = (kPageBytes + kRound - 1) / kRound; // staged 16-byte chunks per thread per page
-  __shared__ __attribute__((aligned(16))) unsigned char lds_kv[2][kStagePages][kPageBytes];
 
   const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nA = scal[S_D_NA];
-  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != (int)gridDim.x || slots_needed(scal, dm.Hkv, a.inline_prefix) > a.partial_cap) {
+  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != (int)gridDim.x || slots_needed(scal, dm.Hkv) > a.partial_cap) {
     // a row buffer smaller than the active list, a launch that does not match the plan, or a scratch
     // buffer too small for the plan's partial results
     if (blockIdx.x == 0 && threadIdx.x == 0) record_error(scal, SART_E_INVALID, a.call_seq);
     return;
   }
-  const int chunk = scal[S_D_CHUNK], npc = scal[S_D_NPC];
-  const int n_items = scal[S_D_NITEMS];
   const long long S = (long long)nA * dm.Hkv;
   const int n_waves = gridDim.x * kAttnWaves;
-  const long long prompt_slot_base = (long long)scal[S_D_NOWN] + S;                        // inline prompt pieces
-  const long long prefix_base = (long long)scal[S_D_NOWN] + S;                             // LDS prompt chunks (the other mode)
+  const long long prompt_slot_base = (long long)scal[S_D_NOWN] + S;
   const uint16_t* q = (const uint16_t*)a.q;
   const unsigned char* pool = (const unsigned char*)c.pool;
   const int* __restrict__ bt = scal[S_BTSEL] ? bt1 : bt0;
-  // workgroup role (see Cut): streaming workgroups come first in the grid
-  const int n_own_wg = scal[S_D_NOWN] / kAttnWaves;
-  const bool dedicated = n_own_wg < (int)gridDim.x;
-  const bool prompt_wg = (int)blockIdx.x >= n_own_wg;
-  const bool prompt_first = (blockIdx.x & 1) == 0;
   WaveState<D> st;
   uint4 qreg[KQ];
 
-  for (int phase = 0; phase < 2; ++phase) {
-    if ((phase == 0) == prompt_first) {
-      // ---- shared prompt items (LDS prompt mode) ----------------------------
-      if (FP8 || (dedicated && !prompt_wg)) continue;
-      const int it0 = dedicated ? (int)blockIdx.x - n_own_wg : (int)blockIdx.x;
-      const int it_step = dedicated ? (int)gridDim.x - n_own_wg : (int)gridDim.x;
-      for (int it = it0; it < n_items; it += it_step) {
-        const int4 d0 = *(const int4*)(item_desc + 8LL * it);
-        const int4 d1 = *(const int4*)(item_desc + 8LL * it + 4);
-        const int first = d0.x, cnt = d0.y, plen = d0.z, h = d0.w, ck = d1.x, bg = d1.y, r = d1.z;
-        const int pp = ceil_div(plen, 16);
-        const int p0 = ck * chunk, p1 = min(pp, p0 + chunk);
-        const int slot_in_req = bg * kAttnWaves + wv;
-        const bool have_row = slot_in_req < cnt;
-        const int row = first + slot_in_req;
-        const int* __restrict__ ptab = prefix_table + (long long)r * dm.max_pp;
-        if (have_row) { load_q<D>(qreg, q, dm, row, h); st.reset(); }
-
-        const int nst = ceil_div(p1 - p0, kStagePages);
-        uint4 greg[kStagePages][kCPT];
-        auto g_load = [&](int stg) {
-#pragma unroll
-          for (int k = 0; k < kStagePages; ++k) {
-            const int p = p0 + stg * kStagePages + k;
-            if (p < p1) {
-              const unsigned char* src = pool + tile_base(dm, ptab[p], h) * 2 + threadIdx.x * 16;
-#pragma unroll
-              for (int j = 0; j < kCPT; ++j)
-                if (j * kRound + (int)threadIdx.x * 16 < kPageBytes) greg[k][j] = *(const uint4*)(src + j * kRound);
-            }
-          }
-        };
-        auto l_store = [&](int stg) {
-#pragma unroll
-          for (int k = 0; k < kStagePages; ++k) {
-            const int p = p0 + stg * kStagePages + k;
-            if (p < p1) {
-#pragma unroll
-              for (int j = 0; j < kCPT; ++j)
-                if (j * kRound + (int)threadIdx.x * 16 < kPageBytes)
-                  *(uint4*)(&lds_kv[stg & 1][k][j * kRound + threadIdx.x * 16]) = greg[k][j];
-            }
-          }
-        };
-        __syncthreads();   // the previous item's readers are done with both buffers
-        g_load(0);
-        l_store(0);
-        __syncthreads();
-        for (int stg = 0; stg < nst; ++stg) {
-          if (stg + 1 < nst) g_load(stg + 1);
-          if (have_row) {
-#pragma unroll
-            for (int k = 0; k < kStagePages; ++k) {
-              const int p = p0 + stg * kStagePages + k;
-              if (p < p1) {
-                uint4 kq[KQ], vq[KQ];
-#pragma unroll
-                for (int i = 0; i < KQ; ++i) {
-                  kq[i] = *(const uint4*)(&lds_kv[stg & 1][k][i * 1024 + lane * 16]);
-                  vq[i] = *(const uint4*)(&lds_kv[stg & 1][k][kTileBytes + i * 1024 + lane * 16]);
-                }
-                const int nvalid = min(16, plen - p * 16);
-                if (nvalid == 16) process_page<D, true>(st, kq, vq, qreg, 16, 16, a.scale_log2);
-                else process_page<D, false>(st, kq, vq, qreg, nvalid, nvalid, a.scale_log2);
-              }
-            }
-          }
-          if (stg + 1 < nst) l_store(stg + 1);
-          __syncthreads();
-        }
-        if (have_row)
-          store_partial<D, false>(st, a.partials, prefix_base + ((long long)row * dm.Hkv + h) * npc + ck, dm);
-      }
-      continue;
-    }
-
-    // ---- streaming phase: this wave's range of the own line and / or of the
-    //      prompt line (inline prompt mode); one partial per piece ---------------
+  {
+    // ---- this wave's prompt work items and its range of the own line; one partial result per piece -------
     const Cut cut = load_cut(scal);
     const long long wave_id = (long long)blockIdx.x * kAttnWaves + wv;
     // where the wave starts, resolved by the planning kernel: one load instead of a chain of lookups
@@ -430,7 +343,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         //      to 16 * kSharedBlocks query rows); its pages are read once and every page feeds the tile's
         //      blocks (rows = (branch, head of the group), branch-major).  One partial per (branch, kv head,
         //      chunk), in the slots the per-branch blocks would have used. -------------------------------
-        if (a.inline_prefix == 2 && wave_id >= n_waves - cut.n_prompt) {
+        if (a.prompt_mode == 2 && wave_id >= n_waves - cut.n_prompt) {
           const int r16 = lane & 15, g4 = lane >> 4;
           const long long pf = partial_floats(dm.G, D);
           int cursor = wd3.z;
@@ -449,7 +362,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
             const int rows = cnt * dm.G, ntile = ceil_div(rows, 16 * kSharedBlocks);
             const int local = (int)(item - istart);
             const int rt = local % ntile, ck = (local / ntile) % nck, h = local / (ntile * nck);
-            const int r0 = ck * cut.pb, rn = min(cut.pb, pp - r0);
+            const int cs = prompt_chunk_pages(pp, nck), r0 = ck * cs, rn = min(cs, pp - r0);
             const int n_last = min(16, plen - (r0 + rn - 1) * 16);
             const int row0 = rt * 16 * kSharedBlocks;
             const int nb = min(kSharedBlocks, ceil_div(rows - row0, 16));          // blocks with rows (wave-uniform)
@@ -541,7 +454,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
 
         // ---- per-branch prompt blocks (prompt mode 1): block u is (request, kv head, chunk, branch); served before
         //      the own range, all waves at the same time, so that the branches' re-reads of a chunk hit in L2 -----
-        if (a.inline_prefix == 1 && wave_id >= n_waves - cut.n_prompt) {
+        if (a.prompt_mode == 1 && wave_id >= n_waves - cut.n_prompt) {
           const long long i = wave_id - (n_waves - cut.n_prompt);
           int cursor = tb.wave_row[n_waves + i];                       // live request index
           for (long long u = prompt_range_of_wave(i, cut.n_prompt); u < cut.n_blocks; u += cut.n_prompt) {
@@ -551,7 +464,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
             const int pp = ceil_div(plen, 16), nck = ceil_div(pp, cut.pb);
             const int local = (int)(u - tb.live_item_start[cursor]);
             const int j = local % cnt, ck = (local / cnt) % nck, h = local / (cnt * nck);
-            const int r0 = ck * cut.pb, rn = min(cut.pb, pp - r0);
+            const int cs = prompt_chunk_pages(pp, nck), r0 = ck * cs, rn = min(cs, pp - r0);
             const int row = tb.req_first[r] + j;
             RowInfo ri{};
             if (a.fused_merge) ri = load_row_info(row_desc, row);
@@ -613,7 +526,7 @@ k_attn_generic(Ctx c, DecodeArgs a) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
-  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != (int)gridDim.x || slots_needed(scal, dm.Hkv, 1) > a.partial_cap) {
+  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != (int)gridDim.x || slots_needed(scal, dm.Hkv) > a.partial_cap) {
     if (blockIdx.x == 0 && threadIdx.x == 0) record_error(scal, SART_E_INVALID, a.call_seq);
     return;
   }
@@ -670,8 +583,9 @@ k_attn_generic(Ctx c, DecodeArgs a) {
         const int local = (int)(u - tb.live_item_start[cursor]);
         const int j = local % cnt, ck = (local / cnt) % nck;
         h = local / (cnt * nck);
-        r0 = ck * cut.pb;
-        rn = min(cut.pb, pp - r0);
+        const int cs = prompt_chunk_pages(pp, nck);
+        r0 = ck * cs;
+        rn = min(cs, pp - r0);
         row = tb.req_first[r] + j;
         table = tb.prefix_table + (long long)r * dm.max_pp;
         slot = prompt_slot_base + u;
@@ -705,38 +619,27 @@ k_attn_generic(Ctx c, DecodeArgs a) {
 // The loads of successive partials are independent, so they overlap.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-k_merge(Ctx c, DecodeArgs a, int inline_prefix) {
+k_merge(Ctx c, DecodeArgs a) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   const int* scal = tb.scal;
-  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != a.n_wg || slots_needed(scal, dm.Hkv, inline_prefix) > a.partial_cap) return;
+  if (a.n_rows < scal[S_NACTIVE] || scal[S_D_NWG] != a.n_wg || slots_needed(scal, dm.Hkv) > a.partial_cap) return;
   const int nA = scal[S_D_NA];
-  const int chunk = scal[S_D_CHUNK], npc = scal[S_D_NPC];
   const Cut cut = load_cut(scal);
   const int D = dm.d, G = dm.G, D4 = D >> 2;
   const long long pf = partial_floats(G, D);
   const long long S = (long long)nA * dm.Hkv;
   const long long prompt_slot_base = (long long)cut.n_own + S;
-  const long long prefix_base = (long long)cut.n_own + S;
   for (long long seg = blockIdx.x; seg < S; seg += gridDim.x) {
     const int row = (int)(seg / dm.Hkv), h = (int)(seg % dm.Hkv);
-    // slot ranges: [pa, pa+pn) prompt pieces or chunks, [sa, sa+sn) own pieces; the row's facts come from the
-    // plan's descriptor (one load), so that the partial results can be requested right after it
+    // slot ranges: [pa, pa + pn * pstride) prompt pieces (one block per prompt chunk: first slot of the row +
+    // (head * chunks + chunk) * branches), [sa, sa + sn) own pieces; the row's facts come from the plan's
+    // descriptor (one load), so that the partial results can be requested right after it
     const RowInfo ri = load_row_info(tb.row_desc, row);
-    long long pa = 0, sa = 0, pstride = 1, w0;
-    int pn = 0, sn;
-    if (inline_prefix) {
-      // one block per prompt chunk: first slot of the row + (head * chunks + chunk) * branches
-      pn = ri.nck;
-      pstride = ri.cnt;
-      pa = prompt_slot_base + ri.pslot + (long long)h * ri.nck * ri.cnt;
-    } else {
-      const int pp = ceil_div(tb.prefix_len[tb.active[row] / dm.Nb], dm.pt);
-      if (pp > 0) {
-        pn = ceil_div(pp, chunk);
-        pa = prefix_base + seg * npc;
-      }
-    }
+    const int pn = ri.nck;
+    const long long pstride = ri.cnt, pa = prompt_slot_base + ri.pslot + (long long)h * ri.nck * ri.cnt;
+    long long sa, w0;
+    int sn;
     own_pieces(cut, dm.Hkv, ri, h, w0, sn);
     sa = w0 + seg;
     for (int e = threadIdx.x; e < G * D4; e += blockDim.x) {
@@ -751,9 +654,9 @@ void launch_decode(const Ctx& c, const DecodeArgs& a_in, hipStream_t s) {
   const Dims& dm = c.dm;
   const bool mfma = dm.layout != SART_LAYOUT_NATURAL;
   DecodeArgs a = a_in;
-  // the matrix-core kernel merges in its own last writers when the prompts are read inline; the LDS prompt
-  // mode and the generic kernel leave their partial results to the merge kernel
-  a.fused_merge = a_in.fused_merge && mfma && a.inline_prefix != 0;
+  // the matrix-core kernel can merge in its own last writers; the generic kernel always leaves its partial
+  // results to the merge kernel
+  a.fused_merge = a_in.fused_merge && mfma;
   if (a.ev[0]) (void)hipEventRecord(a.ev[0], s);
   if (a.ev[1]) (void)hipEventRecord(a.ev[1], s);
   // profiling with repeats > 1 launches the (idempotent) attention kernel that many times
@@ -761,7 +664,7 @@ void launch_decode(const Ctx& c, const DecodeArgs& a_in, hipStream_t s) {
   for (int rep = 0; rep < (a.repeats > 1 ? a.repeats : 1); ++rep) {
   if (mfma) {
     auto go = [&](auto kern) {
-      hipLaunchKernelGGL(kern, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], c.tb.bt[1], c.tb.item_desc,
+      hipLaunchKernelGGL(kern, dim3(a.n_wg), dim3(kAttnThreads), 0, s, c, a, c.tb.bt[0], c.tb.bt[1],
                          c.tb.prefix_table, c.tb.wave_desc, c.tb.row_desc);
     };
     const bool fp8 = dm.layout == SART_LAYOUT_MFMA16_FP8;
@@ -777,7 +680,7 @@ void launch_decode(const Ctx& c, const DecodeArgs& a_in, hipStream_t s) {
   if (!a.fused_merge) {
     long long blocks = (long long)dm.H * dm.Hkv;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(k_merge, dim3((unsigned)blocks), dim3(256), 0, s, c, a, a.inline_prefix);
+    hipLaunchKernelGGL(k_merge, dim3((unsigned)blocks), dim3(256), 0, s, c, a);
   }
   if (a.ev[3]) (void)hipEventRecord(a.ev[3], s);
 }

@@ -82,19 +82,15 @@ __device__ inline void record_error(int* scal, int code, int call_seq) {
 //
 //   page_cum[a]   exclusive scan over active rows of their private pages; the
 //                 own line has page_cum[nA] * Hkv units.
-//   prompt blocks (inline prompt mode) blocks of pb pages, pb sized so that the
+//   prompt blocks blocks of pb pages, pb sized so that the
 //                 blocks about fill the prompt waves once; request r owns blocks
 //                 req_pstart[r] + ((head * chunks + chunk) * branches + branch);
 //                 live_req[k] lists the live requests with a prompt in active
-//                 order, live_item_start[k] their first block.
+//                 order, live_item_start[k] their first work item (a block, or, with
+//                 shared rows, a (request, kv head, chunk, row tile)).
 //   cut           see Cut; wave_row[w] = active row holding the first unit of own
 //                 range w; wave_row[n_waves + i] = index k of the live request
-//                 owning the first block of prompt wave i.
-//   items         (LDS prompt mode) shared-prompt work: one per (live request,
-//                 kv head, prompt chunk, group of kAttnWaves branches), eight
-//                 ints each: {first row, live branches, prompt tokens, kv head,
-//                 chunk, group, request, 0}; the chunk is sized so that the
-//                 items about fill the prompt workgroups once.
+//                 owning the first work item of wave i.
 // ---------------------------------------------------------------------------
 constexpr int kPlanLdsRows = 4096;   // active rows whose page_cum and lengths the plan keeps in LDS
 constexpr int kPlanLdsLive = 1024;   // live requests whose fields the plan keeps in LDS
@@ -104,7 +100,6 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   const Tables& tb = c.tb;
   int* scal = tb.scal;
   const int tid = threadIdx.x;
-  __shared__ int s_npc;
   __shared__ int s_scan[3 * 17];
   __shared__ int s_cum[kPlanLdsRows + 1];
   __shared__ int s_seq[kPlanLdsRows];         // tokens of the active rows
@@ -115,9 +110,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   (void)lds;
   __syncthreads();                       // the caller's table updates are visible
   const int nA = scal[S_NACTIVE];
-  if (tid == 0) s_npc = 0;
-  // w: weight of a live request with a prompt, on its first row.  Inline mode:
-  // its (branch, page) count on the prompt line; LDS mode: its item pages.
+  // w: weight of a live request with a prompt, on its first row: the prompt pages its work items read
   int carry = 0, w_carry = 0, l_carry = 0;
   for (int base = 0; base < nA; base += kPlanThreads) {
     const int i = base + tid;
@@ -133,11 +126,9 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
         plen = tb.prefix_len[r];
         cnt = tb.refcnt[r];
         const int pp = ceil_div(plen, dm.pt);
-        // pages a wave reads for the request's prompt, per kv head: once per branch, once per
-        // tile of 16 * kSharedBlocks query rows (shared rows), or (LDS mode) once per group of branches
-        w = pc.inline_prefix == 2 ? pp * ceil_div(cnt * dm.G, 16 * kSharedBlocks)
-            : pc.inline_prefix   ? pp * cnt
-                                 : pp * ceil_div(cnt, kAttnWaves) * dm.Hkv;
+        // pages read for the request's prompt, per kv head: once per tile of 16 * kSharedBlocks query
+        // rows (shared rows), or once per branch
+        w = pc.prompt_mode == 2 ? pp * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : pp * cnt;
         tb.req_first[r] = i;
       }
     }
@@ -164,12 +155,10 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   const int n_waves = pc.n_wg * kAttnWaves;
   Cut cut;
   cut.u_own = (long long)carry * dm.Hkv;
-  const long long u_prompt = pc.inline_prefix ? (long long)w_carry * dm.Hkv : 0;   // prompt units of the step
-  // workgroup roles: the last n_wg_prompt workgroups serve the prompt line (or the
-  // LDS-staged prompt items); with none dedicated every wave serves both lines
-  const int wg_prompt = pc.n_wg_prompt < pc.n_wg ? pc.n_wg_prompt : pc.n_wg - 1;
-  cut.n_own = (pc.n_wg - wg_prompt) * kAttnWaves;
-  cut.n_prompt = u_prompt > 0 ? (wg_prompt > 0 ? wg_prompt * kAttnWaves : n_waves) : 0;
+  const long long u_prompt = (long long)w_carry * dm.Hkv;   // prompt units of the step
+  // every wave serves both its share of the prompt work items and its range of the own line
+  cut.n_own = n_waves;
+  cut.n_prompt = u_prompt > 0 ? n_waves : 0;
   cut.pb = cut.n_prompt > 0 ? (int)((u_prompt + cut.n_prompt - 1) / cut.n_prompt) : 1;
   cut.pb = ceil_div(cut.pb < 1 ? 1 : cut.pb, 4) * 4;        // whole rings of page buffers
   cut.n_blocks = 0;
@@ -186,12 +175,8 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     cut.pe = per_wave + sk;
     cut.po = per_wave - sk;
   }
-  int chunk = pc.chunk_pages;
-  if (chunk <= 0) chunk = ceil_div(pc.inline_prefix ? 0 : w_carry, wg_prompt > 0 ? wg_prompt : pc.n_wg);
-  chunk = ceil_div(chunk < 1 ? 1 : chunk, kStagePages) * kStagePages;
   __syncthreads();                       // live_req, req_first, page_cum, req_pstart written
-  int n_items = 0;
-  if (pc.inline_prefix) {
+  {
     // first prompt block (partial slot) and first work item of every live request.  The blocks are the
     // prompts' partial results, one slot each: should there be more than max(4 per wave, one per (row, kv
     // head)), the block size is doubled until they fit (one block per prompt at the latest), so that
@@ -210,7 +195,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
           const int plen = in_lds ? s_lplen[k] : tb.prefix_len[r], cnt = in_lds ? s_lcnt[k] : tb.refcnt[r];
           const int nck = ceil_div(ceil_div(plen, dm.pt), cut.pb);
           blocks = dm.Hkv * nck * cnt;
-          items = pc.inline_prefix == 2 ? dm.Hkv * nck * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : blocks;
+          items = pc.prompt_mode == 2 ? dm.Hkv * nck * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : blocks;
         }
         int ex3[3], tot3[3];
         block_excl_scan3(blocks, items, 0, s_scan, ex3, tot3);
@@ -233,54 +218,19 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       if (n_live <= kPlanLdsLive) s_item[n_live] = i_carry;
     }
     __syncthreads();
-  } else {
-    // item offsets per live request
-    int i_carry = 0;
-    for (int base = 0; base < n_live; base += kPlanThreads) {
-      const int k = base + tid;
-      int items = 0;
-      if (k < n_live) {
-        const int r = tb.live_req[k];
-        const int nck = ceil_div(ceil_div(tb.prefix_len[r], dm.pt), chunk);
-        items = dm.Hkv * nck * ceil_div(tb.refcnt[r], kAttnWaves);
-        atomicMax(&s_npc, nck);
-      }
-      int ti;
-      const int ex = block_excl_scan(items, s_scan, ti);
-      if (k < n_live) tb.live_item_start[k] = i_carry + ex;
-      i_carry += ti;
-    }
-    n_items = i_carry;
-    if (tid == 0) tb.live_item_start[n_live] = n_items;
-    __syncthreads();
-    for (int it = tid; it < n_items; it += kPlanThreads) {
-      int lo = 0, hi = n_live - 1;
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (tb.live_item_start[mid] <= it) lo = mid; else hi = mid - 1;
-      }
-      const int r = tb.live_req[lo];
-      int local = it - tb.live_item_start[lo];
-      const int cnt = tb.refcnt[r], plen = tb.prefix_len[r];
-      const int nck = ceil_div(ceil_div(plen, dm.pt), chunk), ngr = ceil_div(cnt, kAttnWaves);
-      const int bg = local % ngr; local /= ngr;
-      int4* d = (int4*)(tb.item_desc + 8LL * it);
-      d[0] = make_int4(tb.req_first[r], cnt, plen, local / nck);
-      d[1] = make_int4(local % nck, bg, r, 0);
-    }
   }
   // What the pieces of a row need to merge in the attention kernel itself, 8 ints per active row:
   //   [0] page_cum of the row  [1] its private pages  [2] its private tokens
   //   [3] writers of prompt partial results per kv head: chunks x row tiles holding the branch's rows
-  //       (shared rows), chunks (per-branch blocks), 0 without a prompt or in the LDS prompt mode
+  //       (shared rows), chunks (per-branch blocks), 0 without a prompt
   //   [4] first prompt partial slot of the row, relative to the prompts' slots: chunk ck of kv head h is
   //       slot [4] + (h * [6] + ck) * [5]   [5] live branches of the request   [6] prompt chunks   [7] 0
   for (int i = tid; i < nA; i += kPlanThreads) {
     const int r = tb.active[i] / dm.Nb;
     const int j = i - tb.req_first[r], cnt = tb.refcnt[r];
     const int pp = ceil_div(tb.prefix_len[r], dm.pt);
-    const int nck = pc.inline_prefix && pp > 0 ? ceil_div(pp, cut.pb) : 0;
-    const int tiles = pc.inline_prefix == 2 ? ((j + 1) * dm.G - 1) / (16 * kSharedBlocks) - (j * dm.G) / (16 * kSharedBlocks) + 1 : 1;
+    const int nck = pp > 0 ? ceil_div(pp, cut.pb) : 0;
+    const int tiles = pc.prompt_mode == 2 ? ((j + 1) * dm.G - 1) / (16 * kSharedBlocks) - (j * dm.G) / (16 * kSharedBlocks) + 1 : 1;
     const int c0 = nA <= kPlanLdsRows ? s_cum[i] : tb.page_cum[i], c1 = nA <= kPlanLdsRows ? s_cum[i + 1] : tb.page_cum[i + 1];
     int4* rd = (int4*)(tb.row_desc + 8LL * i);
     rd[0] = make_int4(c0, c1 - c0, i < kPlanLdsRows ? s_seq[i] : tb.seq_len[i], nck * tiles);
@@ -293,7 +243,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   // loads before its first tile load:
   //   [0..3]   own range: active row of its first unit, page_cum of that row,
   //            private pages of the row, tokens of the row
-  //   [8..15]  first prompt item (inline modes): request, its live branches,
+  //   [8..15]  first prompt item: request, its live branches,
   //            prompt tokens, first active row, first partial slot of the
   //            request, first work item of the request, live request index,
   //            1 if the wave has an item
@@ -327,15 +277,13 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
           if (its[mid] <= b) lo = mid; else hi = mid - 1;
         }
         k = lo;
-        if (pc.inline_prefix) {
-          if (in_lds) {
-            d2 = make_int4(s_lreq[k], s_lcnt[k], s_lplen[k], s_lfirst[k]);
-            d3 = make_int4(s_lpstart[k], its[k], k, 1);
-          } else {
-            const int r = tb.live_req[k];
-            d2 = make_int4(r, tb.refcnt[r], tb.prefix_len[r], tb.req_first[r]);
-            d3 = make_int4(tb.req_pstart[r], its[k], k, 1);
-          }
+        if (in_lds) {
+          d2 = make_int4(s_lreq[k], s_lcnt[k], s_lplen[k], s_lfirst[k]);
+          d3 = make_int4(s_lpstart[k], its[k], k, 1);
+        } else {
+          const int r = tb.live_req[k];
+          d2 = make_int4(r, tb.refcnt[r], tb.prefix_len[r], tb.req_first[r]);
+          d3 = make_int4(tb.req_pstart[r], its[k], k, 1);
         }
       }
       tb.wave_row[n_waves + i] = k;
@@ -353,10 +301,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     scal[S_D_PB] = cut.pb;
     scal[S_D_NBLOCKS] = cut.n_blocks;
     scal[S_D_NPITEMS] = cut.n_pitems;
-    scal[S_D_NITEMS] = n_items;
     scal[S_D_NLIVE] = n_live;
-    scal[S_D_CHUNK] = chunk;
-    scal[S_D_NPC] = s_npc;
     scal[S_D_NWG] = pc.n_wg;
   }
   __syncthreads();

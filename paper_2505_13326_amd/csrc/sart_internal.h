@@ -13,7 +13,6 @@ constexpr int kWave = 64;
 constexpr int kPlanThreads = 1024;     // single-workgroup planning kernels
 constexpr int kAttnWaves = 4;          // waves per attention workgroup (one per SIMD, one workgroup per CU)
 constexpr int kAttnThreads = kAttnWaves * kWave;
-constexpr int kStagePages = 4;         // prefix pages staged in LDS per pipeline stage
 constexpr int kPfBlocks = 2;           // prefill: 16-row blocks per wave (two waves per SIMD fit the registers)
 constexpr int kPfTileRows = 16 * kPfBlocks * kAttnWaves;   // prefill: rows of one workgroup tile
 constexpr int kSharedBlocks = 1;       // shared-rows prompt mode: 16-row blocks of a row tile (1: every wave gets a
@@ -43,14 +42,11 @@ enum Scalar {
   S_APPENDOK,     // the last layer-0 append passed its validation and no call changed the state since
   S_D_PER_EVEN,   // units per wave of an even workgroup
   S_D_PER_ODD,    // units per wave of an odd workgroup
-  S_D_NITEMS,     // prefix workgroup items
   S_D_NLIVE,      // live requests with a non-empty prompt
-  S_D_CHUNK,      // prefix chunk in pages
-  S_D_NPC,        // prefix chunks per (row, kv head) slot stride
   S_D_NWG,        // attention workgroups the plan was made for
   S_D_UOWN,       // units of the own region (branches' private pages)
   S_D_NOWN,       // ranges (waves) serving the own region
-  S_D_NPROMPT,    // waves serving the prompt blocks (the last ones of the grid, or all)
+  S_D_NPROMPT,    // waves serving the prompt work items (all of them, or 0 without prompts)
   S_D_PB,         // pages per prompt block
   S_D_NBLOCKS,    // prompt blocks (partial slots of the prompts)
   S_D_NPITEMS,    // prompt work items of the streaming phase (= blocks unless rows are shared)
@@ -98,7 +94,6 @@ struct Tables {
   int* page_cum;         // [H+1] exclusive scan of private pages over active rows
   int* live_req;         // [max_req] live requests with prompt, active order
   int* live_item_start;  // [max_req+1] exclusive scan of prefix items
-  int* item_desc;        // [max items][8] shared-prompt work items
   int* wave_row;         // [max attention waves] own ranges: active row of the first unit; prompt ranges: live request index
   int* req_pstart;       // [max_req] first prompt block of the request
   int* wave_desc;        // [max attention waves][16] where each wave starts (see refresh_decode_plan)
@@ -109,12 +104,10 @@ struct Tables {
 // Launch shape the decode plan is made for (host-chosen, passed to every
 // planning kernel).
 struct PlanCfg {
-  int n_wg;           // persistent attention workgroups in total
-  int chunk_pages;    // prompt chunk in pages; <= 0: sized on the device
-  int inline_prefix;  // prompt mode: 0 staged in LDS, 1 blocks read by every branch, 2 blocks' pages read once for
-                      // all query rows of the request (shared rows)
+  int n_wg;           // persistent attention workgroups
+  int prompt_mode;    // how the prompts are read: 1 in blocks per (chunk, branch), 2 in blocks whose pages are read once
+                      // for a tile of 16 query rows of the request (shared rows)
   int skew_permille;  // even workgroups take (1000+skew)/1000 of the mean range, odd ones the rest
-  int n_wg_prompt;    // the last n_wg_prompt workgroups serve the shared prompts only (0: all do both)
 };
 
 struct Ctx {
@@ -128,13 +121,12 @@ struct Ctx {
 //   own line      every active row's private pages, ordered (row, kv head, page),
 //                 cut into one contiguous range per wave (a range may cross rows;
 //                 a long row is split over many waves).
-//   prompt blocks (inline prompt mode) every live request's prompt is read once
-//                 per branch, in blocks of pb pages ordered (request, kv head,
-//                 chunk, branch): the blocks of the request's branches for one
-//                 chunk are neighbours, go to waves of one workgroup (or of
-//                 workgroups on one XCD) and are read at the same time, at the
-//                 start of the kernel, so all but the first reader hit in cache.
-// Every wave serves its prompt block(s), then its own-line range.  Workgroups are
+//   prompt blocks every live request's prompt is read in blocks of pb pages,
+//                 once per branch or once per tile of 16 query rows of the
+//                 request; the work items over one chunk are neighbours, go to
+//                 waves of one workgroup (or of workgroups on one XCD) and are
+//                 read at the same time, so all but the first reader hit in cache.
+// Every wave serves its prompt work item(s) and its own-line range.  Workgroups are
 // dispatched round-robin over the 8 XCDs and on MI355X the odd XCDs stream
 // measurably slower than the even ones, so own ranges come in pairs of
 // workgroups: waves of an even workgroup take pe units, those of the following
@@ -143,7 +135,7 @@ struct Cut {
   int pe, po;            // units per own range of even / odd workgroups
   long long u_own;       // units on the own line
   int n_own;             // ranges [0, n_own) serve the own line
-  int n_prompt;          // waves serving prompt blocks: the last n_prompt of the grid
+  int n_prompt;          // waves serving prompt work items (all, or 0)
   int pb;                // pages per prompt block
   int n_blocks;          // prompt blocks; block b's partial goes to slot n_own + S + b
   int n_pitems;          // prompt work items: the blocks themselves, or (request, kv head, chunk, row tile)
@@ -231,7 +223,7 @@ struct DecodeArgs {
   int n_rows;
   float scale_log2;     // scale * log2(e)
   int n_wg;             // persistent attention workgroups (the plan's)
-  int inline_prefix;    // the plan's prompt mode
+  int prompt_mode;      // the plan's prompt mode (1 or 2)
   float* partials;      // scratch
   long long partial_cap; // partial slots available
   int* seg_count;       // scratch: arrival counters of the in-kernel merge, one per (row, kv head), zero between kernels

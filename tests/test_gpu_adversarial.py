@@ -2,7 +2,7 @@
 partial results: running maxima that rise with every page, pieces whose maxima
 are tens of binary orders apart, weights that underflow, one dominant key at the
 very end of a long branch, equal keys, a context of a single prompt token, and
-one very long branch beside many short ones.  Each case runs under the three
+one very long branch beside many short ones.  Each case runs under the two
 ways the matrix-core kernel reads the shared prompt and is compared with the
 float64 oracle (and with the closed form where there is one) at the bf16 bound."""
 import numpy as np
@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 HQ, HKV, D = 28, 4, 128
 G = HQ // HKV
-PROMPT_MODES = {"lds": 0, "per-branch": 1, "shared-rows": 2}
+PROMPT_MODES = {"per-branch": 1, "shared-rows": 2}
 
 
 def _bf16(x):
@@ -44,7 +44,7 @@ def _check(o, g, q, mode, launches=((0, 80), (64, 0), (7, 300))):
     ref = o.attention(q)
     worst = 0.0
     for n_wg, skew in launches:
-        g.c.set_decode_launch(n_wg, 0, 0, PROMPT_MODES[mode], skew)
+        g.c.set_decode_launch(n_wg, PROMPT_MODES[mode], skew)
         outs = []
         for in_kernel in (False, True):           # merged by the merge kernel / by the attention kernel's last writers
             g.c.set_merge_mode(in_kernel)

@@ -90,7 +90,7 @@ def test_fp8_decode_and_prefill_small(shape, scales):
     for e in (o, g):
         assert e.append(orc.SEQ_BRANCH, None, None, k[act], v[act]) == orc.OK
     for n_wg, pmode in ((3, 1), (64, 2), (256, 1), (256, 2)):      # prompt blocks per branch / shared by the request's rows
-        g.c.set_decode_launch(n_wg, 0, 0, pmode, 50)
+        g.c.set_decode_launch(n_wg, pmode, 50)
         compare_attention(cfg, o, g, wl.query(cfg, 1), tol=TOL_FP8)
     # prefill over the same prompts
     q = wl.prefix_query(cfg, 1)

@@ -118,7 +118,7 @@ def test_cfg1_tiny_decode_prune_decode():
     print(f"cfg1 max abs err {e1:.3g} / {e2:.3g}")
 
 
-@pytest.mark.parametrize("mode", ["mfma16-lds", "mfma16-inline", "mfma16-shared", "natural"])
+@pytest.mark.parametrize("mode", ["mfma16-per-branch", "mfma16-shared-rows", "natural"])
 @pytest.mark.parametrize("shape", [(28, 4, 128), (40, 8, 128), (8, 2, 64), (16, 1, 128), (64, 8, 128)],
                          ids=["g7", "g5", "g4d64", "g16", "g8-70b"])
 def test_bf16_small_all_rows(shape, mode):
@@ -134,15 +134,15 @@ def test_bf16_small_all_rows(shape, mode):
     o, g = _pair(cfg, wl.pages_needed(cfg, L) + 4, int(-(-L.max() // 16)) + 1,
                  free_order=wl.free_order(cfg, wl.pages_needed(cfg, L) + 4), force_natural_layout=natural)
     assert g.c.layout == (0 if natural else 1)
-    pmode = {"mfma16-lds": 0, "mfma16-inline": 1, "mfma16-shared": 2, "natural": 1}[mode]
+    pmode = {"mfma16-per-branch": 1, "mfma16-shared-rows": 2, "natural": 1}[mode]
     g.c.set_decode_launch(prompt_mode=pmode)
     populate(cfg, [o, g], L)
     assert_state_equal(o.state(), g.state())
     err = compare_attention(cfg, o, g, wl.query(cfg, 0))
     print(f"shape {shape} {mode}: max abs err {err:.3g}")
     # other launch shapes cut the unit line elsewhere; the result must not depend on it
-    for n_wg, n_pw, chunk, skew in ((3, 1, 4, 45), (64, 0, 8, 300), (1000, 900, 0, -200), (256, -1, 0, 0), (1, 0, 0, 50)):
-        g.c.set_decode_launch(n_wg, n_pw, chunk, pmode, skew)
+    for n_wg, skew in ((3, 45), (64, 300), (1000, -200), (256, 0), (1, 50)):
+        g.c.set_decode_launch(n_wg, pmode, skew)
         for in_kernel in (False, True):        # the merge kernel / the attention kernel's last writers
             g.c.set_merge_mode(in_kernel)
             compare_attention(cfg, o, g, wl.query(cfg, 1))

@@ -74,7 +74,3 @@ def test_static_scratch_refuses_what_does_not_fit():
     # the same cache with a row buffer the array can serve is accepted (no active branch: nothing to write)
     big.decode_attention(q[:256], out=out[:256], static_scratch=True)
     assert big.sync_status() == 0 and torch.all(out == 3.0)
-    # the LDS-staged prompt mode is not served
-    big.set_decode_launch(prompt_mode=0)
-    with pytest.raises(sart.SartError):
-        big.decode_attention(q[:256], out=out[:256], static_scratch=True)
