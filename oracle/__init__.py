@@ -16,7 +16,7 @@ _SRC = os.path.join(_DIR, "sart_oracle.c")
 _LIB = os.path.join(_DIR, "libsart_oracle.so")
 
 OK, E_INVALID, E_OOM_PAGES, E_STATE = 0, 1, 2, 3
-UNUSED, ACTIVE, COMPLETED, PRUNED, EARLY_STOPPED = range(5)
+UNUSED, ACTIVE, COMPLETED, PRUNED, EARLY_STOPPED, WAITING = range(6)
 SEQ_PREFIX, SEQ_BRANCH = 0, 1
 DROP_LOWEST_K, KEEP_TOP_K, THRESHOLD = 0, 1, 2
 
@@ -45,6 +45,8 @@ def _load():
         L.orc_attention.argtypes = [vp, vp, C.c_int, C.c_double, ip, C.c_int, dp, dp]
         L.orc_prefill_attention.argtypes = [vp, C.c_int, vp, C.c_int, C.c_double, dp, dp]
         L.orc_finish.argtypes = [vp, C.c_int, ip]
+        L.orc_start.argtypes = [vp, C.c_int, ip]
+        L.orc_set_start_waiting.argtypes = [vp, C.c_int]
         L.orc_set_fp8.argtypes = [vp, C.c_double, C.c_double]
         L.orc_fp8_roundtrip.argtypes = [vp, C.c_int, C.c_double, vp, vp]
         L.orc_fp8_roundtrip.restype = None
@@ -87,7 +89,7 @@ class OracleCache:
 
     def __init__(self, *, n_q_heads, n_kv_heads, head_dim, page_tokens, num_pages, max_requests,
                  branches_per_request, finish_quota, max_pages_per_branch, max_prefix_pages, dtype,
-                 free_order=None, k_scale=1.0, v_scale=1.0):
+                 free_order=None, k_scale=1.0, v_scale=1.0, start_waiting=False):
         self.L = _load()
         self.Hq, self.Hkv, self.d, self.pt = n_q_heads, n_kv_heads, head_dim, page_tokens
         self.num_pages, self.max_req, self.Nb = num_pages, max_requests, branches_per_request
@@ -100,6 +102,8 @@ class OracleCache:
                                    max_prefix_pages, 0 if dtype == "f32" else 1, _iptr(fo))
         if not self.h:
             raise ValueError("orc_create rejected the description")
+        if start_waiting:       # a request's branches are created WAITING and join the batch through start()
+            assert self.L.orc_set_start_waiting(self.h, 1) == OK
         if dtype == "fp8":      # bf16 in and out, K and V kept as 8-bit floats (E4M3) of x / scale
             # a cache description carries its scales as float32
             if self.L.orc_set_fp8(self.h, float(np.float32(k_scale)), float(np.float32(v_scale))) != OK:
@@ -157,6 +161,11 @@ class OracleCache:
         if rc != OK:
             return rc
         return (out, ws) if want_wsum else out
+
+    def start(self, handles) -> int:
+        """Waiting branches join the batch (Algorithm 1, main workflow)."""
+        h = _i32(handles)
+        return self.L.orc_start(self.h, len(h), _iptr(h))
 
     def finish(self, handles) -> int:
         h = _i32(handles)

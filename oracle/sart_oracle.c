@@ -8,7 +8,10 @@
  * baseline leg may load it.
  *
  * What follows the paper (arXiv 2505.13326):
- *   - Algorithm 1, Prefill: after prefilling a request, N branches are created.
+ *   - Algorithm 1, Prefill: after prefilling a request, N branches are created
+ *     and pushed into the queue of awaiting branches; the main workflow moves
+ *     awaiting branches into the batch one by one while it has room (so a
+ *     request's branches need not start decoding together: Section 4).
  *   - Algorithm 1, Decode: completed branches are removed and counted; an
  *     incomplete branch is pruned iff num_pruned < max_num_pruned and its
  *     reward < threshold; a request is finished when num_completed >= M or
@@ -47,7 +50,7 @@
 #include <string.h>
 
 enum { ORC_OK = 0, ORC_E_INVALID = 1, ORC_E_OOM_PAGES = 2, ORC_E_STATE = 3 };
-enum { BR_UNUSED = 0, BR_ACTIVE = 1, BR_COMPLETED = 2, BR_PRUNED = 3, BR_EARLY_STOPPED = 4 };
+enum { BR_UNUSED = 0, BR_ACTIVE = 1, BR_COMPLETED = 2, BR_PRUNED = 3, BR_EARLY_STOPPED = 4, BR_WAITING = 5 };
 enum { SEQ_PREFIX = 0, SEQ_BRANCH = 1 };
 enum { PRUNE_DROP_LOWEST_K = 0, PRUNE_KEEP_TOP_K = 1, PRUNE_THRESHOLD = 2 };
 enum { DT_F32 = 0, DT_BF16 = 1 };
@@ -55,6 +58,8 @@ enum { DT_F32 = 0, DT_BF16 = 1 };
 typedef struct {
   int Hq, Hkv, d, pt, num_pages, max_req, Nb, Q, max_bp, max_pp, dtype;
   size_t esize;
+  int start_waiting;    /* 1: a request's branches are created WAITING (awaiting branches of Algorithm 1) and join
+                           the batch through orc_start; 0: they are created ACTIVE, all at once */
   int fp8;              /* 1: the cache keeps K and V as 8-bit floats (inputs stay bf16) */
   double kv_scale[2];   /* fp8: stored code = round(x / scale); K, V */
   unsigned char* pool;
@@ -64,7 +69,7 @@ typedef struct {
   int* req_used;        /* 0 never created, 1 created */
   int* prefix_len;      /* P_r */
   int* prefix_table;    /* [max_req][max_pp], -1 padded */
-  int* refcnt;          /* active branches of the request */
+  int* refcnt;          /* branches of the request that still hold its prefix: active and waiting ones */
   int* num_completed;
   int* num_pruned;
   int* branch_appended; /* a branch of r already received tokens */
@@ -284,9 +289,13 @@ int orc_append(orc* o, int kind, int n_seqs, const int* ids, const int* n_tokens
         o->refcnt[r] = o->Nb;
         for (int j = 0; j < o->Nb; ++j) {
           int b = r * o->Nb + j;
-          o->state[b] = BR_ACTIVE;
           o->seq_len[b] = 0;
-          o->active[o->n_active++] = b;
+          if (o->start_waiting) {
+            o->state[b] = BR_WAITING;              /* pushed into the queue of awaiting branches */
+          } else {
+            o->state[b] = BR_ACTIVE;
+            o->active[o->n_active++] = b;
+          }
         }
       }
       table = o->prefix_table + (size_t)r * o->max_pp;
@@ -448,7 +457,7 @@ int orc_prefill_attention(const orc* o, int r, const void* q, int n_q, double sc
  *      their prefix pages in ascending logical order;
  *  (3) the active list keeps the survivors in their old relative order.
  */
-static void terminate(orc* o, const int* new_state) {
+static void terminate(orc* o, const int* new_state, const unsigned char* stop_waiting) {
   unsigned char* touched = (unsigned char*)calloc(o->max_req, 1);
   for (int a = 0; a < o->n_active; ++a) {
     if (!new_state[a]) continue;
@@ -460,6 +469,17 @@ static void terminate(orc* o, const int* new_state) {
     o->state[b] = new_state[a];
     o->refcnt[r]--;
     touched[r] = 1;
+  }
+  /* awaiting branches of a request that is stopped early never start: they hold no pages of their own */
+  for (int r = 0; stop_waiting && r < o->max_req; ++r) {
+    if (!stop_waiting[r]) continue;
+    for (int j = 0; j < o->Nb; ++j) {
+      int b = r * o->Nb + j;
+      if (o->state[b] != BR_WAITING) continue;
+      o->state[b] = BR_EARLY_STOPPED;
+      o->refcnt[r]--;
+      touched[r] = 1;
+    }
   }
   for (int r = 0; r < o->max_req; ++r) {
     if (!touched[r] || o->refcnt[r] != 0) continue;
@@ -473,6 +493,44 @@ static void terminate(orc* o, const int* new_state) {
   for (int a = w; a < o->n_active; ++a) o->active[a] = -1;
   o->n_active = w;
   free(touched);
+}
+
+/*
+ * A waiting branch joins the batch (Algorithm 1, main workflow: while the batch
+ * has room, an awaiting branch is popped from the branch queue and appended to
+ * the current batch).  The listed branches, all WAITING, become ACTIVE in list
+ * order; each is placed right after the last active branch of its request, or at
+ * the end of the active list when the request has none (so a request's branches
+ * stay neighbours in the list, in the order they started).
+ */
+int orc_start(orc* o, int n, const int* handles) {
+  const int H = o->max_req * o->Nb;
+  if (n < 0 || (n > 0 && !handles)) return ORC_E_INVALID;
+  for (int i = 0; i < n; ++i)
+    if (handles[i] < 0 || handles[i] >= H) return ORC_E_INVALID;
+  if (is_dup(handles, n, H)) return ORC_E_INVALID;
+  for (int i = 0; i < n; ++i)
+    if (o->state[handles[i]] != BR_WAITING) return ORC_E_STATE;
+  for (int i = 0; i < n; ++i) {
+    const int b = handles[i], r = b / o->Nb;
+    int pos = o->n_active;                       /* no active branch of r: the end of the list */
+    for (int a = 0; a < o->n_active; ++a)
+      if (o->active[a] / o->Nb == r) pos = a + 1;
+    for (int a = o->n_active; a > pos; --a) o->active[a] = o->active[a - 1];
+    o->active[pos] = b;
+    o->n_active++;
+    o->state[b] = BR_ACTIVE;
+    o->seq_len[b] = 0;
+  }
+  return ORC_OK;
+}
+
+/* Branches are created WAITING from now on (before the first request is created). */
+int orc_set_start_waiting(orc* o, int on) {
+  for (int r = 0; r < o->max_req; ++r)
+    if (o->req_used[r]) return ORC_E_STATE;
+  o->start_waiting = on != 0;
+  return ORC_OK;
 }
 
 /*
@@ -495,14 +553,20 @@ int orc_finish(orc* o, int n, const int* handles) {
     o->num_completed[handles[i] / o->Nb]++;
   }
   const int quota_on = o->Q >= 1 && o->Q <= o->Nb;
+  unsigned char* stop_waiting = (unsigned char*)calloc(o->max_req, 1);
   for (int a = 0; a < o->n_active; ++a) {
     int b = o->active[a], r = b / o->Nb;
     if (listed[b]) new_state[a] = BR_COMPLETED;
     else if (quota_on && o->num_completed[r] >= o->Q) new_state[a] = BR_EARLY_STOPPED;
   }
-  terminate(o, new_state);
+  for (int i = 0; i < n; ++i) {
+    int r = handles[i] / o->Nb;
+    if (quota_on && o->num_completed[r] >= o->Q) stop_waiting[r] = 1;   /* the remaining branches, awaiting ones too */
+  }
+  terminate(o, new_state, stop_waiting);
   free(new_state);
   free(listed);
+  free(stop_waiting);
   return ORC_OK;
 }
 
@@ -564,7 +628,7 @@ int orc_prune(orc* o, int mode, int k, const int* k_per_req, const float* thr, c
     for (int i = 0; i < n_victims; ++i) new_state[members[i]] = BR_PRUNED;
     o->num_pruned[r] += n_victims;
   }
-  terminate(o, new_state);
+  terminate(o, new_state, NULL);
   free(new_state);
   free(members);
   return ORC_OK;

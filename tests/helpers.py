@@ -7,11 +7,11 @@ import oracle as orc
 
 
 def make_oracle(*, Hq=4, Hkv=1, d=64, pt=16, num_pages=64, max_req=2, Nb=4, Q=0, max_bp=32, max_pp=16,
-                dtype="f32", free_order=None):
+                dtype="f32", free_order=None, start_waiting=False):
     return orc.OracleCache(n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, page_tokens=pt, num_pages=num_pages,
                            max_requests=max_req, branches_per_request=Nb, finish_quota=Q,
                            max_pages_per_branch=max_bp, max_prefix_pages=max_pp, dtype=dtype,
-                           free_order=free_order)
+                           free_order=free_order, start_waiting=start_waiting)
 
 
 class DenseShadow:
@@ -67,6 +67,8 @@ def check_invariants(st, *, pt, num_pages, Nb, max_req):
         pages += list(row[:n])
     assert len(set(int(h) for h in st["active_handles"][:nA])) == nA
     assert np.sum(st["branch_state"] == orc.ACTIVE) == nA
+    waiting = (st["branch_state"] == orc.WAITING).reshape(max_req, Nb).sum(axis=1)
+    live = live + waiting                     # awaiting branches hold the prompt too
     np.testing.assert_array_equal(st["prefix_refcnt"], live)
     for r in range(max_req):
         n = -(-int(st["prefix_lens"][r]) // pt)
@@ -110,6 +112,8 @@ def run_golden_scenario(scn, engine, Hkv, d, np_dtype, done=None):
                               threshold=step.get("threshold"), max_pruned=step.get("max_pruned"))
         elif op == "finish":
             rc = engine.finish(step["handles"])
+        elif op == "start":
+            rc = engine.start(step["handles"])
         else:
             raise ValueError(op)
         assert rc == step["status"], (scn["name"], i, op, rc)

@@ -18,7 +18,7 @@ with open(GOLDEN) as f:
 def test_hand_worked_traces(scn):
     d = scn["desc"]
     o = make_oracle(Hq=2, Hkv=1, d=8, pt=d["pt"], num_pages=d["num_pages"], max_req=d["max_req"], Nb=d["Nb"],
-                    Q=d["Q"], max_bp=d["max_bp"], max_pp=d["max_pp"])
+                    Q=d["Q"], max_bp=d["max_bp"], max_pp=d["max_pp"], start_waiting=d.get("start_waiting", False))
     run_golden_scenario(scn, o, 1, 8, np.float32, done=o.request_done)
 
 

@@ -7,12 +7,12 @@ from oracle.scheduler import serve
 
 
 def _run(*, R=10, N=8, M=4, alpha=0.5, beta=4, B=32, T=10, seed=0, arrive_every=1, reward_fn=None, targets=None,
-         pt=4, P=5):
+         pt=4, P=5, on_step=None):
     rng = np.random.default_rng(seed)
     targets = rng.integers(3, 60, size=R * N) if targets is None else targets
     num_pages = B * (int(targets.max()) // pt + T // pt + 4) + R * 2 + 16
     o = make_oracle(Hq=1, Hkv=1, d=8, pt=pt, num_pages=num_pages, max_req=R, Nb=N, Q=M,
-                    max_bp=int(targets.max()) // pt + 2, max_pp=2)
+                    max_bp=int(targets.max()) // pt + 2, max_pp=2, start_waiting=True)
     one = np.ones((R * N, 1, 8), np.float32)
     table = np.random.default_rng(seed + 1).random((400, R * N)).astype(np.float32)
     reward = reward_fn or (lambda hs, rnd: table[rnd % 400, hs])
@@ -30,7 +30,7 @@ def _run(*, R=10, N=8, M=4, alpha=0.5, beta=4, B=32, T=10, seed=0, arrive_every=
     answers, stats = serve(o, N=N, M=M, alpha=alpha, beta=beta, B=B, T=T,
                            arrivals=[(r, r * arrive_every) for r in range(R)],
                            prompt_kv=lambda r: (one[:P], one[:P]), targets=targets,
-                           step_kv=lambda s: (one, one), reward=reward, on_round=on_round)
+                           step_kv=lambda s: (one, one), reward=reward, on_round=on_round, on_step=on_step)
     return o, answers, stats, log, targets, reward, num_pages
 
 
@@ -91,3 +91,40 @@ def test_fcfs_admission_under_batch_limit():
     assert adm[0] == 0 and adm[1] == 0 and adm[2] > 0
     assert adm == sorted(adm)                                   # first come, first served
     assert stats["max_active"] <= 16
+
+
+def test_branches_of_a_request_need_not_start_together():
+    """B = 3 with N = 2: the batch is filled branch by branch (Algorithm 1, main workflow), so request 1 gets
+    one branch into the first batch and the other waits in branch_queue until a place is free.  Worked by hand
+    (no pruning: equal rewards; M = N = 2; T = 4; tokens to generate b00 6, b01 3, b10 5, b11 2):
+      round 0: Prefill(0) queues b00 b01, both start; Prefill(1) queues b10 b11, b10 starts, the batch is full;
+               steps 1-4: b01 completes at step 3.
+      round 1: b11 starts (its first token is step 5); b10 completes at step 5; b00 and b11 complete at step 6.
+    So request 1's earliest completed branch (b10, 5 tokens, step 5) is not its shortest (b11, 2 tokens, step 6):
+    Section 4, last paragraph."""
+    batches = {}
+    o, answers, stats, log, *_ = _run(R=2, N=2, M=2, B=3, T=4, arrive_every=0, targets=np.array([6, 3, 5, 2]),
+                                      reward_fn=lambda hs, rnd: np.full(len(hs), 0.7, np.float32),
+                                      on_step=lambda s, c, batch: batches.__setitem__(s, list(batch)))
+    assert batches[1] == [0, 1, 2] and batches[4] == [0, 2]          # b01 left after step 3
+    assert batches[5] == [0, 2, 3] and batches[6] == [0, 3]          # b11 joined behind its request's b10
+    assert answers[0]["completed"] == [(1, 3), (0, 6)] and answers[1]["completed"] == [(2, 5), (3, 6)]
+    assert answers[0]["started"] == {0: 1, 1: 1} and answers[1]["started"] == {2: 1, 3: 5}
+    assert answers[0]["done_round"] == 1 and answers[1]["done_round"] == 1 and answers[1]["done_step"] == 6
+    assert stats["max_active"] == 3 and stats["branch_steps"] == 3 + 3 + 3 + 2 + 3 + 2
+
+
+def test_early_stop_ends_the_awaiting_branches_too():
+    """N = 3, M = 1, B = 2: b02 is still in branch_queue when b01 completes at step 2; the request is answered and
+    b00 (running) and b02 (never started) are both ended, the prompt is released, and request 1 takes the places."""
+    o, answers, stats, log, *_ = _run(R=2, N=3, M=1, B=2, T=3, arrive_every=0, targets=np.array([9, 2, 4, 5, 5, 1]),
+                                      reward_fn=lambda hs, rnd: np.full(len(hs), 0.7, np.float32))
+    st = o.state()
+    assert list(st["branch_state"][:3]) == [orc.EARLY_STOPPED, orc.COMPLETED, orc.EARLY_STOPPED]
+    assert answers[0]["completed"] == [(1, 2)] and answers[0]["started"] == {0: 1, 1: 1} and answers[0]["answer"] == 1
+    # round 0 decodes 2 steps only (the batch is empty after step 2); request 1 is prefilled in round 1 (the batch
+    # was full in round 0): b10, b11 start at step 3 and both complete at step 7 (5 tokens each); the first of
+    # them ends the request: b12 never starts
+    assert answers[1]["admitted_round"] == 1 and answers[1]["started"] == {3: 3, 4: 3}
+    assert answers[1]["completed"][0][1] == 7 and st["branch_state"][5] == orc.EARLY_STOPPED
+    assert st["n_active"][0] == 0 and np.all(st["prefix_refcnt"] == 0)
