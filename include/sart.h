@@ -85,7 +85,8 @@ typedef enum {
   SART_BRANCH_ACTIVE = 1,
   SART_BRANCH_COMPLETED = 2,
   SART_BRANCH_PRUNED = 3,
-  SART_BRANCH_EARLY_STOPPED = 4
+  SART_BRANCH_EARLY_STOPPED = 4,
+  SART_BRANCH_WAITING = 5       /* created, holds the prompt, not yet in the batch (see sart_start_branches) */
 } sart_branch_state;
 
 typedef enum {
@@ -133,6 +134,11 @@ typedef struct {
                                         handed out first.                        */
   float k_scale;                /* SART_FP8_E4M3 only: scale of K, of V;         */
   float v_scale;                /* <= 0 means 1                                  */
+  int32_t branches_start_waiting; /* nonzero: a request's Nb branches are created
+                                   WAITING (Algorithm 1's queue of awaiting
+                                   branches) and enter the batch one by one
+                                   through sart_start_branches; 0: they are
+                                   created ACTIVE, all at once                   */
 } sart_cache_desc;
 
 typedef struct {
@@ -275,6 +281,22 @@ sart_status sart_prune_branches(sart_cache* cache, const sart_prune_policy* poli
 sart_status sart_finish_branch(sart_cache* cache, int32_t n,
                                const int32_t* handles /*HOST*/, void* stream);
 
+/* A waiting branch joins the batch (Algorithm 1, main scheduling workflow: while
+ * the current batch has room, an awaiting branch is popped from the branch queue
+ * and appended to it; Section 4: so the branches of a request need not start
+ * decoding together).  Only for caches created with branches_start_waiting.
+ * The listed branches, all WAITING (else SART_E_STATE, nothing changes), become
+ * ACTIVE with no private tokens; each takes the place right after the last
+ * active branch of its request, or, if the request has none, the end of the
+ * active list (what inserting them one by one in list order gives), so a
+ * request's branches stay neighbours in the active order; the rows behind them
+ * move up with their block tables.  Until it starts a waiting branch holds its
+ * request's prompt (it counts in prefix_refcnt) but no row of q, out or scores;
+ * sart_prune_branches never sees it; when its request reaches Q completions it
+ * is ended with the others (SART_BRANCH_EARLY_STOPPED). */
+sart_status sart_start_branches(sart_cache* cache, int32_t n,
+                                const int32_t* handles /*HOST*/, void* stream);
+
 /* A8 without a host list: completes every active branch whose length (private
  * tokens) has reached target_len[handle] (DEVICE, max_requests * Nb entries, by
  * handle), exactly as sart_finish_branch would for the list of those branches
@@ -298,7 +320,7 @@ sart_status sart_sync_status(sart_cache* cache);
  *   free_top        [1]
  *   prefix_tables   [max_requests, max_prefix_pages]  -1 padded / released
  *   prefix_lens     [max_requests]      prompt tokens (kept after release)
- *   prefix_refcnt   [max_requests]      active branches of the request
+ *   prefix_refcnt   [max_requests]      branches holding the prompt: active + waiting
  *   branch_state    [max_requests*Nb]   by handle
  *   req_counters    [max_requests, 2]   completed, pruned */
 sart_status sart_get_state(sart_cache* cache, int32_t* n_active,

@@ -13,7 +13,7 @@ import numpy as np
 OK, E_INVALID, E_OOM_PAGES, E_STATE, E_HIP = range(5)
 F32, BF16, FP8_E4M3 = 0, 1, 2
 SEQ_PREFIX, SEQ_BRANCH = 0, 1
-UNUSED, ACTIVE, COMPLETED, PRUNED, EARLY_STOPPED = range(5)
+UNUSED, ACTIVE, COMPLETED, PRUNED, EARLY_STOPPED, WAITING = range(6)
 DROP_LOWEST_K, KEEP_TOP_K, THRESHOLD = 0, 1, 2
 LAYOUT_NATURAL, LAYOUT_MFMA16, LAYOUT_MFMA16_FP8 = 0, 1, 2
 DEFAULT_SKEW_PERMILLE = 80   # the library's default of sart_set_decode_launch's skew_permille
@@ -40,7 +40,7 @@ class _Desc(C.Structure):
                 ("max_prefix_pages", C.c_int32), ("kv_dtype", C.c_int32),
                 ("force_natural_layout", C.c_int32), ("kv_pool", C.c_void_p),
                 ("kv_pool_bytes", C.c_size_t), ("initial_free_order", _ip), ("k_scale", C.c_float),
-                ("v_scale", C.c_float)]
+                ("v_scale", C.c_float), ("branches_start_waiting", C.c_int32)]
 
 
 class _Policy(C.Structure):
@@ -63,6 +63,7 @@ _SIGNATURES = {
                                          C.c_void_p]),
     "sart_prune_branches": (C.c_int, [C.c_void_p, C.POINTER(_Policy), C.c_void_p, C.c_int32, C.c_void_p]),
     "sart_finish_branch": (C.c_int, [C.c_void_p, C.c_int32, _ip, C.c_void_p]),
+    "sart_start_branches": (C.c_int, [C.c_void_p, C.c_int32, _ip, C.c_void_p]),
     "sart_finish_reached": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "sart_device_views": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
     "sart_sync_status": (C.c_int, [C.c_void_p]),
@@ -135,7 +136,8 @@ class SartCache:
 
     def __init__(self, *, n_q_heads, n_kv_heads, head_dim, page_tokens=16, num_pages, max_requests,
                  branches_per_request, finish_quota=0, max_pages_per_branch, max_prefix_pages, dtype="bf16",
-                 free_order=None, kv_pool=None, force_natural_layout=False, n_layers=1, k_scale=1.0, v_scale=1.0):
+                 free_order=None, kv_pool=None, force_natural_layout=False, n_layers=1, k_scale=1.0, v_scale=1.0,
+                 start_waiting=False):
         import torch
         self.lib = load_library()
         self.Hq, self.Hkv, self.d, self.pt = n_q_heads, n_kv_heads, head_dim, page_tokens
@@ -146,7 +148,7 @@ class SartCache:
         self.n_layers = n_layers
         d = _Desc(n_layers, n_q_heads, n_kv_heads, head_dim, page_tokens, num_pages, max_requests, branches_per_request,
                   finish_quota, max_pages_per_branch, max_prefix_pages, {"f32": F32, "bf16": BF16, "fp8": FP8_E4M3}[dtype],
-                  1 if force_natural_layout else 0, None, 0, None, float(k_scale), float(v_scale))
+                  1 if force_natural_layout else 0, None, 0, None, float(k_scale), float(v_scale), 1 if start_waiting else 0)
         self.pool_bytes = int(self.lib.sart_pool_bytes(C.byref(d)))
         self._pool = kv_pool  # keep the tensor alive
         if kv_pool is not None:
@@ -260,6 +262,15 @@ class SartCache:
         pol = _Policy(int(mode), int(k), _ptr(kp), _ptr(th, _fp), _ptr(mp))
         rc = self.lib.sart_prune_branches(self.h, C.byref(pol), C.c_void_p(scores.data_ptr()), scores.numel(),
                                           _stream_handle(stream))
+        if status:
+            return rc if rc != OK else self.sync_status()
+        self._check(rc)
+        return OK
+
+    def start_branches(self, handles, stream=None, status=False):
+        """sart_start_branches: waiting branches join the batch."""
+        h = _i32(handles)
+        rc = self.lib.sart_start_branches(self.h, len(h), _ptr(h), _stream_handle(stream))
         if status:
             return rc if rc != OK else self.sync_status()
         self._check(rc)

@@ -186,6 +186,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   c->k_scale = d->kv_dtype == SART_FP8_E4M3 && d->k_scale > 0.f ? d->k_scale : 1.0f;
   c->v_scale = d->kv_dtype == SART_FP8_E4M3 && d->v_scale > 0.f ? d->v_scale : 1.0f;
   dm.k_scale = c->k_scale; dm.v_scale = c->v_scale;
+  dm.start_waiting = d->branches_start_waiting != 0;
   dm.tile_elems = (long long)dm.pt * dm.d;
   dm.page_elems = (long long)dm.Hkv * 2 * dm.tile_elems;
 
@@ -199,7 +200,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   ALLOC(tb.scal, S_COUNT);
   ALLOC(tb.free_stack, dm.num_pages);
   ALLOC(tb.req_used, R); ALLOC(tb.prefix_len, R); ALLOC(tb.prefix_table, R * dm.max_pp);
-  ALLOC(tb.refcnt, R); ALLOC(tb.num_completed, R); ALLOC(tb.num_pruned, R); ALLOC(tb.branch_appended, R);
+  ALLOC(tb.refcnt, R); ALLOC(tb.nact, R); ALLOC(tb.req_tmp, R); ALLOC(tb.num_completed, R); ALLOC(tb.num_pruned, R); ALLOC(tb.branch_appended, R);
   ALLOC(tb.br_state, H); ALLOC(tb.active_idx_of, H); ALLOC(tb.active, H); ALLOC(tb.seq_len, H);
   ALLOC(tb.bt[0], H * dm.max_bp); ALLOC(tb.bt[1], H * dm.max_bp);
   ALLOC(tb.new_state, H); ALLOC(tb.mv_push_off, H); ALLOC(tb.mv_new_idx, H);
@@ -552,6 +553,35 @@ sart_status sart_finish_branch(sart_cache* c, int32_t n, const int32_t* handles,
   rc = stage_upload(c, s, n, st);
   if (rc != SART_OK) return rc;
   launch_finish(c->ctx, c->plan, n, s->dev, nullptr, ++c->call_seq, st);
+  HIP_TRY(hipEventRecord(s->done, st));
+  HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
+
+sart_status sart_start_branches(sart_cache* c, int32_t n, const int32_t* handles, void* stream) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  const Dims& dm = c->ctx.dm;
+  if (!dm.start_waiting) return fail(SART_E_INVALID, "the cache was not created with branches_start_waiting");
+  if (n < 0 || (n > 0 && !handles)) return fail(SART_E_INVALID, "bad handle list");
+  if (n > dm.H) return fail(SART_E_INVALID, "more handles than branches");
+  if (n == 0) return SART_OK;
+  {
+    std::vector<char> seen(dm.H, 0);
+    for (int i = 0; i < n; ++i) {
+      if (handles[i] < 0 || handles[i] >= dm.H) return fail(SART_E_INVALID, "handle %d out of range", handles[i]);
+      if (seen[handles[i]]) return fail(SART_E_INVALID, "duplicate handle %d", handles[i]);
+      seen[handles[i]] = 1;
+    }
+  }
+  hipStream_t st = (hipStream_t)stream;
+  note_stream(c, stream);
+  StageSlot* s;
+  sart_status rc = stage_begin(c, &s);
+  if (rc != SART_OK) return rc;
+  memcpy(s->host, handles, (size_t)n * sizeof(int));
+  rc = stage_upload(c, s, n, st);
+  if (rc != SART_OK) return rc;
+  launch_start(c->ctx, c->plan, n, s->dev, ++c->call_seq, st);
   HIP_TRY(hipEventRecord(s->done, st));
   HIP_TRY(hipGetLastError());
   return SART_OK;

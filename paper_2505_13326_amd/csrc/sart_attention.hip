@@ -354,7 +354,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
             if (!resolved) {                                           // rare: more items than waves
               while (item >= tb.live_item_start[cursor + 1]) ++cursor; // the live request owning the item
               r = tb.live_req[cursor];
-              cnt = tb.refcnt[r]; plen = tb.prefix_len[r]; first_row = tb.req_first[r]; pstart = tb.req_pstart[r];
+              cnt = tb.nact[r]; plen = tb.prefix_len[r]; first_row = tb.req_first[r]; pstart = tb.req_pstart[r];
               istart = tb.live_item_start[cursor];
             }
             resolved = false;
@@ -460,7 +460,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
           for (long long u = prompt_range_of_wave(i, cut.n_prompt); u < cut.n_blocks; u += cut.n_prompt) {
             while (u >= tb.live_item_start[cursor + 1]) ++cursor;      // the live request owning block u
             const int r = tb.live_req[cursor];
-            const int cnt = tb.refcnt[r], plen = tb.prefix_len[r];
+            const int cnt = tb.nact[r], plen = tb.prefix_len[r];
             const int pp = ceil_div(plen, 16), nck = ceil_div(pp, cut.pb);
             const int local = (int)(u - tb.live_item_start[cursor]);
             const int j = local % cnt, ck = (local / cnt) % nck, h = local / (cnt * nck);
@@ -577,7 +577,7 @@ k_attn_generic(Ctx c, DecodeArgs a) {
       } else {
         while (u >= tb.live_item_start[cursor + 1]) ++cursor;
         const int r = tb.live_req[cursor];
-        const int cnt = tb.refcnt[r];
+        const int cnt = tb.nact[r];
         tokens = tb.prefix_len[r];
         const int pp = ceil_div(tokens, pt), nck = ceil_div(pp, cut.pb);
         const int local = (int)(u - tb.live_item_start[cursor]);

@@ -31,7 +31,7 @@ __global__ void k_init_tables(Ctx c, const int* free_order) {
     tb.free_stack[i] = free_order ? free_order[j] : j;
   }
   for (long long i = tid; i < dm.max_req; i += nth) {
-    tb.req_used[i] = 0; tb.prefix_len[i] = 0; tb.refcnt[i] = 0; tb.num_completed[i] = 0;
+    tb.req_used[i] = 0; tb.prefix_len[i] = 0; tb.refcnt[i] = 0; tb.nact[i] = 0; tb.req_tmp[i] = 0; tb.num_completed[i] = 0;
     tb.num_pruned[i] = 0; tb.branch_appended[i] = 0; tb.req_first[i] = 0; tb.req_push_off[i] = -1;
     tb.req_touched[i] = 0;
   }
@@ -168,11 +168,18 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
       table = tb.prefix_table + (long long)id * dm.max_pp;
       tb.prefix_len[id] = len + n;
       if (!tb.req_used[id]) {
+        // Algorithm 1, Prefill: the request's Nb branches exist from now on, either in the batch at once or
+        // awaiting (holding the prompt, but no place in the active list until sart_start_branches)
         tb.req_used[id] = 1;
         tb.refcnt[id] = dm.Nb;
+        tb.nact[id] = dm.start_waiting ? 0 : dm.Nb;
         const int first = nA + tb.tmp_b[i] * dm.Nb;
         for (int j = 0; j < dm.Nb; ++j) {
           const int b = id * dm.Nb + j;
+          if (dm.start_waiting) {
+            tb.br_state[b] = SART_BRANCH_WAITING;
+            continue;
+          }
           tb.br_state[b] = SART_BRANCH_ACTIVE;
           tb.active[first + j] = b;
           tb.seq_len[first + j] = 0;
@@ -189,7 +196,7 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
   }
   __syncthreads();
   if (tid == 0) {
-    const int na_new = nA + carry_new * dm.Nb;
+    const int na_new = nA + (dm.start_waiting ? 0 : carry_new * dm.Nb);
     scal[S_NACTIVE] = na_new;
     scal[S_FREETOP] = top - carry;
     const int sel = scal[S_BTSEL];
@@ -308,7 +315,7 @@ void launch_append(const Ctx& c, const PlanCfg& pc, const AppendArgs& a, hipStre
 //  (3) survivors keep their relative order.
 // The pushes themselves and the block-table rows are moved by k_terminate_move.
 // ---------------------------------------------------------------------------
-__device__ void terminate_plan(const Ctx& c, const PlanCfg& pc, int* lds) {
+__device__ void terminate_plan(const Ctx& c, const PlanCfg& pc, int* lds, bool stop_waiting) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
@@ -343,7 +350,18 @@ __device__ void terminate_plan(const Ctx& c, const PlanCfg& pc, int* lds) {
     tb.br_state[b] = tb.new_state[a];
     tb.active_idx_of[b] = -1;
     atomicSub(&tb.refcnt[r], 1);
+    atomicSub(&tb.nact[r], 1);
     tb.req_touched[r] = 1;
+  }
+  // a request that reached its quota is over: its awaiting branches never start (they hold no pages of their own)
+  if (stop_waiting && dm.start_waiting && dm.Q >= 1 && dm.Q <= dm.Nb) {
+    for (int b = tid; b < dm.H; b += kPlanThreads) {
+      const int r = b / dm.Nb;
+      if (tb.br_state[b] != SART_BRANCH_WAITING || tb.num_completed[r] < dm.Q) continue;
+      tb.br_state[b] = SART_BRANCH_EARLY_STOPPED;
+      atomicSub(&tb.refcnt[r], 1);
+      tb.req_touched[r] = 1;
+    }
   }
   __syncthreads();
   // requests whose last branch left: prefix pushes in ascending request id
@@ -487,7 +505,7 @@ k_prune_plan(Ctx c, PlanCfg pc, PruneArgs a) {
   __syncthreads();
   for (int i = tid; i < nA; i += kPlanThreads) {
     const int b = tb.active[i], r = b / dm.Nb;
-    const int first = tb.req_first[r], live = tb.refcnt[r];
+    const int first = tb.req_first[r], live = tb.nact[r];
     const float sc = a.scores[i];
     int room = 0x7fffffff;
     if (a.maxp) { room = a.maxp[r] - tb.num_pruned[r]; if (room < 0) room = 0; }
@@ -515,7 +533,7 @@ k_prune_plan(Ctx c, PlanCfg pc, PruneArgs a) {
   for (int i = tid; i < nA; i += kPlanThreads)
     if (tb.new_state[i]) atomicAdd(&tb.num_pruned[tb.active[i] / dm.Nb], 1);
   __syncthreads();
-  terminate_plan(c, pc, lds);
+  terminate_plan(c, pc, lds, false);
 }
 
 void launch_prune(const Ctx& c, const PlanCfg& pc, const PruneArgs& a, hipStream_t s) {
@@ -577,13 +595,155 @@ k_finish_plan(Ctx c, PlanCfg pc, int n, const int* handles, const int* targets, 
         tb.new_state[a] = SART_BRANCH_EARLY_STOPPED;
   }
   __syncthreads();
-  terminate_plan(c, pc, lds);
+  terminate_plan(c, pc, lds, true);
 }
 
 void launch_finish(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, const int* targets_dev, int call_seq,
                    hipStream_t s) {
   hipLaunchKernelGGL(k_finish_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, n, handles_dev, targets_dev, call_seq);
   launch_move(c, s);
+}
+
+// ---------------------------------------------------------------------------
+// Waiting branches join the batch (Algorithm 1, main workflow: while the batch
+// has room, an awaiting branch is popped from the branch queue and appended to
+// the current batch).  The listed branches, all WAITING, become ACTIVE; each is
+// placed right after the last active branch of its request, or, when the
+// request has none, at the end of the list (request by request in the order of
+// first appearance in the list): what inserting them one by one in list order
+// gives.  So a request's rows stay neighbours in the active list.
+//   new index of old row a   = a + started branches of the requests whose rows end before a
+//   place of list entry i    = new index of its request's last row + 1 + rank of i among the
+//                              list's entries of that request, or
+//                              old rows + all branches placed behind rows + offset of the
+//                              request's group among the row-less requests + rank
+// The block-table rows move with their branches into the other buffer
+// (k_start_move); a started branch's row is empty.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kPlanThreads)
+k_start_plan(Ctx c, PlanCfg pc, int n, const int* handles, int call_seq) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  int* scal = tb.scal;
+  __shared__ int lds[17];
+  __shared__ int s_bad;
+  const int tid = threadIdx.x;
+  const int nA = scal[S_NACTIVE];
+  if (tid == 0) s_bad = 0;
+  __syncthreads();
+  for (int i = tid; i < n; i += kPlanThreads)
+    if (tb.br_state[handles[i]] != SART_BRANCH_WAITING) s_bad = 1;
+  __syncthreads();
+  if (s_bad) {
+    if (tid == 0) record_error(scal, SART_E_STATE, call_seq);
+    return;
+  }
+  if (tid == 0) scal[S_APPENDOK] = 0;        // rows move: no more writes to other layers for the last append
+  for (int r = tid; r < dm.max_req; r += kPlanThreads) { tb.req_touched[r] = 0; tb.req_tmp[r] = 0; }
+  find_request_starts(c, nA);
+  __syncthreads();
+  // per list entry: its rank among the list's entries of its request; per request: how many of its branches start
+  for (int i = tid; i < n; i += kPlanThreads) {
+    const int r = handles[i] / dm.Nb;
+    int rank = 0;
+    for (int j = 0; j < i; ++j) rank += handles[j] / dm.Nb == r;
+    tb.tmp_a[i] = rank;
+    atomicAdd(&tb.req_touched[r], 1);
+  }
+  __syncthreads();
+  // old rows: shifted by the branches placed behind the requests that end before them; scratch copies of the
+  // small active-order arrays
+  int carry = 0;
+  for (int base = 0; base < nA; base += kPlanThreads) {
+    const int a = base + tid;
+    int v = 0;
+    if (a < nA) {
+      tb.new_state[a] = tb.active[a];
+      tb.mv_push_off[a] = tb.seq_len[a];
+      if (a > 0) {
+        const int r = tb.active[a] / dm.Nb, prev = tb.active[a - 1] / dm.Nb;
+        if (prev != r) v = tb.req_touched[prev];
+      }
+    }
+    int tot;
+    const int ex = block_excl_scan(v, lds, tot);
+    if (a < nA) tb.mv_new_idx[a] = a + carry + ex + v;
+    carry += tot;
+  }
+  __syncthreads();
+  const int behind_rows = carry + (nA > 0 ? tb.req_touched[tb.active[nA - 1] / dm.Nb] : 0);
+  // requests without a row: groups at the end, in order of first appearance in the list
+  int carry_g = 0;
+  for (int base = 0; base < n; base += kPlanThreads) {
+    const int i = base + tid;
+    int v = 0, r = 0;
+    if (i < n) {
+      r = handles[i] / dm.Nb;
+      if (tb.nact[r] == 0 && tb.tmp_a[i] == 0) v = tb.req_touched[r];
+    }
+    int tot;
+    const int ex = block_excl_scan(v, lds, tot);
+    if (v > 0) tb.req_tmp[r] = carry_g + ex;
+    carry_g += tot;
+  }
+  __syncthreads();
+  const int na_new = nA + n;
+  for (int u = tid; u < na_new; u += kPlanThreads) tb.ap_id[u] = -1;     // new row -> old row it comes from (-1: a started branch)
+  __syncthreads();
+  for (int a = tid; a < nA; a += kPlanThreads) {
+    const int ni = tb.mv_new_idx[a], b = tb.new_state[a];
+    tb.active[ni] = b;
+    tb.seq_len[ni] = tb.mv_push_off[a];
+    tb.active_idx_of[b] = ni;
+    tb.ap_id[ni] = a;
+  }
+  for (int i = tid; i < n; i += kPlanThreads) {
+    const int b = handles[i], r = b / dm.Nb;
+    const int pos = tb.nact[r] > 0 ? tb.mv_new_idx[tb.req_first[r] + tb.nact[r] - 1] + 1 + tb.tmp_a[i]
+                                   : nA + behind_rows + tb.req_tmp[r] + tb.tmp_a[i];
+    tb.active[pos] = b;
+    tb.seq_len[pos] = 0;
+    tb.active_idx_of[b] = pos;
+    tb.br_state[b] = SART_BRANCH_ACTIVE;
+  }
+  __syncthreads();
+  for (int r = tid; r < dm.max_req; r += kPlanThreads) tb.nact[r] += tb.req_touched[r];
+  if (tid == 0) {
+    const int old_sel = scal[S_BTSEL], new_sel = old_sel ^ 1;
+    scal[S_T_NA_OLD] = nA;
+    scal[S_T_NA_NEW] = na_new;
+    scal[S_T_BT_OLD] = old_sel;
+    scal[S_T_CLEAR_HI] = scal[S_BTHI0 + new_sel];
+    scal[S_BTHI0 + new_sel] = na_new;
+    scal[S_BTSEL] = new_sel;
+    scal[S_NACTIVE] = na_new;
+    scal[S_CALLOK] = 1;
+  }
+  refresh_decode_plan(c, pc, lds);
+}
+
+// The block-table rows of the start plan: one workgroup per row of the new buffer.
+__global__ void __launch_bounds__(256)
+k_start_move(Ctx c) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  const int* scal = tb.scal;
+  if (!scal[S_CALLOK]) return;
+  const int na_new = scal[S_T_NA_NEW], clear_hi = scal[S_T_CLEAR_HI];
+  const int* bt_old = tb.bt[scal[S_T_BT_OLD]];
+  int* bt_new = tb.bt[scal[S_T_BT_OLD] ^ 1];
+  const int rows = na_new > clear_hi ? na_new : clear_hi;
+  for (int u = blockIdx.x; u < rows; u += gridDim.x) {
+    const int src = u < na_new ? tb.ap_id[u] : -1;        // rows past the new list go back to -1
+    int* dst = bt_new + (long long)u * dm.max_bp;
+    for (int p = threadIdx.x; p < dm.max_bp; p += blockDim.x) dst[p] = src >= 0 ? bt_old[(long long)src * dm.max_bp + p] : -1;
+  }
+}
+
+void launch_start(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, int call_seq, hipStream_t s) {
+  hipLaunchKernelGGL(k_start_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, n, handles_dev, call_seq);
+  const int blocks = c.dm.H < 2048 ? c.dm.H : 2048;
+  hipLaunchKernelGGL(k_start_move, dim3(blocks), dim3(256), 0, s, c);
 }
 
 // Stand-alone refresh of the decode plan (after sart_alloc_cache and when the

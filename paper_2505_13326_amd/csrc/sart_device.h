@@ -124,7 +124,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       np = ceil_div(len, dm.pt);
       if (first) {
         plen = tb.prefix_len[r];
-        cnt = tb.refcnt[r];
+        cnt = tb.nact[r];
         const int pp = ceil_div(plen, dm.pt);
         // pages read for the request's prompt, per kv head: once per tile of 16 * kSharedBlocks query
         // rows (shared rows), or once per branch
@@ -192,7 +192,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
         if (k < n_live) {
           const bool in_lds = k < kPlanLdsLive;
           r = in_lds ? s_lreq[k] : tb.live_req[k];
-          const int plen = in_lds ? s_lplen[k] : tb.prefix_len[r], cnt = in_lds ? s_lcnt[k] : tb.refcnt[r];
+          const int plen = in_lds ? s_lplen[k] : tb.prefix_len[r], cnt = in_lds ? s_lcnt[k] : tb.nact[r];
           const int nck = ceil_div(ceil_div(plen, dm.pt), cut.pb);
           blocks = dm.Hkv * nck * cnt;
           items = pc.prompt_mode == 2 ? dm.Hkv * nck * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : blocks;
@@ -227,7 +227,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   //       slot [4] + (h * [6] + ck) * [5]   [5] live branches of the request   [6] prompt chunks   [7] 0
   for (int i = tid; i < nA; i += kPlanThreads) {
     const int r = tb.active[i] / dm.Nb;
-    const int j = i - tb.req_first[r], cnt = tb.refcnt[r];
+    const int j = i - tb.req_first[r], cnt = tb.nact[r];
     const int pp = ceil_div(tb.prefix_len[r], dm.pt);
     const int nck = pp > 0 ? ceil_div(pp, cut.pb) : 0;
     const int tiles = pc.prompt_mode == 2 ? ((j + 1) * dm.G - 1) / (16 * kSharedBlocks) - (j * dm.G) / (16 * kSharedBlocks) + 1 : 1;
@@ -282,7 +282,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
           d3 = make_int4(s_lpstart[k], its[k], k, 1);
         } else {
           const int r = tb.live_req[k];
-          d2 = make_int4(r, tb.refcnt[r], tb.prefix_len[r], tb.req_first[r]);
+          d2 = make_int4(r, tb.nact[r], tb.prefix_len[r], tb.req_first[r]);
           d3 = make_int4(tb.req_pstart[r], its[k], k, 1);
         }
       }

@@ -55,6 +55,7 @@ enum Scalar {
 
 struct Dims {
   int Hq, Hkv, G, d, pt, num_pages, max_req, Nb, Q, max_bp, max_pp, H, dtype, layout, esize;
+  int start_waiting;      // a request's branches are created WAITING and join the batch through sart_start_branches
   long long tile_elems;   // pt * d: elements of one K (or V) tile
   long long page_elems;   // Hkv * 2 * tile_elems
   float k_scale, v_scale;           // 8-bit float caches: K and V are stored as codes of x / scale
@@ -67,7 +68,9 @@ struct Tables {
   int* req_used;
   int* prefix_len;
   int* prefix_table;     // [max_req][max_pp]
-  int* refcnt;
+  int* refcnt;           // branches that hold the request's prefix: active and waiting ones
+  int* nact;             // the request's rows in the active list
+  int* req_tmp;          // [max_req] scratch of the start plan
   int* num_completed;
   int* num_pruned;
   int* branch_appended;
@@ -216,6 +219,7 @@ void launch_prune(const Ctx& c, const PlanCfg& pc, const PruneArgs& a, hipStream
 void launch_finish(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, const int* targets_dev, int call_seq,
                    hipStream_t s);
 void launch_plan(const Ctx& c, const PlanCfg& pc, hipStream_t s);
+void launch_start(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, int call_seq, hipStream_t s);
 
 struct DecodeArgs {
   const void* q;

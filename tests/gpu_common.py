@@ -32,6 +32,12 @@ class GpuEngine:
     def finish(self, handles):
         return self.c.finish_branch(handles, status=True)
 
+    def start(self, handles):
+        try:
+            return self.c.start_branches(handles, status=True)
+        except Exception as e:                       # host-side refusals (duplicates, range) are statuses here
+            return getattr(e, "status", orc.E_INVALID)
+
     def state(self):
         return self.c.get_state()
 

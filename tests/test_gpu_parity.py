@@ -36,7 +36,8 @@ def test_golden_traces_on_gpu(scn):
     d = scn["desc"]
     g = GpuEngine(n_q_heads=2, n_kv_heads=1, head_dim=8, page_tokens=d["pt"], num_pages=d["num_pages"],
                   max_requests=d["max_req"], branches_per_request=d["Nb"], finish_quota=d["Q"],
-                  max_pages_per_branch=d["max_bp"], max_prefix_pages=d["max_pp"], dtype="f32")
+                  max_pages_per_branch=d["max_bp"], max_prefix_pages=d["max_pp"], dtype="f32",
+                  start_waiting=d.get("start_waiting", False))
     run_golden_scenario(scn, g, 1, 8, np.float32)
 
 
@@ -377,3 +378,104 @@ def test_decode_is_deterministic_and_leaves_inputs_alone():
     st1 = g.state()
     g.c.decode_attention(q)
     assert_state_equal(st1, g.state())          # attention never changes the integer state
+
+
+# ---------------------------------------------------------------------------
+# waiting branches (Algorithm 1's branch queue): created WAITING, started one by one
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,pt,d", [("f32", 4, 8), ("bf16", 16, 64)])
+def test_random_op_sequences_with_waiting_branches(dtype, pt, d):
+    """Random prefix / start / append / prune / finish sequences on caches whose branches are created WAITING
+    (errors included): status and the whole integer state agree with the oracle after every call, and the
+    attention of the final state too."""
+    rng = np.random.default_rng(77)
+    R, Nb, num_pages, max_bp, max_pp = 6, 4, 140, 6, 3
+    npd = np.float32 if dtype == "f32" else np.uint16
+    for trial in range(6):
+        kw = dict(n_q_heads=2, n_kv_heads=1, head_dim=d, page_tokens=pt, num_pages=num_pages, max_requests=R,
+                  branches_per_request=Nb, finish_quota=int(rng.integers(0, 4)), max_pages_per_branch=max_bp,
+                  max_prefix_pages=max_pp, dtype=dtype, start_waiting=True)
+        fo = rng.permutation(num_pages).astype(np.int32) if trial % 2 else None
+        o, g = orc.OracleCache(free_order=fo, **kw), GpuEngine(free_order=fo, **kw)
+
+        def draw(n):
+            x = rng.standard_normal((n, 1, d)).astype(np.float32)
+            return x if dtype == "f32" else wl.f32_to_bf16_bits(x)
+        next_req = 0
+        for step in range(60):
+            st = o.state()
+            nA = int(st["n_active"][0])
+            waiting = np.flatnonzero(st["branch_state"] == orc.WAITING)
+            op = int(rng.integers(0, 8))
+            if op == 0 and next_req < R:
+                n = int(rng.integers(1, max_pp * pt + 1))
+                k, v = draw(n), draw(n)
+                rc = [e.append(orc.SEQ_PREFIX, [next_req], [n], k, v) for e in (o, g)]
+                next_req += 1
+            elif op in (1, 2, 3) and len(waiting):
+                m = int(rng.integers(1, min(len(waiting), 5) + 1))
+                pool = waiting if rng.random() < 0.85 else np.arange(R * Nb)      # sometimes a branch that is not waiting
+                hs = rng.choice(pool, size=min(m, len(pool)), replace=False)
+                rc = [e.start(hs) for e in (o, g)]
+            elif op in (4, 5) and nA:
+                n = rng.integers(0, 2 * pt, size=nA)
+                k, v = draw(int(n.sum())), draw(int(n.sum()))
+                rc = [e.append(orc.SEQ_BRANCH, None, n, k, v) for e in (o, g)]
+            elif op == 6 and nA:
+                sc = rng.random(nA).astype(np.float32)
+                kwp = dict(k=int(rng.integers(0, 3)), threshold=rng.random(R).astype(np.float32),
+                           max_pruned=rng.integers(0, Nb + 1, size=R))
+                mode = int(rng.integers(0, 3))
+                rc = [e.prune(mode, sc, **kwp) for e in (o, g)]
+            elif op == 7 and nA:
+                hs = rng.choice(st["active_handles"][:nA], size=int(rng.integers(1, min(nA, 3) + 1)), replace=False)
+                rc = [e.finish(hs) for e in (o, g)]
+            else:
+                continue
+            assert rc[0] == rc[1], (trial, step, op, rc)
+            so, sg = o.state(), g.state()
+            assert_state_equal(so, sg)
+            check_invariants(sg, pt=pt, num_pages=num_pages, Nb=Nb, max_req=R)
+        nA = int(o.state()["n_active"][0])
+        if nA:
+            q = draw(R * Nb).reshape(R * Nb, 1, d).repeat(2, axis=1)
+            compare_attention(wl.scaled(wl.CONFIGS[2], dtype=dtype), o, g, q)
+
+
+def test_starting_branches_among_thousands_of_rows():
+    """The start plan's scans run over more than one chunk of 1024 rows: 700 requests x 4 branches, started in
+    three calls that interleave requests with and without rows already in the batch."""
+    rng = np.random.default_rng(5)
+    R, Nb, d, pt = 700, 4, 64, 16
+    num_pages = R * Nb * 2 + R + 64
+    kw = dict(n_q_heads=4, n_kv_heads=2, head_dim=d, page_tokens=pt, num_pages=num_pages, max_requests=R,
+              branches_per_request=Nb, finish_quota=2, max_pages_per_branch=3, max_prefix_pages=1, dtype="bf16",
+              start_waiting=True)
+    o, g = orc.OracleCache(**kw), GpuEngine(**kw)
+
+    def draw(n, heads):
+        return wl.f32_to_bf16_bits(rng.standard_normal((n, heads, d)).astype(np.float32))
+    for r0 in range(0, R, 100):
+        ids = np.arange(r0, min(R, r0 + 100))
+        P = rng.integers(1, pt + 1, size=len(ids))
+        k, v = draw(int(P.sum()), 2), draw(int(P.sum()), 2)
+        for e in (o, g):
+            assert e.append(orc.SEQ_PREFIX, ids, P, k, v) == orc.OK
+    order = rng.permutation(R * Nb)
+    for part in (order[:1100], order[1100:2300], order[2300:]):
+        for e in (o, g):
+            assert e.start(part) == orc.OK
+        assert_state_equal(o.state(), g.state())
+        nA = int(o.state()["n_active"][0])
+        L = rng.integers(0, 2 * pt, size=nA)
+        k, v = draw(int(L.sum()), 2), draw(int(L.sum()), 2)
+        for e in (o, g):
+            assert e.append(orc.SEQ_BRANCH, None, L % (pt // 2 + 1), k[:int((L % (pt // 2 + 1)).sum())], v[:int((L % (pt // 2 + 1)).sum())]) == orc.OK
+        assert_state_equal(o.state(), g.state())
+    st = g.state()
+    check_invariants(st, pt=pt, num_pages=num_pages, Nb=Nb, max_req=R)
+    nA = int(st["n_active"][0])
+    assert nA == R * Nb
+    q = draw(R * Nb, 4)
+    rows = sorted(set(rng.integers(0, nA, size=40).tolist() + [0, 1023, 1024, 2047, 2048, nA - 1]))
+    compare_attention(wl.scaled(wl.CONFIGS[2], dtype="bf16"), o, g, q, rows=rows)

@@ -1,5 +1,6 @@
 """Algorithm 1 end to end: the HIP-side scheduler against the oracle-side one on the same seeded
-request stream (continuous batching with admission into freed pages, early stop, two-phase pruning).
+request stream (continuous batching branch by branch through the branch queue, with B not a multiple of N so that
+requests sit half in the batch and half in the queue; early stop; two-phase pruning; pages reused).
 Integer state is compared after every maintenance round (digest), attention on sampled rows every step."""
 import hashlib
 
@@ -28,17 +29,17 @@ def _digest(st):
 def test_sart_scheduler_matches_oracle():
     import torch
     from paper_2505_13326_amd.scheduler import SartParams, serve
-    R, N, M, B, T = 14, 8, 4, 32, 25
+    R, N, M, B, T = 14, 8, 4, 29, 25
     cfg = wl.scaled(wl.CONFIGS[3], n_requests=R, prompt_len=200, quota=M)
     rng = np.random.default_rng(77)
     targets = np.maximum(3, np.rint(60 * np.exp(0.8 * rng.standard_normal(R * N)))).astype(np.int64)
     targets = np.minimum(targets, 400)
-    # a pool too small for everything at once: admission has to wait for freed pages
-    num_pages = B * (T // 16 + 2) + 4 * 13 + B * 14
+    # B is configured for the pool (Section 5.1): room for B branches of the longest length and the live prompts
     max_bp = 400 // 16 + 2
+    num_pages = B * max_bp + R * 13
     kw = dims(cfg, num_pages, max_bp, max_pp=13)
     fo = wl.free_order(cfg, num_pages)
-    o, g = orc.OracleCache(free_order=fo, **kw), GpuEngine(free_order=fo, **kw)
+    o, g = orc.OracleCache(free_order=fo, start_waiting=True, **kw), GpuEngine(free_order=fo, start_waiting=True, **kw)
     arrivals = [(r, r // 3) for r in range(R)]
     reward_table = np.random.default_rng(5).random((64, R * N)).astype(np.float32)
     reward = lambda hs, rnd: reward_table[rnd % 64, np.asarray(hs)]
@@ -84,12 +85,14 @@ def test_sart_scheduler_matches_oracle():
         a, b = ans_o[r], res_g[r]
         assert (a["done_round"], a["done_step"], a["answer"], a["admitted_round"]) == \
                (b.done_round, b.done_step, b.answer, b.admitted_round)
-        assert a["completed"] == b.completed
+        assert a["completed"] == b.completed and a["started"] == b.started
     assert worst[0] <= TOL["bf16"]
     st = g.state()
     assert st["n_active"][0] == 0 and st["free_top"][0] == num_pages
     late = [res_g[r].admitted_round for r in range(R)]
     assert max(l - r // 3 for r, l in enumerate(late)) > 0      # somebody had to queue for room
+    split = [r for r in range(R) if len(set(res_g[r].started.values())) > 1]
+    assert split, "no request had its branches start at different steps"
     assert stats_g["min_free_pages"] < num_pages - 100           # the pool was in use ...
     assert not np.array_equal(st["free_stack"], fo[::-1])        # ... and its pages came back in another order
     print(f"scheduler: {stats_g}, max abs attention err {worst[0]:.3g}, admitted rounds {late}")

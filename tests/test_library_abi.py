@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported_and_bound():
 def test_pool_bytes_and_null_checks_need_no_gpu():
     lib = sart.load_library()
     from paper_2505_13326_amd.binding import _Desc
-    d = _Desc(1, 28, 4, 128, 16, 1000, 16, 8, 0, 1025, 32, sart.BF16, 0, None, 0, None)
+    d = _Desc(1, 28, 4, 128, 16, 1000, 16, 8, 0, 1025, 32, sart.BF16, 0, None, 0, None, 1.0, 1.0, 0)
     assert lib.sart_pool_bytes(C.byref(d)) == 1000 * 16 * 2 * 4 * 128 * 2
     out = C.c_void_p()
     d.n_q_heads = 30  # not a multiple of the KV heads
