@@ -9,7 +9,7 @@ import pytest
 
 import oracle as orc
 import workloads as wl
-from gpu_common import TOL, GpuEngine, dims, populate
+from gpu_common import TOL, GpuEngine, compare_attention, dims, populate
 from helpers import check_invariants
 from oracle.trace import run_trace as oracle_trace
 
@@ -111,9 +111,10 @@ def test_trace_matches_oracle_after_every_call(size):
           f"max abs attention err {worst[0]:.3g}")
 
 
-def test_graph_driven_trace_ends_in_the_same_state():
+def test_graph_driven_trace_ends_where_the_oracle_ends():
     """The loop that keeps the step on the device (one recorded graph: gather, append, attention,
-    completion by target length) must leave the cache exactly where the host-driven loop leaves it."""
+    completion by target length) and the host-driven loop must both leave the cache exactly where the
+    oracle's own step loop leaves its cache: whole integer state, branch-steps, and the last steps' attention."""
     import torch
     from paper_2505_13326_amd.trace import run_trace, run_trace_graph
     cfg = wl.scaled(wl.CONFIGS[3], n_requests=5, length_params=(150, 0.8), length_cap=1200, n_steps=130, prune_every=20)
@@ -123,6 +124,12 @@ def test_graph_driven_trace_ends_in_the_same_state():
     kw = dims(cfg, num_pages, (cfg.length_cap + cfg.n_steps) // 16 + 2)
     fo = wl.free_order(cfg, num_pages)
 
+    o = orc.OracleCache(free_order=fo, **kw)
+    populate(cfg, [o], L)
+    res_o = oracle_trace(o, targets=targets, step_kv=lambda s: wl.step_kv(cfg, s), n_steps=cfg.n_steps,
+                         prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: wl.scores(cfg, e))
+    want = (res_o["branch_steps"], _digest(o.state()))
+
     def dev(x):
         return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).view(torch.bfloat16).cuda()
 
@@ -130,12 +137,12 @@ def test_graph_driven_trace_ends_in_the_same_state():
     qs = {s: dev(wl.query(cfg, s)) for s in range(1, cfg.n_steps + 1)}
     args = dict(targets=targets, step_kv=lambda s: kvs[s], query=lambda s: qs[s], n_steps=cfg.n_steps,
                 prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: torch.from_numpy(wl.scores(cfg, e)).cuda())
-    ends = []
     for loop in (run_trace, run_trace_graph):
         g = GpuEngine(free_order=fo, **kw)
         populate(cfg, [g], L)
         res = loop(g.c, **args)
         st, rc = g.c.get_state(with_status=True)
         assert rc == 0
-        ends.append((res["branch_steps"], _digest(st)))
-    assert ends[0] == ends[1], ends
+        assert (res["branch_steps"], _digest(st)) == want, loop.__name__
+        if int(st["n_active"][0]):                      # what is left attends alike on both sides
+            compare_attention(cfg, o, g, wl.query(cfg, cfg.n_steps + 1))
