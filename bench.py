@@ -118,7 +118,7 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
 def bench_trace(args, cfg, sart, wl, np, torch):
     """Config 3: the whole 400-step early-stop / prune loop (append + attention + finish + prune, host
     step loop included).  value = branch-decode-steps per second over the loop.  Returns the JSON record."""
-    from paper_2505_13326_amd.trace import run_trace, run_trace_graph
+    from paper_2505_13326_amd.trace import run_trace, run_trace_device
     L = wl.lengths(cfg)
     targets = (L + wl.remaining_tokens(cfg)).reshape(-1)
     num_pages = wl.pages_needed(cfg, L, growth_tokens=cfg.n_steps) + 64
@@ -151,10 +151,10 @@ def bench_trace(args, cfg, sart, wl, np, torch):
         cache = new_cache()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        if args.graph:   # the step (gather, append, attention, completion) replayed from one HIP graph
-            res = run_trace_graph(cache, targets=targets, step_kv=lambda s: kvs[s], query=lambda s: qs[s],
-                                  n_steps=cfg.n_steps, prune_every=cfg.prune_every, prune_k=cfg.prune_k,
-                                  scores=lambda e: scs[e])
+        if not args.host_loop:   # the step stays on the device: rows by handle, nothing read back between prunes
+            res = run_trace_device(cache, targets=targets, step_kv=lambda s: kvs[s], query=lambda s: qs[s],
+                                   n_steps=cfg.n_steps, prune_every=cfg.prune_every, prune_k=cfg.prune_k,
+                                   scores=lambda e: scs[e], out=out, graph=args.graph)
         else:
             res = run_trace(cache, targets=targets, step_kv=lambda s: kvs[s], query=lambda s: qs[s], n_steps=cfg.n_steps,
                             prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: scs[e], out=out)
@@ -163,7 +163,7 @@ def bench_trace(args, cfg, sart, wl, np, torch):
         assert cache.sync_status() == 0
         cache.close()
     dt = float(np.mean(times[1:]))
-    busy = int(np.sum(res["active_per_step"] > 0)) if "active_per_step" in res else cfg.n_steps
+    busy = int(np.sum(res["active_per_step"] > 0)) if "active_per_step" in res else res["steps_enqueued"]
 
     # ---- the attention kernel's share of the loop: one more pass with HIP events around every step's kernel
     #      (each read waits for the device, so this pass is not the timed one) -------------------------------
@@ -221,7 +221,9 @@ def bench_trace(args, cfg, sart, wl, np, torch):
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"cfg3 {cfg.name}: {cfg.n_requests} requests x {cfg.nb} branches, quota {cfg.quota}, "
                                f"{cfg.n_steps} steps, prune {cfg.prune_k} lowest every {cfg.prune_every} steps; whole "
-                               "loop incl. host driver" + (", step replayed from a HIP graph" if args.graph else ""), "branch_steps": res["branch_steps"],
+                               "loop incl. host driver" + (", device-driven step (rows by handle, no state read back between prunes)"
+                                                          + (" replayed from a HIP graph" if args.graph else "")
+                                                          if not args.host_loop else ", host-driven step"), "branch_steps": res["branch_steps"],
                    "steps_with_active_branches": busy, "loop_s": round(dt, 4)},
         "roofline": roofline, "cpu_baseline": cpu}
 
@@ -516,7 +518,9 @@ def main():
     ap.add_argument("--merge", default="kernel", choices=["in-kernel", "kernel"], help="where a step's partial results "
                     "are merged: by the separate merge kernel (default) or by the attention kernel's last writers")
     ap.add_argument("--no-stagger", action="store_true", help="every wave serves its prompt work before its own range")
-    ap.add_argument("--graph", action="store_true", help="replay the step (append + attention) from a HIP graph")
+    ap.add_argument("--graph", action="store_true", help="replay the step (append + attention) from a HIP graph (cfg3: the device-driven step)")
+    ap.add_argument("--host-loop", action="store_true", help="cfg3: the host-driven step (the host gathers the active rows and lists the completed "
+                    "branches, reading the state back after every call that changes the batch) instead of the device-driven one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
     args = ap.parse_args()

@@ -338,6 +338,30 @@ sart_status sart_get_state(sart_cache* cache, int32_t* n_active,
  * their contents change with every state-changing call, in stream order. */
 sart_status sart_device_views(sart_cache* cache, const int32_t** active_handles, const int32_t** n_active);
 
+/* The decode step with rows addressed by branch handle, for a step loop that
+ * never waits for the device (Algorithm 1, Decode: the batch decodes for T
+ * steps between two maintenance rounds; the caller need not know which
+ * branches are still in the batch to run them).  Row b of k, v, q and out
+ * belongs to branch handle b, whatever its place in the active order; all four
+ * hold max_requests * Nb rows; rows of branches that are not ACTIVE are neither
+ * read nor written.  Otherwise sart_append_active_by_handle is
+ * sart_append_tokens(SART_SEQ_BRANCH, SART_ALL_ACTIVE(max_requests * Nb), NULL,
+ * NULL, k, v, layer) and sart_decode_attention_by_handle is
+ * sart_decode_attention: same results for the same branches, same errors,
+ * nothing staged from the host, so both replay from a HIP graph.  With
+ * sart_finish_reached a whole step needs no gather by the caller and no state
+ * read back. */
+sart_status sart_append_active_by_handle(sart_cache* cache, const void* k, const void* v /*DEVICE [max_requests*Nb, Hkv, d]*/,
+                                         int32_t layer, void* stream);
+sart_status sart_decode_attention_by_handle(sart_cache* cache, int32_t layer, const void* q /*DEVICE [max_requests*Nb, Hq, d]*/,
+                                            float* out /*DEVICE [max_requests*Nb, Hq, d]*/, float scale, void* stream);
+
+/* The active count as of the last state-changing kernel that has run, read
+ * without waiting for the device (the kernels store it to pinned host memory).
+ * It lags the calls still queued: a loop that never reads the state back uses it
+ * to notice, a few steps late, that the batch has drained.  -1: null cache. */
+int32_t sart_active_count_hint(const sart_cache* cache);
+
 /* Text of the last host-side error of this thread. */
 const char* sart_last_error(void);
 

@@ -65,6 +65,9 @@ _SIGNATURES = {
     "sart_finish_branch": (C.c_int, [C.c_void_p, C.c_int32, _ip, C.c_void_p]),
     "sart_start_branches": (C.c_int, [C.c_void_p, C.c_int32, _ip, C.c_void_p]),
     "sart_finish_reached": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sart_append_active_by_handle": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
+    "sart_decode_attention_by_handle": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]),
+    "sart_active_count_hint": (C.c_int32, [C.c_void_p]),
     "sart_device_views": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
     "sart_sync_status": (C.c_int, [C.c_void_p]),
     "sart_get_state": (C.c_int, [C.c_void_p] + [_ip] * 11),
@@ -291,6 +294,29 @@ class SartCache:
         assert target_len.is_cuda and target_len.dtype == torch.int32 and target_len.is_contiguous()
         assert target_len.numel() == self.max_req * self.Nb
         self._check(self.lib.sart_finish_reached(self.h, C.c_void_p(target_len.data_ptr()), _stream_handle(stream)))
+
+    def append_active_by_handle(self, k, v, stream=None, layer=0):
+        """sart_append_active_by_handle.  k, v: device tensors [max_requests * Nb, Hkv, d], row = branch handle."""
+        k = self._dev(k, (self.Hkv, self.d))
+        v = self._dev(v, (self.Hkv, self.d))
+        assert k.shape[0] == v.shape[0] == self.max_req * self.Nb
+        self._check(self.lib.sart_append_active_by_handle(self.h, C.c_void_p(k.data_ptr()), C.c_void_p(v.data_ptr()), int(layer),
+                                                          _stream_handle(stream)))
+
+    def decode_attention_by_handle(self, q, out, scale=0.0, stream=None, layer=0):
+        """sart_decode_attention_by_handle.  q, out: device tensors [max_requests * Nb, Hq, d], row = branch handle;
+        rows of branches that are not active are left as they are."""
+        import torch
+        q = self._dev(q, (self.Hq, self.d))
+        assert q.shape[0] == self.max_req * self.Nb
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
+        self._check(self.lib.sart_decode_attention_by_handle(self.h, int(layer), C.c_void_p(q.data_ptr()),
+                                                             C.c_void_p(out.data_ptr()), float(scale), _stream_handle(stream)))
+        return out
+
+    def active_count_hint(self) -> int:
+        """sart_active_count_hint: the active count without waiting for the device (it lags queued calls)."""
+        return int(self.lib.sart_active_count_hint(self.h))
 
     def device_views(self):
         """sart_device_views as torch int32 tensors over the library's memory (read-only by convention):

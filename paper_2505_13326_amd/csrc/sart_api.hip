@@ -70,6 +70,7 @@ struct sart_cache {
   int profiling = 0;                   // 0 off, n >= 1: events around n attention launches
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   bool ev_valid = false;
+  int* host_nactive = nullptr;         // pinned host int the kernels store the active count to (sart_active_count_hint)
 };
 
 namespace {
@@ -235,6 +236,9 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   ALLOC(tb.row_desc, 8 * H);
   ALLOC(tb.seg_count, H * dm.Hkv);
   HIP_TRY(hipMemset(tb.seg_count, 0, H * dm.Hkv * sizeof(int)));
+  HIP_TRY(hipHostMalloc((void**)&c->host_nactive, 64, hipHostMallocMapped));
+  *c->host_nactive = 0;
+  HIP_TRY(hipHostGetDevicePointer((void**)&tb.host_nactive, c->host_nactive, 0));
   // partial slots: one per own range (wave), one per (row, kv head) a range boundary falls in, and the prompts'
   // blocks, which the planning kernel keeps to max(S, 4 per wave)
   const long long S = (long long)H * dm.Hkv, max_waves = (long long)c->max_wg * kAttnWaves;
@@ -284,11 +288,35 @@ sart_status sart_free_cache(sart_cache* c) {
   }
   for (int i = 0; i < 4; ++i)
     if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+  if (c->host_nactive) (void)hipHostFree(c->host_nactive);
   delete c;
   return SART_OK;
 }
 
 int32_t sart_cache_layout(const sart_cache* c) { return c ? c->ctx.dm.layout : -1; }
+
+// One token for every active branch, the count read on the device.  n_seqs = -rows of k and v; by_handle: the
+// rows are addressed by branch handle (then rows = max_requests * Nb).
+static sart_status append_all_active(sart_cache* c, int n_seqs, int by_handle, const void* k, const void* v, int32_t layer,
+                                     void* stream) {
+  const Dims& dm = c->ctx.dm;
+  const int kind = SART_SEQ_BRANCH;
+  if (!k || !v) return fail(SART_E_INVALID, "null k or v");
+  hipStream_t st = (hipStream_t)stream;
+  note_stream(c, stream);
+  AppendArgs a{};
+  a.kind = kind; a.n_seqs = n_seqs; a.total_rows = n_seqs < -dm.H ? dm.H : -n_seqs; a.k = k; a.v = v;
+  a.call_seq = ++c->call_seq;
+  a.write_only = layer > 0;
+  a.by_handle = by_handle;
+  const long long mark = by_handle ? -2 : -1;               // what a layer > 0 append of the same step must repeat
+  if (layer == 0) { c->last_kind = kind; c->last_n_seqs = n_seqs; c->last_has_ids = 0; c->last_has_ntok = 0; c->last_total = mark; }
+  else if (c->last_kind != kind || c->last_n_seqs != n_seqs || c->last_total != mark)
+    return fail(SART_E_INVALID, "an append to layer %d must repeat the step's layer-0 append", layer);
+  launch_append(layer_ctx(c, layer), c->plan, a, st);
+  HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
 
 sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, const int32_t* ids,
                                const int32_t* n_tokens, const void* k, const void* v, int32_t layer,
@@ -297,21 +325,8 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
   const Dims& dm = c->ctx.dm;
   if (layer < 0 || layer >= c->desc.n_layers) return fail(SART_E_INVALID, "layer out of range");
   if (kind != SART_SEQ_PREFIX && kind != SART_SEQ_BRANCH) return fail(SART_E_INVALID, "unknown sequence kind");
-  if (n_seqs < 0 && kind == SART_SEQ_BRANCH && !ids && !n_tokens) {   // SART_ALL_ACTIVE(rows)
-    if (!k || !v) return fail(SART_E_INVALID, "null k or v");
-    hipStream_t st = (hipStream_t)stream;
-    note_stream(c, stream);
-    AppendArgs a{};
-    a.kind = kind; a.n_seqs = n_seqs; a.total_rows = n_seqs < -dm.H ? dm.H : -n_seqs; a.k = k; a.v = v;
-    a.call_seq = ++c->call_seq;
-    a.write_only = layer > 0;
-    if (layer == 0) { c->last_kind = kind; c->last_n_seqs = n_seqs; c->last_has_ids = 0; c->last_has_ntok = 0; c->last_total = -1; }
-    else if (c->last_kind != kind || c->last_n_seqs != n_seqs || c->last_total != -1)
-      return fail(SART_E_INVALID, "an append to layer %d must repeat the step's layer-0 append", layer);
-    launch_append(layer_ctx(c, layer), c->plan, a, st);
-    HIP_TRY(hipGetLastError());
-    return SART_OK;
-  }
+  if (n_seqs < 0 && kind == SART_SEQ_BRANCH && !ids && !n_tokens)     // SART_ALL_ACTIVE(rows)
+    return append_all_active(c, n_seqs, 0, k, v, layer, stream);
   if (n_seqs < 0) return fail(SART_E_INVALID, "negative n_seqs");
   if (kind == SART_SEQ_PREFIX && !ids && n_seqs > 0) return fail(SART_E_INVALID, "prefix append needs request ids");
   const int limit = kind == SART_SEQ_PREFIX ? dm.max_req : dm.H;
@@ -376,9 +391,20 @@ sart_status sart_append_tokens(sart_cache* c, int32_t kind, int32_t n_seqs, cons
   return SART_OK;
 }
 
+sart_status sart_append_active_by_handle(sart_cache* c, const void* k, const void* v, int32_t layer, void* stream) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (layer < 0 || layer >= c->desc.n_layers) return fail(SART_E_INVALID, "layer out of range");
+  return append_all_active(c, -c->ctx.dm.H, 1, k, v, layer, stream);
+}
+
+int32_t sart_active_count_hint(const sart_cache* c) {
+  return c && c->host_nactive ? *(volatile const int*)c->host_nactive : -1;
+}
+
 // Shared by the two decode entry points: `partials` / `partial_cap` name the scratch the kernels use.
 static sart_status decode_common(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows, float scale,
-                                 void* stream, float* partials, long long partial_cap, int* seg_count, bool profile) {
+                                 void* stream, float* partials, long long partial_cap, int* seg_count, bool profile,
+                                 bool by_handle = false) {
   const Dims& dm = c->ctx.dm;
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)dm.d);
   hipStream_t st = (hipStream_t)stream;
@@ -392,6 +418,7 @@ static sart_status decode_common(sart_cache* c, int32_t layer, const void* q, fl
   a.partials = partials; a.partial_cap = partial_cap; a.seg_count = seg_count;
   a.fused_merge = c->merge_mode;
   a.stagger_prompt = c->stagger_prompt;
+  a.by_handle = by_handle;
   a.call_seq = ++c->call_seq;
   for (int i = 0; i < 4; ++i) a.ev[i] = profile && c->profiling ? c->ev[i] : nullptr;
   a.repeats = profile ? c->profiling : 0;
@@ -414,6 +441,14 @@ sart_status sart_decode_attention(sart_cache* c, int32_t layer, const void* q, f
   sart_status rc = check_decode_args(c, layer, q, out, n_rows);
   if (rc != SART_OK) return rc;
   return decode_common(c, layer, q, out, n_rows, scale, stream, c->partials, c->partial_cap, c->ctx.tb.seg_count, true);
+}
+
+sart_status sart_decode_attention_by_handle(sart_cache* c, int32_t layer, const void* q, float* out, float scale,
+                                            void* stream) {
+  const int n_rows = c ? c->ctx.dm.H : 0;
+  sart_status rc = check_decode_args(c, layer, q, out, n_rows);
+  if (rc != SART_OK) return rc;
+  return decode_common(c, layer, q, out, n_rows, scale, stream, c->partials, c->partial_cap, c->ctx.tb.seg_count, true, true);
 }
 
 sart_status sart_decode_attention_static(sart_cache* c, int32_t layer, const void* q, float* out, int32_t n_rows,

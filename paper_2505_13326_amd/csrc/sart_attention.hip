@@ -117,10 +117,16 @@ __device__ inline void store_partial(const WaveState<D>& st, float* partials, lo
 // output rows.  No wave ever waits for another.  The counter is back to zero
 // when the kernel ends.
 // ---------------------------------------------------------------------------
-struct RowInfo { int cum, pages, seq, prompt_writers, pslot, cnt, nck; };   // see refresh_decode_plan (row_desc)
+struct RowInfo { int cum, pages, seq, prompt_writers, pslot, cnt, nck, handle; };   // see refresh_decode_plan (row_desc)
 __device__ inline RowInfo load_row_info(const int* __restrict__ row_desc, int row) {
   const int4 x = ((const int4*)(row_desc + 8LL * row))[0], y = ((const int4*)(row_desc + 8LL * row))[1];
-  return RowInfo{x.x, x.y, x.z, x.w, y.x, y.y, y.z};
+  return RowInfo{x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
+}
+// The row of q and out that belongs to active row `row`: the row itself, or the branch's handle when the
+// caller addresses its buffers by handle.
+__device__ inline int io_row(const DecodeArgs& a, const RowInfo& ri, int row) { return a.by_handle ? ri.handle : row; }
+__device__ inline int io_row(const DecodeArgs& a, const int* __restrict__ row_desc, int row) {
+  return a.by_handle ? row_desc[8LL * row + 7] : row;
 }
 // the own-line pieces of (row, kv head h): first range w0 and their number sn
 __device__ inline void own_pieces(const Cut& cut, int Hkv, const RowInfo& ri, int h, long long& w0, int& sn) {
@@ -179,7 +185,7 @@ __device__ inline void fold_segment(const DecodeArgs& a, const Dims& dm, long lo
   const long long pa = prompt_slot_base + ri.pslot + (long long)h * ri.nck * ri.cnt;
   for (int e = lane; e < dm.G * D4; e += 64) {
     const int r = e / D4, d4 = e % D4;
-    fold_columns<true>(a.partials, a.out + ((long long)row * dm.Hq + h * dm.G + r) * D, pf, dm.G, D, r, d4, pa, ri.cnt, ri.nck, sa,
+    fold_columns<true>(a.partials, a.out + ((long long)io_row(a, ri, row) * dm.Hq + h * dm.G + r) * D, pf, dm.G, D, r, d4, pa, ri.cnt, ri.nck, sa,
                        sn, a.v_scale);
   }
 }
@@ -197,7 +203,7 @@ __device__ inline void finish_piece(const DecodeArgs& a, const Dims& dm, const C
     const float l = sum_over_rows(st.l);
     if (r >= dm.G) return;
     const float inv = l > 0.f ? 1.0f / l : 0.f;
-    float* orow = a.out + ((long long)row * dm.Hq + h * dm.G + r) * D;
+    float* orow = a.out + ((long long)io_row(a, ri, row) * dm.Hq + h * dm.G + r) * D;
 #pragma unroll
     for (int b = 0; b < D / 16; ++b) *(f32x4*)(orow + b * 16 + 4 * g) = st.o[b] * (inv * a.v_scale);
     return;
@@ -322,7 +328,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
     // every call, so that the page ids stay scalar loads in each instance of the streaming loop.
     auto run_piece = [&](auto once, const int* __restrict__ table, int row, int h, int r0, int rn, int n_last, long long slot,
                          const RowInfo& ri) {
-      load_q<D>(qreg, q, dm, row, h);
+      load_q<D>(qreg, q, dm, io_row(a, ri, row), h);
       st.reset();
       stream_pages(once, table, r0, rn, n_last, h,
                    [&](const uint4* kq, const uint4* vq) { process_raw<D, FP8, true>(st, kq, vq, qreg, 16, 16, a.scale_log2); },
@@ -377,7 +383,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
               const int j = fc / dm.G, g = fc % dm.G;
               br[b] = have ? j : -1;
               hd[b] = g;
-              const uint16_t* qrow = q + ((long long)(first_row + j) * dm.Hq + h * dm.G + g) * D;
+              const uint16_t* qrow = q + ((long long)io_row(a, row_desc, first_row + j) * dm.Hq + h * dm.G + g) * D;
     #pragma unroll
               for (int i = 0; i < KQ; ++i) qb[b][i] = *(const uint4*)(qrow + i * 32 + g4 * 8);
               sb[b].reset();
@@ -467,7 +473,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
             const int cs = prompt_chunk_pages(pp, nck), r0 = ck * cs, rn = min(cs, pp - r0);
             const int row = tb.req_first[r] + j;
             RowInfo ri{};
-            if (a.fused_merge) ri = load_row_info(row_desc, row);
+            if (a.fused_merge || a.by_handle) ri = load_row_info(row_desc, row);
             run_piece(std::false_type{}, prefix_table + (long long)r * dm.max_pp, row, h, r0, rn, min(16, plen - (r0 + rn - 1) * 16),
                       prompt_slot_base + u, ri);
           }
@@ -508,7 +514,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         const RowInfo ri = load_row_info(row_desc, row);
         if (ri.pages != 0 || ri.prompt_writers != 0) continue;
         for (int e = lane; e < dm.G * (D / 4); e += 64)
-          *(f32x4*)(a.out + ((long long)row * dm.Hq + h * dm.G) * D + 4LL * e) = f32x4{0.f, 0.f, 0.f, 0.f};
+          *(f32x4*)(a.out + ((long long)io_row(a, ri, row) * dm.Hq + h * dm.G) * D + 4LL * e) = f32x4{0.f, 0.f, 0.f, 0.f};
       }
     }
   }
@@ -592,7 +598,7 @@ k_attn_generic(Ctx c, DecodeArgs a) {
       }
       float* pbase = a.partials + slot * partial_floats(dm.G, D);
       for (int r = 0; r < dm.G; ++r) {
-        const T* qrow = q + ((long long)row * dm.Hq + h * dm.G + r) * D;
+        const T* qrow = q + ((long long)io_row(a, tb.row_desc, row) * dm.Hq + h * dm.G + r) * D;
         float m = -__builtin_inff(), l = 0.f;
         float o[4] = {0.f, 0.f, 0.f, 0.f};   // d = lane + 64*c
         generic_row<T>(dm, pool, table, r0, rn, tokens, h, qrow, a.scale_log2, m, l, o);
@@ -644,7 +650,7 @@ k_merge(Ctx c, DecodeArgs a) {
     sa = w0 + seg;
     for (int e = threadIdx.x; e < G * D4; e += blockDim.x) {
       const int r = e / D4, d4 = e % D4;
-      fold_columns<false>(a.partials, a.out + ((long long)row * dm.Hq + h * G + r) * D, pf, G, D, r, d4, pa, pstride, pn, sa, sn,
+      fold_columns<false>(a.partials, a.out + ((long long)io_row(a, ri, row) * dm.Hq + h * G + r) * D, pf, G, D, r, d4, pa, pstride, pn, sa, sn,
                           a.v_scale);
     }
   }

@@ -198,6 +198,7 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
   if (tid == 0) {
     const int na_new = nA + (dm.start_waiting ? 0 : carry_new * dm.Nb);
     scal[S_NACTIVE] = na_new;
+    publish_active_count(tb, na_new);
     scal[S_FREETOP] = top - carry;
     const int sel = scal[S_BTSEL];
     if (scal[S_BTHI0 + sel] < na_new) scal[S_BTHI0 + sel] = na_new;
@@ -271,8 +272,9 @@ k_append_write(Ctx c, AppendArgs a) {
                                : bt + (long long)i * dm.max_bp;
     const int page = table[pos / dm.pt], slot = pos % dm.pt;
     const long long kb = tile_base(dm, page, head), vb = kb + dm.tile_elems;
-    const T* ksrc = (const T*)a.k + (row * dm.Hkv + head) * dm.d;
-    const T* vsrc = (const T*)a.v + (row * dm.Hkv + head) * dm.d;
+    const long long src = a.by_handle ? (long long)tb.ap_id[i] : row;      // rows of k and v by handle or in list order
+    const T* ksrc = (const T*)a.k + (src * dm.Hkv + head) * dm.d;
+    const T* vsrc = (const T*)a.v + (src * dm.Hkv + head) * dm.d;
     if (dm.dtype == SART_FP8_E4M3) {
       // bf16 in, one byte out: nearest E4M3 code of x / scale (ties to even), magnitude clamped to 448
       if constexpr (sizeof(T) == 2) {
@@ -407,6 +409,7 @@ __device__ void terminate_plan(const Ctx& c, const PlanCfg& pc, int* lds, bool s
     scal[S_BTHI0 + new_sel] = na_new;
     scal[S_BTSEL] = new_sel;
     scal[S_NACTIVE] = na_new;
+    publish_active_count(tb, na_new);
     scal[S_FREETOP] = top + priv_pages + carry_r;
     scal[S_CALLOK] = 1;
   }
@@ -717,6 +720,7 @@ k_start_plan(Ctx c, PlanCfg pc, int n, const int* handles, int call_seq) {
     scal[S_BTHI0 + new_sel] = na_new;
     scal[S_BTSEL] = new_sel;
     scal[S_NACTIVE] = na_new;
+    publish_active_count(tb, na_new);
     scal[S_CALLOK] = 1;
   }
   refresh_decode_plan(c, pc, lds);

@@ -69,6 +69,12 @@ __device__ inline void block_excl_scan3(int v0, int v1, int v2, int* lds, int* e
 }
 
 // First error of a call wins and stays until the host reads it.
+// The active count as the host may peek at it without waiting for the device: one int in pinned host
+// memory, stored (through to the host) by the thread that changes the count.
+__device__ inline void publish_active_count(const Tables& tb, int n) {
+  __hip_atomic_store(tb.host_nactive, n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __device__ inline void record_error(int* scal, int code, int call_seq) {
   if (scal[S_ERR] == 0) {
     scal[S_ERR] = code;
@@ -224,9 +230,9 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   //   [3] writers of prompt partial results per kv head: chunks x row tiles holding the branch's rows
   //       (shared rows), chunks (per-branch blocks), 0 without a prompt
   //   [4] first prompt partial slot of the row, relative to the prompts' slots: chunk ck of kv head h is
-  //       slot [4] + (h * [6] + ck) * [5]   [5] live branches of the request   [6] prompt chunks   [7] 0
+  //       slot [4] + (h * [6] + ck) * [5]   [5] live branches of the request   [6] prompt chunks   [7] the branch's handle
   for (int i = tid; i < nA; i += kPlanThreads) {
-    const int r = tb.active[i] / dm.Nb;
+    const int handle = tb.active[i], r = handle / dm.Nb;
     const int j = i - tb.req_first[r], cnt = tb.nact[r];
     const int pp = ceil_div(tb.prefix_len[r], dm.pt);
     const int nck = pp > 0 ? ceil_div(pp, cut.pb) : 0;
@@ -234,7 +240,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     const int c0 = nA <= kPlanLdsRows ? s_cum[i] : tb.page_cum[i], c1 = nA <= kPlanLdsRows ? s_cum[i + 1] : tb.page_cum[i + 1];
     int4* rd = (int4*)(tb.row_desc + 8LL * i);
     rd[0] = make_int4(c0, c1 - c0, i < kPlanLdsRows ? s_seq[i] : tb.seq_len[i], nck * tiles);
-    rd[1] = make_int4(nck ? tb.req_pstart[r] + j : 0, cnt, nck, 0);
+    rd[1] = make_int4(nck ? tb.req_pstart[r] + j : 0, cnt, nck, handle);
   }
   // Where every wave starts.  wave_row (generic kernel): active row of an own
   // range's first unit and, after those entries, the live request of a prompt

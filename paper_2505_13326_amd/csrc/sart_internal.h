@@ -101,6 +101,7 @@ struct Tables {
   int* req_pstart;       // [max_req] first prompt block of the request
   int* wave_desc;        // [max attention waves][16] where each wave starts (see refresh_decode_plan)
   int* row_desc;         // [H][8] per active row: what a piece of the row needs to know to merge (see refresh_decode_plan)
+  int* host_nactive;     // one int in pinned host memory: the active count, stored again whenever it changes
   int* seg_count;        // [H * Hkv] arrivals per (row, kv head) in the running attention kernel; 0 between kernels
 };
 
@@ -203,6 +204,7 @@ struct AppendArgs {
   const void* v;
   int call_seq;
   int write_only;      // layer > 0: write the rows of the last layer-0 append again, into this layer's pool
+  int by_handle;       // all-active form: the row of k and v that belongs to a branch is its handle, not its active index
 };
 void launch_append(const Ctx& c, const PlanCfg& pc, const AppendArgs& a, hipStream_t s);
 
@@ -233,6 +235,7 @@ struct DecodeArgs {
   int* seg_count;       // scratch: arrival counters of the in-kernel merge, one per (row, kv head), zero between kernels
   int fused_merge;      // the attention kernel's last writer of a (row, kv head) merges its partial results
   int stagger_prompt;   // half of the workgroups serve their prompt work after their own range instead of before
+  int by_handle;        // rows of q and out are addressed by branch handle instead of by active index
   int call_seq;
   float v_scale;        // 8-bit float caches: what the output is multiplied by (1 otherwise)
   hipEvent_t ev[4];     // optional profiling events (null: none)

@@ -90,34 +90,32 @@ def run_trace(cache, *, targets, step_kv, query, n_steps, prune_every=0, prune_k
             "done_step": done_step}
 
 
-def run_trace_graph(cache, *, targets, step_kv, query, n_steps, prune_every=0, prune_k=0, scores=None):
-    """The same loop with the step kept on the device: gathering the active branches' inputs (through
-    sart_device_views), sart_append_tokens(SART_ALL_ACTIVE), sart_decode_attention and sart_finish_reached are
-    recorded into one HIP graph and replayed once per step; the host only copies the step's inputs into the
-    graph's source buffers (no wait) and comes back for the state at the pruning steps.
-    Returns dict(branch_steps)."""
+def run_trace_device(cache, *, targets, step_kv, query, n_steps, prune_every=0, prune_k=0, scores=None, out=None,
+                     graph=False, poll_every=8, on_step=None):
+    """The same loop with the step kept on the device: the host never learns which branches are in the batch.
+    Per step sart_append_active_by_handle, sart_decode_attention_by_handle (inputs and output addressed by
+    branch handle, so nobody gathers rows) and sart_finish_reached are enqueued without waiting; the host
+    comes back for the state only at the pruning steps, and notices that the batch has drained through
+    sart_active_count_hint (polled every `poll_every` steps; it lags, so a few empty steps may be enqueued).
+    graph=True: the three calls are recorded once into a HIP graph that reads the step's K, V and Q from fixed
+    buffers (the host copies each step's inputs there, without waiting) and is replayed once per step.
+    out: optional float32 device tensor [R*Nb, Hq, d] (rows by handle).  on_step(s, cache, out): hook after each
+    step's calls are enqueued (tests; a hook that reads `out` waits for the device itself).
+    Returns dict(branch_steps, steps_enqueued)."""
     import torch
     Nb, R = cache.Nb, cache.max_req
     H = R * Nb
-    act_view, n_view = cache.device_views()
+    _, n_view = cache.device_views()
     tdev = torch.from_numpy(np.ascontiguousarray(targets, dtype=np.int32)).cuda()
-    k1, v1 = step_kv(1)
-    src_k, src_v, src_q = torch.empty_like(k1), torch.empty_like(v1), torch.empty_like(query(1))
-    kbuf, vbuf, qbuf = torch.empty_like(k1), torch.empty_like(v1), torch.empty_like(src_q)
-    out = torch.empty(src_q.shape, dtype=torch.float32, device="cuda")
+    q1 = query(1)
+    if out is None:
+        out = torch.empty(q1.shape, dtype=torch.float32, device="cuda")
     count = torch.zeros(1, dtype=torch.int64, device="cuda")
+    assert cache.sync_status() == 0                     # the hint below is current from here on
 
-    def load(s):
-        k, v = step_kv(s)
-        src_k.copy_(k); src_v.copy_(v); src_q.copy_(query(s))
-
-    def body():
-        idx = act_view.clamp(0, H - 1).long()          # entries past the active count may hold anything
-        torch.index_select(src_k, 0, idx, out=kbuf)
-        torch.index_select(src_v, 0, idx, out=vbuf)
-        torch.index_select(src_q, 0, idx, out=qbuf)
-        cache.append_tokens(SEQ_BRANCH, None, None, kbuf, vbuf, all_active=True)
-        cache.decode_attention(qbuf, out=out)
+    def body(k, v, q):
+        cache.append_active_by_handle(k, v)
+        cache.decode_attention_by_handle(q, out)
         count.add_(n_view)                              # branches decoded in this step
         cache.finish_reached(tdev)
 
@@ -128,33 +126,47 @@ def run_trace_graph(cache, *, targets, step_kv, query, n_steps, prune_every=0, p
             return event
         st = cache.get_state(fields=("n_active", "active_handles", "req_counters"))
         n = int(st["n_active"][0])
-        drained[0] = n == 0                             # nothing left to decode: the remaining steps are no-ops
+        drained[0] = n == 0
         if n:
             act_dev = torch.from_numpy(st["active_handles"][:n].astype(np.int64)).cuda()
             cap = np.where(st["req_counters"][:, 0] == 0, Nb // 2, Nb - 1).astype(np.int32)
             cache.prune_branches(DROP_LOWEST_K, scores(event)[act_dev].contiguous(), k=prune_k, max_pruned=cap)
         return event + 1
 
-    # step 1 runs eagerly on a side stream (the warm-up a capture needs), the rest replays the recording
-    load(1)
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        body()
-    torch.cuda.current_stream().wait_stream(side)
-    event = maybe_prune(1, 0)
-    graph = torch.cuda.CUDAGraph()
-    if n_steps >= 2:
-        load(2)
-        torch.cuda.synchronize()
-        with torch.cuda.graph(graph):
-            body()
-    for s in range(2, n_steps + 1):
-        if drained[0]:
+    event, steps = 0, 0
+    g = None
+    if graph:
+        k1, v1 = step_kv(1)
+        src_k, src_v, src_q = torch.empty_like(k1), torch.empty_like(v1), torch.empty_like(q1)
+
+        def load(s):
+            k, v = step_kv(s)
+            src_k.copy_(k); src_v.copy_(v); src_q.copy_(query(s))
+    for s in range(1, n_steps + 1):
+        if drained[0] or (s % poll_every == 0 and cache.active_count_hint() == 0):
             break
-        if s > 2:
+        if not graph:
+            k, v = step_kv(s)
+            body(k, v, query(s))
+        elif s == 1:
+            # step 1 runs eagerly on a side stream (the warm-up a capture needs), step 2 is recorded
+            load(1)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                body(src_k, src_v, src_q)
+            torch.cuda.current_stream().wait_stream(side)
+        else:
             load(s)
-        graph.replay()
+            if g is None:
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    body(src_k, src_v, src_q)
+            g.replay()
+        steps += 1
+        if on_step:
+            on_step(s, cache, out)
         event = maybe_prune(s, event)
     torch.cuda.synchronize()
-    return {"branch_steps": int(count.item())}
+    return {"branch_steps": int(count.item()), "steps_enqueued": steps}

@@ -380,6 +380,57 @@ def test_decode_is_deterministic_and_leaves_inputs_alone():
     assert_state_equal(st1, g.state())          # attention never changes the integer state
 
 
+@pytest.mark.parametrize("mode", ["mfma16-per-branch", "mfma16-shared-rows", "natural"])
+def test_rows_addressed_by_handle(mode):
+    """sart_append_active_by_handle / sart_decode_attention_by_handle against the oracle after the batch was
+    thinned (so active order and handle order differ): the appended token lands in the same place as through
+    the list form (whole integer state equal, attention equal), output rows of active branches match the
+    oracle, every other row of `out` is left alone; both merge forms, several launch shapes."""
+    import torch
+    natural = mode == "natural"
+    cfg = wl.scaled(wl.CONFIGS[2], n_requests=4, nb=6, prompt_len=100, length_params=(200, 0.8), length_cap=1500)
+    L = wl.lengths(cfg)
+    L[1, 2], L[2, 0] = 16, 31
+    pages = wl.pages_needed(cfg, L) + 40
+    o, g = _pair(cfg, pages, int(-(-L.max() // 16)) + 2, free_order=wl.free_order(cfg, pages), force_natural_layout=natural)
+    pmode = {"mfma16-per-branch": 1, "mfma16-shared-rows": 2, "natural": 1}[mode]
+    g.c.set_decode_launch(prompt_mode=pmode)
+    populate(cfg, [o, g], L)
+    sc = wl.scores(cfg, 0)
+    st = o.state()
+    act = st["active_handles"][:int(st["n_active"][0])]
+    assert o.prune(orc.DROP_LOWEST_K, sc[act], k=2) == orc.OK and g.prune(orc.DROP_LOWEST_K, sc[act], k=2) == orc.OK
+    st = o.state()
+    act = st["active_handles"][:int(st["n_active"][0])]
+    assert o.finish([act[0], act[5]]) == orc.OK and g.finish([act[0], act[5]]) == orc.OK
+    H = cfg.n_handles
+    for step in (1, 2):
+        K, V = wl.step_kv(cfg, step)
+        st = o.state()
+        act = st["active_handles"][:int(st["n_active"][0])]
+        assert o.append(orc.SEQ_BRANCH, None, None, K[act], V[act]) == orc.OK
+        g.c.append_active_by_handle(K, V)
+        assert_state_equal(o.state(), g.state())
+        q = wl.query(cfg, step)
+        ref = o.attention(q[act])
+        qd = g.c._dev(q, (cfg.n_q_heads, cfg.head_dim))
+        for n_wg, skew in ((0, 80), (3, 45), (64, 300)):
+            g.c.set_decode_launch(n_wg, pmode, skew)
+            for in_kernel in (False, True):
+                g.c.set_merge_mode(in_kernel)
+                out = torch.full((H, cfg.n_q_heads, cfg.head_dim), -7.5, dtype=torch.float32, device="cuda")
+                g.c.decode_attention_by_handle(qd, out)
+                got = out.cpu().numpy()
+                assert g.c.sync_status() == 0
+                assert float(np.abs(got[act].astype(np.float64) - ref).max()) <= TOL["bf16"]
+                assert np.all(got[np.setdiff1d(np.arange(H), act)] == -7.5)
+                same = g.c.decode_attention(qd[torch.as_tensor(act, device="cuda").long()]).cpu().numpy()
+                assert np.array_equal(same, got[act])           # the list form computes the same bits
+        g.c.set_merge_mode(False)
+        g.c.set_decode_launch(prompt_mode=pmode)
+    assert g.c.active_count_hint() == int(o.state()["n_active"][0])
+
+
 # ---------------------------------------------------------------------------
 # waiting branches (Algorithm 1's branch queue): created WAITING, started one by one
 # ---------------------------------------------------------------------------

@@ -111,12 +111,15 @@ def test_trace_matches_oracle_after_every_call(size):
           f"max abs attention err {worst[0]:.3g}")
 
 
-def test_graph_driven_trace_ends_where_the_oracle_ends():
-    """The loop that keeps the step on the device (one recorded graph: gather, append, attention,
-    completion by target length) and the host-driven loop must both leave the cache exactly where the
-    oracle's own step loop leaves its cache: whole integer state, branch-steps, and the last steps' attention."""
+def test_device_driven_trace_ends_where_the_oracle_ends():
+    """The loops that keep the step on the device (rows addressed by branch handle, completion by target
+    length, nothing read back between pruning steps; enqueued call by call, or recorded once into a HIP
+    graph and replayed) and the host-driven loop must all leave the cache exactly where the oracle's own step
+    loop leaves its cache: whole integer state, branch-steps, the attention of what is left; at sampled steps
+    the by-handle output rows of the active branches equal the oracle's attention and the other rows are
+    untouched."""
     import torch
-    from paper_2505_13326_amd.trace import run_trace, run_trace_graph
+    from paper_2505_13326_amd.trace import run_trace, run_trace_device
     cfg = wl.scaled(wl.CONFIGS[3], n_requests=5, length_params=(150, 0.8), length_cap=1200, n_steps=130, prune_every=20)
     L = wl.lengths(cfg)
     targets = (L + wl.remaining_tokens(cfg)).reshape(-1)
@@ -127,8 +130,10 @@ def test_graph_driven_trace_ends_where_the_oracle_ends():
     o = orc.OracleCache(free_order=fo, **kw)
     populate(cfg, [o], L)
     res_o = oracle_trace(o, targets=targets, step_kv=lambda s: wl.step_kv(cfg, s), n_steps=cfg.n_steps,
-                         prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: wl.scores(cfg, e))
+                         prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: wl.scores(cfg, e),
+                         query=lambda s: wl.query(cfg, s))
     want = (res_o["branch_steps"], _digest(o.state()))
+    busy = int(np.sum(res_o["active_per_step"] > 0))
 
     def dev(x):
         return torch.from_numpy(np.ascontiguousarray(x).view(np.int16)).view(torch.bfloat16).cuda()
@@ -137,12 +142,36 @@ def test_graph_driven_trace_ends_where_the_oracle_ends():
     qs = {s: dev(wl.query(cfg, s)) for s in range(1, cfg.n_steps + 1)}
     args = dict(targets=targets, step_kv=lambda s: kvs[s], query=lambda s: qs[s], n_steps=cfg.n_steps,
                 prune_every=cfg.prune_every, prune_k=cfg.prune_k, scores=lambda e: torch.from_numpy(wl.scores(cfg, e)).cuda())
-    for loop in (run_trace, run_trace_graph):
+    H = cfg.n_handles
+    sentinel = 12345.0
+    for name, loop, extra in (("host", run_trace, {}), ("device", run_trace_device, {"graph": False}),
+                              ("device, graph", run_trace_device, {"graph": True})):
         g = GpuEngine(free_order=fo, **kw)
         populate(cfg, [g], L)
-        res = loop(g.c, **args)
+        worst = [0.0]
+        if loop is run_trace_device:
+            out = torch.full((H, cfg.n_q_heads, cfg.head_dim), sentinel, dtype=torch.float32, device="cuda")
+
+            def on_step(s, cache, o_dev):
+                if s % 7 == 0:
+                    o_dev.fill_(sentinel)                       # before the calls of a sampled step are enqueued
+                if s % 7 != 1 or s not in res_o["outputs"]:
+                    return
+                act, ref = res_o["outputs"][s]
+                got = o_dev.cpu().numpy()                       # waits for the step
+                worst[0] = max(worst[0], float(np.abs(got[act].astype(np.float64) - ref).max()))
+                rest = np.setdiff1d(np.arange(H), act)
+                assert np.all(got[rest] == sentinel), "a row of a branch outside the batch was written"
+            extra = dict(extra, out=out, on_step=on_step)
+        res = loop(g.c, **args, **extra)
         st, rc = g.c.get_state(with_status=True)
         assert rc == 0
-        assert (res["branch_steps"], _digest(st)) == want, loop.__name__
+        assert (res["branch_steps"], _digest(st)) == want, name
+        assert worst[0] <= TOL["bf16"], (name, worst[0])
+        if loop is run_trace_device:
+            assert busy <= res["steps_enqueued"] <= busy + cfg.prune_every, (name, busy, res["steps_enqueued"])
+            assert g.c.active_count_hint() == int(st["n_active"][0])
         if int(st["n_active"][0]):                      # what is left attends alike on both sides
             compare_attention(cfg, o, g, wl.query(cfg, cfg.n_steps + 1))
+        print(f"{name}: {res['branch_steps']} branch-steps, max abs by-handle attention err {worst[0]:.3g}, "
+              f"steps enqueued {res.get('steps_enqueued', busy)} for {busy} with active branches")
