@@ -70,6 +70,7 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
     out = torch.empty((R * P, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
     ids, nq = list(range(R)), [P] * R
     assert cache.sync_status() == 0
+    cache.set_prefill_kernel(args.prefill_kernel)
     K, W = args.steps, args.warmup
     for _ in range(W):
         cache.prefill_attention(ids, nq, q, out=out)
@@ -86,7 +87,7 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
     assert cache.sync_status() == 0
     flops = R * 4.0 * cfg.head_dim * cfg.n_q_heads * P * (P + 1) / 2
     kv_bytes = R * P * cfg.token_bytes
-    roofline = {"bound": "mfma", "kernel": "k_prefill_lds8" if cfg.dtype == "bf16" else "k_prefill_mfma", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
+    roofline = {"bound": "mfma", "kernel": ("k_prefill_lds8" if args.prefill_kernel else "k_prefill_x32") if cfg.dtype == "bf16" and args.kv_dtype != "fp8" else "k_prefill_mfma", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
                 "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / (k_ms * 1e-3) / 1e12 / 2500.0, 4), "traffic": None,
                 "algorithmic_flops_per_launch": int(flops), "kernel_ms_avg": round(k_ms, 4),
                 "note": "events on the call's stream around all timed calls (validation kernel included)"}
@@ -521,6 +522,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="replay the step (append + attention) from a HIP graph (cfg3: the device-driven step)")
     ap.add_argument("--host-loop", action="store_true", help="cfg3: the host-driven step (the host gathers the active rows and lists the completed "
                     "branches, reading the state back after every call that changes the batch) instead of the device-driven one")
+    ap.add_argument("--prefill-kernel", type=int, default=0, choices=[0, 1], help="prefillN on bf16 caches: 0 = 32 rows per wave "
+                    "(32x32x16 products, default), 1 = 16 rows per wave (16x16x32 products)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
     args = ap.parse_args()

@@ -246,7 +246,7 @@ sart_status sart_decode_attention_static(sart_cache* cache, int32_t layer,
  * n_q[i] = P: the whole prompt at once; smaller: one chunk of a chunked prefill
  * (append the chunk with sart_append_tokens(SART_SEQ_PREFIX), then attend with
  * the chunk's queries).  Decode branches of the request are not involved.
- *   request_ids, n_q   host arrays [n_seqs]; ids in [0, max_requests), n_q >= 0;
+ *   request_ids, n_q   host arrays [n_seqs], n_seqs <= min(max_requests, 65535); ids in [0, max_requests), n_q >= 0;
  *   q                  device, [sum n_q][Hq][head_dim], kv_dtype, rows in list order;
  *   out                device, [sum n_q][Hq][head_dim], float32;
  *   scale              <= 0: 1 / sqrt(head_dim).

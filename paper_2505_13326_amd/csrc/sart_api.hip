@@ -65,6 +65,7 @@ struct sart_cache {
   long long partial_cap = 0;
   PlanCfg plan{0, 0, 0};               // launch shape of the decode plan
   int stagger_prompt = 1;              // see sart_set_prompt_stagger
+  int prefill_variant = 0;             // see sart_set_prefill_kernel
   int merge_mode = 0;                  // 1: merged inside the attention kernel where it can be, 0: by the merge kernel (faster, measured)
   int max_wg = 0;
   int profiling = 0;                   // 0 off, n >= 1: events around n attention launches
@@ -234,6 +235,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   ALLOC(tb.req_pstart, R);
   ALLOC(tb.wave_desc, (size_t)16 * c->max_wg * kAttnWaves);
   ALLOC(tb.row_desc, 8 * H);
+  ALLOC(tb.pf_seq, 4 * R);
   ALLOC(tb.seg_count, H * dm.Hkv);
   HIP_TRY(hipMemset(tb.seg_count, 0, H * dm.Hkv * sizeof(int)));
   HIP_TRY(hipHostMalloc((void**)&c->host_nactive, 64, hipHostMallocMapped));
@@ -481,18 +483,19 @@ sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs,
   if (!c) return fail(SART_E_INVALID, "null cache");
   if (layer < 0 || layer >= c->desc.n_layers) return fail(SART_E_INVALID, "layer out of range");
   const Dims& dm = c->ctx.dm;
-  if (n_seqs < 0 || n_seqs > dm.max_req) return fail(SART_E_INVALID, "n_seqs out of range");
+  if (n_seqs < 0 || n_seqs > dm.max_req || n_seqs > 65535) return fail(SART_E_INVALID, "n_seqs out of range (at most max_requests and 65535)");
   if (n_seqs > 0 && (!request_ids || !n_q)) return fail(SART_E_INVALID, "null request_ids or n_q");
-  long long total = 0, tiles = 0;
+  long long total = 0, max_tiles = 0;
   const int rows_per_tile = kPfTileRows;                    // the matrix-core kernel's workgroup tile
   for (int i = 0; i < n_seqs; ++i) {
     if (request_ids[i] < 0 || request_ids[i] >= dm.max_req)
       return fail(SART_E_INVALID, "request %d out of range at %d", request_ids[i], i);
     if (n_q[i] < 0 || n_q[i] > dm.max_pp * dm.pt) return fail(SART_E_INVALID, "n_q out of range at %d", i);
     total += n_q[i];
-    tiles += (long long)dm.Hkv * (((long long)n_q[i] * dm.G + rows_per_tile - 1) / rows_per_tile);
+    const long long tiles = (long long)dm.Hkv * (((long long)n_q[i] * dm.G + rows_per_tile - 1) / rows_per_tile);
+    if (tiles > max_tiles) max_tiles = tiles;
   }
-  if (total > 0x7fffffffLL / dm.Hq || tiles > 0x7fffffffLL) return fail(SART_E_INVALID, "too many queries in one call");
+  if (total > 0x7fffffffLL / dm.Hq || max_tiles > 0x7fffffffLL) return fail(SART_E_INVALID, "too many queries in one call");
   if (total > 0 && (!q || !out)) return fail(SART_E_INVALID, "null q or out");
   if (n_seqs == 0) return SART_OK;
   if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)dm.d);
@@ -505,19 +508,18 @@ sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs,
   a.n_seqs = n_seqs; a.q = q; a.out = out; a.call_seq = ++c->call_seq;
   a.scale_log2 = scale * 1.44269504088896340736f * c->k_scale;
   a.v_scale = c->v_scale;
-  a.total_q = (int)total; a.n_tiles = (int)tiles;
+  a.total_q = (int)total; a.max_tiles = (int)max_tiles;
+  a.variant = c->prefill_variant;
   int* hbuf = s->host;
-  int qo = 0, to = 0;
+  int qo = 0;
   for (int i = 0; i < n_seqs; ++i) {
     hbuf[i] = request_ids[i];
     hbuf[n_seqs + i] = n_q[i];
     hbuf[2 * n_seqs + i] = qo;
-    hbuf[3 * n_seqs + i] = to;
     qo += n_q[i];
-    to += dm.Hkv * (int)(((long long)n_q[i] * dm.G + rows_per_tile - 1) / rows_per_tile);
   }
-  a.ids = s->dev; a.nq = s->dev + n_seqs; a.q_off = s->dev + 2 * n_seqs; a.tile_start = s->dev + 3 * n_seqs;
-  rc = stage_upload(c, s, (size_t)4 * n_seqs, st);
+  a.ids = s->dev; a.nq = s->dev + n_seqs; a.q_off = s->dev + 2 * n_seqs;
+  rc = stage_upload(c, s, (size_t)3 * n_seqs, st);
   if (rc != SART_OK) return rc;
   launch_prefill(layer_ctx(c, layer), a, st);
   HIP_TRY(hipEventRecord(s->done, st));
@@ -730,6 +732,13 @@ sart_status sart_read_probe_shaped(const void* buf, size_t bytes, const int32_t*
 sart_status sart_set_prompt_stagger(sart_cache* c, int32_t on) {
   if (!c) return fail(SART_E_INVALID, "null cache");
   c->stagger_prompt = on != 0;
+  return SART_OK;
+}
+
+sart_status sart_set_prefill_kernel(sart_cache* c, int32_t variant) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (variant != 0 && variant != 1) return fail(SART_E_INVALID, "variant must be 0 or 1");
+  c->prefill_variant = variant;
   return SART_OK;
 }
 

@@ -101,6 +101,7 @@ struct Tables {
   int* req_pstart;       // [max_req] first prompt block of the request
   int* wave_desc;        // [max attention waves][16] where each wave starts (see refresh_decode_plan)
   int* row_desc;         // [H][8] per active row: what a piece of the row needs to know to merge (see refresh_decode_plan)
+  int* pf_seq;           // [max_req][4] prefill: request, queries, first q row, prompt tokens of every listed sequence
   int* host_nactive;     // one int in pinned host memory: the active count, stored again whenever it changes
   int* seg_count;        // [H * Hkv] arrivals per (row, kv head) in the running attention kernel; 0 between kernels
 };
@@ -254,14 +255,14 @@ struct PrefillArgs {
   const int* ids;         // device: request of every listed sequence
   const int* nq;          // device: queries per sequence (its last nq prompt tokens)
   const int* q_off;       // device: first row of the sequence in q / out
-  const int* tile_start;  // device: first workgroup tile of the sequence (matrix-core kernel)
   const void* q;
   float* out;
   float scale_log2;
   float v_scale;          // 8-bit float caches: what the output is multiplied by (1 otherwise)
   int call_seq;
-  int n_tiles;
+  int max_tiles;          // workgroup tiles of the listed sequence that has most (matrix-core kernels: grid x)
   int total_q;
+  int variant;            // bf16 caches: 0 the 32-rows-per-wave kernel, 1 the 16-rows-per-wave kernel
 };
 void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s);
 
