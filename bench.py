@@ -70,7 +70,6 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
     out = torch.empty((R * P, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
     ids, nq = list(range(R)), [P] * R
     assert cache.sync_status() == 0
-    cache.set_prefill_kernel(args.prefill_kernel)
     K, W = args.steps, args.warmup
     for _ in range(W):
         cache.prefill_attention(ids, nq, q, out=out)
@@ -87,7 +86,7 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
     assert cache.sync_status() == 0
     flops = R * 4.0 * cfg.head_dim * cfg.n_q_heads * P * (P + 1) / 2
     kv_bytes = R * P * cfg.token_bytes
-    roofline = {"bound": "mfma", "kernel": ("k_prefill_lds8" if args.prefill_kernel else "k_prefill_x32") if cfg.dtype == "bf16" and args.kv_dtype != "fp8" else "k_prefill_mfma", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
+    roofline = {"bound": "mfma", "kernel": "k_prefill_x32" if cfg.dtype == "bf16" and args.kv_dtype != "fp8" else "k_prefill_mfma", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
                 "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / (k_ms * 1e-3) / 1e12 / 2500.0, 4), "traffic": None,
                 "algorithmic_flops_per_launch": int(flops), "kernel_ms_avg": round(k_ms, 4),
                 "note": "events on the call's stream around all timed calls (validation kernel included)"}
@@ -107,13 +106,13 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
         dt_cpu = time.perf_counter() - t1
         cpu = {"value": round(n * flops / R / dt_cpu / 1e12, 5), "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
                "sample": f"whole prompts of {n} of {R} requests, float64", "seconds": round(dt_cpu, 2)}
-    print(json.dumps({
+    return ({
         "metric": "prefill attention, algorithmic causal flops per second", "value": round(flops / dt / 1e12, 2),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(dt * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"prompts of config {cfg.cfg_id}: {R} requests x {P} tokens, Hq {cfg.n_q_heads} / Hkv "
                                f"{cfg.n_kv_heads}, d {cfg.head_dim}, one call", "kv_bytes": kv_bytes},
-        "roofline": roofline, "cpu_baseline": cpu}))
+        "roofline": roofline, "cpu_baseline": cpu})
 
 
 def bench_trace(args, cfg, sart, wl, np, torch):
@@ -522,8 +521,6 @@ def main():
     ap.add_argument("--graph", action="store_true", help="replay the step (append + attention) from a HIP graph (cfg3: the device-driven step)")
     ap.add_argument("--host-loop", action="store_true", help="cfg3: the host-driven step (the host gathers the active rows and lists the completed "
                     "branches, reading the state back after every call that changes the batch) instead of the device-driven one")
-    ap.add_argument("--prefill-kernel", type=int, default=0, choices=[0, 1], help="prefillN on bf16 caches: 0 = 32 rows per wave "
-                    "(32x32x16 products, default), 1 = 16 rows per wave (16x16x32 products)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
     args = ap.parse_args()
@@ -567,6 +564,11 @@ def main():
         torch.cuda.empty_cache()
         sub = bench_trace(args, wl.CONFIGS[3], sart, wl, np, torch)
         line["cfg3"] = {k: sub[k] for k in keep if k in sub}
+        torch.cuda.empty_cache()
+        # Algorithm 1's Prefill over config 4's prompts (a dense contraction: held against the matrix-core peak)
+        args.steps, args.warmup = 20, 3
+        sub = bench_prefill(args, wl.CONFIGS[4], sart, wl, np, torch)
+        line["prefill4"] = {k: sub[k] for k in keep if k in sub}
         print(json.dumps(line), flush=True)
         return
     cfg = wl.CONFIGS[int(args.workload[-1])]
@@ -575,7 +577,8 @@ def main():
     if args.requests > 0:
         cfg = wl.scaled(cfg, n_requests=args.requests)
     if args.workload.startswith("prefill"):
-        return bench_prefill(args, cfg, sart, wl, np, torch)
+        print(json.dumps(bench_prefill(args, cfg, sart, wl, np, torch)), flush=True)
+        return
     if cfg.cfg_id == 3:
         print(json.dumps(bench_trace(args, cfg, sart, wl, np, torch)), flush=True)
         return

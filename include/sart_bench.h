@@ -82,11 +82,6 @@ sart_status sart_set_prompt_stagger(sart_cache* cache, int32_t on);
  * counter's round trip while no other wave can use its SIMD. */
 sart_status sart_set_merge_mode(sart_cache* cache, int32_t in_kernel);
 
-/* Which kernel sart_prefill_attention runs on bf16 caches: 0 (the default) 32
- * query rows per wave on the 32x32x16 product, 1 the earlier form with 16 rows
- * per wave on the 16x16x32 product.  Same results up to rounding order. */
-sart_status sart_set_prefill_kernel(sart_cache* cache, int32_t variant);
-
 #ifdef __cplusplus
 }
 #endif

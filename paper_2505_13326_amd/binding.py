@@ -75,7 +75,6 @@ _SIGNATURES = {
     "sart_last_decode_ms": (C.c_int, [C.c_void_p, _fp, _fp]),
     "sart_set_decode_launch": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
     "sart_set_merge_mode": (C.c_int, [C.c_void_p, C.c_int32]),
-    "sart_set_prefill_kernel": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_set_prompt_stagger": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_read_probe": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "sart_read_probe_shaped": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
@@ -368,9 +367,6 @@ class SartCache:
 
     def set_prompt_stagger(self, on: bool):
         self._check(self.lib.sart_set_prompt_stagger(self.h, 1 if on else 0))
-
-    def set_prefill_kernel(self, variant: int):
-        self._check(self.lib.sart_set_prefill_kernel(self.h, int(variant)))
 
     def set_merge_mode(self, in_kernel: bool):
         self._check(self.lib.sart_set_merge_mode(self.h, 1 if in_kernel else 0))

@@ -65,7 +65,6 @@ struct sart_cache {
   long long partial_cap = 0;
   PlanCfg plan{0, 0, 0};               // launch shape of the decode plan
   int stagger_prompt = 1;              // see sart_set_prompt_stagger
-  int prefill_variant = 0;             // see sart_set_prefill_kernel
   int merge_mode = 0;                  // 1: merged inside the attention kernel where it can be, 0: by the merge kernel (faster, measured)
   int max_wg = 0;
   int profiling = 0;                   // 0 off, n >= 1: events around n attention launches
@@ -509,7 +508,6 @@ sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs,
   a.scale_log2 = scale * 1.44269504088896340736f * c->k_scale;
   a.v_scale = c->v_scale;
   a.total_q = (int)total; a.max_tiles = (int)max_tiles;
-  a.variant = c->prefill_variant;
   int* hbuf = s->host;
   int qo = 0;
   for (int i = 0; i < n_seqs; ++i) {
@@ -732,13 +730,6 @@ sart_status sart_read_probe_shaped(const void* buf, size_t bytes, const int32_t*
 sart_status sart_set_prompt_stagger(sart_cache* c, int32_t on) {
   if (!c) return fail(SART_E_INVALID, "null cache");
   c->stagger_prompt = on != 0;
-  return SART_OK;
-}
-
-sart_status sart_set_prefill_kernel(sart_cache* c, int32_t variant) {
-  if (!c) return fail(SART_E_INVALID, "null cache");
-  if (variant != 0 && variant != 1) return fail(SART_E_INVALID, "variant must be 0 or 1");
-  c->prefill_variant = variant;
   return SART_OK;
 }
 

@@ -196,49 +196,7 @@ __device__ inline bf16x8 pair_softmax(WaveState<D>& st, f32x4 s0, f32x4 s1, int 
   const uint2 pb = __builtin_bit_cast(uint2, __builtin_convertvector(p1, bf16x4));
   return __builtin_bit_cast(bf16x8, uint4{pa.x, pa.y, pb.x, pb.y});
 }
-// The same update against a lagging reference: st.m is not the running maximum but a reference that is
-// raised (and the accumulators rescaled) only when some row's scores exceed it by more than 2^kLag, which
-// after the first pairs is rare; until then p may exceed 1 (by at most 2^kLag: harmless in fp32 and bf16,
-// and l and O / l do not depend on the reference).  Because the largest weight is then no longer exactly 1,
-// the denominator must be summed from the same bf16-rounded weights the O^T product uses, or their rounding
-// (2^-9) shows in the output: lsum is a matrix-core accumulator fed by one more product per pair, a tile of
-// ones times P^T (every element of a lane's lsum is the sum for the lane's query row); st.l is not used.
-constexpr float kLag = 24.f;
-template <int D, bool FULL>
-__device__ inline bf16x8 pair_softmax_lagging(WaveState<D>& st, f32x4& lsum, f32x4 s0, f32x4 s1, int nvalid_row,
-                                              float scale_log2) {
-  if (!FULL) {
-    const int t0 = 4 * ((threadIdx.x & 63) >> 4);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (t0 + j >= nvalid_row) s0[j] = -__builtin_inff();
-      if (16 + t0 + j >= nvalid_row) s1[j] = -__builtin_inff();
-    }
-  }
-  // the test needs no row maximum: a lane looks at its own eight scores, the vote does the rest
-  const float mine = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])), fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
-  if (__any(mine * scale_log2 > st.m + kLag)) {     // also the first pair: st.m = -inf
-    const float mx = max_over_rows(mine) * scale_log2;
-    const float m_new = fmaxf(st.m, mx);
-    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
-    st.m = m_new;
-    lsum *= alpha;
-#pragma unroll
-    for (int b = 0; b < D / 16; ++b) st.o[b] *= alpha;
-  }
-  f32x4 p0, p1;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    p0[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[j], scale_log2, -st.m));
-    p1[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[j], scale_log2, -st.m));
-  }
-  const uint2 pa = __builtin_bit_cast(uint2, __builtin_convertvector(p0, bf16x4));
-  const uint2 pb = __builtin_bit_cast(uint2, __builtin_convertvector(p1, bf16x4));
-  const bf16x8 pp = __builtin_bit_cast(bf16x8, uint4{pa.x, pa.y, pb.x, pb.y});
-  const uint4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};     // eight bf16 1.0
-  lsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones), pp, lsum, 0, 0, 0);
-  return pp;
-}
+constexpr float kLag = 24.f;     // prefill on bf16 caches: how far (in binary orders) a score may exceed the softmax reference
 template <int D, bool FULL>
 __device__ inline void pair_pv(WaveState<D>& st, const uint4* vq0, const uint4* vq1, bf16x8 pp, int nvalid) {
   uint4 va[D / 32], vb[D / 32];

@@ -262,7 +262,6 @@ struct PrefillArgs {
   int call_seq;
   int max_tiles;          // workgroup tiles of the listed sequence that has most (matrix-core kernels: grid x)
   int total_q;
-  int variant;            // bf16 caches: 0 the 32-rows-per-wave kernel, 1 the 16-rows-per-wave kernel
 };
 void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s);
 

@@ -16,8 +16,9 @@
 // rows' positions and mask scores only on the pairs that straddle them.  No
 // split over the sequence: one wave sees a row's whole context, so there is no
 // merge.  Two kernels: k_prefill_mfma (8-bit float caches: every wave loads its
-// page pairs into registers and expands them there) and k_prefill_lds8 (bf16
-// caches: pairs staged once per workgroup in LDS, 8 waves per tile).
+// page pairs into registers and expands them there, 16x16x32 products) and
+// k_prefill_x32 (bf16 caches: pairs staged once per workgroup in LDS, 32x32x16
+// products, 32 rows per wave).
 #include <type_traits>
 
 #include "sart_attn_tile.h"
@@ -71,12 +72,16 @@ __device__ inline bool prefill_tile(const Dims& dm, const Tables& tb, PfTile& t)
   const int tiles_per_head = ceil_div(t.nq * dm.G, kPfTileRows);
   const int local = blockIdx.x;
   if (local >= tiles_per_head * dm.Hkv) return false;
-  t.h = local / tiles_per_head;
-  t.rt = tiles_per_head - 1 - local % tiles_per_head;
+  // Neighbouring blocks take the kv heads in turn: workgroups are dealt to the 8 XCDs round-robin, so with 8
+  // kv heads (or a divisor of 8) every XCD serves few heads and the K/V pages that a head's tiles share stay
+  // in that XCD's L2 (measured on 64 x 1024-token prompts, 8 kv heads: with head-major order the workgroups
+  // pulled 8 TB/s of K/V through the fabric and waited for it)
+  t.h = local % dm.Hkv;
+  t.rt = tiles_per_head - 1 - local / dm.Hkv;
   return true;
 }
 
-// (Launched for 8-bit float caches; bf16 caches take k_prefill_lds8 below.)
+// (Launched for 8-bit float caches; bf16 caches take k_prefill_x32 below.)
 template <int D, bool FP8>
 __global__ void __launch_bounds__(kAttnThreads, 2)
 k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
@@ -222,142 +227,9 @@ k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   }
 }
 
-// The same computation for bf16 caches with K and V staged in LDS by the workgroup
-// and more waves in flight: the tile's 128 rows go to 8 waves of 16 rows (112
-// registers, so four waves share a SIMD and there is always one to switch to
-// while another waits for a product, an LDS read or the barrier), and each page
-// pair is fetched from memory once per workgroup - one 16-byte chunk of two tiles
-// per thread - into a ring of three LDS stages (pair p is computed on while pair
-// p + 1 is written and pair p + 2 is in flight: one barrier per pair).  V is
-// written to LDS already in the layout of the O^T product's operand; operands are
-// read from LDS slab by slab, right before their products.  Measured against the
-// register kernel above: 452 vs 433 TFLOP/s on 64 x 1024-token prompts, 684 vs
-// 605 on 64 x 8192.
-template <int D>
-__global__ void __launch_bounds__(512, 4)
-k_prefill_lds8(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
-  constexpr int NW = 8, NB = 1;
-  static_assert(16 * NB * NW == kPfTileRows, "the host sizes the grid for tiles of kPfTileRows rows");
-  const Dims& dm = c.dm;
-  const Tables& tb = c.tb;
-  if (!tb.scal[S_CALLOK]) return;
-  constexpr int KQ = D / 32;
-  constexpr int kTileBytes = 16 * D * 2, kPageBytes = 2 * kTileBytes;
-  constexpr int kChunks = kTileBytes / 16;                 // 16-byte chunks of one K (or V) tile
-  constexpr int kStages = 3;
-  // one stage: K of the pair's first and second page as stored, then V lo and V hi operands
-  __shared__ uint4 lds[kStages][4][kChunks];
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int r16 = lane & 15, g4 = lane >> 4;
-  PfTile pt;
-  if (!prefill_tile(dm, tb, pt)) return;
-  const int req = pt.req, nq = pt.nq, plen = pt.plen, h = pt.h, rt = pt.rt;
-  const int n_rows = nq * dm.G;
-  const int row_w0 = rt * (16 * NB * NW) + wv * (16 * NB);
-  const bool wave_has_rows = row_w0 < n_rows;              // a wave without rows still helps to load
-  const int p_first = plen - nq;
-  const long long q_row0 = pt.q_row0;
-  const uint16_t* q = (const uint16_t*)a.q;
-  const unsigned char* pool = (const unsigned char*)c.pool;
-  const int* __restrict__ table = prefix_table + (long long)req * dm.max_pp;
-  const long long page_bytes = dm.page_elems * 2;
-
-  f32x4 lsum = {0.f, 0.f, 0.f, 0.f};                   // softmax denominators of the lane's query row (see pair_softmax_lagging)
-  WaveState<D> st[NB];
-  uint4 qreg[NB][KQ];
-  int pos[NB], lo_pos[NB], hi_pos[NB];
-  long long out_row[NB];
-#pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    const int row0 = row_w0 + 16 * b;
-    const int row = row0 + r16;
-    const bool have = row < n_rows;
-    const int rc = have ? row : n_rows - 1;
-    const int ql = rc / dm.G, g = rc % dm.G;
-    pos[b] = p_first + ql;
-    lo_pos[b] = row0 < n_rows ? p_first + row0 / dm.G : -1;
-    hi_pos[b] = row0 < n_rows ? p_first + min(row0 + 15, n_rows - 1) / dm.G : -1;
-    const long long qrow = ((q_row0 + ql) * dm.Hq + h * dm.G + g) * D;
-    out_row[b] = have ? qrow : -1;
-#pragma unroll
-    for (int k = 0; k < KQ; ++k) qreg[b][k] = *(const uint4*)(q + qrow + k * 32 + g4 * 8);
-    st[b].reset();
-  }
-  // pages the tile needs (its last row's context) and those this wave needs
-  const int tile_last_pos = p_first + min((rt + 1) * (16 * NB * NW) - 1, n_rows - 1) / dm.G;
-  const int n_pages = tile_last_pos / 16 + 1;
-  const int n_pairs = (n_pages + 1) >> 1;
-  const int wave_last_pos = wave_has_rows ? p_first + min(row_w0 + (16 * NB) - 1, n_rows - 1) / dm.G : -1;
-  const int wave_pairs = wave_has_rows ? wave_last_pos / 32 + 1 : 0;
-
-  // loader: threads 0..kChunks-1 move chunk t of the two K tiles, the next kChunks threads chunk t of the two V tiles
-  static_assert(2 * kChunks <= NW * 64, "one chunk pair per thread");
-  uint4 ga, gb;
-  const bool ld_k = tid < kChunks, ld_v = tid >= kChunks && tid < 2 * kChunks;
-  const int lch = ld_k ? tid : tid - kChunks;
-  auto g_load = [&](int pr) {
-    const unsigned char* b0 = pool + (long long)table[2 * pr] * page_bytes + (long long)h * kPageBytes + (ld_v ? kTileBytes : 0);
-    const unsigned char* b1 = pool + (long long)table[min(2 * pr + 1, n_pages - 1)] * page_bytes + (long long)h * kPageBytes + (ld_v ? kTileBytes : 0);
-    if (ld_k || ld_v) { ga = *(const uint4*)(b0 + lch * 16); gb = *(const uint4*)(b1 + lch * 16); }
-  };
-  auto l_store = [&](int stage) {
-    if (ld_k) { lds[stage][0][lch] = ga; lds[stage][1][lch] = gb; }
-    if (ld_v) {
-      lds[stage][2][lch] = uint4{ga.x, ga.y, gb.x, gb.y};
-      lds[stage][3][lch] = uint4{ga.z, ga.w, gb.z, gb.w};
-    }
-  };
-  g_load(0);
-  l_store(0);
-  g_load(min(1, n_pairs - 1));
-  __syncthreads();
-  for (int pr = 0; pr < n_pairs; ++pr) {
-    const int stage = pr % kStages;
-    l_store((pr + 1) % kStages);                           // pair pr + 1 (loaded a turn ago), read a turn from now
-    g_load(min(pr + 2, n_pairs - 1));
-    if (pr < wave_pairs) {
-      const int t0 = pr * 32;
-      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int k = 0; k < KQ; ++k) {
-        const bf16x8 qk = __builtin_bit_cast(bf16x8, qreg[0][k]);
-        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lds[stage][0][k * 64 + lane]), qk, s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lds[stage][1][k * 64 + lane]), qk, s1, 0, 0, 0);
-      }
-      const bool full = t0 + 31 <= lo_pos[0];
-      const int nvalid = min(32, min(plen, n_pages * 16) - t0);
-      const bf16x8 pp = full ? pair_softmax_lagging<D, true>(st[0], lsum, s0, s1, 32, a.scale_log2)
-                             : pair_softmax_lagging<D, false>(st[0], lsum, s0, s1, min(nvalid, pos[0] + 1 - t0), a.scale_log2);
-      if (full) {
-#pragma unroll
-        for (int k = 0; k < KQ; ++k) {
-          st[0].o[2 * k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lds[stage][2][k * 64 + lane]), pp, st[0].o[2 * k], 0, 0, 0);
-          st[0].o[2 * k + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lds[stage][3][k * 64 + lane]), pp, st[0].o[2 * k + 1], 0, 0, 0);
-        }
-      } else {   // tokens the pair does not hold may be anything: zero their V
-        uint4 lo[KQ], hi[KQ];
-#pragma unroll
-        for (int k = 0; k < KQ; ++k) { lo[k] = lds[stage][2][k * 64 + lane]; hi[k] = lds[stage][3][k * 64 + lane]; }
-        pair_pv_lohi<D, false>(st[0], lo, hi, pp, nvalid);
-      }
-    }
-    __syncthreads();
-  }
-  if (!wave_has_rows) return;
-#pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    const float l = lsum[0];
-    if (out_row[b] < 0) continue;
-    const float inv = a.v_scale / l;
-    float* o = a.out + out_row[b];
-#pragma unroll
-    for (int k = 0; k < D / 16; ++k) *(f32x4*)(o + k * 16 + 4 * g4) = st[b].o[k] * inv;
-  }
-}
-
-// bf16 caches, second form: 32 query rows per wave on the 32x32x16 product, so that an operand read
-// from LDS feeds twice the arithmetic, and two waves per SIMD with the whole tile state in registers.
+// bf16 caches: K and V staged in LDS once per workgroup, 32 query rows per wave on the 32x32x16 product, so
+// that an operand read from LDS feeds twice the arithmetic of the 16x16x32 product, two waves per SIMD with
+// the whole tile state in registers.
 //   S^T (32 tokens x 32 rows) = K (32 x 16 per step) Q^T : A = the pair's K as stored (lane l: token l % 32,
 //        8 head-dim elements (2 s + l / 32) * 8 ..), B = Q^T from registers, D / 16 steps;
 //   O^T (32 of d x 32 rows) += V^T P^T per 32-column block of d and per page of the pair: the contraction
@@ -366,7 +238,7 @@ k_prefill_lds8(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
 //        lane's own sixteen weights, converted and packed, and no data crosses lanes; the loader writes V
 //        into LDS in that operand order (two 8-byte pieces per stored chunk).
 // The 128 rows of a tile go to 4 waves; a page pair is fetched once per workgroup into a ring of three LDS
-// stages (one barrier per pair).  Softmax against a lagging reference (see pair_softmax_lagging): a lane
+// stages (one barrier per pair).  Softmax against a lagging reference (the reference is raised, and the accumulators rescaled, only when some score exceeds it by 2^kLag; until then a weight may exceed 1, which is harmless in fp32 and bf16, and l and O / l do not depend on the reference): a lane
 // holds half of its query row's tokens, the other half sits 32 lanes away; the denominator is summed from
 // the bf16-rounded weights with the packed dot product (v_dot2c_f32_bf16), per half, and joined at the end.
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -644,14 +516,9 @@ void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s) {
       hipLaunchKernelGGL(kern, dim3(a.max_tiles, a.n_seqs), dim3(kAttnThreads), 0, s, c, a, c.tb.prefix_table);
     };
     const bool fp8 = dm.layout == SART_LAYOUT_MFMA16_FP8;
-    if (!fp8) {   // bf16: the LDS-staged kernel with 8 waves per tile
-      if (a.variant == 1) {
-        if (dm.d == 128) hipLaunchKernelGGL(k_prefill_lds8<128>, dim3(a.max_tiles, a.n_seqs), dim3(512), 0, s, c, a, c.tb.prefix_table);
-        else hipLaunchKernelGGL(k_prefill_lds8<64>, dim3(a.max_tiles, a.n_seqs), dim3(512), 0, s, c, a, c.tb.prefix_table);
-      } else {
-        if (dm.d == 128) hipLaunchKernelGGL(k_prefill_x32<128>, dim3(a.max_tiles, a.n_seqs), dim3(256), 0, s, c, a, c.tb.prefix_table);
-        else hipLaunchKernelGGL(k_prefill_x32<64>, dim3(a.max_tiles, a.n_seqs), dim3(256), 0, s, c, a, c.tb.prefix_table);
-      }
+    if (!fp8) {   // bf16: the LDS-staged kernel
+      if (dm.d == 128) hipLaunchKernelGGL(k_prefill_x32<128>, dim3(a.max_tiles, a.n_seqs), dim3(256), 0, s, c, a, c.tb.prefix_table);
+      else hipLaunchKernelGGL(k_prefill_x32<64>, dim3(a.max_tiles, a.n_seqs), dim3(256), 0, s, c, a, c.tb.prefix_table);
       return;
     }
     if (dm.d == 128) go(k_prefill_mfma<128, true>); else go(k_prefill_mfma<64, true>);   // 8-bit float caches
