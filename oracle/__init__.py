@@ -46,6 +46,7 @@ def _load():
         L.orc_prefill_attention.argtypes = [vp, C.c_int, vp, C.c_int, C.c_double, dp, dp]
         L.orc_finish.argtypes = [vp, C.c_int, ip]
         L.orc_start.argtypes = [vp, C.c_int, ip]
+        L.orc_fork.argtypes = [vp, C.c_int, ip, ip]
         L.orc_set_start_waiting.argtypes = [vp, C.c_int]
         L.orc_set_fp8.argtypes = [vp, C.c_double, C.c_double]
         L.orc_fp8_roundtrip.argtypes = [vp, C.c_int, C.c_double, vp, vp]
@@ -166,6 +167,13 @@ class OracleCache:
         """Waiting branches join the batch (Algorithm 1, main workflow)."""
         h = _i32(handles)
         return self.L.orc_start(self.h, len(h), _iptr(h))
+
+    def fork(self, src, dst) -> int:
+        """Branches split: dst[i] (WAITING) joins the batch as a copy of src[i] (ACTIVE), sharing its full pages."""
+        s_, d_ = _i32(src), _i32(dst)
+        if len(s_) != len(d_):
+            return E_INVALID
+        return self.L.orc_fork(self.h, len(s_), _iptr(s_), _iptr(d_))
 
     def finish(self, handles) -> int:
         h = _i32(handles)

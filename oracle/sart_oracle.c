@@ -22,6 +22,10 @@
  *     request; a branch's KV cache is released as soon as it is pruned,
  *     early-stopped or completed; the prefix is released only when all
  *     branches have terminated.
+ *   - Section 2 (tree-based search, e.g. Rebase, which the evaluation compares
+ *     against: a reasoning trajectory is expanded into several continuations):
+ *     orc_fork lets a branch split, the copies sharing the KV pages of what they
+ *     have in common; a shared page is released when its last holder ends.
  *   - Section 4 (prefilling is done as in plain LLM inference) and Section 2
  *     (one token generated per decode step): the attention is the
  *     textbook one, softmax(q K^T / sqrt(d)) V of one query over all cached
@@ -77,6 +81,7 @@ typedef struct {
   int* state;
   int* seq_len;
   int* block_table;     /* [max_req*Nb][max_bp], -1 padded */
+  int* page_ref;        /* [num_pages] branches whose block table holds the page (0: not a branch's page) */
   /* active list */
   int n_active;
   int* active;
@@ -117,6 +122,7 @@ orc* orc_create(int Hq, int Hkv, int d, int pt, int num_pages, int max_req, int 
   o->state = ints(H, BR_UNUSED);
   o->seq_len = ints(H, 0);
   o->block_table = ints(H * max_bp, -1);
+  o->page_ref = ints(num_pages, 0);
   o->n_active = 0;
   o->active = ints(H, -1);
   return o;
@@ -126,7 +132,7 @@ void orc_destroy(orc* o) {
   if (!o) return;
   free(o->pool); free(o->free_stack); free(o->req_used); free(o->prefix_len);
   free(o->prefix_table); free(o->refcnt); free(o->num_completed); free(o->num_pruned);
-  free(o->branch_appended); free(o->state); free(o->seq_len); free(o->block_table);
+  free(o->branch_appended); free(o->state); free(o->seq_len); free(o->block_table); free(o->page_ref);
   free(o->active); free(o);
 }
 
@@ -308,7 +314,10 @@ int orc_append(orc* o, int kind, int n_seqs, const int* ids, const int* n_tokens
     }
     for (int t = 0; t < n; ++t, ++tok) {
       int pos = *len;
-      if (pos % o->pt == 0) table[pos / o->pt] = pop_page(o); /* first token of a new page */
+      if (pos % o->pt == 0) {                                  /* first token of a new page */
+        table[pos / o->pt] = pop_page(o);
+        if (kind == SEQ_BRANCH) o->page_ref[table[pos / o->pt]] = 1;
+      }
       int page = table[pos / o->pt], slot = pos % o->pt;
       for (int h = 0; h < o->Hkv; ++h) {
         size_t src = tok * row + (size_t)h * o->d * o->esize;
@@ -464,7 +473,10 @@ static void terminate(orc* o, const int* new_state, const unsigned char* stop_wa
     int b = o->active[a], r = b / o->Nb;
     int* bt = o->block_table + (size_t)b * o->max_bp;
     int np = ceil_div(o->seq_len[b], o->pt);
-    for (int p = 0; p < np; ++p) { push_page(o, bt[p]); bt[p] = -1; }
+    for (int p = 0; p < np; ++p) {                              /* a page shared after a fork goes with its last holder */
+      if (--o->page_ref[bt[p]] == 0) push_page(o, bt[p]);
+      bt[p] = -1;
+    }
     o->seq_len[b] = 0;
     o->state[b] = new_state[a];
     o->refcnt[r]--;
@@ -521,6 +533,52 @@ int orc_start(orc* o, int n, const int* handles) {
     o->n_active++;
     o->state[b] = BR_ACTIVE;
     o->seq_len[b] = 0;
+  }
+  return ORC_OK;
+}
+
+/*
+ * A branch splits (tree search over reasoning trajectories, Section 2: a
+ * trajectory is expanded into several continuations).  dst[i], a WAITING branch
+ * of the request of src[i], joins the batch as a copy of the ACTIVE branch
+ * src[i]: same private tokens so far.  The two share the pages that are full at
+ * this moment (a page is then held by several block tables, at the same logical
+ * index in each, and goes back to the free stack when its last holder ends); a
+ * partly filled last page is copied into a fresh page, so every branch appends
+ * into a page of its own.  List entries are handled in order: dst[i] takes its
+ * place in the batch as in orc_start (behind its request's last active branch),
+ * then pops its page, if it needs one.  The same src may be listed several times.
+ */
+int orc_fork(orc* o, int n, const int* src, const int* dst) {
+  const int H = o->max_req * o->Nb;
+  if (n < 0 || (n > 0 && (!src || !dst))) return ORC_E_INVALID;
+  for (int i = 0; i < n; ++i) {
+    if (src[i] < 0 || src[i] >= H || dst[i] < 0 || dst[i] >= H) return ORC_E_INVALID;
+    if (src[i] / o->Nb != dst[i] / o->Nb) return ORC_E_INVALID;      /* a branch splits within its request */
+  }
+  if (is_dup(dst, n, H)) return ORC_E_INVALID;
+  int need = 0;
+  for (int i = 0; i < n; ++i) {
+    if (o->state[src[i]] != BR_ACTIVE || o->state[dst[i]] != BR_WAITING) return ORC_E_STATE;
+    need += o->seq_len[src[i]] % o->pt != 0;
+  }
+  if (need > o->free_top) return ORC_E_OOM_PAGES;
+  const size_t page_bytes = (size_t)o->pt * o->Hkv * 2 * o->d * o->esize;
+  for (int i = 0; i < n; ++i) {
+    const int one = dst[i];
+    int rc = orc_start(o, 1, &one);
+    if (rc != ORC_OK) return rc;                                     /* cannot happen: checked above */
+    const int L = o->seq_len[src[i]], full = L / o->pt;
+    const int* from = o->block_table + (size_t)src[i] * o->max_bp;
+    int* to = o->block_table + (size_t)dst[i] * o->max_bp;
+    for (int p = 0; p < full; ++p) { to[p] = from[p]; o->page_ref[from[p]]++; }
+    if (L % o->pt) {
+      const int page = pop_page(o);
+      o->page_ref[page] = 1;
+      to[full] = page;
+      memcpy(o->pool + (size_t)page * page_bytes, o->pool + (size_t)from[full] * page_bytes, page_bytes);
+    }
+    o->seq_len[dst[i]] = L;
   }
   return ORC_OK;
 }

@@ -47,7 +47,9 @@ class DenseShadow:
 def check_invariants(st, *, pt, num_pages, Nb, max_req):
     """Page conservation and reference counts (spec invariant):
     free + private pages of active branches + prefix pages of live requests ==
-    num_pages, no page listed twice, refcnt[r] == number of active branches."""
+    num_pages, no page listed twice - except that branches of one request may hold a page together after a
+    fork, then at the same logical index and with every earlier page shared too -, refcnt[r] == number of
+    active and waiting branches."""
     nA = int(st["n_active"][0])
     top = int(st["free_top"][0])
     pages = list(st["free_stack"][:top])
@@ -57,6 +59,7 @@ def check_invariants(st, *, pt, num_pages, Nb, max_req):
     assert np.all(st["seq_lens"][nA:] == 0)
     assert np.all(st["block_tables"][nA:] == -1)
     live = np.zeros(max_req, np.int64)
+    holders = {}                                  # branch page -> (logical index, request, rows holding it)
     for a in range(nA):
         b = int(st["active_handles"][a])
         assert st["branch_state"][b] == orc.ACTIVE
@@ -64,7 +67,17 @@ def check_invariants(st, *, pt, num_pages, Nb, max_req):
         n = -(-int(st["seq_lens"][a]) // pt)
         row = st["block_tables"][a]
         assert np.all(row[:n] >= 0) and np.all(row[n:] == -1), (a, n, row)
-        pages += list(row[:n])
+        for l in range(n):
+            pg = int(row[l])
+            if pg in holders:
+                l0, r0, rows0 = holders[pg]
+                assert (l0, r0) == (l, b // Nb), f"page {pg} shared at different places"
+                for a0 in rows0:                  # who shares page l shares what comes before it
+                    assert np.array_equal(st["block_tables"][a0][:l], row[:l])
+                rows0.append(a)
+            else:
+                holders[pg] = (l, b // Nb, [a])
+                pages.append(pg)
     assert len(set(int(h) for h in st["active_handles"][:nA])) == nA
     assert np.sum(st["branch_state"] == orc.ACTIVE) == nA
     waiting = (st["branch_state"] == orc.WAITING).reshape(max_req, Nb).sum(axis=1)
@@ -114,6 +127,8 @@ def run_golden_scenario(scn, engine, Hkv, d, np_dtype, done=None):
             rc = engine.finish(step["handles"])
         elif op == "start":
             rc = engine.start(step["handles"])
+        elif op == "fork":
+            rc = engine.fork(step["src"], step["dst"])
         else:
             raise ValueError(op)
         assert rc == step["status"], (scn["name"], i, op, rc)
