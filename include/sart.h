@@ -297,6 +297,27 @@ sart_status sart_finish_branch(sart_cache* cache, int32_t n,
 sart_status sart_start_branches(sart_cache* cache, int32_t n,
                                 const int32_t* handles /*HOST*/, void* stream);
 
+/* A branch splits (Section 2: tree search over reasoning trajectories expands
+ * a trajectory into several continuations; the evaluation's Rebase baseline is
+ * such a method).  Only for caches created with branches_start_waiting.
+ * dst[i], a WAITING branch of the same request as src[i] (else SART_E_INVALID at
+ * once), joins the batch as a copy of the ACTIVE branch src[i]: the same private
+ * tokens so far, in every layer.  It takes its place like a started branch
+ * (sart_start_branches: behind its request's last active branch; list order).
+ * The two share the pages that are full at this moment - such a page is listed in
+ * several rows of block_tables, at the same logical index, and returns to the
+ * free stack when the last branch holding it ends, at that branch's turn of the
+ * release order (Section 4's rule for the shared prompt, applied to what branches
+ * have in common).  A partly filled last page is copied into a freshly popped
+ * page (pops in list order), so every branch appends into a page of its own.
+ * The same src may be listed several times; dst must not repeat.
+ * Device-detected, sticky, nothing changes: a src that is not ACTIVE or a dst
+ * that is not WAITING (SART_E_STATE); fewer free pages than partly filled pages
+ * to copy (SART_E_OOM_PAGES).  sart_decode_attention reads shared pages once per
+ * branch that holds them; only the prompt is read once per request. */
+sart_status sart_fork_branches(sart_cache* cache, int32_t n, const int32_t* src /*HOST*/,
+                               const int32_t* dst /*HOST*/, void* stream);
+
 /* A8 without a host list: completes every active branch whose length (private
  * tokens) has reached target_len[handle] (DEVICE, max_requests * Nb entries, by
  * handle), exactly as sart_finish_branch would for the list of those branches

@@ -64,6 +64,7 @@ _SIGNATURES = {
     "sart_prune_branches": (C.c_int, [C.c_void_p, C.POINTER(_Policy), C.c_void_p, C.c_int32, C.c_void_p]),
     "sart_finish_branch": (C.c_int, [C.c_void_p, C.c_int32, _ip, C.c_void_p]),
     "sart_start_branches": (C.c_int, [C.c_void_p, C.c_int32, _ip, C.c_void_p]),
+    "sart_fork_branches": (C.c_int, [C.c_void_p, C.c_int32, _ip, _ip, C.c_void_p]),
     "sart_finish_reached": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "sart_append_active_by_handle": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "sart_decode_attention_by_handle": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]),
@@ -274,6 +275,17 @@ class SartCache:
         """sart_start_branches: waiting branches join the batch."""
         h = _i32(handles)
         rc = self.lib.sart_start_branches(self.h, len(h), _ptr(h), _stream_handle(stream))
+        if status:
+            return rc if rc != OK else self.sync_status()
+        self._check(rc)
+        return OK
+
+    def fork_branches(self, src, dst, stream=None, status=False):
+        """sart_fork_branches: dst[i] (waiting) joins the batch as a copy of src[i] (active), sharing its full pages."""
+        s_, d_ = _i32(src), _i32(dst)
+        if len(s_) != len(d_):
+            raise ValueError("src and dst differ in length")
+        rc = self.lib.sart_fork_branches(self.h, len(s_), _ptr(s_), _ptr(d_), _stream_handle(stream))
         if status:
             return rc if rc != OK else self.sync_status()
         self._check(rc)

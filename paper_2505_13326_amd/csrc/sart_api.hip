@@ -235,6 +235,12 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   ALLOC(tb.wave_desc, (size_t)16 * c->max_wg * kAttnWaves);
   ALLOC(tb.row_desc, 8 * H);
   ALLOC(tb.pf_seq, 4 * R);
+  ALLOC(tb.mv_first, H);
+  ALLOC(tb.page_extra, (size_t)dm.num_pages);
+  ALLOC(tb.page_owner, (size_t)dm.num_pages);
+  HIP_TRY(hipMemset(tb.mv_first, 0, H * sizeof(int)));
+  HIP_TRY(hipMemset(tb.page_extra, 0, (size_t)dm.num_pages * sizeof(int)));
+  HIP_TRY(hipMemset(tb.page_owner, 0xff, (size_t)dm.num_pages * sizeof(int)));
   ALLOC(tb.seg_count, H * dm.Hkv);
   HIP_TRY(hipMemset(tb.seg_count, 0, H * dm.Hkv * sizeof(int)));
   HIP_TRY(hipHostMalloc((void**)&c->host_nactive, 64, hipHostMallocMapped));
@@ -593,8 +599,8 @@ sart_status sart_finish_branch(sart_cache* c, int32_t n, const int32_t* handles,
   return SART_OK;
 }
 
-sart_status sart_start_branches(sart_cache* c, int32_t n, const int32_t* handles, void* stream) {
-  if (!c) return fail(SART_E_INVALID, "null cache");
+// Shared by sart_start_branches (src == null) and sart_fork_branches.
+static sart_status start_common(sart_cache* c, int32_t n, const int32_t* handles, const int32_t* src, void* stream) {
   const Dims& dm = c->ctx.dm;
   if (!dm.start_waiting) return fail(SART_E_INVALID, "the cache was not created with branches_start_waiting");
   if (n < 0 || (n > 0 && !handles)) return fail(SART_E_INVALID, "bad handle list");
@@ -606,6 +612,10 @@ sart_status sart_start_branches(sart_cache* c, int32_t n, const int32_t* handles
       if (handles[i] < 0 || handles[i] >= dm.H) return fail(SART_E_INVALID, "handle %d out of range", handles[i]);
       if (seen[handles[i]]) return fail(SART_E_INVALID, "duplicate handle %d", handles[i]);
       seen[handles[i]] = 1;
+      if (!src) continue;
+      if (src[i] < 0 || src[i] >= dm.H) return fail(SART_E_INVALID, "source handle %d out of range", src[i]);
+      if (src[i] / dm.Nb != handles[i] / dm.Nb)
+        return fail(SART_E_INVALID, "branch %d cannot continue branch %d of another request", handles[i], src[i]);
     }
   }
   hipStream_t st = (hipStream_t)stream;
@@ -614,12 +624,24 @@ sart_status sart_start_branches(sart_cache* c, int32_t n, const int32_t* handles
   sart_status rc = stage_begin(c, &s);
   if (rc != SART_OK) return rc;
   memcpy(s->host, handles, (size_t)n * sizeof(int));
-  rc = stage_upload(c, s, n, st);
+  if (src) memcpy(s->host + n, src, (size_t)n * sizeof(int));
+  rc = stage_upload(c, s, src ? 2 * (size_t)n : (size_t)n, st);
   if (rc != SART_OK) return rc;
-  launch_start(c->ctx, c->plan, n, s->dev, ++c->call_seq, st);
+  launch_start(c->ctx, c->plan, n, s->dev, src ? s->dev + n : nullptr, c->desc.n_layers, c->layer_bytes, ++c->call_seq, st);
   HIP_TRY(hipEventRecord(s->done, st));
   HIP_TRY(hipGetLastError());
   return SART_OK;
+}
+
+sart_status sart_start_branches(sart_cache* c, int32_t n, const int32_t* handles, void* stream) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  return start_common(c, n, handles, nullptr, stream);
+}
+
+sart_status sart_fork_branches(sart_cache* c, int32_t n, const int32_t* src, const int32_t* dst, void* stream) {
+  if (!c) return fail(SART_E_INVALID, "null cache");
+  if (n > 0 && !src) return fail(SART_E_INVALID, "null source list");
+  return start_common(c, n, dst, src, stream);
 }
 
 sart_status sart_finish_reached(sart_cache* c, const int32_t* target_len, void* stream) {

@@ -326,13 +326,57 @@ __device__ void terminate_plan(const Ctx& c, const PlanCfg& pc, int* lds, bool s
   const int top = scal[S_FREETOP];
   for (int r = tid; r < dm.max_req; r += kPlanThreads) { tb.req_touched[r] = 0; tb.req_push_off[r] = -1; }
   __syncthreads();
+  // Branches that were split share pages: a page goes back to the free stack with its last holder, at that
+  // holder's turn.  Holders of a page hold every earlier page of theirs together too, so the pages a victim
+  // releases are the tail [mv_first, pages) of its row.  One wave per victim row: (1) every page loses a
+  // holder and notes the highest victim row holding it; (2) a row counts its leading pages that stay (someone
+  // else still holds them, or a later victim releases them); (3) the releasing row resets the page's counters.
+  const bool shared_pages = scal[S_ANY_FORK] != 0;
+  if (shared_pages) {
+    const int* bt_cur = tb.bt[scal[S_BTSEL]];
+    const int lane = tid & 63, wave = tid >> 6, n_waves = kPlanThreads >> 6;
+    for (int a = wave; a < nA; a += n_waves) {
+      if (!tb.new_state[a]) continue;
+      const int np = ceil_div(tb.seq_len[a], dm.pt);
+      for (int l = lane; l < np; l += 64) {
+        const int pg = bt_cur[(long long)a * dm.max_bp + l];
+        atomicSub(&tb.page_extra[pg], 1);
+        atomicMax(&tb.page_owner[pg], a);
+      }
+    }
+    __syncthreads();
+    for (int a = wave; a < nA; a += n_waves) {
+      if (!tb.new_state[a]) continue;
+      const int np = ceil_div(tb.seq_len[a], dm.pt);
+      int stay = 0;
+      for (int l = lane; l < np; l += 64) {
+        const int pg = bt_cur[(long long)a * dm.max_bp + l];
+        stay += !(tb.page_extra[pg] < 0 && tb.page_owner[pg] == a);
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) stay += __shfl_xor(stay, off, 64);
+      if (lane == 0) tb.mv_first[a] = stay;
+    }
+    __syncthreads();
+    for (int a = wave; a < nA; a += n_waves) {
+      if (!tb.new_state[a]) continue;
+      const int np = ceil_div(tb.seq_len[a], dm.pt);
+      for (int l = lane; l < np; l += 64) {
+        const int pg = bt_cur[(long long)a * dm.max_bp + l];
+        if (tb.page_owner[pg] != a) continue;
+        if (tb.page_extra[pg] < 0) tb.page_extra[pg] = 0;
+        tb.page_owner[pg] = -1;
+      }
+    }
+    __syncthreads();
+  }
   // scans over active rows: pages pushed by victims, new index of survivors
   int carry_p = 0, carry_s = 0;
   for (int base = 0; base < nA; base += kPlanThreads) {
     const int a = base + tid;
     int np = 0, keep = 0;
     if (a < nA) {
-      if (tb.new_state[a]) np = ceil_div(tb.seq_len[a], dm.pt); else keep = 1;
+      if (tb.new_state[a]) np = ceil_div(tb.seq_len[a], dm.pt) - (shared_pages ? tb.mv_first[a] : 0); else keep = 1;
     }
     int tp, ts;
     const int exp_ = block_excl_scan(np, lds, tp);
@@ -436,9 +480,10 @@ k_terminate_move(Ctx c) {
         const int* src = bt_old + (long long)u * dm.max_bp;
         const int off = tb.mv_push_off[u];
         if (off >= 0) {
-          for (int p = threadIdx.x; p < dm.max_bp; p += blockDim.x) {
+          const int first = scal[S_ANY_FORK] ? tb.mv_first[u] : 0;      // earlier pages stay with other holders
+          for (int p = first + threadIdx.x; p < dm.max_bp; p += blockDim.x) {
             const int page = src[p];
-            if (page >= 0) tb.free_stack[top + off + p] = page;
+            if (page >= 0) tb.free_stack[top + off + p - first] = page;
           }
         } else {
           int* dst = bt_new + (long long)tb.mv_new_idx[u] * dm.max_bp;
@@ -623,8 +668,14 @@ void launch_finish(const Ctx& c, const PlanCfg& pc, int n, const int* handles_de
 // The block-table rows move with their branches into the other buffer
 // (k_start_move); a started branch's row is empty.
 // ---------------------------------------------------------------------------
+// A split (src != null; tree search expands a trajectory into several
+// continuations, Section 2): list entry i joins as a copy of the ACTIVE branch
+// src[i] - its length, its block-table row (copied by k_start_move like a moved
+// row), sharing the pages that are full; a partly filled last page is replaced
+// by a freshly popped page that k_fork_fix fills (pages popped in list order).
+// ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kPlanThreads)
-k_start_plan(Ctx c, PlanCfg pc, int n, const int* handles, int call_seq) {
+k_start_plan(Ctx c, PlanCfg pc, int n, const int* handles, const int* src, int call_seq) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
@@ -632,14 +683,37 @@ k_start_plan(Ctx c, PlanCfg pc, int n, const int* handles, int call_seq) {
   __shared__ int s_bad;
   const int tid = threadIdx.x;
   const int nA = scal[S_NACTIVE];
+  const int top = scal[S_FREETOP];
   if (tid == 0) s_bad = 0;
   __syncthreads();
-  for (int i = tid; i < n; i += kPlanThreads)
+  for (int i = tid; i < n; i += kPlanThreads) {
     if (tb.br_state[handles[i]] != SART_BRANCH_WAITING) s_bad = 1;
+    if (src && tb.br_state[src[i]] != SART_BRANCH_ACTIVE) s_bad = 1;
+  }
   __syncthreads();
   if (s_bad) {
     if (tid == 0) record_error(scal, SART_E_STATE, call_seq);
     return;
+  }
+  int fork_pages = 0;                          // pages the copies of partly filled last pages need
+  if (src) {
+    for (int base = 0; base < n; base += kPlanThreads) {
+      const int i = base + tid;
+      int need = 0;
+      if (i < n) {
+        const int old_row = tb.active_idx_of[src[i]];
+        tb.mv_first[i] = old_row;              // (the rows move below: kept for the entry's length and row copy; scratch)
+        need = tb.seq_len[old_row] % dm.pt != 0;
+      }
+      int tot;
+      const int ex = block_excl_scan(need, lds, tot);
+      if (i < n) tb.tmp_b[i] = need ? fork_pages + ex : -1;      // which pop is the entry's, for now
+      fork_pages += tot;
+    }
+    if (fork_pages > top) {
+      if (tid == 0) record_error(scal, SART_E_OOM_PAGES, call_seq);
+      return;
+    }
   }
   if (tid == 0) scal[S_APPENDOK] = 0;        // rows move: no more writes to other layers for the last append
   for (int r = tid; r < dm.max_req; r += kPlanThreads) { tb.req_touched[r] = 0; tb.req_tmp[r] = 0; }
@@ -705,13 +779,22 @@ k_start_plan(Ctx c, PlanCfg pc, int n, const int* handles, int call_seq) {
     const int pos = tb.nact[r] > 0 ? tb.mv_new_idx[tb.req_first[r] + tb.nact[r] - 1] + 1 + tb.tmp_a[i]
                                    : nA + behind_rows + tb.req_tmp[r] + tb.tmp_a[i];
     tb.active[pos] = b;
-    tb.seq_len[pos] = 0;
+    tb.seq_len[pos] = src ? tb.mv_push_off[tb.mv_first[i]] : 0;      // a copy starts with its source's length
+    if (src) tb.ap_id[pos] = tb.mv_first[i];                          // and its row of the block table
     tb.active_idx_of[b] = pos;
     tb.br_state[b] = SART_BRANCH_ACTIVE;
   }
   __syncthreads();
+  if (src) {
+    // what k_fork_fix needs per entry: its row (tmp_a) and the page popped for it (tmp_b, -1: none)
+    for (int i = tid; i < n; i += kPlanThreads) {
+      tb.tmp_a[i] = tb.active_idx_of[handles[i]];
+      if (tb.tmp_b[i] >= 0) tb.tmp_b[i] = tb.free_stack[top - 1 - tb.tmp_b[i]];
+    }
+  }
   for (int r = tid; r < dm.max_req; r += kPlanThreads) tb.nact[r] += tb.req_touched[r];
   if (tid == 0) {
+    if (src) { scal[S_FREETOP] = top - fork_pages; scal[S_ANY_FORK] = 1; }
     const int old_sel = scal[S_BTSEL], new_sel = old_sel ^ 1;
     scal[S_T_NA_OLD] = nA;
     scal[S_T_NA_NEW] = na_new;
@@ -744,10 +827,40 @@ k_start_move(Ctx c) {
   }
 }
 
-void launch_start(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, int call_seq, hipStream_t s) {
-  hipLaunchKernelGGL(k_start_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, n, handles_dev, call_seq);
+// After a split's rows were copied: entry i's row shares its full pages (one more holder each) and, where the
+// source's last page is partly filled, gets the page popped for it with that page's contents in every layer.
+__global__ void __launch_bounds__(256)
+k_fork_fix(Ctx c, int n, int n_layers, long long layer_bytes) {
+  const Dims& dm = c.dm;
+  const Tables& tb = c.tb;
+  const int* scal = tb.scal;
+  if (!scal[S_CALLOK]) return;
+  int* bt = tb.bt[scal[S_BTSEL]];
+  const long long page_bytes = dm.page_elems * dm.esize;
+  for (int i = blockIdx.x; i < n; i += gridDim.x) {
+    const int row = tb.tmp_a[i], len = tb.seq_len[row], full = len / dm.pt;
+    int* my = bt + (long long)row * dm.max_bp;
+    for (int p = threadIdx.x; p < full; p += blockDim.x) atomicAdd(&tb.page_extra[my[p]], 1);
+    const int fresh = tb.tmp_b[i];
+    if (fresh < 0) continue;
+    const int old = my[full];
+    for (int l = 0; l < n_layers; ++l) {
+      const uint4* from = (const uint4*)((const unsigned char*)c.pool + l * layer_bytes + old * page_bytes);
+      uint4* to = (uint4*)((unsigned char*)c.pool + l * layer_bytes + fresh * page_bytes);
+      for (long long x = threadIdx.x; x < page_bytes / 16; x += blockDim.x) to[x] = from[x];
+    }
+    __syncthreads();                           // every thread has read `old`
+    if (threadIdx.x == 0) my[full] = fresh;
+  }
+}
+
+void launch_start(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, const int* src_dev, int n_layers,
+                  size_t layer_bytes, int call_seq, hipStream_t s) {
+  hipLaunchKernelGGL(k_start_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, n, handles_dev, src_dev, call_seq);
   const int blocks = c.dm.H < 2048 ? c.dm.H : 2048;
   hipLaunchKernelGGL(k_start_move, dim3(blocks), dim3(256), 0, s, c);
+  if (src_dev && n > 0)
+    hipLaunchKernelGGL(k_fork_fix, dim3(n < 2048 ? n : 2048), dim3(256), 0, s, c, n, n_layers, (long long)layer_bytes);
 }
 
 // Stand-alone refresh of the decode plan (after sart_alloc_cache and when the

@@ -50,6 +50,7 @@ enum Scalar {
   S_D_PB,         // pages per prompt block
   S_D_NBLOCKS,    // prompt blocks (partial slots of the prompts)
   S_D_NPITEMS,    // prompt work items of the streaming phase (= blocks unless rows are shared)
+  S_ANY_FORK,     // some branch was split since the cache was created: branch pages may be shared
   S_COUNT = 32
 };
 
@@ -85,6 +86,9 @@ struct Tables {
   int* new_state;        // [H]
   int* mv_push_off;      // [H]  -1 for survivors
   int* mv_new_idx;       // [H]
+  int* mv_first;         // [H] a terminating row's first page that goes back to the free stack (0 unless pages are shared)
+  int* page_extra;       // [num_pages] holders of a branch page beyond the first (0 unless branches were split)
+  int* page_owner;       // [num_pages] scratch of the terminate pass, -1 between passes
   int* tmp_a;            // [H]
   int* tmp_b;            // [H]
   int* req_first;        // [max_req] first active index of the request
@@ -222,7 +226,10 @@ void launch_prune(const Ctx& c, const PlanCfg& pc, const PruneArgs& a, hipStream
 void launch_finish(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, const int* targets_dev, int call_seq,
                    hipStream_t s);
 void launch_plan(const Ctx& c, const PlanCfg& pc, hipStream_t s);
-void launch_start(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, int call_seq, hipStream_t s);
+// src_dev != null: the listed branches join as copies of the branches src_dev lists (a split); the pool has
+// n_layers layers, layer_bytes apart
+void launch_start(const Ctx& c, const PlanCfg& pc, int n, const int* handles_dev, const int* src_dev, int n_layers,
+                  size_t layer_bytes, int call_seq, hipStream_t s);
 
 struct DecodeArgs {
   const void* q;

@@ -38,6 +38,12 @@ class GpuEngine:
         except Exception as e:                       # host-side refusals (duplicates, range) are statuses here
             return getattr(e, "status", orc.E_INVALID)
 
+    def fork(self, src, dst):
+        try:
+            return self.c.fork_branches(src, dst, status=True)
+        except Exception as e:                       # host-side refusals are statuses here
+            return getattr(e, "status", orc.E_INVALID)
+
     def state(self):
         return self.c.get_state()
 

@@ -436,12 +436,13 @@ def test_rows_addressed_by_handle(mode):
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype,pt,d", [("f32", 4, 8), ("bf16", 16, 64)])
 def test_random_op_sequences_with_waiting_branches(dtype, pt, d):
-    """Random prefix / start / append / prune / finish sequences on caches whose branches are created WAITING
-    (errors included): status and the whole integer state agree with the oracle after every call, and the
-    attention of the final state too."""
+    """Random prefix / start / split / append / prune / finish sequences on caches whose branches are created
+    WAITING (errors included): status and the whole integer state agree with the oracle after every call, and
+    the attention of every fifth state and of the final one too (split branches read shared and copied pages)."""
     rng = np.random.default_rng(77)
     R, Nb, num_pages, max_bp, max_pp = 6, 4, 140, 6, 3
     npd = np.float32 if dtype == "f32" else np.uint16
+    splits_done = 0
     for trial in range(6):
         kw = dict(n_q_heads=2, n_kv_heads=1, head_dim=d, page_tokens=pt, num_pages=num_pages, max_requests=R,
                   branches_per_request=Nb, finish_quota=int(rng.integers(0, 4)), max_pages_per_branch=max_bp,
@@ -457,8 +458,22 @@ def test_random_op_sequences_with_waiting_branches(dtype, pt, d):
             st = o.state()
             nA = int(st["n_active"][0])
             waiting = np.flatnonzero(st["branch_state"] == orc.WAITING)
-            op = int(rng.integers(0, 8))
-            if op == 0 and next_req < R:
+            op = int(rng.integers(0, 10))
+            if op in (8, 9) and len(waiting) and nA:
+                # splits: waiting branches continue active branches of their request (sometimes a wrong pair)
+                act = st["active_handles"][:nA]
+                src, dst = [], []
+                for b in rng.permutation(waiting)[:int(rng.integers(1, 4))]:
+                    cand = act[act // Nb == b // Nb] if rng.random() < 0.9 else act
+                    if len(cand):
+                        src.append(int(rng.choice(cand))); dst.append(int(b))
+                if not src:
+                    continue
+                if rng.random() < 0.1:
+                    dst[0] = int(rng.choice(act))                                     # not waiting
+                rc = [e.fork(src, dst) for e in (o, g)]
+                splits_done += rc[0] == orc.OK
+            elif op == 0 and next_req < R:
                 n = int(rng.integers(1, max_pp * pt + 1))
                 k, v = draw(n), draw(n)
                 rc = [e.append(orc.SEQ_PREFIX, [next_req], [n], k, v) for e in (o, g)]
@@ -487,10 +502,93 @@ def test_random_op_sequences_with_waiting_branches(dtype, pt, d):
             so, sg = o.state(), g.state()
             assert_state_equal(so, sg)
             check_invariants(sg, pt=pt, num_pages=num_pages, Nb=Nb, max_req=R)
+            if step % 5 == 4 and int(so["n_active"][0]):
+                q = draw(R * Nb).reshape(R * Nb, 1, d).repeat(2, axis=1)
+                compare_attention(wl.scaled(wl.CONFIGS[2], dtype=dtype), o, g, q)
         nA = int(o.state()["n_active"][0])
         if nA:
             q = draw(R * Nb).reshape(R * Nb, 1, d).repeat(2, axis=1)
             compare_attention(wl.scaled(wl.CONFIGS[2], dtype=dtype), o, g, q)
+    assert splits_done >= 3, splits_done
+
+
+def test_split_branches_at_the_7b_like_shape():
+    """Tree search at a real head geometry: 6 requests x 8 branches, prompts of 300 tokens; one branch per request
+    runs 1000+ tokens, splits into three, those run on and split again until all 8 exist; branches are pruned and
+    finished along the way.  Whole integer state and every row's attention against the oracle after each phase;
+    two layers (the copy of a partly filled page must reach every layer)."""
+    rng = np.random.default_rng(21)
+    cfg = wl.scaled(wl.CONFIGS[2], n_requests=6, nb=8, prompt_len=300, quota=8)
+    R, Nb, pt = cfg.n_requests, cfg.nb, 16
+    num_pages, max_bp = 1400, 100
+    kw = dims(cfg, num_pages, max_bp)
+    fo = wl.free_order(cfg, num_pages)
+    o0, o1 = orc.OracleCache(free_order=fo, start_waiting=True, **kw), orc.OracleCache(free_order=fo, start_waiting=True, **kw)
+    g = GpuEngine(free_order=fo, start_waiting=True, n_layers=2, **kw)
+
+    def bits(shape):
+        return wl.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+
+    def both_layers(fn_oracle, fn_gpu):
+        for o in (o0, o1):
+            assert fn_oracle(o) == orc.OK
+        assert fn_gpu() == orc.OK
+
+    def append(kind, ids, ns):
+        n = int(np.sum(ns))
+        k0, v0, k1, v1 = (bits((n, cfg.n_kv_heads, cfg.head_dim)) for _ in range(4))
+        assert o0.append(kind, ids, ns, k0, v0) == orc.OK and o1.append(kind, ids, ns, k1, v1) == orc.OK
+        assert g.c.append_tokens(kind, ids, ns, k0, v0, status=True) == orc.OK
+        assert g.c.append_tokens(kind, ids, ns, k1, v1, status=True, layer=1) == orc.OK
+
+    def check():
+        so = o0.state()
+        assert_state_equal(so, o1.state())
+        assert_state_equal(so, g.state())
+        check_invariants(so, pt=pt, num_pages=num_pages, Nb=Nb, max_req=R)
+        nA = int(so["n_active"][0])
+        act = so["active_handles"][:nA]
+        q = bits((nA, cfg.n_q_heads, cfg.head_dim))
+        worst = 0.0
+        for layer, o in enumerate((o0, o1)):
+            got = g.c.decode_attention(q, layer=layer).cpu().numpy().astype(np.float64)
+            worst = max(worst, float(np.abs(got - o.attention(q)).max()))
+        assert g.c.sync_status() == 0 and worst <= TOL["bf16"], worst
+        return act, worst
+
+    for r in range(R):
+        append(orc.SEQ_PREFIX, [r], [cfg.prompt_len])
+    roots = [r * Nb for r in range(R)]
+    both_layers(lambda o: o.start(roots), lambda: g.start(roots))
+    append(orc.SEQ_BRANCH, roots, [int(x) for x in rng.integers(1000, 1100, size=R)])        # some end mid-page, some not
+    src = [r * Nb for r in range(R) for _ in range(3)]
+    dst = [r * Nb + j for r in range(R) for j in (1, 2, 3)]
+    both_layers(lambda o: o.fork(src, dst), lambda: g.fork(src, dst))
+    act, w1 = check()
+    assert len(act) == 4 * R
+    append(orc.SEQ_BRANCH, None, [int(x) for x in rng.integers(0, 40, size=len(act))])
+    # second generation: branches 1 and 3 of every request split (1 twice)
+    src = [r * Nb + j for r in range(R) for j in (1, 1, 3, 2)]
+    dst = [r * Nb + j for r in range(R) for j in (4, 5, 6, 7)]
+    both_layers(lambda o: o.fork(src, dst), lambda: g.fork(src, dst))
+    act, w2 = check()
+    assert len(act) == 8 * R
+    append(orc.SEQ_BRANCH, None, [int(x) for x in rng.integers(1, 30, size=len(act))])
+    check()
+    sc = rng.random(len(act)).astype(np.float32)
+    both_layers(lambda o: o.prune(orc.DROP_LOWEST_K, sc, k=3), lambda: g.prune(orc.DROP_LOWEST_K, sc, k=3))
+    act, _ = check()
+    fin = [int(b) for b in act[::3]]
+    both_layers(lambda o: o.finish(fin), lambda: g.finish(fin))
+    act, w3 = check()
+    held = o0.state()["block_tables"][:len(act)].ravel()
+    assert np.unique(held[held >= 0], return_counts=True)[1].max() > 1, "no page is shared any more: the case lost its point"
+    rest = [int(b) for b in act]
+    both_layers(lambda o: o.finish(rest), lambda: g.finish(rest))
+    st = g.state()
+    assert_state_equal(o0.state(), st)
+    assert int(st["free_top"][0]) == num_pages
+    print(f"split branches: max abs attention err {max(w1, w2, w3):.3g}")
 
 
 def test_starting_branches_among_thousands_of_rows():
