@@ -505,7 +505,7 @@ def main():
                          "of config N")
     ap.add_argument("--free-order", default="scattered", choices=["scattered", "identity"])
     ap.add_argument("--workgroups", type=int, default=0, help="attention workgroups (0 = library default)")
-    ap.add_argument("--prompt-mode", type=int, default=-1, help="1 = prompt blocks read by every branch, 2 = prompt blocks read once for a tile of 16 of a request's query rows, -1 = library default")
+    ap.add_argument("--prompt-mode", type=int, default=-1, help="0 = chosen per step by the library (default), 1 = prompt blocks read by every branch, 2 = prompt blocks read once for a tile of 16 of a request's query rows, -1 = library default")
     ap.add_argument("--skew", type=int, default=None, help="per-mille of work moved from odd to even workgroups (default: library's)")
     ap.add_argument("--prompt-len", type=int, default=-1, help="override the workload's prompt length (experiments)")
     ap.add_argument("--requests", type=int, default=-1, help="override the workload's number of requests (experiments)")

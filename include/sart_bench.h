@@ -46,19 +46,23 @@ sart_status sart_read_probe_shaped(const void* buf, size_t bytes, const int32_t*
 /* Tuning knobs of the decode launch (defaults are chosen for MI355X):
  *   n_workgroups   persistent attention grid of 4-wave workgroups (<= 0: one per
  *                  CU);
- *   prompt_mode    how the shared prompt is read.  2 (default on the matrix-core
- *                  layouts) = in blocks of prompt pages, each read once per tile
- *                  of 16 query rows of the request (rows = (branch, head of the
- *                  GQA group), branch-major: with G = 7 and 8 branches, 4 tiles
- *                  instead of 8 per-branch reads, every row of the matrix-core
- *                  tile used); the items are ordered (request, kv head, chunk,
- *                  tile) and neighbours are served at the same time by waves of
- *                  one workgroup / XCD, so the tiles' re-reads of a chunk hit in
- *                  L2.  1 = the same with one block per (chunk, branch), G of 16
- *                  tile rows used; natural-layout caches always use 1.  -1 =
- *                  keep the current mode.  (A mode that staged each prompt chunk
- *                  in LDS once per workgroup was measured 2.5 to 3 times slower
- *                  on prompt-heavy workloads and is not in the library.)
+ *   prompt_mode    how the shared prompt is read, in blocks of prompt pages.
+ *                  1 = one read of a block per branch of the request (G of the
+ *                  matrix-core tile's 16 rows used); 2 = one read per tile of 16
+ *                  query rows of the request (rows = (branch, head of the GQA
+ *                  group), branch-major: with G = 7 and 8 branches, 4 tiles
+ *                  instead of 8 per-branch reads).  In both the items are
+ *                  ordered so that the readers of a block run at the same time
+ *                  on one XCD and all but the first read hit in its L2.
+ *                  0 (default on the matrix-core layouts) = the planning kernel
+ *                  chooses per step: per branch, whose longer items stream
+ *                  better, unless the tiles save a wave about 48 prompt pages or
+ *                  more, or the step has little private work to hide the prompts
+ *                  behind (measured over a grid of shapes).  Natural-layout
+ *                  caches always use 1.  -1 = keep the current setting.  (A mode
+ *                  that staged each prompt chunk in LDS once per workgroup was
+ *                  measured 2.5 to 3 times slower on prompt-heavy workloads and
+ *                  is not in the library.)
  *   skew_permille  work moved from odd to even workgroups, in 1/1000 of the
  *                  mean per-wave range (workgroups go round-robin to the 8 XCDs,
  *                  and the odd XCDs stream about 10 % slower); default 80,

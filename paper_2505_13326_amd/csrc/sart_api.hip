@@ -228,7 +228,7 @@ sart_status sart_alloc_cache(const sart_cache_desc* d, sart_cache** out) {
   c->max_wg = cus * 16;
   c->plan.n_wg = cus;                // one 4-wave workgroup per CU, one wave per SIMD
   // prompt blocks read once per tile of 16 query rows of the request (matrix-core layouts), per branch otherwise
-  c->plan.prompt_mode = dm.layout == SART_LAYOUT_NATURAL ? 1 : 2;
+  c->plan.prompt_mode = dm.layout == SART_LAYOUT_NATURAL ? 1 : 0;    // 0: the planning kernel chooses per step
   c->plan.skew_permille = kDefaultSkewPermille;
   ALLOC(tb.wave_row, (size_t)2 * c->max_wg * kAttnWaves);
   ALLOC(tb.req_pstart, R);
@@ -421,7 +421,6 @@ static sart_status decode_common(sart_cache* c, int32_t layer, const void* q, fl
   a.scale_log2 = scale * 1.44269504088896340736f * c->k_scale;
   a.v_scale = c->v_scale;
   a.n_wg = c->plan.n_wg;
-  a.prompt_mode = c->plan.prompt_mode;
   a.partials = partials; a.partial_cap = partial_cap; a.seg_count = seg_count;
   a.fused_merge = c->merge_mode;
   a.stagger_prompt = c->stagger_prompt;
@@ -763,7 +762,7 @@ sart_status sart_set_merge_mode(sart_cache* c, int32_t in_kernel) {
 
 sart_status sart_set_decode_launch(sart_cache* c, int32_t n_workgroups, int32_t prompt_mode, int32_t skew_permille) {
   if (!c) return fail(SART_E_INVALID, "null cache");
-  if (prompt_mode != -1 && prompt_mode != 1 && prompt_mode != 2) return fail(SART_E_INVALID, "prompt_mode must be -1, 1 or 2");
+  if (prompt_mode < -1 || prompt_mode > 2) return fail(SART_E_INVALID, "prompt_mode must be -1, 0, 1 or 2");
   if (skew_permille < -500 || skew_permille > 500) return fail(SART_E_INVALID, "skew_permille out of range");
   if (n_workgroups > c->max_wg) return fail(SART_E_INVALID, "at most %d workgroups", c->max_wg);
   hipDeviceProp_t prop;

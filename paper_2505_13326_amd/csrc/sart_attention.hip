@@ -260,6 +260,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
   {
     // ---- this wave's prompt work items and its range of the own line; one partial result per piece -------
     const Cut cut = load_cut(scal);
+    const int prompt_mode = scal[S_D_PMODE];             // how the plan had this step's prompts read
     const long long wave_id = (long long)blockIdx.x * kAttnWaves + wv;
     // where the wave starts, resolved by the planning kernel: one load instead of a chain of lookups
     const int4 wd0 = ((const int4*)(wave_desc + 16LL * wave_id))[0];
@@ -349,7 +350,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
         //      to 16 * kSharedBlocks query rows); its pages are read once and every page feeds the tile's
         //      blocks (rows = (branch, head of the group), branch-major).  One partial per (branch, kv head,
         //      chunk), in the slots the per-branch blocks would have used. -------------------------------
-        if (a.prompt_mode == 2 && wave_id >= n_waves - cut.n_prompt) {
+        if (prompt_mode == 2 && wave_id >= n_waves - cut.n_prompt) {
           const int r16 = lane & 15, g4 = lane >> 4;
           const long long pf = partial_floats(dm.G, D);
           int cursor = wd3.z;
@@ -460,7 +461,7 @@ k_attn_mfma(Ctx c, DecodeArgs a, const int* __restrict__ bt0, const int* __restr
 
         // ---- per-branch prompt blocks (prompt mode 1): block u is (request, kv head, chunk, branch); served before
         //      the own range, all waves at the same time, so that the branches' re-reads of a chunk hit in L2 -----
-        if (a.prompt_mode == 1 && wave_id >= n_waves - cut.n_prompt) {
+        if (prompt_mode == 1 && wave_id >= n_waves - cut.n_prompt) {
           const long long i = wave_id - (n_waves - cut.n_prompt);
           int cursor = tb.wave_row[n_waves + i];                       // live request index
           for (long long u = prompt_range_of_wave(i, cut.n_prompt); u < cut.n_blocks; u += cut.n_prompt) {

@@ -113,10 +113,14 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   // row, first partial slot, first work item (searched per wave)
   __shared__ int s_lreq[kPlanLdsLive], s_lcnt[kPlanLdsLive], s_lplen[kPlanLdsLive], s_lfirst[kPlanLdsLive],
       s_lpstart[kPlanLdsLive], s_item[kPlanLdsLive + 1];
+  __shared__ int s_w2;                          // prompt pages read with one read per row tile, summed over the live requests
+  __shared__ int s_it1, s_it2;                  // work items of the two ways to read the prompts (estimate)
   (void)lds;
+  if (tid == 0) { s_w2 = 0; s_it1 = 0; s_it2 = 0; }
   __syncthreads();                       // the caller's table updates are visible
   const int nA = scal[S_NACTIVE];
-  // w: weight of a live request with a prompt, on its first row: the prompt pages its work items read
+  // w: weight of a live request with a prompt, on its first row: the prompt pages its work items read when
+  // every branch reads them; w2: when every tile of 16 * kSharedBlocks query rows does
   int carry = 0, w_carry = 0, l_carry = 0;
   for (int base = 0; base < nA; base += kPlanThreads) {
     const int i = base + tid;
@@ -132,9 +136,10 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
         plen = tb.prefix_len[r];
         cnt = tb.nact[r];
         const int pp = ceil_div(plen, dm.pt);
-        // pages read for the request's prompt, per kv head: once per tile of 16 * kSharedBlocks query
-        // rows (shared rows), or once per branch
-        w = pc.prompt_mode == 2 ? pp * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : pp * cnt;
+        // pages read for the request's prompt, per kv head: once per branch, or once per tile of
+        // 16 * kSharedBlocks query rows (shared rows)
+        w = pp * cnt;
+        if (w > 0) atomicAdd(&s_w2, pp * ceil_div(cnt * dm.G, 16 * kSharedBlocks));
         tb.req_first[r] = i;
       }
     }
@@ -161,12 +166,45 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   const int n_waves = pc.n_wg * kAttnWaves;
   Cut cut;
   cut.u_own = (long long)carry * dm.Hkv;
-  const long long u_prompt = (long long)w_carry * dm.Hkv;   // prompt units of the step
+  __syncthreads();                       // s_w2 is complete
+  // How the prompts are read this step (unless the caller fixed it).  Per branch (1): every branch of a
+  // request reads every chunk of its prompt, all but the first read hitting in L2.  Per row tile (2): a chunk
+  // is read once for 16 query rows of the request's branches: 16 / G branches share a read.  Measured, the
+  // prompts' pages are cheap while the other half of the waves streams private pages (L2 hits: about a tenth
+  // of a private page's time) and the per-branch form, with its longer items, is the faster one by 3-12 us
+  // over a grid of shapes (2-32 branches per request, prompts of 256-2048 tokens, G = 5 and 7) - unless the
+  // tiles save a wave about 48 or more prompt pages, or the step has little private work to hide the prompts
+  // behind (then every prompt page saved counts).  cost = most prompt pages a wave reads, whole items.
+  const long long u1 = (long long)w_carry * dm.Hkv, u2 = (long long)s_w2 * dm.Hkv;
+  auto block_pages = [&](long long u) {
+    int pb = u > 0 ? (int)((u + n_waves - 1) / n_waves) : 1;
+    return ceil_div(pb < 1 ? 1 : pb, 4) * 4;              // whole rings of page buffers
+  };
+  int mode = pc.prompt_mode;
+  if (mode != 1 && mode != 2) {
+    mode = 1;
+    if (u1 > 0) {
+      const int pb1 = block_pages(u1), pb2 = block_pages(u2);
+      for (int k = tid; k < n_live; k += kPlanThreads) {
+        const bool in_lds = k < kPlanLdsLive;
+        const int r = in_lds ? s_lreq[k] : tb.live_req[k];
+        const int plen = in_lds ? s_lplen[k] : tb.prefix_len[r], cnt = in_lds ? s_lcnt[k] : tb.nact[r];
+        const int pp = ceil_div(plen, dm.pt);
+        atomicAdd(&s_it1, dm.Hkv * ceil_div(pp, pb1) * cnt);
+        atomicAdd(&s_it2, dm.Hkv * ceil_div(pp, pb2) * ceil_div(cnt * dm.G, 16 * kSharedBlocks));
+      }
+      __syncthreads();
+      const int it1 = s_it1, it2 = s_it2;
+      const long long cost1 = (long long)ceil_div(it1, n_waves) * pb1, cost2 = (long long)ceil_div(it2, n_waves) * pb2;
+      const long long own_per_wave = (cut.u_own + n_waves - 1) / n_waves;
+      if (cost1 - cost2 >= (own_per_wave < 48 ? own_per_wave : 48)) mode = 2;
+    }
+  }
+  const long long u_prompt = mode == 2 ? u2 : u1;           // prompt units of the step
   // every wave serves both its share of the prompt work items and its range of the own line
   cut.n_own = n_waves;
   cut.n_prompt = u_prompt > 0 ? n_waves : 0;
-  cut.pb = cut.n_prompt > 0 ? (int)((u_prompt + cut.n_prompt - 1) / cut.n_prompt) : 1;
-  cut.pb = ceil_div(cut.pb < 1 ? 1 : cut.pb, 4) * 4;        // whole rings of page buffers
+  cut.pb = block_pages(u_prompt);
   cut.n_blocks = 0;
   cut.n_pitems = 0;
   int per_wave = (int)((cut.u_own + cut.n_own - 1) / (cut.n_own > 0 ? cut.n_own : 1));
@@ -201,7 +239,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
           const int plen = in_lds ? s_lplen[k] : tb.prefix_len[r], cnt = in_lds ? s_lcnt[k] : tb.nact[r];
           const int nck = ceil_div(ceil_div(plen, dm.pt), cut.pb);
           blocks = dm.Hkv * nck * cnt;
-          items = pc.prompt_mode == 2 ? dm.Hkv * nck * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : blocks;
+          items = mode == 2 ? dm.Hkv * nck * ceil_div(cnt * dm.G, 16 * kSharedBlocks) : blocks;
         }
         int ex3[3], tot3[3];
         block_excl_scan3(blocks, items, 0, s_scan, ex3, tot3);
@@ -236,7 +274,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     const int j = i - tb.req_first[r], cnt = tb.nact[r];
     const int pp = ceil_div(tb.prefix_len[r], dm.pt);
     const int nck = pp > 0 ? ceil_div(pp, cut.pb) : 0;
-    const int tiles = pc.prompt_mode == 2 ? ((j + 1) * dm.G - 1) / (16 * kSharedBlocks) - (j * dm.G) / (16 * kSharedBlocks) + 1 : 1;
+    const int tiles = mode == 2 ? ((j + 1) * dm.G - 1) / (16 * kSharedBlocks) - (j * dm.G) / (16 * kSharedBlocks) + 1 : 1;
     const int c0 = nA <= kPlanLdsRows ? s_cum[i] : tb.page_cum[i], c1 = nA <= kPlanLdsRows ? s_cum[i + 1] : tb.page_cum[i + 1];
     int4* rd = (int4*)(tb.row_desc + 8LL * i);
     rd[0] = make_int4(c0, c1 - c0, i < kPlanLdsRows ? s_seq[i] : tb.seq_len[i], nck * tiles);
@@ -307,6 +345,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     scal[S_D_PB] = cut.pb;
     scal[S_D_NBLOCKS] = cut.n_blocks;
     scal[S_D_NPITEMS] = cut.n_pitems;
+    scal[S_D_PMODE] = mode;
     scal[S_D_NLIVE] = n_live;
     scal[S_D_NWG] = pc.n_wg;
   }

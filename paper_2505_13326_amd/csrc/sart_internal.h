@@ -50,6 +50,7 @@ enum Scalar {
   S_D_PB,         // pages per prompt block
   S_D_NBLOCKS,    // prompt blocks (partial slots of the prompts)
   S_D_NPITEMS,    // prompt work items of the streaming phase (= blocks unless rows are shared)
+  S_D_PMODE,      // how the step's prompts are read: 1 per branch, 2 per tile of 16 query rows (chosen by the plan)
   S_ANY_FORK,     // some branch was split since the cache was created: branch pages may be shared
   S_COUNT = 32
 };
@@ -237,7 +238,6 @@ struct DecodeArgs {
   int n_rows;
   float scale_log2;     // scale * log2(e)
   int n_wg;             // persistent attention workgroups (the plan's)
-  int prompt_mode;      // the plan's prompt mode (1 or 2)
   float* partials;      // scratch
   long long partial_cap; // partial slots available
   int* seg_count;       // scratch: arrival counters of the in-kernel merge, one per (row, kv head), zero between kernels
