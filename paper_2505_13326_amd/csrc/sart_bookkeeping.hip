@@ -63,7 +63,7 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
   const int tid = threadIdx.x;
   const int nA = scal[S_NACTIVE];
   const int top = scal[S_FREETOP];
-  if (tid == 0) { s_err = 0x7fffffff; scal[S_APPENDOK] = 0; }
+  if (tid == 0) { s_err = 0x7fffffff; scal[S_APPENDOK] = 0; scal[S_PLAN_DEFERRED] = 0; }
   __syncthreads();
   if (!a.ids && a.n_seqs >= 0 && a.n_seqs != nA) {
     if (tid == 0) record_error(scal, SART_E_INVALID, a.call_seq);
@@ -108,8 +108,11 @@ k_append_plan(Ctx c, PlanCfg pc, AppendArgs a) {
       scal[S_FREETOP] = top - total;
       scal[S_CALLOK] = 1;
       scal[S_APPENDOK] = 1;
+      if (a.defer_plan) scal[S_PLAN_DEFERRED] = 1;
     }
-    refresh_decode_plan(c, pc, lds);
+    // the decode plan of the lengthened rows: here, or (decode step) by one more workgroup of the kernel that
+    // writes the rows, so that the two run side by side instead of one after the other
+    if (!a.defer_plan) refresh_decode_plan(c, pc, lds);
     return;
   }
   // pass 1: validate, compute pages needed, stash id / start length
@@ -230,21 +233,13 @@ __device__ inline unsigned e4m3_code_of_quotient(float x, float scale) {
   return (__double_as_longlong(t) < 0 ? 0x80u : 0u) | code;
 }
 
-// One wave copies one (token, kv head) row of K and V into its page slot.
+// One wave copies one (token, kv head) row of K and V into its page slot; the calling kernel's waves are
+// numbered wave = 0 .. nwaves - 1.
 template <typename T>
-__global__ void __launch_bounds__(256)
-k_append_write(Ctx c, AppendArgs a) {
+__device__ inline void append_write_rows(const Ctx& c, const AppendArgs& a, long long wave, long long nwaves) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
-  if (!tb.scal[a.write_only ? S_APPENDOK : S_CALLOK]) {
-    // a write to a layer > 0 whose layer-0 append failed on the device, or after rows moved (a finish or
-    // prune since): nothing is written, and the caller is told (sticky)
-    if (a.write_only && blockIdx.x == 0 && threadIdx.x == 0) record_error(tb.scal, SART_E_STATE, a.call_seq);
-    return;
-  }
   const int lane = threadIdx.x & 63;
-  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
   // n_seqs < 0: one row per active branch (a branch append leaves the active list as it is)
   const long long units = (a.n_seqs < 0 ? (long long)tb.scal[S_NACTIVE] : a.total_rows) * dm.Hkv;
   const int* bt = tb.bt[tb.scal[S_BTSEL]];
@@ -295,10 +290,51 @@ k_append_write(Ctx c, AppendArgs a) {
   }
 }
 
-void launch_append(const Ctx& c, const PlanCfg& pc, const AppendArgs& a, hipStream_t s) {
+template <typename T>
+__global__ void __launch_bounds__(256)
+k_append_write(Ctx c, AppendArgs a) {
+  const Tables& tb = c.tb;
+  if (!tb.scal[a.write_only ? S_APPENDOK : S_CALLOK]) {
+    // a write to a layer > 0 whose layer-0 append failed on the device, or after rows moved (a finish or
+    // prune since): nothing is written, and the caller is told (sticky)
+    if (a.write_only && blockIdx.x == 0 && threadIdx.x == 0) record_error(tb.scal, SART_E_STATE, a.call_seq);
+    return;
+  }
+  append_write_rows<T>(c, a, ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6, ((long long)gridDim.x * blockDim.x) >> 6);
+}
+
+// The decode step's form: the last workgroup computes the decode plan the append plan left to it, the others
+// write the rows - neither needs the other's result.
+template <typename T>
+__global__ void __launch_bounds__(kPlanThreads)
+k_append_write_and_plan(Ctx c, PlanCfg pc, AppendArgs a) {
+  const Tables& tb = c.tb;
+  if (!tb.scal[S_CALLOK]) return;
+  if (blockIdx.x == gridDim.x - 1) {
+    __shared__ int lds[17];
+    if (tb.scal[S_PLAN_DEFERRED]) refresh_decode_plan(c, pc, lds);
+    return;
+  }
+  append_write_rows<T>(c, a, ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6,
+                       ((long long)(gridDim.x - 1) * blockDim.x) >> 6);
+}
+
+void launch_append(const Ctx& c, const PlanCfg& pc, const AppendArgs& a_in, hipStream_t s) {
+  AppendArgs a = a_in;
+  // the decode step's append (one token for every active row, no lists): plan and writes side by side
+  a.defer_plan = !a.write_only && a.kind == SART_SEQ_BRANCH && !a.ids && !a.ntok && a.total_rows > 0;
   if (!a.write_only) hipLaunchKernelGGL(k_append_plan, dim3(1), dim3(kPlanThreads), 0, s, c, pc, a);
   if (a.total_rows <= 0) return;
   const long long units = a.total_rows * c.dm.Hkv;
+  if (a.defer_plan) {
+    long long wb = (units + 15) / 16;                    // 16 waves per workgroup
+    if (wb > 2048) wb = 2048;
+    if (c.dm.dtype == SART_F32)
+      hipLaunchKernelGGL(k_append_write_and_plan<float>, dim3((unsigned)wb + 1), dim3(kPlanThreads), 0, s, c, pc, a);
+    else
+      hipLaunchKernelGGL(k_append_write_and_plan<uint16_t>, dim3((unsigned)wb + 1), dim3(kPlanThreads), 0, s, c, pc, a);
+    return;
+  }
   long long blocks = (units + 3) / 4;
   if (blocks > 8192) blocks = 8192;
   if (c.dm.dtype == SART_F32)

@@ -51,6 +51,7 @@ enum Scalar {
   S_D_NBLOCKS,    // prompt blocks (partial slots of the prompts)
   S_D_NPITEMS,    // prompt work items of the streaming phase (= blocks unless rows are shared)
   S_D_PMODE,      // how the step's prompts are read: 1 per branch, 2 per tile of 16 query rows (chosen by the plan)
+  S_PLAN_DEFERRED,// the append plan left the decode plan to the write kernel's extra workgroup
   S_ANY_FORK,     // some branch was split since the cache was created: branch pages may be shared
   S_COUNT = 32
 };
@@ -210,6 +211,7 @@ struct AppendArgs {
   const void* v;
   int call_seq;
   int write_only;      // layer > 0: write the rows of the last layer-0 append again, into this layer's pool
+  int defer_plan;      // decode step's append: the write kernel's extra workgroup computes the decode plan, beside the writes
   int by_handle;       // all-active form: the row of k and v that belongs to a branch is its handle, not its active index
 };
 void launch_append(const Ctx& c, const PlanCfg& pc, const AppendArgs& a, hipStream_t s);
