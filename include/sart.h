@@ -336,7 +336,8 @@ sart_status sart_sync_status(sart_cache* cache);
  *   n_active        [1]
  *   active_handles  [max_requests*Nb]   first n_active valid, rest -1
  *   seq_lens        [max_requests*Nb]   private tokens, active order, rest 0
- *   block_tables    [max_requests*Nb, max_pages_per_branch]  active order, -1 padded
+ *   block_tables    [max_requests*Nb, max_pages_per_branch]  active order, -1 padded (after sart_fork_branches
+ *                   rows of one request may list the same page, at the same index)
  *   free_stack      [num_pages]         first free_top valid (top = last), rest -1
  *   free_top        [1]
  *   prefix_tables   [max_requests, max_prefix_pages]  -1 padded / released
