@@ -303,19 +303,19 @@ k_append_write(Ctx c, AppendArgs a) {
   append_write_rows<T>(c, a, ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6, ((long long)gridDim.x * blockDim.x) >> 6);
 }
 
-// The decode step's form: the last workgroup computes the decode plan the append plan left to it, the others
+// The decode step's form: the first workgroup computes the decode plan the append plan left to it, the others
 // write the rows - neither needs the other's result.
 template <typename T>
 __global__ void __launch_bounds__(kPlanThreads)
 k_append_write_and_plan(Ctx c, PlanCfg pc, AppendArgs a) {
   const Tables& tb = c.tb;
   if (!tb.scal[S_CALLOK]) return;
-  if (blockIdx.x == gridDim.x - 1) {
+  if (blockIdx.x == 0) {                          // dispatched first: it is the longer of the two jobs
     __shared__ int lds[17];
     if (tb.scal[S_PLAN_DEFERRED]) refresh_decode_plan(c, pc, lds);
     return;
   }
-  append_write_rows<T>(c, a, ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6,
+  append_write_rows<T>(c, a, ((long long)(blockIdx.x - 1) * blockDim.x + threadIdx.x) >> 6,
                        ((long long)(gridDim.x - 1) * blockDim.x) >> 6);
 }
 

@@ -122,11 +122,13 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   // w: weight of a live request with a prompt, on its first row: the prompt pages its work items read when
   // every branch reads them; w2: when every tile of 16 * kSharedBlocks query rows does
   int carry = 0, w_carry = 0, l_carry = 0;
+  int my_handle = -1, my_live = -1;      // of active row tid (the first chunk of rows): its branch, the live index its request would have
   for (int base = 0; base < nA; base += kPlanThreads) {
     const int i = base + tid;
     int np = 0, w = 0, first = 0, r = 0, cnt = 0, plen = 0;
     if (i < nA) {
       const int b = tb.active[i];
+      if (base == 0) my_handle = b;
       r = b / dm.Nb;
       first = i == 0 || tb.active[i - 1] / dm.Nb != r;
       const int len = tb.seq_len[i];
@@ -154,6 +156,8 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       tb.live_req[k] = r;
       if (k < kPlanLdsLive) { s_lreq[k] = r; s_lcnt[k] = cnt; s_lplen[k] = plen; s_lfirst[k] = i; }
     }
+    // a request's rows are neighbours: the last live request that starts at or before row i is row i's own, if it has a prompt
+    if (base == 0) my_live = l_carry + ex3[2] + (w > 0) - 1;
     carry += tot3[0];
     w_carry += tot3[1];
     l_carry += tot3[2];
@@ -270,15 +274,27 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   //   [4] first prompt partial slot of the row, relative to the prompts' slots: chunk ck of kv head h is
   //       slot [4] + (h * [6] + ck) * [5]   [5] live branches of the request   [6] prompt chunks   [7] the branch's handle
   for (int i = tid; i < nA; i += kPlanThreads) {
-    const int handle = tb.active[i], r = handle / dm.Nb;
-    const int j = i - tb.req_first[r], cnt = tb.nact[r];
-    const int pp = ceil_div(tb.prefix_len[r], dm.pt);
+    int handle, r, j, cnt, pp, pstart;
+    if (i == tid && my_live < kPlanLdsLive) {
+      // the first chunk of rows, from registers and the LDS copies: no dependent trips to memory
+      handle = my_handle; r = handle / dm.Nb;
+      const bool live = my_live >= 0 && s_lreq[my_live] == r;
+      j = live ? i - s_lfirst[my_live] : 0;
+      cnt = live ? s_lcnt[my_live] : 0;
+      pp = live ? ceil_div(s_lplen[my_live], dm.pt) : 0;
+      pstart = live ? s_lpstart[my_live] : 0;
+    } else {
+      handle = tb.active[i]; r = handle / dm.Nb;
+      j = i - tb.req_first[r]; cnt = tb.nact[r];
+      pp = ceil_div(tb.prefix_len[r], dm.pt);
+      pstart = tb.req_pstart[r];
+    }
     const int nck = pp > 0 ? ceil_div(pp, cut.pb) : 0;
     const int tiles = mode == 2 ? ((j + 1) * dm.G - 1) / (16 * kSharedBlocks) - (j * dm.G) / (16 * kSharedBlocks) + 1 : 1;
     const int c0 = nA <= kPlanLdsRows ? s_cum[i] : tb.page_cum[i], c1 = nA <= kPlanLdsRows ? s_cum[i + 1] : tb.page_cum[i + 1];
     int4* rd = (int4*)(tb.row_desc + 8LL * i);
     rd[0] = make_int4(c0, c1 - c0, i < kPlanLdsRows ? s_seq[i] : tb.seq_len[i], nck * tiles);
-    rd[1] = make_int4(nck ? tb.req_pstart[r] + j : 0, cnt, nck, handle);
+    rd[1] = make_int4(nck ? pstart + j : 0, cnt, nck, handle);
   }
   // Where every wave starts.  wave_row (generic kernel): active row of an own
   // range's first unit and, after those entries, the live request of a prompt
