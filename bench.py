@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM traffic of the dominant kernel per launch: NOT measured in this run but copied from the rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE summary under profiles/ (k_attn_mfma_hbm_traffic_and_sq_counters.md), which states the
 # commands; None = not measured for that workload
-MEASURED_TRAFFIC_BYTES = {"cfg2": 1447136256, "cfg4": 10912237773}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 1450971988, "cfg4": 10911881798}
 
 
 def _request_arrays(wl, cfg, r, L):
