@@ -141,7 +141,6 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
         // pages read for the request's prompt, per kv head: once per branch, or once per tile of
         // 16 * kSharedBlocks query rows (shared rows)
         w = pp * cnt;
-        if (w > 0) atomicAdd(&s_w2, pp * ceil_div(cnt * dm.G, 16 * kSharedBlocks));
         tb.req_first[r] = i;
       }
     }
@@ -170,7 +169,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   const int n_waves = pc.n_wg * kAttnWaves;
   Cut cut;
   cut.u_own = (long long)carry * dm.Hkv;
-  __syncthreads();                       // s_w2 is complete
+  __syncthreads();
   // How the prompts are read this step (unless the caller fixed it).  Per branch (1): every branch of a
   // request reads every chunk of its prompt, all but the first read hitting in L2.  Per row tile (2): a chunk
   // is read once for 16 query rows of the request's branches: 16 / G branches share a read.  Measured, the
@@ -179,28 +178,45 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   // over a grid of shapes (2-32 branches per request, prompts of 256-2048 tokens, G = 5 and 7) - unless the
   // tiles save a wave about 48 or more prompt pages, or the step has little private work to hide the prompts
   // behind (then every prompt page saved counts).  cost = most prompt pages a wave reads, whole items.
-  const long long u1 = (long long)w_carry * dm.Hkv, u2 = (long long)s_w2 * dm.Hkv;
+  // sums over the live requests (their fields are in LDS for the first kPlanLdsLive): within the wave first,
+  // then one LDS atomic per wave (many lanes adding to one LDS word take tens of cycles each)
+  auto live_sums = [&](auto&& term, int* s_a, int* s_b) {
+    int a1 = 0, a2 = 0;
+    for (int k = tid; k < n_live; k += kPlanThreads) {
+      const bool in_lds = k < kPlanLdsLive;
+      const int r = in_lds ? s_lreq[k] : tb.live_req[k];
+      const int plen = in_lds ? s_lplen[k] : tb.prefix_len[r], cnt = in_lds ? s_lcnt[k] : tb.nact[r];
+      term(ceil_div(plen, dm.pt), cnt, a1, a2);
+    }
+    if (tid < ((n_live + 63) & ~63)) {
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) { a1 += __shfl_xor(a1, off, 64); a2 += __shfl_xor(a2, off, 64); }
+      if ((tid & 63) == 0) { atomicAdd(s_a, a1); if (s_b) atomicAdd(s_b, a2); }
+    }
+    __syncthreads();
+  };
+  const long long u1 = (long long)w_carry * dm.Hkv;
   auto block_pages = [&](long long u) {
-    int pb = u > 0 ? (int)((u + n_waves - 1) / n_waves) : 1;
+    int pb = u > 0 ? (int)div_nn(u + n_waves - 1, n_waves) : 1;
     return ceil_div(pb < 1 ? 1 : pb, 4) * 4;              // whole rings of page buffers
   };
   int mode = pc.prompt_mode;
+  long long u2 = 0;
+  if (mode != 1 && u1 > 0) {
+    live_sums([&](int pp, int cnt, int& a1, int&) { a1 += pp * ceil_div(cnt * dm.G, 16 * kSharedBlocks); }, &s_w2, nullptr);
+    u2 = (long long)__builtin_amdgcn_readfirstlane(s_w2) * dm.Hkv;
+  }
   if (mode != 1 && mode != 2) {
     mode = 1;
     if (u1 > 0) {
       const int pb1 = block_pages(u1), pb2 = block_pages(u2);
-      for (int k = tid; k < n_live; k += kPlanThreads) {
-        const bool in_lds = k < kPlanLdsLive;
-        const int r = in_lds ? s_lreq[k] : tb.live_req[k];
-        const int plen = in_lds ? s_lplen[k] : tb.prefix_len[r], cnt = in_lds ? s_lcnt[k] : tb.nact[r];
-        const int pp = ceil_div(plen, dm.pt);
-        atomicAdd(&s_it1, dm.Hkv * ceil_div(pp, pb1) * cnt);
-        atomicAdd(&s_it2, dm.Hkv * ceil_div(pp, pb2) * ceil_div(cnt * dm.G, 16 * kSharedBlocks));
-      }
-      __syncthreads();
-      const int it1 = s_it1, it2 = s_it2;
+      live_sums([&](int pp, int cnt, int& a1, int& a2) {
+        a1 += dm.Hkv * ceil_div(pp, pb1) * cnt;
+        a2 += dm.Hkv * ceil_div(pp, pb2) * ceil_div(cnt * dm.G, 16 * kSharedBlocks);
+      }, &s_it1, &s_it2);
+      const int it1 = __builtin_amdgcn_readfirstlane(s_it1), it2 = __builtin_amdgcn_readfirstlane(s_it2);   // uniform, and known to be so
       const long long cost1 = (long long)ceil_div(it1, n_waves) * pb1, cost2 = (long long)ceil_div(it2, n_waves) * pb2;
-      const long long own_per_wave = (cut.u_own + n_waves - 1) / n_waves;
+      const long long own_per_wave = div_nn(cut.u_own + n_waves - 1, n_waves);
       if (cost1 - cost2 >= (own_per_wave < 48 ? own_per_wave : 48)) mode = 2;
     }
   }
@@ -211,7 +227,7 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   cut.pb = block_pages(u_prompt);
   cut.n_blocks = 0;
   cut.n_pitems = 0;
-  int per_wave = (int)((cut.u_own + cut.n_own - 1) / (cut.n_own > 0 ? cut.n_own : 1));
+  int per_wave = (int)div_nn(cut.u_own + cut.n_own - 1, cut.n_own > 0 ? cut.n_own : 1);
   if (per_wave < 1) per_wave = 1;
   // even / odd workgroups: pe + po = 2 * per_wave, po >= 1; an odd number of
   // own workgroups leaves the last one without a partner, so no skew then
