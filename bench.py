@@ -46,6 +46,34 @@ def _request_arrays(wl, cfg, r, L):
     return r, pk, pv, ids, ns, np.concatenate([x[0] for x in kv]), np.concatenate([x[1] for x in kv])
 
 
+def mfma_probe_rates(sart, np, torch, shapes=((0, 512),), seconds=0.15):
+    """What the matrix cores sustain on this machine on nothing but bf16 products from registers, for operands that
+    are zero and operands drawn like the prompts' K/V (standard normal, rounded to bf16): the clock follows the
+    power drawn and the power follows the operand values.  shapes: (product shape of sart_mfma_probe,
+    workgroups) pairs; each is run for about `seconds` and the rate of the last launch is reported."""
+    rng = np.random.default_rng(20250513)
+    data = {"zeros": np.zeros(8192, np.float32), "normal_bf16": rng.standard_normal(8192).astype(np.float32)}
+    rates = {}
+    for shape, n_wg in shapes:
+        sink = torch.empty(n_wg * 256, dtype=torch.float32, device="cuda")
+        for name, host in data.items():
+            ops = torch.from_numpy(host).to(torch.bfloat16).cuda()
+            rounds, left, rate = 2000, seconds * 1e3, 0.0
+            while left > 0:
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                ev[0].record()
+                sart.mfma_probe(ops, rounds, n_wg, sink, shape=shape)
+                ev[1].record()
+                torch.cuda.synchronize()
+                ms = ev[0].elapsed_time(ev[1])
+                rate = n_wg * 4 * rounds * 524288.0 / (ms * 1e-3) / 1e12
+                left -= ms
+                rounds = max(2000, int(rounds * 25.0 / max(ms, 1e-3)))       # launches of about 25 ms
+            key = name if len(shapes) == 1 else f"{('32x32x16', '16x16x32')[shape]}_{n_wg // 256}_waves_per_simd_{name}"
+            rates[key] = round(rate, 1)
+    return rates
+
+
 def bench_prefill(args, cfg, sart, wl, np, torch):
     """Prefill attention (Algorithm 1, Prefill) over the prompts of a configuration: one library call attends
     every request's whole prompt (causal).  The prompts' K/V are appended beforehand (not timed: they are the
@@ -86,10 +114,14 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
     assert cache.sync_status() == 0
     flops = R * 4.0 * cfg.head_dim * cfg.n_q_heads * P * (P + 1) / 2
     kv_bytes = R * P * cfg.token_bytes
-    roofline = {"bound": "mfma", "kernel": "k_prefill_x32" if cfg.dtype == "bf16" and args.kv_dtype != "fp8" else "k_prefill_mfma", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
+    roofline = {"bound": "mfma", "kernel": "k_prefill_b16" if cfg.dtype == "bf16" and args.kv_dtype != "fp8" else "k_prefill_mfma", "achieved": round(flops / (k_ms * 1e-3) / 1e12, 2),
                 "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / (k_ms * 1e-3) / 1e12 / 2500.0, 4), "traffic": None,
                 "algorithmic_flops_per_launch": int(flops), "kernel_ms_avg": round(k_ms, 4),
                 "note": "events on the call's stream around all timed calls (validation kernel included)"}
+    if cfg.dtype == "bf16" and args.kv_dtype != "fp8":
+        probe = mfma_probe_rates(sart, np, torch, shapes=((1, 512),))     # the kernel's own product shape and waves per SIMD
+        roofline["mfma_probe_tflops"] = probe
+        roofline["frac_of_mfma_probe"] = round(roofline["achieved"] / probe["normal_bf16"], 4)
     cpu = None
     if not args.no_cpu_baseline:
         import oracle as orc
@@ -499,7 +531,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="all", choices=["all", "cfg2", "cfg3", "cfg4", "cfg5", "copy", "probe", "prefill4", "prefill5"],
+    ap.add_argument("--workload", default="all", choices=["all", "cfg2", "cfg3", "cfg4", "cfg5", "copy", "probe", "mfma_probe", "prefill4", "prefill5"],
                     help="all = config 4 (the headline) with configs 2 and 3 nested in the same line; copy = a plain 1 GiB device copy, the known-size kernel that calibrates the "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters; prefillN = prefill attention over the prompts "
                          "of config N")
@@ -553,6 +585,11 @@ def main():
         return
     if args.workload == "probe":
         return bench_probe_sweep(args, sart, np, torch)
+    if args.workload == "mfma_probe":
+        print(json.dumps({"metric": "bf16 matrix-core products from registers and nothing else, by product shape and waves per SIMD",
+                          "unit": "TFLOP/s", "value": mfma_probe_rates(sart, np, torch, shapes=((0, 512), (0, 256), (1, 512), (1, 256)), seconds=0.8),
+                          "peak": 2500.0}))
+        return
     if args.workload == "all":
         # the headline: config 4 (largest single-GPU configuration), with config 2 and the config 3 trace nested
         line = bench_decode(args, wl.CONFIGS[4], "cfg4", sart, wl, np, torch, args.steps, args.warmup)

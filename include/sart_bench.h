@@ -43,6 +43,18 @@ sart_status sart_read_probe(const void* buf, size_t bytes, const int32_t* chunk_
 sart_status sart_read_probe_shaped(const void* buf, size_t bytes, const int32_t* chunk_order, int32_t n_workgroups,
                                    int32_t depth, int32_t flavour, int32_t interleave, void* stream);
 
+/* Measurement aid, no part of the method: n_workgroups of 4 waves (a CU takes two of them: 256 workgroups =
+ * one wave per SIMD on MI355X, 512 = two) each run `rounds` rounds of 524288 flops of bf16 matrix-core products
+ * on operands held in registers, and nothing else.  shape 0: 16 products 32x32x16 per round, 8 into one
+ * accumulator and 8 into four others (the prefill kernel's own sequence of products); shape 1: 32 products
+ * 16x16x32 into 8 accumulators in turn.  A wave holds 8 A and 8 B operands per lane, read once from
+ * `operands` (DEVICE, 16 KiB: operand i of lane l at byte (i * 64 + l) * 16, A operands first; the same for
+ * every wave).  sink (DEVICE, n_workgroups * 256 floats) receives a sum per lane.  Asynchronous on `stream`;
+ * the caller times it.  The rate depends on the operand values (zeros draw less power, and the clock follows
+ * the power): bench.py reports the prefill kernel's rate against this one's on the same box. */
+sart_status sart_mfma_probe(const void* operands, int64_t rounds, int32_t n_workgroups, int32_t shape, float* sink,
+                            void* stream);
+
 /* Tuning knobs of the decode launch (defaults are chosen for MI355X):
  *   n_workgroups   persistent attention grid of 4-wave workgroups (<= 0: one per
  *                  CU);

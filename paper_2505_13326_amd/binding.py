@@ -78,6 +78,7 @@ _SIGNATURES = {
     "sart_set_merge_mode": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_set_prompt_stagger": (C.c_int, [C.c_void_p, C.c_int32]),
     "sart_read_probe": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+    "sart_mfma_probe": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "sart_read_probe_shaped": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                          C.c_void_p]),
     "sart_last_error": (C.c_char_p, []),
@@ -117,6 +118,16 @@ def read_probe(buf, chunk_order=None, stream=None, shape=None):
     else:
         rc = lib.sart_read_probe_shaped(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), order,
                                         *[int(x) for x in shape], _stream_handle(stream))
+    if rc != OK:
+        raise SartError(rc, lib.sart_last_error().decode())
+
+
+def mfma_probe(operands, rounds, n_workgroups, sink, shape=0, stream=None):
+    """sart_mfma_probe over torch device tensors (measurement aid): operands 16 KiB, sink n_workgroups * 256 floats."""
+    lib = load_library()
+    assert operands.numel() * operands.element_size() >= 16384 and sink.numel() >= n_workgroups * 256 and sink.element_size() == 4
+    rc = lib.sart_mfma_probe(C.c_void_p(operands.data_ptr()), int(rounds), int(n_workgroups), int(shape), C.c_void_p(sink.data_ptr()),
+                             _stream_handle(stream))
     if rc != OK:
         raise SartError(rc, lib.sart_last_error().decode())
 

@@ -489,16 +489,16 @@ sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs,
   const Dims& dm = c->ctx.dm;
   if (n_seqs < 0 || n_seqs > dm.max_req || n_seqs > 65535) return fail(SART_E_INVALID, "n_seqs out of range (at most max_requests and 65535)");
   if (n_seqs > 0 && (!request_ids || !n_q)) return fail(SART_E_INVALID, "null request_ids or n_q");
-  long long total = 0, max_tiles = 0;
-  const int rows_per_tile = kPfTileRows;                    // the matrix-core kernel's workgroup tile
+  long long total = 0, max_nq = 0;
   for (int i = 0; i < n_seqs; ++i) {
     if (request_ids[i] < 0 || request_ids[i] >= dm.max_req)
       return fail(SART_E_INVALID, "request %d out of range at %d", request_ids[i], i);
     if (n_q[i] < 0 || n_q[i] > dm.max_pp * dm.pt) return fail(SART_E_INVALID, "n_q out of range at %d", i);
     total += n_q[i];
-    const long long tiles = (long long)dm.Hkv * (((long long)n_q[i] * dm.G + rows_per_tile - 1) / rows_per_tile);
-    if (tiles > max_tiles) max_tiles = tiles;
+    if (n_q[i] > max_nq) max_nq = n_q[i];
   }
+  const int rows_per_tile = prefill_tile_rows(dm, max_nq * dm.G);     // the matrix-core kernel's workgroup tile
+  const long long max_tiles = (long long)dm.Hkv * ((max_nq * dm.G + rows_per_tile - 1) / rows_per_tile);
   if (total > 0x7fffffffLL / dm.Hq || max_tiles > 0x7fffffffLL) return fail(SART_E_INVALID, "too many queries in one call");
   if (total > 0 && (!q || !out)) return fail(SART_E_INVALID, "null q or out");
   if (n_seqs == 0) return SART_OK;
@@ -512,7 +512,7 @@ sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs,
   a.n_seqs = n_seqs; a.q = q; a.out = out; a.call_seq = ++c->call_seq;
   a.scale_log2 = scale * 1.44269504088896340736f * c->k_scale;
   a.v_scale = c->v_scale;
-  a.total_q = (int)total; a.max_tiles = (int)max_tiles;
+  a.total_q = (int)total; a.max_tiles = (int)max_tiles; a.tile_rows = rows_per_tile;
   int* hbuf = s->host;
   int qo = 0;
   for (int i = 0; i < n_seqs; ++i) {
@@ -744,6 +744,16 @@ sart_status sart_read_probe_shaped(const void* buf, size_t bytes, const int32_t*
   if (flavour < 0 || flavour > 1) return fail(SART_E_INVALID, "probe flavour must be 0 (plain) or 1 (non-temporal)");
   launch_read_probe(buf, (long long)(bytes / 8192), chunk_order, n_workgroups, depth, flavour, interleave != 0,
                     (hipStream_t)stream);
+  HIP_TRY(hipGetLastError());
+  return SART_OK;
+}
+
+sart_status sart_mfma_probe(const void* operands, int64_t rounds, int32_t n_workgroups, int32_t shape, float* sink, void* stream) {
+  if (!operands || !sink) return fail(SART_E_INVALID, "the matrix-core probe needs its operand and result buffers");
+  if (rounds < 1 || rounds > (1ll << 30)) return fail(SART_E_INVALID, "probe rounds out of range");
+  if (n_workgroups < 1 || n_workgroups > 65536) return fail(SART_E_INVALID, "probe workgroups out of range");
+  if (shape < 0 || shape > 1) return fail(SART_E_INVALID, "probe shape must be 0 (32x32x16) or 1 (16x16x32)");
+  launch_mfma_probe(operands, rounds, n_workgroups, shape, sink, (hipStream_t)stream);
   HIP_TRY(hipGetLastError());
   return SART_OK;
 }

@@ -275,12 +275,15 @@ struct PrefillArgs {
   float v_scale;          // 8-bit float caches: what the output is multiplied by (1 otherwise)
   int call_seq;
   int max_tiles;          // workgroup tiles of the listed sequence that has most (matrix-core kernels: grid x)
+  int tile_rows;          // rows of a workgroup tile (prefill_tile_rows)
   int total_q;
 };
 void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s);
+int prefill_tile_rows(const Dims& dm, long long max_rows);   // rows of one kv head per workgroup tile of the prefill kernel, for a call whose longest sequence has max_rows rows per kv head
 
 void launch_init_tables(const Ctx& c, const int* free_order_dev, hipStream_t s);
 void launch_read_probe(const void* buf, long long n_chunks, const int* order, int n_workgroups, int depth, int flavour,
                        int interleave, hipStream_t s);
+void launch_mfma_probe(const void* operands, long long iters, int n_workgroups, int shape, float* sink, hipStream_t s);
 
 }  // namespace sart

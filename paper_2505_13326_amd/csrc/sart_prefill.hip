@@ -16,9 +16,8 @@
 // rows' positions and mask scores only on the pairs that straddle them.  No
 // split over the sequence: one wave sees a row's whole context, so there is no
 // merge.  Two kernels: k_prefill_mfma (8-bit float caches: every wave loads its
-// page pairs into registers and expands them there, 16x16x32 products) and
-// k_prefill_x32 (bf16 caches: pairs staged once per workgroup in LDS, 32x32x16
-// products, 32 rows per wave).
+// page pairs into registers and expands them there) and k_prefill_b16 (bf16
+// caches: pairs staged once per workgroup in LDS, two 16-row blocks per wave).
 #include <type_traits>
 
 #include "sart_attn_tile.h"
@@ -66,10 +65,10 @@ __device__ inline int last_le(const int* v, int n, int x) {
 // tile x of sequence y, or nothing when that sequence has fewer tiles.  A tile is kPfTileRows rows of one kv
 // head; a sequence's later rows (longer contexts) come first.
 struct PfTile { int req, nq, plen, h, rt; long long q_row0; };
-__device__ inline bool prefill_tile(const Dims& dm, const Tables& tb, PfTile& t) {
+__device__ inline bool prefill_tile(const Dims& dm, const Tables& tb, int tile_rows, PfTile& t) {
   const int4 sq = ((const int4*)tb.pf_seq)[blockIdx.y];
   t.req = sq.x; t.nq = sq.y; t.q_row0 = sq.z; t.plen = sq.w;
-  const int tiles_per_head = ceil_div(t.nq * dm.G, kPfTileRows);
+  const int tiles_per_head = ceil_div(t.nq * dm.G, tile_rows);
   const int local = blockIdx.x;
   if (local >= tiles_per_head * dm.Hkv) return false;
   // Neighbouring blocks take the kv heads in turn: workgroups are dealt to the 8 XCDs round-robin, so with 8
@@ -81,7 +80,7 @@ __device__ inline bool prefill_tile(const Dims& dm, const Tables& tb, PfTile& t)
   return true;
 }
 
-// (Launched for 8-bit float caches; bf16 caches take k_prefill_x32 below.)
+// (Launched for 8-bit float caches; bf16 caches take k_prefill_b16 below.)
 template <int D, bool FP8>
 __global__ void __launch_bounds__(kAttnThreads, 2)
 k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
@@ -94,7 +93,7 @@ k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r16 = lane & 15, g4 = lane >> 4;
   PfTile pt;
-  if (!prefill_tile(dm, tb, pt)) return;
+  if (!prefill_tile(dm, tb, a.tile_rows, pt)) return;
   const int req = pt.req, nq = pt.nq, plen = pt.plen, h = pt.h, rt = pt.rt;
   const int n_rows = nq * dm.G;
   const int row_w0 = rt * kPfRowsPerWg + wv * kPfRowsPerWave;
@@ -227,47 +226,39 @@ k_prefill_mfma(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   }
 }
 
-// bf16 caches: K and V staged in LDS once per workgroup, 32 query rows per wave on the 32x32x16 product, so
-// that an operand read from LDS feeds twice the arithmetic of the 16x16x32 product, two waves per SIMD with
-// the whole tile state in registers.
-//   S^T (32 tokens x 32 rows) = K (32 x 16 per step) Q^T : A = the pair's K as stored (lane l: token l % 32,
-//        8 head-dim elements (2 s + l / 32) * 8 ..), B = Q^T from registers, D / 16 steps;
-//   O^T (32 of d x 32 rows) += V^T P^T per 32-column block of d and per page of the pair: the contraction
-//        index (l / 32) * 8 + e of page t stands for token 16 t + 8 (e / 4) + 4 (l / 32) + e % 4, which is
-//        where the score accumulator holds that token's weight (element 8 t + e of the lane), so P^T is the
-//        lane's own sixteen weights, converted and packed, and no data crosses lanes; the loader writes V
-//        into LDS in that operand order (two 8-byte pieces per stored chunk).
-// The 128 rows of a tile go to 4 waves; a page pair is fetched once per workgroup into a ring of three LDS
-// stages (one barrier per pair).  Softmax against a lagging reference (the reference is raised, and the accumulators rescaled, only when some score exceeds it by 2^kLag; until then a weight may exceed 1, which is harmless in fp32 and bf16, and l and O / l do not depend on the reference): a lane
-// holds half of its query row's tokens, the other half sits 32 lanes away; the denominator is summed from
-// the bf16-rounded weights with the packed dot product (v_dot2c_f32_bf16), per half, and joined at the end.
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
-__device__ inline float max_with_partner32(float x) {       // max with the lane 32 away
-  const unsigned u = __float_as_uint(x);
-  const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
-}
-__device__ inline float sum_with_partner32(float x) {
-  const unsigned u = __float_as_uint(x);
-  const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return __uint_as_float(a[0]) + __uint_as_float(a[1]);
-}
-template <int D>
-__global__ void __launch_bounds__(256, 2)
-k_prefill_x32(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
-  constexpr int NW = 4, ROWS = 32;
-  static_assert(ROWS * NW == kPfTileRows, "the host sizes the grid for tiles of kPfTileRows rows");
+// bf16 caches: NW waves of 32 query rows (a tile of 128 or 256 rows of one kv head), two waves per SIMD with
+// the whole tile state in registers.  A page pair is fetched once per workgroup into a ring of three LDS stages
+// (one barrier per pair); a wave's 32 rows are two blocks of 16 on the 16x16x32 product, and every K and V
+// operand read from LDS serves both blocks.  Lane (r = l % 16, g = l / 16) holds, per block, row r: its Q^T
+// operands, the scores of tokens 4 g .. 4 g + 3 of either page, and the output columns 16 j + 4 g .. + 3 of
+// every 16-column slab j.
+//   S^T (16 tokens x 16 rows) = K (16 x 32 per step) Q^T per page and block: the A operand of step i is chunk
+//        i * 64 + l of the page's K tile as stored;
+//   O^T (16 of d x 16 rows) += V^T P^T per slab and block over the pair's 32 tokens: contraction index
+//        g * 8 + e is token 4 g + e % 4 of page e / 4, so P^T is the lane's own 4 + 4 weights, and the A operand
+//        of slab 2 i + half is that half of chunk i * 64 + l of the first page's V tile, then of the second's:
+//        the loader writes the chunks' halves into LDS in that order.
+// Softmax against a lagging reference: the reference of a row is raised, and its accumulators rescaled, only
+// when some score exceeds it by 2^kLag (one wave vote per pair over both blocks); until then a weight may
+// exceed 1, which is harmless in fp32 and bf16, and l and O / l do not depend on the reference.  A row's
+// tokens are spread over the four lanes r, r + 16, r + 32, r + 48: the denominator is summed per lane from
+// the bf16-rounded weights with the packed dot product (v_dot2c_f32_bf16) and joined at the end.
+template <int D, int NW>
+__global__ void __launch_bounds__(64 * NW, 8 / NW)
+k_prefill_b16(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
+  constexpr int ROWS = 32, NB = 2;
+  static_assert(NW == 4 || NW == 8, "one or two workgroups of two waves per SIMD");
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   if (!tb.scal[S_CALLOK]) return;
-  constexpr int KS = D / 16;                               // steps of the score product
-  constexpr int NBLK = D / 32;                             // 32-row blocks of O^T
+  constexpr int KQ = D / 32;                               // steps of a score product = chunks per lane and tile
+  constexpr int NS = D / 16;                               // 16-column slabs of O^T
   constexpr int kTileBytes = 16 * D * 2, kPageBytes = 2 * kTileBytes;
   constexpr int kChunks = kTileBytes / 16;                 // 16-byte chunks of one K (or V) tile
   constexpr int kStages = 3;
-  // one stage: K operands of the pair, then the V operands of its first and of its second page; the array also
-  // stages the output at the end (d = 64: that needs more than the three stages)
+  // one stage: the K tiles of the pair's two pages as stored, then the V operands (2 * kChunks slots of two
+  // 8-byte pieces); the array also stages the output at the end (d = 64: that needs more than the three stages)
   constexpr int kRowStride = 64 + 4;                       // floats per staged output row: 64 columns + padding
   constexpr int kOutFloats = ROWS * kRowStride + 2 * ROWS; // per wave: 32 rows, then their output offsets
   constexpr int kStagesAlloc = (NW * kOutFloats * 4 + 64 * kChunks - 1) / (64 * kChunks) > kStages
@@ -275,9 +266,9 @@ k_prefill_x32(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   __shared__ uint4 lds[kStagesAlloc][4 * kChunks];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int col = lane & 31, hh = lane >> 5;
+  const int r16 = lane & 15, g4 = lane >> 4;
   PfTile pt;
-  if (!prefill_tile(dm, tb, pt)) return;
+  if (!prefill_tile(dm, tb, a.tile_rows, pt)) return;
   const int req = pt.req, nq = pt.nq, plen = pt.plen, h = pt.h, rt = pt.rt;
   const int n_rows = nq * dm.G;
   const int row_w0 = rt * (ROWS * NW) + wv * ROWS;
@@ -288,23 +279,29 @@ k_prefill_x32(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   const int* __restrict__ table = prefix_table + (long long)req * dm.max_pp;
   const long long page_bytes = dm.page_elems * 2;
 
-  // this lane's query row: (query, head of the group), query-major; rows past the end shadow the last one
-  const int row = row_w0 + col;
-  const bool have = row < n_rows;
-  const int rc = have ? row : n_rows - 1;
-  const int ql = rc / dm.G, g = rc % dm.G;
-  const int pos = p_first + ql;
+  // this lane's two query rows: (query, head of the group), query-major; rows past the end shadow the last one
+  int pos[NB];
+  long long qrow[NB];
+  bool have[NB];
+  uint4 qreg[NB][KQ];
+  f32x4 O[NB][NS];
+  float m_ref[NB], lsum[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    const int row = row_w0 + 16 * b + r16;
+    have[b] = row < n_rows;
+    const int rc = have[b] ? row : n_rows - 1;
+    const int ql = rc / dm.G, g = rc % dm.G;
+    pos[b] = p_first + ql;
+    qrow[b] = ((pt.q_row0 + ql) * dm.Hq + h * dm.G + g) * D;
+#pragma unroll
+    for (int i = 0; i < KQ; ++i) qreg[b][i] = *(const uint4*)(q + qrow[b] + i * 32 + g4 * 8);
+#pragma unroll
+    for (int j = 0; j < NS; ++j) O[b][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    m_ref[b] = -__builtin_inff();
+    lsum[b] = 0.f;
+  }
   const int lo_pos = wave_has_rows ? p_first + row_w0 / dm.G : -1;
-  const long long qrow = ((pt.q_row0 + ql) * dm.Hq + h * dm.G + g) * D;
-  uint4 qreg[KS];
-#pragma unroll
-  for (int s = 0; s < KS; ++s) qreg[s] = *(const uint4*)(q + qrow + s * 16 + hh * 8);
-  f32x16 O[NBLK];
-#pragma unroll
-  for (int b = 0; b < NBLK; ++b)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) O[b][e] = 0.f;
-  float m_ref = -__builtin_inff(), lsum = 0.f;
 
   // pages the tile needs (its last row's context) and those this wave needs
   const int tile_last_pos = p_first + min((rt + 1) * (ROWS * NW) - 1, n_rows - 1) / dm.G;
@@ -314,54 +311,42 @@ k_prefill_x32(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   const int wave_pairs = wave_has_rows ? wave_last_pos / 32 + 1 : 0;
   const int bound = min(plen, n_pages * 16);               // tokens that exist in the pages the tile reads
 
-  // loader: the pair's two pages go to the two halves of the workgroup (threads 0..127: first page, 128..255:
-  // second page); a thread moves two stored chunks of its page's K tile and two of its V tile into LDS, each
-  // to where the products' operand reads find it: every operand read is then one contiguous KiB per wave
-  // (lane l reads entry l of a 64-entry block), free of bank conflicts.  A thread reads the id of its page
-  // itself, with a vector load two turns ahead: scalar loads return out of order, and one in flight would
-  // turn every wait for an LDS operand into a wait for everything.
-  constexpr int kPerThread = kChunks / 128;                // chunks of a tile per thread: 2 (d = 128) or 1 (d = 64)
-  static_assert(kPerThread >= 1 && kPerThread <= 2, "head_dim 64 or 128");
-  const int pg = tid >> 7, lt = tid & 127;
-  int k_dst[kPerThread], v_src[kPerThread], v_dst[kPerThread];
-#pragma unroll
-  for (int u = 0; u < kPerThread; ++u) {
-    const int ch = lt + 128 * u;
-    // K chunk ch = (8 head-dim elements kg, token r) is the operand of step kg >> 1 for lane (kg & 1) * 32 + pg * 16 + r
-    k_dst[u] = ((ch >> 5) << 6) + (((ch >> 4) & 1) << 5) + pg * 16 + (ch & 15);
-    // V: the stored chunk (32-column block vb, token group tg of 4, column dd) with dd = (ch >> 1) & 15 and
-    // tg = 2 (ch & 1) + ((ch >> 5) & 1), so that neighbouring threads write neighbouring 8-byte pieces: the
-    // chunk's low half (column dd) is piece tg >> 1 of operand lane (tg & 1) * 32 + dd, its high half
-    // (column 16 + dd) the same piece 16 lanes further
-    const int vb = ch >> 6, dd = (ch >> 1) & 15, tg = ((ch & 1) << 1) + ((ch >> 5) & 1);
-    v_src[u] = vb * 64 + tg * 16 + dd;
-    v_dst[u] = ((vb * 64 + (tg & 1) * 32 + dd) << 1) + (tg >> 1);
-  }
+  // loader: the pair's two pages go to the two halves of the workgroup (the first 32 NW threads: first page,
+  // the others: second page); a thread moves kPerThread stored chunks of its page's K tile (to the same place in the stage)
+  // and as many of its V tile (each as two 8-byte pieces, to where the products' operand reads find them:
+  // every operand read is one contiguous KiB per wave).  A thread reads the id of its page itself, with a
+  // vector load two turns ahead: scalar loads return out of order, and one in flight would turn every wait
+  // for an LDS operand into a wait for everything.
+  constexpr int kHalf = 32 * NW;                           // threads per page
+  constexpr int kPerThread = kChunks / kHalf;              // chunks of a tile per thread
+  static_assert(kPerThread * kHalf == kChunks && (kPerThread == 1 || (kPerThread == 2 && kHalf == 128)), "unsupported tile / workgroup shape");
+  const int pg = tid / kHalf, lt = tid % kHalf;
+  const int v_dst0 = (((2 * (lt >> 6)) * 64 + (lt & 63)) << 1) + pg;        // uint2 index of the low half of chunk lt
   const int* my_ids = table + pg;                           // my_ids[2 p]: this thread's page of pair p
   auto page_index = [&](int pr) { return min(2 * pr, n_pages - 1 - pg); };   // an odd last page is paired with itself
   uint4 gk0, gk1, gv0, gv1;                                 // (named registers: arrays captured by the lambdas end up in scratch memory)
   gk1 = gv1 = uint4{0u, 0u, 0u, 0u};
   int pid = my_ids[page_index(0)], pid_next = my_ids[page_index(min(1, n_pairs - 1))];
   auto g_load = [&](int pr_after_next) {   // fetches the pair whose id is in pid; requests the id of a later pair
-    const unsigned char* b = pool + (long long)pid * page_bytes + (long long)h * kPageBytes;
-    gk0 = *(const uint4*)(b + lt * 16);
-    gv0 = *(const uint4*)(b + kTileBytes + v_src[0] * 16);
+    const unsigned char* b = pool + (long long)pid * page_bytes + (long long)h * kPageBytes + lt * 16;
+    gk0 = *(const uint4*)b;
+    gv0 = *(const uint4*)(b + kTileBytes);
     if constexpr (kPerThread == 2) {
-      gk1 = *(const uint4*)(b + (lt + 128) * 16);
-      gv1 = *(const uint4*)(b + kTileBytes + v_src[kPerThread - 1] * 16);
+      gk1 = *(const uint4*)(b + 128 * 16);
+      gv1 = *(const uint4*)(b + kTileBytes + 128 * 16);
     }
     pid = pid_next;
     pid_next = my_ids[page_index(pr_after_next)];
   };
   auto l_store = [&](int stage) {
-    uint2* vdst = (uint2*)&lds[stage][(2 + pg) * kChunks];
-    lds[stage][k_dst[0]] = gk0;
-    vdst[v_dst[0]] = uint2{gv0.x, gv0.y};
-    vdst[v_dst[0] + 32] = uint2{gv0.z, gv0.w};
+    uint2* vdst = (uint2*)&lds[stage][2 * kChunks];
+    lds[stage][pg * kChunks + lt] = gk0;
+    vdst[v_dst0] = uint2{gv0.x, gv0.y};
+    vdst[v_dst0 + 128] = uint2{gv0.z, gv0.w};              // the high half: the next slab's operand, 64 slots on
     if constexpr (kPerThread == 2) {
-      lds[stage][k_dst[kPerThread - 1]] = gk1;
-      vdst[v_dst[kPerThread - 1]] = uint2{gv1.x, gv1.y};
-      vdst[v_dst[kPerThread - 1] + 32] = uint2{gv1.z, gv1.w};
+      lds[stage][pg * kChunks + lt + 128] = gk1;
+      vdst[v_dst0 + 512] = uint2{gv1.x, gv1.y};            // chunk lt + 128: two slab pairs (4 x 64 slots) on
+      vdst[v_dst0 + 512 + 128] = uint2{gv1.z, gv1.w};
     }
   };
 
@@ -375,93 +360,105 @@ k_prefill_x32(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
     g_load(min(pr + 4, n_pairs - 1));                      // pair pr + 2 (or the last pair again)
     if (pr < wave_pairs) {
       const int t0 = pr * 32;
-      uint4 kop[KS], vop[2 * NBLK];
+      uint4 kop[2][KQ], vop[NS];
 #pragma unroll
-      for (int s = 0; s < KS; ++s) kop[s] = lds[stage][s * 64 + lane];
+      for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int i = 0; i < KQ; ++i) kop[p][i] = lds[stage][p * kChunks + i * 64 + lane];
       __builtin_amdgcn_sched_barrier(0);                   // all K operands are requested before anything else is scheduled
 #pragma unroll
-      for (int b = 0; b < 2 * NBLK; ++b) vop[b] = lds[stage][2 * kChunks + b * 64 + lane];
-      f32x16 S;
+      for (int j = 0; j < NS; ++j) vop[j] = lds[stage][2 * kChunks + j * 64 + lane];
+      f32x4 S[NB][2];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) S[e] = 0.f;
+      for (int b = 0; b < NB; ++b) S[b][0] = S[b][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int s = 0; s < KS; ++s)
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop[s]), __builtin_bit_cast(bf16x8, qreg[s]), S, 0, 0, 0);
+      for (int i = 0; i < KQ; ++i)
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+          for (int b = 0; b < NB; ++b)
+            S[b][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kop[p][i]), __builtin_bit_cast(bf16x8, qreg[b][i]), S[b][p], 0, 0, 0);
       const bool full = t0 + 31 <= lo_pos;
       if (!full) {
-        // element e of the lane is token 8 (e / 4) + 4 hh + e % 4 of the pair: masked past the row's position
-        // and past the tokens that exist; the V of tokens that do not exist may be anything: zeroed
-        const int lim = min(pos + 1, bound) - t0;
+        // element j of the lane is token 4 g + j of the first page resp. 16 + 4 g + j (second page): masked past
+        // the row's position and past the tokens that exist; the V of tokens that do not exist may be anything: zeroed
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (8 * (e >> 2) + 4 * hh + (e & 3) >= lim) S[e] = -__builtin_inff();
-        const int nvalid = bound - t0;
+        for (int b = 0; b < NB; ++b) {
+          const int lim = min(pos[b] + 1, bound) - t0;
 #pragma unroll
-        for (int b = 0; b < 2 * NBLK; ++b) {
-          const int tb0 = 16 * (b / NBLK) + 4 * hh;        // first token of the operand's low piece; the high piece is 8 further
-          unsigned mk[4];
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const int tk = tb0 + 8 * (w >> 1) + 2 * (w & 1);
-            mk[w] = (tk < nvalid ? 0x0000ffffu : 0u) | (tk + 1 < nvalid ? 0xffff0000u : 0u);
+          for (int j = 0; j < 4; ++j) {
+            if (4 * g4 + j >= lim) S[b][0][j] = -__builtin_inff();
+            if (16 + 4 * g4 + j >= lim) S[b][1][j] = -__builtin_inff();
           }
-          vop[b].x &= mk[0]; vop[b].y &= mk[1]; vop[b].z &= mk[2]; vop[b].w &= mk[3];
+        }
+        const int nvalid = bound - t0, tk = 4 * g4;
+        const unsigned a01 = (tk + 0 < nvalid ? 0x0000ffffu : 0u) | (tk + 1 < nvalid ? 0xffff0000u : 0u);
+        const unsigned a23 = (tk + 2 < nvalid ? 0x0000ffffu : 0u) | (tk + 3 < nvalid ? 0xffff0000u : 0u);
+        const unsigned b01 = (tk + 16 < nvalid ? 0x0000ffffu : 0u) | (tk + 17 < nvalid ? 0xffff0000u : 0u);
+        const unsigned b23 = (tk + 18 < nvalid ? 0x0000ffffu : 0u) | (tk + 19 < nvalid ? 0xffff0000u : 0u);
+#pragma unroll
+        for (int j = 0; j < NS; ++j) { vop[j].x &= a01; vop[j].y &= a23; vop[j].z &= b01; vop[j].w &= b23; }
+      }
+      float mine[NB];
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        mine[b] = fmaxf(fmaxf(fmaxf(S[b][0][0], S[b][0][1]), fmaxf(S[b][0][2], S[b][0][3])),
+                        fmaxf(fmaxf(S[b][1][0], S[b][1][1]), fmaxf(S[b][1][2], S[b][1][3])));
+      if (__any(mine[0] * a.scale_log2 > m_ref[0] + kLag || mine[1] * a.scale_log2 > m_ref[1] + kLag)) {   // also the first pair: the references are -inf
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          const float mx = max_over_rows(mine[b]) * a.scale_log2;
+          const float m_new = fmaxf(m_ref[b], mx);
+          const float alpha = __builtin_amdgcn_exp2f(m_ref[b] - m_new);
+          m_ref[b] = m_new;
+          lsum[b] *= alpha;
+#pragma unroll
+          for (int j = 0; j < NS; ++j) O[b][j] *= alpha;
         }
       }
-      float mine = S[0];
+      uint4 pp[NB];
 #pragma unroll
-      for (int e = 1; e < 16; ++e) mine = fmaxf(mine, S[e]);
-      if (__any(mine * a.scale_log2 > m_ref + kLag)) {     // also the first pair: the reference is -inf
-        const float mx = max_with_partner32(mine) * a.scale_log2;
-        const float m_new = fmaxf(m_ref, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-        m_ref = m_new;
-        lsum *= alpha;
+      for (int b = 0; b < NB; ++b) {
+        unsigned pk[4];
 #pragma unroll
-        for (int b = 0; b < NBLK; ++b) O[b] *= alpha;
-      }
-      unsigned pk[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[2 * j], a.scale_log2, -m_ref));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[2 * j + 1], a.scale_log2, -m_ref));
-        typedef float f32x2 __attribute__((ext_vector_type(2)));
-        const bf16x2v pb = __builtin_convertvector(f32x2{p0, p1}, bf16x2v);
-        pk[j] = __builtin_bit_cast(unsigned, pb);
-        lsum = __builtin_amdgcn_fdot2_f32_bf16(pb, __builtin_bit_cast(bf16x2v, 0x3f803f80u), lsum, false);
-      }
-#pragma unroll
-      for (int b = 0; b < NBLK; ++b) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const uint4 pt = {pk[4 * t], pk[4 * t + 1], pk[4 * t + 2], pk[4 * t + 3]};
-          O[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop[t * NBLK + b]), __builtin_bit_cast(bf16x8, pt), O[b], 0, 0, 0);
+        for (int w = 0; w < 4; ++w) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[b][w >> 1][2 * (w & 1)], a.scale_log2, -m_ref[b]));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[b][w >> 1][2 * (w & 1) + 1], a.scale_log2, -m_ref[b]));
+          typedef float f32x2 __attribute__((ext_vector_type(2)));
+          const bf16x2v pb = __builtin_convertvector(f32x2{p0, p1}, bf16x2v);
+          pk[w] = __builtin_bit_cast(unsigned, pb);
+          lsum[b] = __builtin_amdgcn_fdot2_f32_bf16(pb, __builtin_bit_cast(bf16x2v, 0x3f803f80u), lsum[b], false);
         }
+        pp[b] = uint4{pk[0], pk[1], pk[2], pk[3]};
       }
+#pragma unroll
+      for (int j = 0; j < NS; ++j)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+          O[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vop[j]), __builtin_bit_cast(bf16x8, pp[b]), O[b][j], 0, 0, 0);
     }
     __syncthreads();
   }
-  // Output.  A lane holds 4-column pieces of its own row: stored from the registers, a wave's store would touch
-  // 64 separate 16-byte pieces.  The tile goes through LDS instead (the stages are free now: every wave is
-  // past the last barrier), 64 columns at a time, each wave in a region of its own, rows padded to 272 bytes
-  // (conflict-free for both the 16-byte writes down a column block and the reads along a row), and leaves in
-  // stores of four 256-byte row segments each.
+  // Output.  A lane holds 4-column pieces of its two rows: stored from the registers, a wave's store would
+  // touch 64 separate 16-byte pieces.  The tile goes through LDS instead (the stages are free now: every wave
+  // is past the last barrier), 64 columns at a time, each wave in a region of its own, rows padded to 272
+  // bytes, and leaves in stores of four 256-byte row segments each.
   if (!wave_has_rows) return;
-  const float l = sum_with_partner32(lsum);
-  const float inv = a.v_scale / l;                         // every row sees at least its own token
   float* wreg = (float*)&lds[0][0] + wv * kOutFloats;
   long long* row_off = (long long*)(wreg + ROWS * kRowStride);      // element offset of every row's output, -1: no row
-  if (hh == 0) row_off[col] = have ? qrow : -1;
+  float inv[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    inv[b] = a.v_scale / sum_over_rows(lsum[b]);           // every row sees at least its own token
+    if (g4 == 0) row_off[16 * b + r16] = have[b] ? qrow[b] : -1;
+  }
 #pragma unroll
   for (int half = 0; half < D / 64; ++half) {
 #pragma unroll
-    for (int bb = 0; bb < 2; ++bb) {
-      const int b = 2 * half + bb;
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        *(f32x4*)(wreg + col * kRowStride + 32 * bb + 8 * j + 4 * hh) =
-            f32x4{O[b][4 * j], O[b][4 * j + 1], O[b][4 * j + 2], O[b][4 * j + 3]} * inv;
-    }
+        *(f32x4*)(wreg + (16 * b + r16) * kRowStride + 16 * j + 4 * g4) = O[b][4 * half + j] * inv[b];
     // (a wave reads only what it wrote itself: no barrier, the compiler's wait for the LDS writes suffices)
 #pragma unroll
     for (int it = 0; it < ROWS / 4; ++it) {
@@ -507,6 +504,14 @@ k_prefill_generic(Ctx c, PrefillArgs a) {
   }
 }
 
+// bf16 caches with head_dim 128: tiles of 256 rows (8 waves, one workgroup per CU: a page pair fetched from the
+// pool serves twice the rows) once a sequence has several of them; 128 rows (4 waves, two workgroups per CU)
+// for short ones and for every other shape.
+int prefill_tile_rows(const Dims& dm, long long max_rows) {
+  if (dm.layout == SART_LAYOUT_MFMA16 && dm.d == 128 && max_rows >= 4 * 2 * kPfTileRows) return 2 * kPfTileRows;
+  return kPfTileRows;
+}
+
 void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s) {
   const Dims& dm = c.dm;
   hipLaunchKernelGGL(k_prefill_check, dim3(1), dim3(256), 0, s, c, a);
@@ -517,8 +522,10 @@ void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s) {
     };
     const bool fp8 = dm.layout == SART_LAYOUT_MFMA16_FP8;
     if (!fp8) {   // bf16: the LDS-staged kernel
-      if (dm.d == 128) hipLaunchKernelGGL(k_prefill_x32<128>, dim3(a.max_tiles, a.n_seqs), dim3(256), 0, s, c, a, c.tb.prefix_table);
-      else hipLaunchKernelGGL(k_prefill_x32<64>, dim3(a.max_tiles, a.n_seqs), dim3(256), 0, s, c, a, c.tb.prefix_table);
+      const dim3 grid(a.max_tiles, a.n_seqs);
+      if (a.tile_rows == 2 * kPfTileRows) hipLaunchKernelGGL((k_prefill_b16<128, 8>), grid, dim3(512), 0, s, c, a, c.tb.prefix_table);
+      else if (dm.d == 128) hipLaunchKernelGGL((k_prefill_b16<128, 4>), grid, dim3(256), 0, s, c, a, c.tb.prefix_table);
+      else hipLaunchKernelGGL((k_prefill_b16<64, 4>), grid, dim3(256), 0, s, c, a, c.tb.prefix_table);
       return;
     }
     if (dm.d == 128) go(k_prefill_mfma<128, true>); else go(k_prefill_mfma<64, true>);   // 8-bit float caches

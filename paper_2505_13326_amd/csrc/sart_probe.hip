@@ -3,6 +3,9 @@
 // them to report what fraction of the rate plain reads reach on the same box the
 // attention kernel achieves, and sweeps their launch shape (workgroups, chunks in
 // flight per wave, load flavour, chunk-to-wave assignment) to find that rate.
+// And a matrix-core kernel that does nothing but 32x32x16 bf16 products on operands it holds in registers:
+// the rate the matrix cores sustain on this machine for given operand values (the clock follows the power drawn,
+// and the power follows the values), which the prefill kernel's rate is reported against.
 #include "sart_internal.h"
 
 namespace sart {
@@ -63,6 +66,59 @@ void launch_read_probe(const void* buf, long long n_chunks, const int* order, in
     case 8: if (nt) go(k_read_probe<8, true>); else go(k_read_probe<8, false>); break;
     default: if (nt) go(k_read_probe<4, true>); else go(k_read_probe<4, false>); break;
   }
+}
+
+// Every wave: 8 A and 8 B operands (16 bytes per lane each) from `operands` (the same 16 KiB for every wave),
+// then `iters` rounds of 524288 flops.  SHAPE 0: 16 products 32x32x16, 8 into one accumulator (a dependent
+// chain, as a score tile over head_dim 128) and 8 into four others (as an output tile): the prefill kernel's
+// own sequence with everything but the products taken out.  SHAPE 1: 32 products 16x16x32 into 8
+// accumulators in turn.  Nothing else: no loads, no LDS, no vector work.
+typedef __bf16 pbf16x8 __attribute__((ext_vector_type(8)));
+typedef float pf32x16 __attribute__((ext_vector_type(16)));
+typedef float pf32x4 __attribute__((ext_vector_type(4)));
+template <int SHAPE>
+__global__ void __launch_bounds__(256, 2)
+k_mfma_probe(const u32x4* __restrict__ operands, long long iters, float* sink) {
+  const int lane = threadIdx.x & 63;
+  u32x4 a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = operands[i * 64 + lane];
+    b[i] = operands[(8 + i) * 64 + lane];
+  }
+  float t = 0.f;
+  if constexpr (SHAPE == 0) {
+    pf32x16 s, o[4];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { s[e] = 0.f; o[0][e] = o[1][e] = o[2][e] = o[3][e] = 0.f; }
+    for (long long it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(pbf16x8, a[i]), __builtin_bit_cast(pbf16x8, b[i]), s, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(pbf16x8, b[i]), __builtin_bit_cast(pbf16x8, a[(i + 3) & 7]), o[i & 3], 0, 0, 0);
+    }
+#pragma unroll
+    for (int e = 0; e < 16; ++e) t += s[e] + o[0][e] + o[1][e] + o[2][e] + o[3][e];
+  } else {
+    pf32x4 o[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = pf32x4{0.f, 0.f, 0.f, 0.f};
+    for (long long it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i)
+        o[i & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(pbf16x8, a[i & 7]), __builtin_bit_cast(pbf16x8, b[(i + (i >> 3)) & 7]), o[i & 7], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t += o[j][0] + o[j][1] + o[j][2] + o[j][3];
+  }
+  if (sink) sink[(long long)blockIdx.x * blockDim.x + threadIdx.x] = t;
+}
+
+void launch_mfma_probe(const void* operands, long long iters, int n_workgroups, int shape, float* sink, hipStream_t s) {
+  if (shape == 0) hipLaunchKernelGGL(k_mfma_probe<0>, dim3(n_workgroups), dim3(256), 0, s, (const u32x4*)operands, iters, sink);
+  else hipLaunchKernelGGL(k_mfma_probe<1>, dim3(n_workgroups), dim3(256), 0, s, (const u32x4*)operands, iters, sink);
 }
 
 }  // namespace sart
