@@ -69,7 +69,7 @@ def mfma_probe_rates(sart, np, torch, shapes=((0, 512),), seconds=0.15):
                 rate = n_wg * 4 * rounds * 524288.0 / (ms * 1e-3) / 1e12
                 left -= ms
                 rounds = max(2000, int(rounds * 25.0 / max(ms, 1e-3)))       # launches of about 25 ms
-            key = name if len(shapes) == 1 else f"{('32x32x16', '16x16x32')[shape]}_{n_wg // 256}_waves_per_simd_{name}"
+            key = f"{('32x32x16', '16x16x32', 'pair_loop_arithmetic')[shape]}_{n_wg // 256}_waves_per_simd_{name}"
             rates[key] = round(rate, 1)
     return rates
 
@@ -119,9 +119,11 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
                 "algorithmic_flops_per_launch": int(flops), "kernel_ms_avg": round(k_ms, 4),
                 "note": "events on the call's stream around all timed calls (validation kernel included)"}
     if cfg.dtype == "bf16" and args.kv_dtype != "fp8":
-        probe = mfma_probe_rates(sart, np, torch, shapes=((1, 512),))     # the kernel's own product shape and waves per SIMD
+        # the kernel's own product shape and waves per SIMD: products alone, and with the softmax between them
+        probe = mfma_probe_rates(sart, np, torch, shapes=((1, 512), (2, 512)))
         roofline["mfma_probe_tflops"] = probe
-        roofline["frac_of_mfma_probe"] = round(roofline["achieved"] / probe["normal_bf16"], 4)
+        roofline["frac_of_mfma_probe"] = round(roofline["achieved"] / probe["16x16x32_2_waves_per_simd_normal_bf16"], 4)
+        roofline["frac_of_pair_loop_arithmetic"] = round(roofline["achieved"] / probe["pair_loop_arithmetic_2_waves_per_simd_normal_bf16"], 4)
     cpu = None
     if not args.no_cpu_baseline:
         import oracle as orc
@@ -587,7 +589,7 @@ def main():
         return bench_probe_sweep(args, sart, np, torch)
     if args.workload == "mfma_probe":
         print(json.dumps({"metric": "bf16 matrix-core products from registers and nothing else, by product shape and waves per SIMD",
-                          "unit": "TFLOP/s", "value": mfma_probe_rates(sart, np, torch, shapes=((0, 512), (0, 256), (1, 512), (1, 256)), seconds=0.8),
+                          "unit": "TFLOP/s", "value": mfma_probe_rates(sart, np, torch, shapes=((0, 512), (0, 256), (1, 512), (1, 256), (2, 512), (2, 256)), seconds=0.8),
                           "peak": 2500.0}))
         return
     if args.workload == "all":

@@ -45,9 +45,12 @@ sart_status sart_read_probe_shaped(const void* buf, size_t bytes, const int32_t*
 
 /* Measurement aid, no part of the method: n_workgroups of 4 waves (a CU takes two of them: 256 workgroups =
  * one wave per SIMD on MI355X, 512 = two) each run `rounds` rounds of 524288 flops of bf16 matrix-core products
- * on operands held in registers, and nothing else.  shape 0: 16 products 32x32x16 per round, 8 into one
+ * on operands held in registers.  shape 0: 16 products 32x32x16 per round, 8 into one
  * accumulator and 8 into four others (the prefill kernel's own sequence of products); shape 1: 32 products
- * 16x16x32 into 8 accumulators in turn.  A wave holds 8 A and 8 B operands per lane, read once from
+ * 16x16x32 into 8 accumulators in turn; shape 2: the arithmetic of the bf16 prefill kernel's loop over page pairs
+ * for head_dim 128 and nothing else of it (16 score products 16x16x32 of two 16-row blocks against two pages,
+ * the softmax of the lane's 16 scores: exp2, conversion to bf16, denominators; 16 output products), the
+ * same flops per round.  A wave holds 8 A and 8 B operands per lane, read once from
  * `operands` (DEVICE, 16 KiB: operand i of lane l at byte (i * 64 + l) * 16, A operands first; the same for
  * every wave).  sink (DEVICE, n_workgroups * 256 floats) receives a sum per lane.  Asynchronous on `stream`;
  * the caller times it.  The rate depends on the operand values (zeros draw less power, and the clock follows

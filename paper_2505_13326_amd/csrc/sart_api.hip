@@ -752,7 +752,7 @@ sart_status sart_mfma_probe(const void* operands, int64_t rounds, int32_t n_work
   if (!operands || !sink) return fail(SART_E_INVALID, "the matrix-core probe needs its operand and result buffers");
   if (rounds < 1 || rounds > (1ll << 30)) return fail(SART_E_INVALID, "probe rounds out of range");
   if (n_workgroups < 1 || n_workgroups > 65536) return fail(SART_E_INVALID, "probe workgroups out of range");
-  if (shape < 0 || shape > 1) return fail(SART_E_INVALID, "probe shape must be 0 (32x32x16) or 1 (16x16x32)");
+  if (shape < 0 || shape > 2) return fail(SART_E_INVALID, "probe shape must be 0 (32x32x16), 1 (16x16x32) or 2 (16x16x32 with the softmax)");
   launch_mfma_probe(operands, rounds, n_workgroups, shape, sink, (hipStream_t)stream);
   HIP_TRY(hipGetLastError());
   return SART_OK;

@@ -76,9 +76,11 @@ void launch_read_probe(const void* buf, long long n_chunks, const int* order, in
 typedef __bf16 pbf16x8 __attribute__((ext_vector_type(8)));
 typedef float pf32x16 __attribute__((ext_vector_type(16)));
 typedef float pf32x4 __attribute__((ext_vector_type(4)));
+typedef float pf32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 pbf16x2 __attribute__((ext_vector_type(2)));
 template <int SHAPE>
 __global__ void __launch_bounds__(256, 2)
-k_mfma_probe(const u32x4* __restrict__ operands, long long iters, float* sink) {
+k_mfma_probe(const u32x4* __restrict__ operands, long long iters, float scale, float* sink) {
   const int lane = threadIdx.x & 63;
   u32x4 a[8], b[8];
 #pragma unroll
@@ -101,6 +103,65 @@ k_mfma_probe(const u32x4* __restrict__ operands, long long iters, float* sink) {
     }
 #pragma unroll
     for (int e = 0; e < 16; ++e) t += s[e] + o[0][e] + o[1][e] + o[2][e] + o[3][e];
+  } else if constexpr (SHAPE == 2) {
+    pf32x4 o[2][8];
+    float m_ref[2] = {4.f, 4.f}, lsum[2] = {0.f, 0.f};
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[blk][j] = pf32x4{0.f, 0.f, 0.f, 0.f};
+    for (long long it = 0; it < iters; ++it) {
+      pf32x4 sc[2][2];
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk) sc[blk][0] = sc[blk][1] = pf32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+          for (int blk = 0; blk < 2; ++blk)
+            sc[blk][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(pbf16x8, a[p * 4 + i]), __builtin_bit_cast(pbf16x8, b[blk * 4 + i]), sc[blk][p], 0, 0, 0);
+      float mine[2];
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk)
+        mine[blk] = fmaxf(fmaxf(fmaxf(sc[blk][0][0], sc[blk][0][1]), fmaxf(sc[blk][0][2], sc[blk][0][3])),
+                          fmaxf(fmaxf(sc[blk][1][0], sc[blk][1][1]), fmaxf(sc[blk][1][2], sc[blk][1][3])));
+      if (__any(mine[0] * scale > m_ref[0] + 24.f || mine[1] * scale > m_ref[1] + 24.f)) {
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+          const float m_new = fmaxf(m_ref[blk], mine[blk] * scale), alpha = __builtin_amdgcn_exp2f(m_ref[blk] - m_new);
+          m_ref[blk] = m_new;
+          lsum[blk] *= alpha;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o[blk][j] *= alpha;
+        }
+      }
+      u32x4 pp[2];
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk) {
+        unsigned pk[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[blk][w >> 1][2 * (w & 1)], scale, -m_ref[blk]));
+          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[blk][w >> 1][2 * (w & 1) + 1], scale, -m_ref[blk]));
+          const pbf16x2 pb = __builtin_convertvector(pf32x2{p0, p1}, pbf16x2);
+          pk[w] = __builtin_bit_cast(unsigned, pb);
+          lsum[blk] = __builtin_amdgcn_fdot2_f32_bf16(pb, __builtin_bit_cast(pbf16x2, 0x3f803f80u), lsum[blk], false);
+        }
+        pp[blk] = u32x4{pk[0], pk[1], pk[2], pk[3]};
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+          o[blk][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(pbf16x8, a[(j + 3) & 7]), __builtin_bit_cast(pbf16x8, pp[blk]), o[blk][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      t += lsum[blk];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) t += o[blk][j][0] + o[blk][j][1] + o[blk][j][2] + o[blk][j][3];
+    }
   } else {
     pf32x4 o[8];
 #pragma unroll
@@ -117,8 +178,9 @@ k_mfma_probe(const u32x4* __restrict__ operands, long long iters, float* sink) {
 }
 
 void launch_mfma_probe(const void* operands, long long iters, int n_workgroups, int shape, float* sink, hipStream_t s) {
-  if (shape == 0) hipLaunchKernelGGL(k_mfma_probe<0>, dim3(n_workgroups), dim3(256), 0, s, (const u32x4*)operands, iters, sink);
-  else hipLaunchKernelGGL(k_mfma_probe<1>, dim3(n_workgroups), dim3(256), 0, s, (const u32x4*)operands, iters, sink);
+  const float scale = 0.1275174f;   // log2(e) / sqrt(128): what a head_dim of 128 multiplies its scores by
+  auto go = [&](auto kern) { hipLaunchKernelGGL(kern, dim3(n_workgroups), dim3(256), 0, s, (const u32x4*)operands, iters, scale, sink); };
+  if (shape == 0) go(k_mfma_probe<0>); else if (shape == 1) go(k_mfma_probe<1>); else go(k_mfma_probe<2>);
 }
 
 }  // namespace sart

@@ -42,7 +42,11 @@ def test_mfma_probe_sums_its_products(shape):
         want = rounds * 0.25 * 32 * (8 * 4 * 4)
     got = sink.cpu().numpy()
     assert np.all(got == want), (got[:4], want)
+    # the loop with the softmax: finite sums (weights 2^(s c - reference) of equal scores, whatever the reference)
+    sart.mfma_probe(ops, rounds, n_wg, sink, shape=2)
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(sink.cpu().numpy())) and np.all(sink.cpu().numpy() > 0)
     with pytest.raises(sart.SartError):
         sart.mfma_probe(ops, 0, n_wg, sink, shape=shape)
     with pytest.raises(sart.SartError):
-        sart.mfma_probe(ops, rounds, n_wg, sink, shape=2)
+        sart.mfma_probe(ops, rounds, n_wg, sink, shape=3)
