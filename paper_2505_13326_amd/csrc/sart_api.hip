@@ -498,7 +498,9 @@ sart_status sart_prefill_attention(sart_cache* c, int32_t layer, int32_t n_seqs,
     if (n_q[i] > max_nq) max_nq = n_q[i];
   }
   const int rows_per_tile = prefill_tile_rows(dm, max_nq * dm.G);     // the matrix-core kernel's workgroup tile
-  const long long max_tiles = (long long)dm.Hkv * ((max_nq * dm.G + rows_per_tile - 1) / rows_per_tile);
+  long long tiles_per_head = (max_nq * dm.G + rows_per_tile - 1) / rows_per_tile;
+  if (rows_per_tile == 2 * kPfTileRows) tiles_per_head = (tiles_per_head + 1) / 2;   // those workgroups take two tiles each
+  const long long max_tiles = (long long)dm.Hkv * tiles_per_head;                    // grid x: workgroups of the longest sequence
   if (total > 0x7fffffffLL / dm.Hq || max_tiles > 0x7fffffffLL) return fail(SART_E_INVALID, "too many queries in one call");
   if (total > 0 && (!q || !out)) return fail(SART_E_INVALID, "null q or out");
   if (n_seqs == 0) return SART_OK;

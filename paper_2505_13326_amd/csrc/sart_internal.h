@@ -274,7 +274,7 @@ struct PrefillArgs {
   float scale_log2;
   float v_scale;          // 8-bit float caches: what the output is multiplied by (1 otherwise)
   int call_seq;
-  int max_tiles;          // workgroup tiles of the listed sequence that has most (matrix-core kernels: grid x)
+  int max_tiles;          // workgroups of the listed sequence that has most (matrix-core kernels: grid x)
   int tile_rows;          // rows of a workgroup tile (prefill_tile_rows)
   int total_q;
 };

@@ -244,11 +244,18 @@ typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
 // exceed 1, which is harmless in fp32 and bf16, and l and O / l do not depend on the reference.  A row's
 // tokens are spread over the four lanes r, r + 16, r + 32, r + 48: the denominator is summed per lane from
 // the bf16-rounded weights with the packed dot product (v_dot2c_f32_bf16) and joined at the end.
-template <int D, int NW>
+// TPW = 2 (8 waves, one workgroup per CU): a workgroup takes two tiles of one kv head one after the other, the
+// j-th heaviest and the j-th lightest (every workgroup of a sequence then has the same number of page pairs),
+// and the K/V stream runs on across the two: while the first tile's last pairs are computed the second tile's
+// first pairs are already on their way into the ring, its Q rows are requested before the first tile's output
+// is staged, and what a tile costs before its first product (descriptor, addresses, the first loads: 4-5 us)
+// is paid once per two tiles.  The output staging then has an LDS area of its own.
+template <int D, int NW, int TPW>
 __global__ void __launch_bounds__(64 * NW, 8 / NW)
 k_prefill_b16(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   constexpr int ROWS = 32, NB = 2;
   static_assert(NW == 4 || NW == 8, "one or two workgroups of two waves per SIMD");
+  static_assert(TPW == 1 || (TPW == 2 && NW == 8), "a second tile needs the staging area of its own that one workgroup per CU has room for");
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   if (!tb.scal[S_CALLOK]) return;
@@ -258,76 +265,100 @@ k_prefill_b16(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
   constexpr int kChunks = kTileBytes / 16;                 // 16-byte chunks of one K (or V) tile
   constexpr int kStages = 3;
   // one stage: the K tiles of the pair's two pages as stored, then the V operands (2 * kChunks slots of two
-  // 8-byte pieces); the array also stages the output at the end (d = 64: that needs more than the three stages)
+  // 8-byte pieces).  With one tile per workgroup the ring also stages the output at the end (d = 64: that
+  // needs more than the three stages).
   constexpr int kRowStride = 64 + 4;                       // floats per staged output row: 64 columns + padding
   constexpr int kOutFloats = ROWS * kRowStride + 2 * ROWS; // per wave: 32 rows, then their output offsets
-  constexpr int kStagesAlloc = (NW * kOutFloats * 4 + 64 * kChunks - 1) / (64 * kChunks) > kStages
-                                   ? (NW * kOutFloats * 4 + 64 * kChunks - 1) / (64 * kChunks) : kStages;
+  constexpr int kStagesOut = (NW * kOutFloats * 4 + 64 * kChunks - 1) / (64 * kChunks);
+  constexpr int kStagesAlloc = TPW == 1 && kStagesOut > kStages ? kStagesOut : kStages;
   __shared__ uint4 lds[kStagesAlloc][4 * kChunks];
+  __shared__ float s_out[TPW == 2 ? NW * kOutFloats : 4];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r16 = lane & 15, g4 = lane >> 4;
-  PfTile pt;
-  if (!prefill_tile(dm, tb, a.tile_rows, pt)) return;
-  const int req = pt.req, nq = pt.nq, plen = pt.plen, h = pt.h, rt = pt.rt;
+  // the workgroup's tiles: block (x, y) is item x of sequence y; neighbouring items take the kv heads in turn
+  const int4 sq = ((const int4*)tb.pf_seq)[blockIdx.y];
+  const int req = sq.x, nq = sq.y, plen = sq.w;
+  const long long q_row0 = sq.z;
   const int n_rows = nq * dm.G;
-  const int row_w0 = rt * (ROWS * NW) + wv * ROWS;
-  const bool wave_has_rows = row_w0 < n_rows;              // a wave without rows still helps to load
+  const int tiles_per_head = ceil_div(n_rows, ROWS * NW);
+  const int items_per_head = TPW == 2 ? (tiles_per_head + 1) >> 1 : tiles_per_head;
+  if ((int)blockIdx.x >= items_per_head * dm.Hkv) return;
+  const int h = blockIdx.x % dm.Hkv, item = blockIdx.x / dm.Hkv;
+  const int rt0 = tiles_per_head - 1 - item;               // a sequence's later rows (longer contexts) come first
+  const int rt1 = item;                                    // the second tile, if it is another one
+  const int n_tiles = TPW == 2 && rt1 < rt0 ? 2 : 1;
   const int p_first = plen - nq;
   const uint16_t* q = (const uint16_t*)a.q;
   const unsigned char* pool = (const unsigned char*)c.pool;
   const int* __restrict__ table = prefix_table + (long long)req * dm.max_pp;
   const long long page_bytes = dm.page_elems * 2;
 
-  // this lane's two query rows: (query, head of the group), query-major; rows past the end shadow the last one
+  // pages a tile needs: its last row's context
+  auto pages_of = [&](int rt) { return (p_first + min((rt + 1) * (ROWS * NW) - 1, n_rows - 1) / dm.G) / 16 + 1; };
+  const int n_pages0 = pages_of(rt0), n_pages1 = n_tiles == 2 ? pages_of(rt1) : 0;
+  const int n_pairs0 = (n_pages0 + 1) >> 1, n_pairs1 = (n_pages1 + 1) >> 1;
+  const int total_pairs = n_pairs0 + n_pairs1;
+
+  // this lane's two query rows of the current tile: (query, head of the group), query-major; rows past the end
+  // shadow the last one
   int pos[NB];
   long long qrow[NB];
   bool have[NB];
   uint4 qreg[NB][KQ];
   f32x4 O[NB][NS];
   float m_ref[NB], lsum[NB];
+  auto rows_of = [&](int rt, int (&pos_)[NB], long long (&qrow_)[NB], bool (&have_)[NB]) {
 #pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    const int row = row_w0 + 16 * b + r16;
-    have[b] = row < n_rows;
-    const int rc = have[b] ? row : n_rows - 1;
-    const int ql = rc / dm.G, g = rc % dm.G;
-    pos[b] = p_first + ql;
-    qrow[b] = ((pt.q_row0 + ql) * dm.Hq + h * dm.G + g) * D;
+    for (int b = 0; b < NB; ++b) {
+      const int row = rt * (ROWS * NW) + wv * ROWS + 16 * b + r16;
+      have_[b] = row < n_rows;
+      const int rc = have_[b] ? row : n_rows - 1;
+      const int ql = rc / dm.G, g = rc % dm.G;
+      pos_[b] = p_first + ql;
+      qrow_[b] = ((q_row0 + ql) * dm.Hq + h * dm.G + g) * D;
+    }
+  };
+  auto load_q = [&](const long long (&qrow_)[NB]) {
 #pragma unroll
-    for (int i = 0; i < KQ; ++i) qreg[b][i] = *(const uint4*)(q + qrow[b] + i * 32 + g4 * 8);
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
-    for (int j = 0; j < NS; ++j) O[b][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    m_ref[b] = -__builtin_inff();
-    lsum[b] = 0.f;
-  }
-  const int lo_pos = wave_has_rows ? p_first + row_w0 / dm.G : -1;
-
-  // pages the tile needs (its last row's context) and those this wave needs
-  const int tile_last_pos = p_first + min((rt + 1) * (ROWS * NW) - 1, n_rows - 1) / dm.G;
-  const int n_pages = tile_last_pos / 16 + 1;
-  const int n_pairs = (n_pages + 1) >> 1;
-  const int wave_last_pos = wave_has_rows ? p_first + min(row_w0 + ROWS - 1, n_rows - 1) / dm.G : -1;
-  const int wave_pairs = wave_has_rows ? wave_last_pos / 32 + 1 : 0;
-  const int bound = min(plen, n_pages * 16);               // tokens that exist in the pages the tile reads
+      for (int i = 0; i < KQ; ++i) qreg[b][i] = *(const uint4*)(q + qrow_[b] + i * 32 + g4 * 8);
+  };
+  auto reset_state = [&]() {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+#pragma unroll
+      for (int j = 0; j < NS; ++j) O[b][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+      m_ref[b] = -__builtin_inff();
+      lsum[b] = 0.f;
+    }
+  };
+  rows_of(rt0, pos, qrow, have);
+  load_q(qrow);
+  reset_state();
 
   // loader: the pair's two pages go to the two halves of the workgroup (the first 32 NW threads: first page,
   // the others: second page); a thread moves kPerThread stored chunks of its page's K tile (to the same place in the stage)
   // and as many of its V tile (each as two 8-byte pieces, to where the products' operand reads find them:
   // every operand read is one contiguous KiB per wave).  A thread reads the id of its page itself, with a
   // vector load two turns ahead: scalar loads return out of order, and one in flight would turn every wait
-  // for an LDS operand into a wait for everything.
+  // for an LDS operand into a wait for everything.  The pairs of the workgroup's tiles are one sequence,
+  // gp = 0 .. total_pairs - 1, through the same page table.
   constexpr int kHalf = 32 * NW;                           // threads per page
   constexpr int kPerThread = kChunks / kHalf;              // chunks of a tile per thread
   static_assert(kPerThread * kHalf == kChunks && (kPerThread == 1 || (kPerThread == 2 && kHalf == 128)), "unsupported tile / workgroup shape");
   const int pg = tid / kHalf, lt = tid % kHalf;
   const int v_dst0 = (((2 * (lt >> 6)) * 64 + (lt & 63)) << 1) + pg;        // uint2 index of the low half of chunk lt
-  const int* my_ids = table + pg;                           // my_ids[2 p]: this thread's page of pair p
-  auto page_index = [&](int pr) { return min(2 * pr, n_pages - 1 - pg); };   // an odd last page is paired with itself
+  const int* my_ids = table + pg;                           // my_ids[2 p]: this thread's page of a tile's pair p
+  auto page_index = [&](int gp) {                           // an odd last page is paired with itself
+    const bool second = TPW == 2 && gp >= n_pairs0;
+    return min(2 * (second ? gp - n_pairs0 : gp), (second ? n_pages1 : n_pages0) - 1 - pg);
+  };
   uint4 gk0, gk1, gv0, gv1;                                 // (named registers: arrays captured by the lambdas end up in scratch memory)
   gk1 = gv1 = uint4{0u, 0u, 0u, 0u};
-  int pid = my_ids[page_index(0)], pid_next = my_ids[page_index(min(1, n_pairs - 1))];
-  auto g_load = [&](int pr_after_next) {   // fetches the pair whose id is in pid; requests the id of a later pair
+  int pid = my_ids[page_index(0)], pid_next = my_ids[page_index(min(1, total_pairs - 1))];
+  auto g_load = [&](int gp_after_next) {   // fetches the pair whose id is in pid; requests the id of a later pair
     const unsigned char* b = pool + (long long)pid * page_bytes + (long long)h * kPageBytes + lt * 16;
     gk0 = *(const uint4*)b;
     gv0 = *(const uint4*)(b + kTileBytes);
@@ -336,7 +367,7 @@ k_prefill_b16(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
       gv1 = *(const uint4*)(b + kTileBytes + 128 * 16);
     }
     pid = pid_next;
-    pid_next = my_ids[page_index(pr_after_next)];
+    pid_next = my_ids[page_index(gp_after_next)];
   };
   auto l_store = [&](int stage) {
     uint2* vdst = (uint2*)&lds[stage][2 * kChunks];
@@ -350,122 +381,148 @@ k_prefill_b16(Ctx c, PrefillArgs a, const int* __restrict__ prefix_table) {
     }
   };
 
-  g_load(min(2, n_pairs - 1));                             // pair 0
+  g_load(min(2, total_pairs - 1));                         // pair 0
   l_store(0);
-  g_load(min(3, n_pairs - 1));                             // pair 1
+  g_load(min(3, total_pairs - 1));                         // pair 1
   __syncthreads();
-  for (int pr = 0; pr < n_pairs; ++pr) {
-    const int stage = pr % kStages;
-    l_store((pr + 1) % kStages);                           // pair pr + 1 (loaded a turn ago), read a turn from now
-    g_load(min(pr + 4, n_pairs - 1));                      // pair pr + 2 (or the last pair again)
-    if (pr < wave_pairs) {
-      const int t0 = pr * 32;
-      uint4 kop[2][KQ], vop[NS];
-#pragma unroll
-      for (int p = 0; p < 2; ++p)
-#pragma unroll
-        for (int i = 0; i < KQ; ++i) kop[p][i] = lds[stage][p * kChunks + i * 64 + lane];
-      __builtin_amdgcn_sched_barrier(0);                   // all K operands are requested before anything else is scheduled
-#pragma unroll
-      for (int j = 0; j < NS; ++j) vop[j] = lds[stage][2 * kChunks + j * 64 + lane];
-      f32x4 S[NB][2];
-#pragma unroll
-      for (int b = 0; b < NB; ++b) S[b][0] = S[b][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int i = 0; i < KQ; ++i)
+  int gp = 0;
+  for (int t = 0; t < n_tiles; ++t) {
+    const int rt = t ? rt1 : rt0;
+    const int n_pages = t ? n_pages1 : n_pages0, n_pairs = t ? n_pairs1 : n_pairs0;
+    const int row_w0 = rt * (ROWS * NW) + wv * ROWS;
+    const bool wave_has_rows = row_w0 < n_rows;            // a wave without rows still helps to load
+    const int lo_pos = wave_has_rows ? p_first + row_w0 / dm.G : -1;
+    const int wave_last_pos = wave_has_rows ? p_first + min(row_w0 + ROWS - 1, n_rows - 1) / dm.G : -1;
+    const int wave_pairs = wave_has_rows ? wave_last_pos / 32 + 1 : 0;     // pairs this wave needs
+    const int bound = min(plen, n_pages * 16);             // tokens that exist in the pages the tile reads
+    for (int pr = 0; pr < n_pairs; ++pr, ++gp) {
+      const int stage = gp % kStages;
+      l_store((gp + 1) % kStages);                         // pair gp + 1 (loaded a turn ago), read a turn from now
+      g_load(min(gp + 4, total_pairs - 1));                // pair gp + 2 (or the last pair again)
+      if (pr < wave_pairs) {
+        const int t0 = pr * 32;
+        uint4 kop[2][KQ], vop[NS];
 #pragma unroll
         for (int p = 0; p < 2; ++p)
 #pragma unroll
-          for (int b = 0; b < NB; ++b)
-            S[b][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kop[p][i]), __builtin_bit_cast(bf16x8, qreg[b][i]), S[b][p], 0, 0, 0);
-      const bool full = t0 + 31 <= lo_pos;
-      if (!full) {
-        // element j of the lane is token 4 g + j of the first page resp. 16 + 4 g + j (second page): masked past
-        // the row's position and past the tokens that exist; the V of tokens that do not exist may be anything: zeroed
+          for (int i = 0; i < KQ; ++i) kop[p][i] = lds[stage][p * kChunks + i * 64 + lane];
+        __builtin_amdgcn_sched_barrier(0);                 // all K operands are requested before anything else is scheduled
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-          const int lim = min(pos[b] + 1, bound) - t0;
+        for (int j = 0; j < NS; ++j) vop[j] = lds[stage][2 * kChunks + j * 64 + lane];
+        f32x4 S[NB][2];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            if (4 * g4 + j >= lim) S[b][0][j] = -__builtin_inff();
-            if (16 + 4 * g4 + j >= lim) S[b][1][j] = -__builtin_inff();
+        for (int b = 0; b < NB; ++b) S[b][0] = S[b][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < KQ; ++i)
+#pragma unroll
+          for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+              S[b][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kop[p][i]), __builtin_bit_cast(bf16x8, qreg[b][i]), S[b][p], 0, 0, 0);
+        const bool full = t0 + 31 <= lo_pos;
+        if (!full) {
+          // element j of the lane is token 4 g + j of the first page resp. 16 + 4 g + j (second page): masked past
+          // the row's position and past the tokens that exist; the V of tokens that do not exist may be anything: zeroed
+#pragma unroll
+          for (int b = 0; b < NB; ++b) {
+            const int lim = min(pos[b] + 1, bound) - t0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              if (4 * g4 + j >= lim) S[b][0][j] = -__builtin_inff();
+              if (16 + 4 * g4 + j >= lim) S[b][1][j] = -__builtin_inff();
+            }
           }
+          const int nvalid = bound - t0, tk = 4 * g4;
+          const unsigned a01 = (tk + 0 < nvalid ? 0x0000ffffu : 0u) | (tk + 1 < nvalid ? 0xffff0000u : 0u);
+          const unsigned a23 = (tk + 2 < nvalid ? 0x0000ffffu : 0u) | (tk + 3 < nvalid ? 0xffff0000u : 0u);
+          const unsigned b01 = (tk + 16 < nvalid ? 0x0000ffffu : 0u) | (tk + 17 < nvalid ? 0xffff0000u : 0u);
+          const unsigned b23 = (tk + 18 < nvalid ? 0x0000ffffu : 0u) | (tk + 19 < nvalid ? 0xffff0000u : 0u);
+#pragma unroll
+          for (int j = 0; j < NS; ++j) { vop[j].x &= a01; vop[j].y &= a23; vop[j].z &= b01; vop[j].w &= b23; }
         }
-        const int nvalid = bound - t0, tk = 4 * g4;
-        const unsigned a01 = (tk + 0 < nvalid ? 0x0000ffffu : 0u) | (tk + 1 < nvalid ? 0xffff0000u : 0u);
-        const unsigned a23 = (tk + 2 < nvalid ? 0x0000ffffu : 0u) | (tk + 3 < nvalid ? 0xffff0000u : 0u);
-        const unsigned b01 = (tk + 16 < nvalid ? 0x0000ffffu : 0u) | (tk + 17 < nvalid ? 0xffff0000u : 0u);
-        const unsigned b23 = (tk + 18 < nvalid ? 0x0000ffffu : 0u) | (tk + 19 < nvalid ? 0xffff0000u : 0u);
-#pragma unroll
-        for (int j = 0; j < NS; ++j) { vop[j].x &= a01; vop[j].y &= a23; vop[j].z &= b01; vop[j].w &= b23; }
-      }
-      float mine[NB];
-#pragma unroll
-      for (int b = 0; b < NB; ++b)
-        mine[b] = fmaxf(fmaxf(fmaxf(S[b][0][0], S[b][0][1]), fmaxf(S[b][0][2], S[b][0][3])),
-                        fmaxf(fmaxf(S[b][1][0], S[b][1][1]), fmaxf(S[b][1][2], S[b][1][3])));
-      if (__any(mine[0] * a.scale_log2 > m_ref[0] + kLag || mine[1] * a.scale_log2 > m_ref[1] + kLag)) {   // also the first pair: the references are -inf
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-          const float mx = max_over_rows(mine[b]) * a.scale_log2;
-          const float m_new = fmaxf(m_ref[b], mx);
-          const float alpha = __builtin_amdgcn_exp2f(m_ref[b] - m_new);
-          m_ref[b] = m_new;
-          lsum[b] *= alpha;
-#pragma unroll
-          for (int j = 0; j < NS; ++j) O[b][j] *= alpha;
-        }
-      }
-      uint4 pp[NB];
-#pragma unroll
-      for (int b = 0; b < NB; ++b) {
-        unsigned pk[4];
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[b][w >> 1][2 * (w & 1)], a.scale_log2, -m_ref[b]));
-          const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[b][w >> 1][2 * (w & 1) + 1], a.scale_log2, -m_ref[b]));
-          typedef float f32x2 __attribute__((ext_vector_type(2)));
-          const bf16x2v pb = __builtin_convertvector(f32x2{p0, p1}, bf16x2v);
-          pk[w] = __builtin_bit_cast(unsigned, pb);
-          lsum[b] = __builtin_amdgcn_fdot2_f32_bf16(pb, __builtin_bit_cast(bf16x2v, 0x3f803f80u), lsum[b], false);
-        }
-        pp[b] = uint4{pk[0], pk[1], pk[2], pk[3]};
-      }
-#pragma unroll
-      for (int j = 0; j < NS; ++j)
+        float mine[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b)
-          O[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vop[j]), __builtin_bit_cast(bf16x8, pp[b]), O[b][j], 0, 0, 0);
+          mine[b] = fmaxf(fmaxf(fmaxf(S[b][0][0], S[b][0][1]), fmaxf(S[b][0][2], S[b][0][3])),
+                          fmaxf(fmaxf(S[b][1][0], S[b][1][1]), fmaxf(S[b][1][2], S[b][1][3])));
+        if (__any(mine[0] * a.scale_log2 > m_ref[0] + kLag || mine[1] * a.scale_log2 > m_ref[1] + kLag)) {   // also the first pair: the references are -inf
+#pragma unroll
+          for (int b = 0; b < NB; ++b) {
+            const float mx = max_over_rows(mine[b]) * a.scale_log2;
+            const float m_new = fmaxf(m_ref[b], mx);
+            const float alpha = __builtin_amdgcn_exp2f(m_ref[b] - m_new);
+            m_ref[b] = m_new;
+            lsum[b] *= alpha;
+#pragma unroll
+            for (int j = 0; j < NS; ++j) O[b][j] *= alpha;
+          }
+        }
+        uint4 pp[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          unsigned pk[4];
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[b][w >> 1][2 * (w & 1)], a.scale_log2, -m_ref[b]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[b][w >> 1][2 * (w & 1) + 1], a.scale_log2, -m_ref[b]));
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            const bf16x2v pb = __builtin_convertvector(f32x2{p0, p1}, bf16x2v);
+            pk[w] = __builtin_bit_cast(unsigned, pb);
+            lsum[b] = __builtin_amdgcn_fdot2_f32_bf16(pb, __builtin_bit_cast(bf16x2v, 0x3f803f80u), lsum[b], false);
+          }
+          pp[b] = uint4{pk[0], pk[1], pk[2], pk[3]};
+        }
+#pragma unroll
+        for (int j = 0; j < NS; ++j)
+#pragma unroll
+          for (int b = 0; b < NB; ++b)
+            O[b][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vop[j]), __builtin_bit_cast(bf16x8, pp[b]), O[b][j], 0, 0, 0);
+      }
+      __syncthreads();
     }
-    __syncthreads();
-  }
-  // Output.  A lane holds 4-column pieces of its two rows: stored from the registers, a wave's store would
-  // touch 64 separate 16-byte pieces.  The tile goes through LDS instead (the stages are free now: every wave
-  // is past the last barrier), 64 columns at a time, each wave in a region of its own, rows padded to 272
-  // bytes, and leaves in stores of four 256-byte row segments each.
-  if (!wave_has_rows) return;
-  float* wreg = (float*)&lds[0][0] + wv * kOutFloats;
-  long long* row_off = (long long*)(wreg + ROWS * kRowStride);      // element offset of every row's output, -1: no row
-  float inv[NB];
+    // The next tile's rows: their Q is requested now (the registers are free) and arrives while this tile's
+    // output is staged.
+    int pos_n[NB];
+    long long qrow_n[NB];
+    bool have_n[NB];
+    if (t + 1 < n_tiles) {
+      rows_of(rt1, pos_n, qrow_n, have_n);
+      load_q(qrow_n);
+    }
+    // Output.  A lane holds 4-column pieces of its two rows: stored from the registers, a wave's store would
+    // touch 64 separate 16-byte pieces.  The tile goes through LDS instead (with one tile per workgroup the
+    // ring's stages, free now: every wave is past the last barrier), 64 columns at a time, each wave in a
+    // region of its own, rows padded to 272 bytes, and leaves in stores of four 256-byte row segments each.
+    if (wave_has_rows) {
+      float* wreg = (TPW == 2 ? s_out : (float*)&lds[0][0]) + wv * kOutFloats;
+      long long* row_off = (long long*)(wreg + ROWS * kRowStride);      // element offset of every row's output, -1: no row
+      float inv[NB];
 #pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    inv[b] = a.v_scale / sum_over_rows(lsum[b]);           // every row sees at least its own token
-    if (g4 == 0) row_off[16 * b + r16] = have[b] ? qrow[b] : -1;
-  }
+      for (int b = 0; b < NB; ++b) {
+        inv[b] = a.v_scale / sum_over_rows(lsum[b]);       // every row sees at least its own token
+        if (g4 == 0) row_off[16 * b + r16] = have[b] ? qrow[b] : -1;
+      }
 #pragma unroll
-  for (int half = 0; half < D / 64; ++half) {
+      for (int half = 0; half < D / 64; ++half) {
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        *(f32x4*)(wreg + (16 * b + r16) * kRowStride + 16 * j + 4 * g4) = O[b][4 * half + j] * inv[b];
-    // (a wave reads only what it wrote itself: no barrier, the compiler's wait for the LDS writes suffices)
+          for (int j = 0; j < 4; ++j)
+            *(f32x4*)(wreg + (16 * b + r16) * kRowStride + 16 * j + 4 * g4) = O[b][4 * half + j] * inv[b];
+        // (a wave reads only what it wrote itself: no barrier, the compiler's wait for the LDS writes suffices)
 #pragma unroll
-    for (int it = 0; it < ROWS / 4; ++it) {
-      const int r = 4 * it + (lane >> 4), dc = (lane & 15) * 4;
-      const long long off = row_off[r];
-      const f32x4 v = *(const f32x4*)(wreg + r * kRowStride + dc);
-      if (off >= 0) *(f32x4*)(a.out + off + 64 * half + dc) = v;
+        for (int it = 0; it < ROWS / 4; ++it) {
+          const int r = 4 * it + (lane >> 4), dc = (lane & 15) * 4;
+          const long long off = row_off[r];
+          const f32x4 v = *(const f32x4*)(wreg + r * kRowStride + dc);
+          if (off >= 0) *(f32x4*)(a.out + off + 64 * half + dc) = v;
+        }
+      }
+    }
+    if (t + 1 < n_tiles) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) { pos[b] = pos_n[b]; qrow[b] = qrow_n[b]; have[b] = have_n[b]; }
+      reset_state();
     }
   }
 }
@@ -523,9 +580,9 @@ void launch_prefill(const Ctx& c, const PrefillArgs& a, hipStream_t s) {
     const bool fp8 = dm.layout == SART_LAYOUT_MFMA16_FP8;
     if (!fp8) {   // bf16: the LDS-staged kernel
       const dim3 grid(a.max_tiles, a.n_seqs);
-      if (a.tile_rows == 2 * kPfTileRows) hipLaunchKernelGGL((k_prefill_b16<128, 8>), grid, dim3(512), 0, s, c, a, c.tb.prefix_table);
-      else if (dm.d == 128) hipLaunchKernelGGL((k_prefill_b16<128, 4>), grid, dim3(256), 0, s, c, a, c.tb.prefix_table);
-      else hipLaunchKernelGGL((k_prefill_b16<64, 4>), grid, dim3(256), 0, s, c, a, c.tb.prefix_table);
+      if (a.tile_rows == 2 * kPfTileRows) hipLaunchKernelGGL((k_prefill_b16<128, 8, 2>), grid, dim3(512), 0, s, c, a, c.tb.prefix_table);
+      else if (dm.d == 128) hipLaunchKernelGGL((k_prefill_b16<128, 4, 1>), grid, dim3(256), 0, s, c, a, c.tb.prefix_table);
+      else hipLaunchKernelGGL((k_prefill_b16<64, 4, 1>), grid, dim3(256), 0, s, c, a, c.tb.prefix_table);
       return;
     }
     if (dm.d == 128) go(k_prefill_mfma<128, true>); else go(k_prefill_mfma<64, true>);   // 8-bit float caches
