@@ -56,6 +56,9 @@ def test_whole_and_chunked_prefill_small(shape, mode):
     # the last n tokens only (what a chunked prefill asks for), an empty list entry, a request listed alone
     _check(cfg, o, g, [4, 2, 3], [37, 0, 100], [qs[4][-37:], qs[2][:0], qs[3]])
     _check(cfg, o, g, [1], [1], [qs[1][-1:]])
+    # a long last chunk after a first chunk (for the wider head groups this takes the 256-row tiles, two per
+    # workgroup, with queries that do not start at the prompt's first token), beside a short one
+    _check(cfg, o, g, [3, 4], [60, 200], [qs[3][-60:], qs[4][-200:]])
 
 
 def test_chunked_prefill_append_then_attend():
