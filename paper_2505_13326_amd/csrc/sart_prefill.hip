@@ -9,7 +9,8 @@
 // Design for MI355X (gfx950).  Unlike decode this is a dense contraction with
 // reuse: a K/V page serves every later query.  The rows of one kv head -
 // (query, head of the GQA group), query-major - are cut into tiles of
-// kPfTileRows, one workgroup per tile, on the matrix-core tile the decode kernel
+// kPfTileRows rows (twice that for long bf16 prompts, then two tiles per
+// workgroup), on the matrix-core tile the decode kernel
 // uses (S^T = K Q^T and O^T += V^T P^T as 16x16x32 bf16 products; online softmax
 // on the vector ALUs).  Pages are taken two at a time (32 tokens): one update of
 // the maximum per 32 tokens.  Blocks skip pairs that lie wholly after their
@@ -61,9 +62,9 @@ __device__ inline int last_le(const int* v, int n, int x) {
   return lo;
 }
 
-// The grid of the matrix-core kernels is (tiles of the longest listed sequence, sequences): block (x, y) is
-// tile x of sequence y, or nothing when that sequence has fewer tiles.  A tile is kPfTileRows rows of one kv
-// head; a sequence's later rows (longer contexts) come first.
+// The grid of the matrix-core kernels is (workgroups of the longest listed sequence, sequences): block (x, y)
+// is workgroup x of sequence y, or nothing when that sequence has fewer.  Here (8-bit float caches) a workgroup
+// is one tile of tile_rows rows of one kv head; a sequence's later rows (longer contexts) come first.
 struct PfTile { int req, nq, plen, h, rt; long long q_row0; };
 __device__ inline bool prefill_tile(const Dims& dm, const Tables& tb, int tile_rows, PfTile& t) {
   const int4 sq = ((const int4*)tb.pf_seq)[blockIdx.y];
