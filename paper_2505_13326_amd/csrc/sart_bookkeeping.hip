@@ -309,12 +309,15 @@ template <typename T>
 __global__ void __launch_bounds__(kPlanThreads)
 k_append_write_and_plan(Ctx c, PlanCfg pc, AppendArgs a) {
   const Tables& tb = c.tb;
-  if (!tb.scal[S_CALLOK]) return;
   if (blockIdx.x == 0) {                          // dispatched first: it is the longer of the two jobs
     __shared__ int lds[17];
-    if (tb.scal[S_PLAN_DEFERRED]) refresh_decode_plan(c, pc, lds);
+    // the flags and what the plan's first pass reads are requested together: the append plan's kernel has
+    // ended, so they are final (one trip to memory, where flag, count and rows would be three in a row)
+    const PlanPre pre = plan_preload(c);
+    if (pre.ok && pre.deferred) refresh_decode_plan<true>(c, pc, lds, pre);
     return;
   }
+  if (!tb.scal[S_CALLOK]) return;
   append_write_rows<T>(c, a, ((long long)(blockIdx.x - 1) * blockDim.x + threadIdx.x) >> 6,
                        ((long long)(gridDim.x - 1) * blockDim.x) >> 6);
 }

@@ -101,7 +101,33 @@ __device__ inline void record_error(int* scal, int code, int call_seq) {
 constexpr int kPlanLdsRows = 4096;   // active rows whose page_cum and lengths the plan keeps in LDS
 constexpr int kPlanLdsLive = 1024;   // live requests whose fields the plan keeps in LDS
 
-__device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int* lds) {
+// What the plan's first pass reads of the first kPlanThreads rows, for a caller that requested it earlier
+// (together with the flags that decide whether it plans at all: one trip to memory instead of three).
+struct PlanPre { int nA, b, b_prev, len, pm_choice, pm_a, pm_b, pm_c, ok, deferred; };
+__device__ inline PlanPre plan_preload(const Ctx& c) {
+  static_assert(S_COUNT <= 64, "the scalar block is read by one wave, a lane per entry");
+  const Tables& tb = c.tb;
+  const int ti = min((int)threadIdx.x, c.dm.H - 1);          // (rows past the active ones: any entry, unused)
+  // the whole scalar block with one load (lane l holds entry l), and this thread's row: four loads in flight
+  // together, all waited for here (the compiler would otherwise move each load to its first use, behind
+  // the branches on the earlier ones)
+  const int sv = tb.scal[min((int)threadIdx.x & 63, (int)S_COUNT - 1)];
+  const int b = tb.active[ti], b_prev = tb.active[max(ti - 1, 0)], len = tb.seq_len[ti];
+  asm volatile("" ::"v"(sv), "v"(b), "v"(b_prev), "v"(len));
+  PlanPre p;
+  p.b = b; p.b_prev = b_prev; p.len = len;
+  p.nA = __builtin_amdgcn_readlane(sv, S_NACTIVE);
+  p.ok = __builtin_amdgcn_readlane(sv, S_CALLOK);
+  p.deferred = __builtin_amdgcn_readlane(sv, S_PLAN_DEFERRED);
+  p.pm_choice = __builtin_amdgcn_readlane(sv, S_PM_CHOICE);
+  p.pm_a = __builtin_amdgcn_readlane(sv, S_PM_SIG_A);
+  p.pm_b = __builtin_amdgcn_readlane(sv, S_PM_SIG_B);
+  p.pm_c = __builtin_amdgcn_readlane(sv, S_PM_SIG_C);
+  return p;
+}
+
+template <bool PRE = false>
+__device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int* lds, PlanPre pre = PlanPre{}) {
   const Dims& dm = c.dm;
   const Tables& tb = c.tb;
   int* scal = tb.scal;
@@ -118,7 +144,8 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   (void)lds;
   if (tid == 0) { s_w2 = 0; s_it1 = 0; s_it2 = 0; }
   __syncthreads();                       // the caller's table updates are visible
-  const int nA = scal[S_NACTIVE];
+  if (!PRE) { pre.nA = scal[S_NACTIVE]; pre.pm_choice = scal[S_PM_CHOICE]; pre.pm_a = scal[S_PM_SIG_A]; pre.pm_b = scal[S_PM_SIG_B]; pre.pm_c = scal[S_PM_SIG_C]; }
+  const int nA = pre.nA;
   // w: weight of a live request with a prompt, on its first row: the prompt pages its work items read when
   // every branch reads them; w2: when every tile of 16 * kSharedBlocks query rows does
   int carry = 0, w_carry = 0, l_carry = 0;
@@ -127,11 +154,12 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
     const int i = base + tid;
     int np = 0, w = 0, first = 0, r = 0, cnt = 0, plen = 0;
     if (i < nA) {
-      const int b = tb.active[i];
+      const bool have = PRE && base == 0;                  // this row's entries came with the preload
+      const int b = have ? pre.b : tb.active[i];
       if (base == 0) my_handle = b;
       r = b / dm.Nb;
-      first = i == 0 || tb.active[i - 1] / dm.Nb != r;
-      const int len = tb.seq_len[i];
+      first = i == 0 || (have ? pre.b_prev : tb.active[i - 1]) / dm.Nb != r;
+      const int len = have ? pre.len : tb.seq_len[i];
       if (i < kPlanLdsRows) s_seq[i] = len;
       np = ceil_div(len, dm.pt);
       if (first) {
@@ -202,6 +230,13 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
   };
   int mode = pc.prompt_mode;
   long long u2 = 0;
+  // (the estimate is two more passes over the live requests: it is repeated only when what it rests on changed)
+  const long long own_per_wave = div_nn(cut.u_own + n_waves - 1, n_waves);
+  const int sig_a = nA, sig_b = w_carry;
+  const int sig_c = (int)((unsigned)n_live * 64u + (unsigned)(own_per_wave < 48 ? own_per_wave : 48) + (unsigned)pc.n_wg * 1000003u);
+  const bool automatic = mode != 1 && mode != 2;
+  const bool known = automatic && pre.pm_choice != 0 && pre.pm_a == sig_a && pre.pm_b == sig_b && pre.pm_c == sig_c;
+  if (known) mode = pre.pm_choice;
   if (mode != 1 && u1 > 0) {
     live_sums([&](int pp, int cnt, int& a1, int&) { a1 += pp * ceil_div(cnt * dm.G, 16 * kSharedBlocks); }, &s_w2, nullptr);
     u2 = (long long)__builtin_amdgcn_readfirstlane(s_w2) * dm.Hkv;
@@ -216,9 +251,11 @@ __device__ inline void refresh_decode_plan(const Ctx& c, const PlanCfg& pc, int*
       }, &s_it1, &s_it2);
       const int it1 = __builtin_amdgcn_readfirstlane(s_it1), it2 = __builtin_amdgcn_readfirstlane(s_it2);   // uniform, and known to be so
       const long long cost1 = (long long)ceil_div(it1, n_waves) * pb1, cost2 = (long long)ceil_div(it2, n_waves) * pb2;
-      const long long own_per_wave = div_nn(cut.u_own + n_waves - 1, n_waves);
       if (cost1 - cost2 >= (own_per_wave < 48 ? own_per_wave : 48)) mode = 2;
     }
+  }
+  if (automatic && !known && tid == 0) {
+    scal[S_PM_CHOICE] = mode; scal[S_PM_SIG_A] = sig_a; scal[S_PM_SIG_B] = sig_b; scal[S_PM_SIG_C] = sig_c;
   }
   const long long u_prompt = mode == 2 ? u2 : u1;           // prompt units of the step
   // every wave serves both its share of the prompt work items and its range of the own line

@@ -53,7 +53,13 @@ enum Scalar {
   S_D_PMODE,      // how the step's prompts are read: 1 per branch, 2 per tile of 16 query rows (chosen by the plan)
   S_PLAN_DEFERRED,// the append plan left the decode plan to the write kernel's extra workgroup
   S_ANY_FORK,     // some branch was split since the cache was created: branch pages may be shared
-  S_COUNT = 32
+  // the plan's last choice of how prompts are read, and what it was made from (the estimate behind it is
+  // repeated only when one of these changes)
+  S_PM_CHOICE,
+  S_PM_SIG_A,     // active rows
+  S_PM_SIG_B,     // prompt pages over the live requests' branches
+  S_PM_SIG_C,     // live requests, private units per wave (up to the rule's cap), attention workgroups
+  S_COUNT = 40
 };
 
 struct Dims {
