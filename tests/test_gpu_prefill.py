@@ -145,3 +145,35 @@ def test_scores_that_keep_rising(slope):
     q = wl.f32_to_bf16_bits(np.ones((P, cfg.n_q_heads, cfg.head_dim), np.float32))
     err = _check(cfg, o, g, [0], [P], [q])
     print(f"rising scores, slope {slope}: max abs err {err:.3g}")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_geometries_and_lengths(seed):
+    """Seeded draws of the head geometry, the prompt lengths of five requests (so that the tiles per kv head come
+    out odd and even, one and many, with ragged last tiles) and the number of trailing queries of each, attended
+    in one call; then the same prompts grown by a random chunk and attended for that chunk only."""
+    rng = np.random.default_rng(4242 + seed)
+    Hkv = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.integers(1, 9))
+    d = 64 if seed % 4 == 3 else 128
+    top = int(rng.choice([90, 260, 700]))
+    cfg = wl.scaled(wl.CONFIGS[2], n_q_heads=Hkv * G, n_kv_heads=Hkv, head_dim=d, n_requests=5, nb=2, prompt_len=top + 130)
+    P = [int(x) for x in rng.integers(1, top + 1, size=5)]
+    grow = [int(x) for x in rng.integers(1, 130, size=5)]
+    max_pp = -(-(top + 130) // 16)
+    pages = sum(-(-(p + g_) // 16) for p, g_ in zip(P, grow)) + 4
+    o, g = _pair(cfg, pages, max_pp, free_order=wl.free_order(cfg, pages))
+    kv = [wl.prefix_kv(cfg, r, P[r] + grow[r]) for r in range(5)]
+    qs = [wl.prefix_query(cfg, r, P[r] + grow[r]) for r in range(5)]
+    for r in range(5):
+        for e in (o, g):
+            assert e.append(orc.SEQ_PREFIX, [r], [P[r]], kv[r][0][:P[r]], kv[r][1][:P[r]]) == orc.OK
+    nq = [int(rng.integers(0, p + 1)) for p in P]
+    nq[int(np.argmax(P))] = max(P)                 # the longest prompt whole: decides the tile size of the call
+    order = [int(x) for x in rng.permutation(5)]
+    _check(cfg, o, g, order, [nq[r] for r in order], [qs[r][P[r] - nq[r]:P[r]] for r in order])
+    for r in range(5):
+        for e in (o, g):
+            assert e.append(orc.SEQ_PREFIX, [r], [grow[r]], kv[r][0][P[r]:], kv[r][1][P[r]:]) == orc.OK
+    err = _check(cfg, o, g, list(range(5)), grow, [qs[r][P[r]:] for r in range(5)])
+    print(f"seed {seed}: Hkv {Hkv} G {G} d {d} prompts {P} + {grow}: max abs err {err:.3g}")
