@@ -92,8 +92,11 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
     qs = []
     for r in range(R):
         k, v = wl.prefix_kv(cfg, r)
+        qr = wl.prefix_query(cfg, r)
+        if args.zero_data:                                   # what the operands' values cost: see --zero-data
+            k, v, qr = np.zeros_like(k), np.zeros_like(v), np.zeros_like(qr)
         cache.append_tokens(sart.SEQ_PREFIX, [r], [P], k, v)
-        qs.append(wl.prefix_query(cfg, r))
+        qs.append(qr)
     q = dev(np.concatenate(qs))
     out = torch.empty((R * P, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
     ids, nq = list(range(R)), [P] * R
@@ -143,7 +146,8 @@ def bench_prefill(args, cfg, sart, wl, np, torch):
     return ({
         "metric": "prefill attention, algorithmic causal flops per second", "value": round(flops / dt / 1e12, 2),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(dt * 1e3, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype,
+        "data": "all zero (measurement aid)" if args.zero_data else "synthetic",
         "config": {"workload": f"prompts of config {cfg.cfg_id}: {R} requests x {P} tokens, Hq {cfg.n_q_heads} / Hkv "
                                f"{cfg.n_kv_heads}, d {cfg.head_dim}, one call", "kv_bytes": kv_bytes},
         "roofline": roofline, "cpu_baseline": cpu})
@@ -555,6 +559,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="replay the step (append + attention) from a HIP graph (cfg3: the device-driven step)")
     ap.add_argument("--host-loop", action="store_true", help="cfg3: the host-driven step (the host gathers the active rows and lists the completed "
                     "branches, reading the state back after every call that changes the batch) instead of the device-driven one")
+    ap.add_argument("--zero-data", action="store_true", help="prefill workloads: all-zero Q, K and V instead of the seeded draws "
+                    "(the matrix cores' clock follows the power drawn, and that the operand values: a measurement aid, not a result)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests the oracle is timed on (0 = auto)")
     args = ap.parse_args()
